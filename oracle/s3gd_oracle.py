@@ -1,0 +1,176 @@
+"""CPU oracle for one S3GD-MV step.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, plain definition of what the HIP library computes.  It
+is imported by the tests, by the smoke check and by the benchmark's CPU
+baseline leg, never by the product path, and it shares no code with the
+kernels.  Every function cites the passage of the paper it writes out.
+
+Readings taken where the paper is silent (the same list is kept in the design
+notes):
+
+* TopK(u) keeps the selected entries of u (it is used as a masked vector in the
+  error-memory update of Algorithm 1), so TopKSign(u)_n = sgn(u_n) on the
+  selected index set and 0 elsewhere (Section 2.1, eqs. "topk"/"topksign").
+* Exactly K indices are selected.  Among equal magnitudes the lowest index
+  wins, i.e. the order is (|u| descending, index ascending).
+* A selected entry equal to +-0 has sgn = 0: it sends no sign and is not part
+  of the support N_m (Section 2.2, "Majority vote").
+* sgn(0) = 0 also decides vote ties and coordinates nobody voted on.
+* The update is evaluated in fp32 with one rounding: x - lr * vote.
+* NaN gradients are outside the input contract and are rejected.
+
+Message format shared with the library's interface (a format, not code):
+word = (index << 1) | (1 if value < 0 else 0), ascending per row, rows padded
+to K words with 0xFFFFFFFF, counts[m] = number of valid words in row m.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PAD = np.uint32(0xFFFFFFFF)
+
+
+def sgn(u: np.ndarray) -> np.ndarray:
+    """sgn(u) = 1{u>0} - 1{u<0}, element-wise (Section 2.1, below eq. "topksign")."""
+    u = np.asarray(u)
+    return (u > 0).astype(np.int8) - (u < 0).astype(np.int8)
+
+
+def _check_row(g: np.ndarray, K: int) -> np.ndarray:
+    g = np.asarray(g)
+    if g.ndim != 1 or g.dtype != np.float32:
+        raise ValueError("a gradient row is a 1-d float32 array")
+    if not 0 <= K <= g.shape[0]:
+        raise ValueError("K must satisfy 0 <= K <= N (sparsity K/N lies in [0,1])")
+    if np.isnan(g).any():
+        raise ValueError("NaN in gradient: outside the input contract")
+    return g
+
+
+def topk_index_set(g: np.ndarray, K: int) -> np.ndarray:
+    """Indices of the K largest-magnitude entries of g, ascending (TopK, eq. "topk").
+
+    Full sort of the pairs (|g_n|, n) by magnitude descending then index
+    ascending; the first K are selected.
+    """
+    g = _check_row(g, K)
+    mag = np.abs(g)  # float comparison on |g|; -0.0 becomes +0.0
+    n = np.arange(g.shape[0], dtype=np.int64)
+    order = np.lexsort((n, -mag))  # last key is primary: -|g| ascending == |g| descending
+    return np.sort(order[:K])
+
+
+def topk_index_set_brute_force(g: np.ndarray, K: int) -> np.ndarray:
+    """Same set from the rank definition, without sorting (tiny N only).
+
+    rank(n) = #{j : |g_j| > |g_n|} + #{j < n : |g_j| == |g_n|}; n is selected
+    iff rank(n) < K.
+    """
+    g = _check_row(g, K)
+    N = g.shape[0]
+    mag = [abs(float(v)) for v in g]
+    sel = []
+    for n in range(N):
+        rank = 0
+        for j in range(N):
+            if mag[j] > mag[n] or (mag[j] == mag[n] and j < n):
+                rank += 1
+        if rank < K:
+            sel.append(n)
+    return np.asarray(sel, dtype=np.int64)
+
+
+def rank_of(g: np.ndarray, n: int) -> int:
+    """rank(n) of the definition above for one coordinate, O(N) vectorised.
+
+    Lets a test decide membership of single coordinates at sizes where a full
+    sort is too slow: n is in the top-K set iff rank_of(g, n) < K.
+    """
+    mag = np.abs(g)
+    t = mag[n]
+    return int(np.count_nonzero(mag > t)) + int(np.count_nonzero(mag[:n] == t))
+
+
+def topk_sign_dense(g: np.ndarray, K: int) -> np.ndarray:
+    """TopKSign(g) as the ternary vector in {-1,0,+1}^N (eq. "topksign")."""
+    out = np.zeros(g.shape[0], dtype=np.int8)
+    S = topk_index_set(g, K)
+    out[S] = sgn(g[S])
+    return out
+
+
+def encode_row(g: np.ndarray, K: int) -> tuple[np.ndarray, int]:
+    """The message worker m sends (Algorithm 1, "send TopKSign(g_m)"): K words, count."""
+    S = topk_index_set(g, K)
+    s = sgn(g[S])
+    keep = s != 0  # zero entries cast no vote and are not in the support
+    words = np.full(K, PAD, dtype=np.uint32)
+    w = (S[keep].astype(np.uint64) << np.uint64(1)) | (s[keep] < 0).astype(np.uint64)
+    words[: w.shape[0]] = w.astype(np.uint32)
+    return words, int(w.shape[0])
+
+
+def topk_sign_encode(G: np.ndarray, K: int) -> tuple[np.ndarray, np.ndarray]:
+    """All M messages: words [M,K] uint32, counts [M] uint32 (Algorithm 1, worker loop)."""
+    G = np.asarray(G)
+    if G.ndim != 2 or G.dtype != np.float32:
+        raise ValueError("gradients are a [M,N] float32 array")
+    M = G.shape[0]
+    if G.shape[1] > (1 << 31) - 2:
+        raise ValueError("index + sign bit + pad word must fit 32 bits")
+    words = np.empty((M, K), dtype=np.uint32)
+    counts = np.empty(M, dtype=np.uint32)
+    for m in range(M):
+        words[m], counts[m] = encode_row(G[m], K)
+    return words, counts
+
+
+def majority_vote(words: np.ndarray, counts: np.ndarray, N: int) -> tuple[np.ndarray, np.ndarray]:
+    """Server side (Section 2.2 "Majority vote"; Algorithm 1 "receive sgn[sum ...]").
+
+    tally_n = sum over workers of TopKSign(g_m)_n; votes_n = sgn(tally_n).
+    Coordinates outside the union of supports keep tally 0 and vote 0.
+    """
+    tally = np.zeros(N, dtype=np.int32)
+    for m in range(words.shape[0]):
+        w = words[m, : int(counts[m])]
+        idx = (w >> np.uint32(1)).astype(np.int64)
+        if idx.size and (idx.max() >= N):
+            raise ValueError("word index out of range")
+        delta = np.where((w & np.uint32(1)) == 1, np.int32(-1), np.int32(1))
+        np.add.at(tally, idx, delta)  # tally[idx[i]] += delta[i] for every i, in order
+    return tally, sgn(tally)
+
+
+def majority_vote_loops(words, counts, N):
+    """The same double loop spelled out in Python (small inputs only)."""
+    tally = [0] * N
+    for m in range(len(words)):
+        for i in range(int(counts[m])):
+            w = int(words[m][i])
+            tally[w >> 1] += -1 if (w & 1) else 1
+    votes = [(t > 0) - (t < 0) for t in tally]
+    return np.asarray(tally, dtype=np.int32), np.asarray(votes, dtype=np.int8)
+
+
+def apply_update(x: np.ndarray, votes: np.ndarray, lr) -> np.ndarray:
+    """x^{t+1} = x^t - delta * vote in fp32, one rounding (eq. "s3gd")."""
+    x = np.asarray(x)
+    if x.dtype != np.float32:
+        raise ValueError("parameters are float32")
+    return (x - np.float32(lr) * votes.astype(np.float32)).astype(np.float32)
+
+
+def step(G: np.ndarray, K: int, x: np.ndarray, lr) -> dict:
+    """One iteration of Algorithm 1 after the gradients exist: encode, vote, update."""
+    words, counts = topk_sign_encode(G, K)
+    tally, votes = majority_vote(words, counts, G.shape[1])
+    return dict(words=words, counts=counts, tally=tally, votes=votes, x=apply_update(x, votes, lr))
+
+
+def step_dense(G: np.ndarray, K: int, x: np.ndarray, lr) -> dict:
+    """Eq. "s3gd" evaluated literally on dense ternary vectors (no message format)."""
+    T = np.stack([topk_sign_dense(G[m], K) for m in range(G.shape[0])]).astype(np.int32)
+    tally = T.sum(axis=0, dtype=np.int32)
+    votes = sgn(tally)
+    return dict(tally=tally, votes=votes, x=apply_update(x, votes, lr))
