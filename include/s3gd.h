@@ -1,0 +1,149 @@
+/*
+ * s3gd.h - C ABI of the S3GD-MV step library for AMD MI355X (gfx950).
+ *
+ * One step of sparse sign SGD with majority vote (Algorithm 1 of the paper, the
+ * lines after the local gradient exists):
+ *
+ *   1. every worker m keeps the K largest-magnitude entries of its gradient
+ *      g_m in R^N and sends only their signs, TopKSign(g_m)   (Section 2.1,
+ *      eqs. "topk" and "topksign"; Section 2.2 "Gradient compression");
+ *   2. the server sums the ternary messages per coordinate and takes the sign
+ *      of the sum, with sgn(0) = 0                            (Section 2.2
+ *      "Majority vote");
+ *   3. the model moves by x <- x - delta * vote               (eq. "s3gd").
+ *
+ * All M workers are held as one row-major [M, N] fp32 tensor on one GPU.
+ *
+ * Conventions
+ *   - Every pointer marked "dev" is DEVICE memory owned by the CALLER; the
+ *     library never frees, reallocates or keeps it after the call's work has
+ *     run.  Pointers marked "host" are ordinary host memory.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and return without synchronising the host.  Outputs are
+ *     valid once the stream has reached that point.
+ *   - Return value: 0 on success, a negative S3GD_E_* code otherwise.  Argument
+ *     checks are done on the host before anything is enqueued; a failed call
+ *     enqueues nothing.  No exceptions, no abort, nothing printed.
+ *   - A context owns only scratch memory.  It is bound to one device and must
+ *     not be used from two host threads or two streams at the same time.
+ *   - Results are deterministic: the same inputs give bit-identical outputs.
+ *
+ * Message format (one 32-bit word per selected non-zero entry)
+ *     word = (n << 1) | (g_{m,n} < 0)
+ *   Words of a row are in ascending n.  A row has K slots; slots beyond
+ *   counts[m] hold S3GD_PAD.  counts[m] == K unless fewer than K entries of the
+ *   row are non-zero: a selected entry that is +0 or -0 has sgn = 0, sends
+ *   nothing and is not in the support set N_m of Section 2.2.
+ *
+ * Selection rule.  Exactly K indices are selected per row.  The paper places
+ *   the threshold between the K-th and (K+1)-th largest magnitude and says
+ *   nothing about equal magnitudes; here the order is (|g| descending, index
+ *   ascending), i.e. among equal magnitudes the lowest index wins.
+ */
+#ifndef S3GD_H
+#define S3GD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define S3GD_API __attribute__((visibility("default")))
+#else
+#define S3GD_API
+#endif
+
+#define S3GD_OK 0
+#define S3GD_E_INVAL (-1) /* NULL pointer, M == 0, N == 0, K > N, size above the context's maxima,  */
+                          /* misaligned buffer, lr negative or not finite, both vote outputs NULL   */
+#define S3GD_E_RANGE (-2) /* N > S3GD_N_LIMIT: index, sign bit and pad word must fit 32 bits         */
+#define S3GD_E_HIP (-3)   /* a HIP runtime call failed; s3gd_last_hip_error() has its code           */
+#define S3GD_E_NOMEM (-4) /* scratch allocation failed                                               */
+#define S3GD_E_NAN (-5)   /* reported by s3gd_last_async_status(): a NaN was seen in grads           */
+
+#define S3GD_PAD 0xFFFFFFFFu
+#define S3GD_N_LIMIT 2147483646ull /* 2^31 - 2 */
+
+typedef struct s3gd_ctx s3gd_ctx; /* opaque */
+typedef void* s3gd_stream_t;      /* hipStream_t */
+
+/* Bytes of device scratch a context created for these maxima allocates.  Pure host function. */
+S3GD_API size_t s3gd_workspace_bytes(uint32_t M_max, uint64_t N_max, uint64_t K_max);
+
+/* Creates a context on `device` and allocates its scratch once (hipMalloc).  Calls with
+ * M <= M_max, N <= N_max, K <= K_max never allocate.  `out` is host memory. */
+S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_max, uint64_t K_max);
+
+/* Frees the scratch.  The caller must have synchronised every stream that used the context. */
+S3GD_API int s3gd_destroy(s3gd_ctx* ctx);
+
+/*
+ * Worker side of Algorithm 1: words[m, :] = TopKSign(g_m) in the message format above
+ * (Section 2.1 eqs. "topk", "topksign"; Section 2.2 "Gradient compression").
+ *
+ *   grads   dev, const  [M, N] fp32, row stride N, 4-byte aligned.  Never modified.  +-Inf is
+ *                       legal; NaN is outside the contract (it is detected and reported through
+ *                       s3gd_last_async_status, the outputs are then unspecified but in bounds).
+ *   words   dev, out    [M, K] uint32, 4-byte aligned.  Every slot is written.
+ *   counts  dev, out    [M] uint32.
+ *   K       0 <= K <= N.  K == 0 writes counts = 0 only.  K == N sends every non-zero sign
+ *           (signSGD with majority vote).
+ * Outputs must not overlap inputs.
+ */
+S3GD_API int s3gd_topk_sign_encode(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K,
+                          uint32_t* words, uint32_t* counts, s3gd_stream_t stream);
+
+/*
+ * Server side: tally[n] = sum_m TopKSign(g_m)_n, votes[n] = sgn(tally[n]) with sgn(0) = 0
+ * (Section 2.2 "Majority vote"; Algorithm 1, the "receive" line).
+ *
+ *   words, counts  dev, const  as written by s3gd_topk_sign_encode: ascending indices < N per row,
+ *                              counts[m] <= K.  Rows with counts[m] == 0 cast no vote.
+ *   tally   dev, out, nullable [N] int32, 16-byte aligned.
+ *   votes   dev, out, nullable [N] int8,  16-byte aligned.  Not both NULL.
+ * Every element of each non-NULL output is written (0 outside the union of supports).
+ */
+S3GD_API int s3gd_majority_vote(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M,
+                       uint64_t N, uint64_t K, int32_t* tally, int8_t* votes, s3gd_stream_t stream);
+
+/*
+ * Model update, eq. "s3gd": x[n] <- fp32(x[n] - lr * votes[n]), one rounding; x[n] is left
+ * bit-identical where votes[n] == 0.
+ *
+ *   x      dev, in/out  [N] fp32, 16-byte aligned.
+ *   votes  dev, const   [N] int8 in {-1, 0, +1}, 16-byte aligned.
+ *   lr     step size delta >= 0, finite.
+ */
+S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, float lr, uint64_t N,
+                      s3gd_stream_t stream);
+
+/*
+ * The three calls above fused into one enqueue, same results.  tally and votes may both be
+ * NULL; then the vote is applied to x without being materialised and only the cache lines of
+ * x that hold a voted coordinate are touched.
+ */
+S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, float* x,
+              float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
+              s3gd_stream_t stream);
+
+/* Synchronises `stream`, then returns 0, or S3GD_E_NAN if the last encode on this context saw a
+ * NaN, or S3GD_E_HIP. */
+S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
+
+/* Diagnostics of the last encode on this context, read back after synchronising `stream`:
+ * out[0] = number of rows, out[1] = rows that took the general multi-pass path because the
+ * single-pass candidate filter did not apply to them.  `out` is host memory, 2 entries. */
+S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
+
+/* hipError_t value of the last failed HIP call made through this context (0 if none). */
+S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx);
+
+S3GD_API const char* s3gd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S3GD_H */

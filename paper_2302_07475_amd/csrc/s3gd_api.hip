@@ -1,0 +1,215 @@
+// C ABI of the library: argument checks, scratch ownership, stage sequencing.
+#include <math.h>
+#include <new>
+
+#include "s3gd_common.h"
+#include "s3gd_kernels.h"
+
+using namespace s3gd;
+
+struct s3gd_ctx {
+  int device;
+  u32 M_max;
+  u64 N_max, K_max;
+  void* base;
+  size_t bytes;
+  Workspace ws;
+  int last_hip;
+};
+
+namespace {
+
+constexpr u32 kMaxRows = 65535;  // rows map to gridDim.y
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+  size_t rs, status, hist, tile_cnt, seg, total;
+};
+
+Layout layout(u32 M, u64 N, u64 /*K*/) {
+  Layout l{};
+  size_t off = 0;
+  l.rs = off;       off = align_up(off + sizeof(RowState) * (size_t)M, 256);
+  l.status = off;   off = align_up(off + sizeof(u32) * 4, 256);
+  l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
+  l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
+  l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * (vote_tiles(N) + 1), 256);
+  l.total = off;
+  return l;
+}
+
+// Makes the context's device current for the duration of a call.
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t err = hipSuccess;
+  explicit DeviceGuard(int dev) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != dev) {
+      err = hipSetDevice(dev);
+      switched = err == hipSuccess;
+    }
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_shape(const s3gd_ctx* c, u32 M, u64 N, u64 K) {
+  if (!c) return S3GD_E_INVAL;
+  if (M == 0 || N == 0) return S3GD_E_INVAL;
+  if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (K > N) return S3GD_E_INVAL;
+  if (M > c->M_max || N > c->N_max || K > c->K_max) return S3GD_E_INVAL;
+  return S3GD_OK;
+}
+
+int hip_fail(s3gd_ctx* c, hipError_t e) {
+  c->last_hip = (int)e;
+  return S3GD_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+S3GD_API size_t s3gd_workspace_bytes(uint32_t M_max, uint64_t N_max, uint64_t K_max) {
+  if (M_max == 0 || N_max == 0 || N_max > S3GD_N_LIMIT) return 0;
+  return layout(M_max, N_max, K_max).total;
+}
+
+S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_max, uint64_t K_max) {
+  if (!out) return S3GD_E_INVAL;
+  *out = nullptr;
+  if (M_max == 0 || M_max > kMaxRows || N_max == 0 || device < 0) return S3GD_E_INVAL;
+  if (N_max > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (K_max > N_max) K_max = N_max;
+  s3gd_ctx* c = new (std::nothrow) s3gd_ctx{};
+  if (!c) return S3GD_E_NOMEM;
+  c->device = device;
+  c->M_max = M_max;
+  c->N_max = N_max;
+  c->K_max = K_max;
+  DeviceGuard g(device);
+  if (g.err != hipSuccess) { delete c; return S3GD_E_HIP; }
+  const Layout l = layout(M_max, N_max, K_max);
+  const hipError_t e = hipMalloc(&c->base, l.total);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return e == hipErrorOutOfMemory ? S3GD_E_NOMEM : S3GD_E_HIP;
+  }
+  c->bytes = l.total;
+  char* b = static_cast<char*>(c->base);
+  c->ws.rs = reinterpret_cast<RowState*>(b + l.rs);
+  c->ws.status = reinterpret_cast<u32*>(b + l.status);
+  c->ws.hist = reinterpret_cast<u32*>(b + l.hist);
+  c->ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
+  c->ws.seg = reinterpret_cast<u32*>(b + l.seg);
+  *out = c;
+  return S3GD_OK;
+}
+
+S3GD_API int s3gd_destroy(s3gd_ctx* ctx) {
+  if (!ctx) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  const hipError_t e = hipFree(ctx->base);
+  delete ctx;
+  return e == hipSuccess ? S3GD_OK : S3GD_E_HIP;
+}
+
+S3GD_API int s3gd_topk_sign_encode(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, uint32_t* words,
+                          uint32_t* counts, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!grads || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_encode(ctx->ws, grads, M, N, K, words, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_majority_vote(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N, uint64_t K,
+                       int32_t* tally, int8_t* votes, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!counts || (K > 0 && !words) || (!tally && !votes)) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(tally, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, nullptr, 0.0f, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, float lr, uint64_t N, s3gd_stream_t stream) {
+  if (!ctx || !x || !votes || N == 0) return S3GD_E_INVAL;
+  if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (N > ctx->N_max) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!aligned(x, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_update(x, votes, lr, N, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, float* x, float lr, uint32_t* words,
+              uint32_t* counts, int32_t* tally, int8_t* votes, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!grads || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) ||
+      !aligned(votes, 16))
+    return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_encode(ctx->ws, grads, M, N, K, words, counts, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
+  e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream) {
+  if (!ctx) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  u32 st[2] = {0, 0};
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) e = hipMemcpy(st, ctx->ws.status, sizeof(st), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  return st[0] ? S3GD_E_NAN : S3GD_OK;
+}
+
+S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out) {
+  if (!ctx || !out) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  u32 st[3] = {0, 0, 0};
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) e = hipMemcpy(st, ctx->ws.status, sizeof(st), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  out[0] = st[2];
+  out[1] = st[1];
+  return S3GD_OK;
+}
+
+S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+S3GD_API const char* s3gd_strerror(int code) {
+  switch (code) {
+    case S3GD_OK: return "ok";
+    case S3GD_E_INVAL: return "invalid argument";
+    case S3GD_E_RANGE: return "N exceeds 2^31 - 2";
+    case S3GD_E_HIP: return "HIP runtime error";
+    case S3GD_E_NOMEM: return "out of device memory";
+    case S3GD_E_NAN: return "NaN in gradients";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,150 @@
+// Shared declarations of the S3GD-MV HIP library (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "s3gd.h"
+
+namespace s3gd {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+// ---- geometry -------------------------------------------------------------------------------
+constexpr int kBlock = 256;                 // threads of the streaming kernels (4 waves)
+constexpr int kWaves = kBlock / 64;
+constexpr int kLoads = 4;                   // 16-byte loads per thread and tile
+constexpr int kTile = kBlock * 4 * kLoads;  // 4096 gradient entries per tile
+constexpr int kHistBins = 2048;             // first radix digit: key bits [30:20]
+constexpr int kVoteTile = 8192;             // coordinates tallied in LDS by one block
+constexpr int kScanBlock = 1024;
+
+// Radix digits of the 31-bit magnitude key, most significant first.
+__host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 20 : (level == 1 ? 10 : 0); }
+__host__ __device__ constexpr int digit_bits(int level) { return level == 0 ? 11 : 10; }
+
+// Per-row selection state, device resident.
+struct RowState {
+  u32 prefix;     // key bits fixed so far (right aligned)
+  u32 k_rem;      // rank still sought inside the current prefix, 1-based from the largest
+  u32 T;          // K-th largest key: the threshold rho taken at the K-th value (eq. "topk")
+  u32 q;          // entries with key == T that are selected (lowest indices first); 0 when T == 0
+  u32 c_gt;       // entries with key > T
+  u32 count;      // words the row emits = c_gt + q
+  u32 mode;       // kModeFast / kModeGeneral
+  u32 n_cand;     // candidates collected by the filter pass
+  u32 L;          // candidate lower bound on the key
+  u32 cand_ok;    // 1 when K <= n_cand <= capacity
+  u32 pad[6];
+};
+static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
+
+constexpr u32 kModeGeneral = 0;
+constexpr u32 kModeFast = 1;
+
+// ---- wave / block primitives ----------------------------------------------------------------
+__device__ __forceinline__ u32 lane_id() {
+  return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+// number of set bits of a wave ballot below the calling lane
+__device__ __forceinline__ u32 ballot_rank(u64 b) {
+  return __builtin_amdgcn_mbcnt_hi((u32)(b >> 32), __builtin_amdgcn_mbcnt_lo((u32)b, 0u));
+}
+__device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {
+  const u32 lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    T o = __shfl_up(v, d, 64);
+    if (lane >= (u32)d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan over the threads of a block (blockDim.x a multiple of 64, at most 1024).
+// `lds` holds at least blockDim.x / 64 entries.  Returns the exclusive prefix; *total = block sum.
+template <typename T>
+__device__ __forceinline__ T block_excl_scan(T v, T* total, T* lds) {
+  const u32 lane = lane_id();
+  const u32 wave = threadIdx.x >> 6;
+  const u32 nw = blockDim.x >> 6;
+  T inc = wave_incl_scan(v);
+  if (lane == 63) lds[wave] = inc;
+  __syncthreads();
+  T base = 0, tot = 0;
+  for (u32 w = 0; w < nw; ++w) {
+    T s = lds[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + inc - v;
+}
+
+// ---- tile of one gradient row in registers ----------------------------------------------------
+// A row starts at a 4-byte aligned address.  `a` = number of fp32 slots between the previous
+// 16-byte boundary and the row start (0..3).  Tiles are laid over the "virtual" index
+// v = n + a, so that every 16-byte load is aligned.  Entry (j, e) of thread t is
+// v = tile*kTile + j*1024 + t*4 + e: ascending v is the order (j, wave, lane, e).
+struct TileRegs {
+  u32 b[kLoads * 4];  // raw fp32 bit patterns
+  u32 valid;          // bit (4j+e) set when the entry lies inside the row
+};
+
+__device__ __forceinline__ void load_tile(const u32* __restrict__ rowv /* row start minus a slots */,
+                                          u32 a, u64 vend /* N + a */, u64 vbase, TileRegs& r) {
+  r.valid = 0;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const u64 v = vbase + (u64)j * (kBlock * 4) + (u64)threadIdx.x * 4;
+    if (v >= a && v + 4 <= vend) {
+      const uint4 q = *reinterpret_cast<const uint4*>(rowv + v);
+      r.b[4 * j + 0] = q.x; r.b[4 * j + 1] = q.y; r.b[4 * j + 2] = q.z; r.b[4 * j + 3] = q.w;
+      r.valid |= 0xFu << (4 * j);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const u64 ve = v + e;
+        if (ve >= a && ve < vend) {
+          r.b[4 * j + e] = rowv[ve];
+          r.valid |= 1u << (4 * j + e);
+        } else {
+          r.b[4 * j + e] = 0;
+        }
+      }
+    }
+  }
+}
+
+// Ranks of flagged entries of a tile in ascending index order.
+// mask: bit (4j+e) of this thread's entries.  base[j] = number of flagged entries of the block that
+// precede this thread's load j.  *total = flagged entries in the block.  lds: kLoads*kWaves entries.
+__device__ __forceinline__ void tile_rank(u32 mask, u32 base[kLoads], u32* total, u32* lds) {
+  const u32 wave = threadIdx.x >> 6;
+  const u32 lane = lane_id();
+  u32 pre[kLoads];
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const u32 c = __popc((mask >> (4 * j)) & 0xFu);  // 0..4
+    const u64 b0 = ballot(c & 1u), b1 = ballot(c & 2u), b2 = ballot(c & 4u);
+    pre[j] = ballot_rank(b0) + 2u * ballot_rank(b1) + 4u * ballot_rank(b2);
+    if (lane == 0) lds[j * kWaves + wave] = __popcll(b0) + 2u * __popcll(b1) + 4u * __popcll(b2);
+  }
+  __syncthreads();
+  u32 run = 0;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if ((u32)w == wave) base[j] = run + pre[j];
+      run += lds[j * kWaves + w];
+    }
+  }
+  *total = run;
+  __syncthreads();
+}
+
+}  // namespace s3gd

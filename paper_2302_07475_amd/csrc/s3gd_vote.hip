@@ -1,0 +1,183 @@
+// Server side of Algorithm 1: signed tally of the workers' messages per coordinate, its sign
+// (sgn(0) = 0 for ties and for coordinates nobody voted on; Section 2.2 "Majority vote") and the
+// model update x <- x - lr * vote (eq. "s3gd").
+//
+// Messages are sorted by index, so each row is cut once into per-tile segments by binary search;
+// a block then owns kVoteTile consecutive coordinates, tallies them with LDS integer atomics and is
+// the only writer of that stretch of the outputs.
+#include "s3gd_common.h"
+#include "s3gd_kernels.h"
+
+namespace s3gd {
+
+constexpr int kRowChunk = 256;  // rows whose segment bounds sit in LDS at once
+
+// seg[m][t] = first position of row m whose index is >= t * kVoteTile (t = 0 .. n_vt).
+__global__ void k_seg_bounds(const u32* __restrict__ words, const u32* __restrict__ counts, u64 K, u32 n_vt, u32 seg_stride,
+                             u32* __restrict__ seg) {
+  const u32 m = blockIdx.y;
+  const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t > n_vt) return;
+  const u32* w = words + (size_t)m * K;
+  const u64 target = ((u64)t * kVoteTile) << 1;
+  u32 lo = 0, hi = counts[m];
+  if ((u64)hi > K) hi = (u32)K;  // a count above the row length is a caller error; stay in bounds
+  while (lo < hi) {
+    const u32 mid = lo + ((hi - lo) >> 1);
+    if ((u64)w[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  seg[(size_t)m * seg_stride + t] = lo;
+}
+
+__device__ __forceinline__ void load_bounds(const u32* __restrict__ seg, u32 seg_stride, u32 m0, u32 M, u32 tile, u32* lo, u32* hi) {
+  const u32 m = m0 + threadIdx.x;
+  if (threadIdx.x < kRowChunk && m < M) {
+    lo[threadIdx.x] = seg[(size_t)m * seg_stride + tile];
+    hi[threadIdx.x] = seg[(size_t)m * seg_stride + tile + 1];
+  }
+}
+
+// Dense variant: writes every element of tally and/or votes, optionally updates x.
+__global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
+                                                       u32 seg_stride, u32 M, u64 N, int32_t* __restrict__ tally,
+                                                       int8_t* __restrict__ votes, float* __restrict__ x, float lr) {
+  __shared__ __attribute__((aligned(16))) int32_t t[kVoteTile];
+  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
+  const u32 tile = blockIdx.x;
+  const u64 base = (u64)tile * kVoteTile;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x * 4; i < kVoteTile; i += kBlock * 4) *reinterpret_cast<int4*>(&t[i]) = make_int4(0, 0, 0, 0);
+  for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
+    __syncthreads();
+    load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
+    __syncthreads();
+    const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
+    for (u32 r = wave; r < rows; r += kWaves) {
+      const u32* w = words + (size_t)(m0 + r) * K;
+      for (u32 i = lo[r] + lane; i < hi[r]; i += 64) {
+        const u32 wd = w[i];
+        const u32 c = (u32)((u64)(wd >> 1) - base);
+        if (c < (u32)kVoteTile) atomicAdd(&t[c], (wd & 1u) ? -1 : 1);  // always true for sorted rows
+      }
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x * 4; c < kVoteTile; c += kBlock * 4) {
+    const u64 n = base + c;
+    if (n >= N) break;
+    const int4 s = *reinterpret_cast<const int4*>(&t[c]);
+    const int v0 = (s.x > 0) - (s.x < 0), v1 = (s.y > 0) - (s.y < 0), v2 = (s.z > 0) - (s.z < 0), v3 = (s.w > 0) - (s.w < 0);
+    if (n + 4 <= N) {
+      if (tally) *reinterpret_cast<int4*>(tally + n) = s;
+      if (votes)
+        *reinterpret_cast<u32*>(votes + n) = (u32)(v0 & 0xFF) | ((u32)(v1 & 0xFF) << 8) | ((u32)(v2 & 0xFF) << 16) | ((u32)(v3 & 0xFF) << 24);
+      if (x && (v0 | v1 | v2 | v3)) {
+        float4 xv = *reinterpret_cast<float4*>(x + n);
+        if (v0) xv.x = xv.x - lr * (float)v0;
+        if (v1) xv.y = xv.y - lr * (float)v1;
+        if (v2) xv.z = xv.z - lr * (float)v2;
+        if (v3) xv.w = xv.w - lr * (float)v3;
+        *reinterpret_cast<float4*>(x + n) = xv;
+      }
+    } else {
+      const int sv[4] = {s.x, s.y, s.z, s.w};
+      const int vv[4] = {v0, v1, v2, v3};
+      for (int e = 0; e < 4 && n + e < N; ++e) {
+        if (tally) tally[n + e] = sv[e];
+        if (votes) votes[n + e] = (int8_t)vv[e];
+        if (x && vv[e]) x[n + e] = x[n + e] - lr * (float)vv[e];
+      }
+    }
+  }
+}
+
+// Sparse variant: only x is produced.  Work is proportional to the number of messages: the LDS
+// tile is zeroed once, every vote is added, then every message's coordinate is claimed with an
+// exchange that hands the tally to exactly one thread and leaves the slot zero for the next tile.
+__global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
+                                                        u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x, float lr) {
+  __shared__ __attribute__((aligned(16))) int32_t t[kVoteTile];
+  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x * 4; i < kVoteTile; i += kBlock * 4) *reinterpret_cast<int4*>(&t[i]) = make_int4(0, 0, 0, 0);
+  for (u32 tile = blockIdx.x; tile < n_vt; tile += gridDim.x) {
+    const u64 base = (u64)tile * kVoteTile;
+    for (int phase = 0; phase < 2; ++phase) {
+      for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
+        __syncthreads();
+        load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
+        __syncthreads();
+        const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
+        for (u32 r = wave; r < rows; r += kWaves) {
+          const u32* w = words + (size_t)(m0 + r) * K;
+          for (u32 i = lo[r] + lane; i < hi[r]; i += 64) {
+            const u32 wd = w[i];
+            const u32 c = (u32)((u64)(wd >> 1) - base);
+            if (c >= (u32)kVoteTile || base + c >= N) continue;  // never true for sorted rows with indices < N
+            if (phase == 0) {
+              atomicAdd(&t[c], (wd & 1u) ? -1 : 1);
+            } else {
+              const int s = atomicExch(&t[c], 0);
+              if (s != 0) {
+                float* p = x + (base + c);
+                *p = *p - lr * (float)((s > 0) - (s < 0));
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// Standalone update from a materialised vote vector, 16 coordinates per thread and step.
+__global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, const int8_t* __restrict__ votes, float lr, u64 N) {
+  const u64 n16 = N / 16;
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) {
+    const uint4 v = *reinterpret_cast<const uint4*>(votes + i * 16);
+    const u32 vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (vw[k] == 0) continue;
+      float4* p = reinterpret_cast<float4*>(x + i * 16 + k * 4);
+      float4 xv = *p;
+      const int a = (int8_t)(vw[k] & 0xFF), b = (int8_t)((vw[k] >> 8) & 0xFF), c = (int8_t)((vw[k] >> 16) & 0xFF),
+                d = (int8_t)(vw[k] >> 24);
+      if (a) xv.x = xv.x - lr * (float)a;
+      if (b) xv.y = xv.y - lr * (float)b;
+      if (c) xv.z = xv.z - lr * (float)c;
+      if (d) xv.w = xv.w - lr * (float)d;
+      *p = xv;
+    }
+  }
+  if (blockIdx.x == 0) {
+    for (u64 n = n16 * 16 + threadIdx.x; n < N; n += blockDim.x) {
+      const int v = votes[n];
+      if (v) x[n] = x[n] - lr * (float)v;
+    }
+  }
+}
+
+hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
+                       int8_t* votes, float* x, float lr, hipStream_t s) {
+  const u32 n_vt = vote_tiles(N);
+  const u32 stride = n_vt + 1;
+  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, ws.seg);
+  if (tally || votes) {
+    k_vote_dense<<<n_vt, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, tally, votes, x, lr);
+  } else {
+    const u32 g = n_vt < 256u * 8u ? n_vt : 256u * 8u;
+    k_vote_sparse<<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_update(float* x, const int8_t* votes, float lr, u64 N, hipStream_t s) {
+  u64 blocks = (N / 16 + kBlock - 1) / kBlock;
+  if (blocks > 256u * 32u) blocks = 256u * 32u;
+  if (blocks < 1) blocks = 1;
+  k_apply_update<<<(u32)blocks, kBlock, 0, s>>>(x, votes, lr, N);
+  return hipGetLastError();
+}
+
+}  // namespace s3gd

@@ -1,0 +1,151 @@
+"""ctypes binding of libs3gd.so: the same entry points as include/s3gd.h.
+
+Only argument marshalling happens here.  PyTorch supplies device memory (tensors) and
+streams; every step of the path runs in the library's HIP kernels.  There is no fallback:
+if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs3gd.so")
+
+OK, E_INVAL, E_RANGE, E_HIP, E_NOMEM, E_NAN = 0, -1, -2, -3, -4, -5
+PAD = 0xFFFFFFFF
+N_LIMIT = (1 << 31) - 2
+
+EXPORTS = (
+    "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
+    "s3gd_apply_update", "s3gd_step", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
+    "s3gd_strerror",
+)
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _u32, _u64, _f32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float, ctypes.c_int
+_lib.s3gd_workspace_bytes.restype = ctypes.c_size_t
+_lib.s3gd_workspace_bytes.argtypes = [_u32, _u64, _u64]
+_lib.s3gd_create.restype = _int
+_lib.s3gd_create.argtypes = [ctypes.POINTER(_vp), _int, _u32, _u64, _u64]
+_lib.s3gd_destroy.restype = _int
+_lib.s3gd_destroy.argtypes = [_vp]
+_lib.s3gd_topk_sign_encode.restype = _int
+_lib.s3gd_topk_sign_encode.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_majority_vote.restype = _int
+_lib.s3gd_majority_vote.argtypes = [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_apply_update.restype = _int
+_lib.s3gd_apply_update.argtypes = [_vp, _vp, _vp, _f32, _u64, _vp]
+_lib.s3gd_step.restype = _int
+_lib.s3gd_step.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.s3gd_last_async_status.restype = _int
+_lib.s3gd_last_async_status.argtypes = [_vp, _vp]
+_lib.s3gd_last_encode_info.restype = _int
+_lib.s3gd_last_encode_info.argtypes = [_vp, _vp, ctypes.POINTER(_u32)]
+_lib.s3gd_last_hip_error.restype = _int
+_lib.s3gd_last_hip_error.argtypes = [_vp]
+_lib.s3gd_strerror.restype = ctypes.c_char_p
+_lib.s3gd_strerror.argtypes = [_int]
+
+raw = _lib  # for tests that call the C ABI with hand-made arguments
+
+
+class S3GDError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        msg = _lib.s3gd_strerror(code).decode()
+        super().__init__(f"{where}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+
+
+def strerror(code: int) -> str:
+    return _lib.s3gd_strerror(code).decode()
+
+
+def workspace_bytes(M_max: int, N_max: int, K_max: int) -> int:
+    return int(_lib.s3gd_workspace_bytes(M_max, N_max, K_max))
+
+
+def _ptr(t: torch.Tensor | None) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Context:
+    """Owns the library's scratch memory for problems up to (M_max, N_max, K_max)."""
+
+    def __init__(self, M_max: int, N_max: int, K_max: int, device: int = 0):
+        self._h = _vp()
+        self.device = device
+        rc = _lib.s3gd_create(ctypes.byref(self._h), device, M_max, N_max, K_max)
+        if rc:
+            self._h = None
+            raise S3GDError(rc, "s3gd_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.s3gd_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def _check(self, rc: int, where: str):
+        if rc:
+            raise S3GDError(rc, where, _lib.s3gd_last_hip_error(self._h))
+
+    # -- the three calls of the paper's problem statement ------------------------------------
+    def topk_sign_encode(self, grads: torch.Tensor, K: int, words: torch.Tensor | None = None,
+                         counts: torch.Tensor | None = None, stream=None):
+        """words[M,K], counts[M] (int32 storage holding uint32 values) = TopKSign of every row."""
+        M, N = grads.shape
+        if words is None:
+            words = torch.empty((M, K), dtype=torch.int32, device=grads.device)
+        if counts is None:
+            counts = torch.empty((M,), dtype=torch.int32, device=grads.device)
+        self._check(_lib.s3gd_topk_sign_encode(self._h, _ptr(grads), M, N, K, _ptr(words), _ptr(counts), _stream(stream)),
+                    "s3gd_topk_sign_encode")
+        return words, counts
+
+    def majority_vote(self, words: torch.Tensor, counts: torch.Tensor, N: int, tally: torch.Tensor | None = None,
+                      votes: torch.Tensor | None = None, stream=None):
+        M, K = words.shape
+        self._check(_lib.s3gd_majority_vote(self._h, _ptr(words), _ptr(counts), M, N, K, _ptr(tally), _ptr(votes),
+                                            _stream(stream)), "s3gd_majority_vote")
+        return tally, votes
+
+    def apply_update(self, x: torch.Tensor, votes: torch.Tensor, lr: float, stream=None):
+        self._check(_lib.s3gd_apply_update(self._h, _ptr(x), _ptr(votes), float(lr), x.numel(), _stream(stream)),
+                    "s3gd_apply_update")
+        return x
+
+    def step(self, grads: torch.Tensor, K: int, x: torch.Tensor, lr: float, words: torch.Tensor, counts: torch.Tensor,
+             tally: torch.Tensor | None = None, votes: torch.Tensor | None = None, stream=None):
+        M, N = grads.shape
+        self._check(_lib.s3gd_step(self._h, _ptr(grads), M, N, K, _ptr(x), float(lr), _ptr(words), _ptr(counts),
+                                   _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step")
+        return x
+
+    # -- diagnostics ---------------------------------------------------------------------------
+    def last_async_status(self, stream=None) -> int:
+        return int(_lib.s3gd_last_async_status(self._h, _stream(stream)))
+
+    def last_encode_info(self, stream=None) -> tuple[int, int]:
+        out = (_u32 * 2)()
+        self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
+        return int(out[0]), int(out[1])

@@ -1,0 +1,195 @@
+"""HIP path vs CPU oracle, element by element and bit for bit, at sizes the oracle finishes in
+seconds.  Tolerance: 0 differing bits on words, counts, tally, votes and fp32 parameters (the
+update is x -/+ lr with one rounding, so no floating-point slack is needed or allowed)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2302_07475_amd import datagen
+from tests.helpers import assert_same, gpu_step, oracle_step
+from tests.test_oracle_pins import check_invariants
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(64, 1 << 21, 1 << 21, device=0)
+    yield c
+    c.close()
+
+
+SCALED = [
+    datagen.C1,
+    datagen.C2.scaled(M=4, N=60_001, K=600),      # odd N: rows start at every 16-byte phase
+    datagen.C3.scaled(M=5, N=50_002, K=50, steps=3),
+    datagen.C4.scaled(M=3, N=40_003, K=400),      # many exact ties at the threshold, exact zeros
+    datagen.C5.scaled(M=4, N=70_000, K=70),
+    datagen.C2.scaled(M=16, N=300_000, K=3_000),
+    datagen.C4.scaled(M=8, N=1_000_000, K=10_000),
+]
+
+
+@pytest.mark.parametrize("cfg", SCALED, ids=lambda c: f"{c.name}-M{c.M}-N{c.N}-K{c.K}")
+@pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "fused"])
+def test_config_recipes_match_oracle(ctx, cfg, fused):
+    x = datagen.params(cfg)
+    lr = datagen.lr32(cfg)
+    for step in range(cfg.steps):
+        G = datagen.gradients(cfg, step=step)
+        want = oracle_step(G, cfg.K, x, lr)
+        got = gpu_step(ctx, G, cfg.K, x, lr, fused=fused)
+        assert_same(got, want, what=f"{cfg.name} step {step}")
+        if step == 0:
+            check_invariants(G, cfg.K, got, x, lr)
+        x = want["x"]  # parameters are carried across steps (Algorithm 1 outer loop)
+
+
+def test_fused_sparse_update_matches(ctx):
+    """Fused call without materialised tally/votes: only x, words, counts come back."""
+    for cfg in (SCALED[1], SCALED[3], SCALED[5]):
+        G = datagen.gradients(cfg)
+        x = datagen.params(cfg)
+        want = oracle_step(G, cfg.K, x, datagen.lr32(cfg))
+        got = gpu_step(ctx, G, cfg.K, x, datagen.lr32(cfg), fused=True, dense_outputs=False)
+        assert_same(got, want, keys=("words", "counts", "x"), what=cfg.name)
+
+
+def _edge_rows():
+    rng = np.random.default_rng(77)
+    N = 9000  # three tiles with a ragged tail
+    rows = {
+        "all_equal": np.full(N, 1.5, dtype=np.float32),
+        "all_equal_neg": np.full(N, -1.5, dtype=np.float32),
+        "all_zero": np.zeros(N, dtype=np.float32),
+        "pm_zero_few_nonzero": np.where(rng.random(N) < 0.01, rng.standard_normal(N), rng.choice([0.0, -0.0], N)).astype(np.float32),
+        "two_valued": rng.choice([1.0, -1.0, 2.0, -2.0], N).astype(np.float32),
+        "inf_mix": np.where(rng.random(N) < 0.001, np.inf, rng.standard_normal(N)).astype(np.float32) * rng.choice([1, -1], N).astype(np.float32),
+        "denormal": (rng.integers(-50, 50, N).astype(np.float32) * np.float32(1e-45)).astype(np.float32),
+        "coarse_grid": (np.rint(rng.standard_normal(N) * 2) / 2).astype(np.float32),
+        "huge_range": (rng.standard_normal(N) * 10.0 ** rng.integers(-30, 30, N)).astype(np.float32),
+    }
+    return rows
+
+
+@pytest.mark.parametrize("name", list(_edge_rows().keys()))
+def test_degenerate_rows(ctx, name):
+    g = _edge_rows()[name]
+    N = g.shape[0]
+    G = np.stack([g, g[::-1].copy(), np.roll(g, 17)])
+    x = np.linspace(-1, 1, N, dtype=np.float32)
+    for K in (1, 2, 63, 64, 65, 4096, 4097, N - 1, N):
+        want = oracle_step(G, K, x, 0.125)
+        got = gpu_step(ctx, G, K, x, 0.125, fused=(K % 2 == 0))
+        assert_same(got, want, what=f"{name} K={K}")
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 63, 64, 65, 1023, 1024, 1025, 4093, 4095, 4096, 4097, 8191, 8192, 8193, 12289])
+def test_ragged_sizes_every_alignment(ctx, N):
+    rng = np.random.default_rng(N)
+    M = 5  # with odd N the five rows start at different 16-byte phases
+    G = (np.rint(rng.standard_normal((M, N)) * 8) / 8).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    for K in sorted({0, 1, min(N, 7), N // 2, N}):
+        want = oracle_step(G, K, x, 1e-3)
+        got = gpu_step(ctx, G, K, x, 1e-3)
+        assert_same(got, want, what=f"N={N} K={K}")
+
+
+def test_unaligned_base_pointer(ctx):
+    """grads only has to be 4-byte aligned: take views that start 1, 2, 3 floats into a buffer."""
+    rng = np.random.default_rng(9)
+    M, N, K = 3, 10_001, 123
+    for off in (1, 2, 3):
+        flat = rng.standard_normal(M * N + 4).astype(np.float32)
+        G = flat[off:off + M * N].reshape(M, N)
+        buf = torch.from_numpy(flat).cuda()
+        g_dev = buf[off:off + M * N].view(M, N)
+        assert g_dev.data_ptr() % 16 == 4 * off
+        x = rng.standard_normal(N).astype(np.float32)
+        want = oracle_step(np.ascontiguousarray(G), K, x, 1e-3)
+        got = gpu_step(ctx, G, K, x, 1e-3, g_dev=g_dev)
+        assert_same(got, want, what=f"offset {off}")
+
+
+def test_single_worker_and_many_workers(ctx):
+    rng = np.random.default_rng(21)
+    for M in (1, 2, 33, 64):
+        N, K = 20_000, 200
+        G = rng.standard_normal((M, N)).astype(np.float32)
+        G[:, :50] = G[0, :50]  # every worker agrees on the first coordinates: hot tally slots
+        x = rng.standard_normal(N).astype(np.float32)
+        want = oracle_step(G, K, x, 1e-3)
+        got = gpu_step(ctx, G, K, x, 1e-3, fused=bool(M & 1))
+        assert_same(got, want, what=f"M={M}")
+
+
+def test_same_input_twice_is_bit_identical(ctx):
+    cfg = SCALED[6]
+    G = datagen.gradients(cfg)
+    x = datagen.params(cfg)
+    a = gpu_step(ctx, G, cfg.K, x, 1e-3)
+    b = gpu_step(ctx, G, cfg.K, x, 1e-3)
+    assert_same(a, b, what="determinism")
+
+
+def test_inputs_are_not_modified(ctx):
+    cfg = SCALED[1]
+    G = datagen.gradients(cfg)
+    g_dev = torch.from_numpy(G).cuda()
+    gpu_step(ctx, G, cfg.K, datagen.params(cfg), 1e-3, g_dev=g_dev)
+    assert np.array_equal(g_dev.cpu().numpy().view(np.uint32), G.view(np.uint32))
+
+
+def test_nan_is_reported_not_hidden(ctx, lib):
+    G = np.ones((2, 5000), dtype=np.float32)
+    G[1, 4321] = np.nan
+    g = torch.from_numpy(G).cuda()
+    ctx.topk_sign_encode(g, 10)
+    assert ctx.last_async_status() == lib.E_NAN
+    g[1, 4321] = 1.0
+    ctx.topk_sign_encode(g, 10)
+    assert ctx.last_async_status() == 0
+
+
+def test_silent_worker_casts_no_vote(ctx):
+    """A worker whose count is zero is ignored by the vote (the server only sums what arrives)."""
+    cfg = SCALED[1]
+    G = datagen.gradients(cfg)
+    x = datagen.params(cfg)
+    dev = torch.device("cuda:0")
+    words, counts = ctx.topk_sign_encode(torch.from_numpy(G).to(dev), cfg.K)
+    counts[2] = 0
+    tally = torch.empty(cfg.N, dtype=torch.int32, device=dev)
+    votes = torch.empty(cfg.N, dtype=torch.int8, device=dev)
+    ctx.majority_vote(words, counts, cfg.N, tally, votes)
+    want = oracle_step(np.delete(G, 2, axis=0), cfg.K, x, 1e-3)
+    assert np.array_equal(tally.cpu().numpy(), want["tally"]) and np.array_equal(votes.cpu().numpy(), want["votes"])
+
+
+def test_argument_errors_enqueue_nothing(ctx, lib):
+    dev = torch.device("cuda:0")
+    g = torch.zeros((2, 100), dtype=torch.float32, device=dev)
+    w = torch.zeros((2, 10), dtype=torch.int32, device=dev)
+    c = torch.zeros((2,), dtype=torch.int32, device=dev)
+    x = torch.zeros((100,), dtype=torch.float32, device=dev)
+    v = torch.zeros((128,), dtype=torch.int8, device=dev)
+    t = torch.zeros((100,), dtype=torch.int32, device=dev)
+    r, h = lib.raw, ctx._h
+    p = lambda z: ctypes.c_void_p(z.data_ptr())
+    assert r.s3gd_topk_sign_encode(h, None, 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode(h, p(g), 0, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode(h, p(g), 2, 100, 101, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode(h, p(g), 65, 100, 10, p(w), p(c), None) == lib.E_INVAL  # above M_max
+    assert r.s3gd_topk_sign_encode(h, p(g), 2, (1 << 31) - 1, 10, p(w), p(c), None) == lib.E_RANGE
+    assert r.s3gd_topk_sign_encode(h, ctypes.c_void_p(g.data_ptr() + 2), 2, 50, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_majority_vote(h, p(w), p(c), 2, 100, 10, None, None, None) == lib.E_INVAL
+    assert r.s3gd_majority_vote(h, p(w), p(c), 2, 100, 10, ctypes.c_void_p(t.data_ptr() + 4), None, None) == lib.E_INVAL
+    assert r.s3gd_apply_update(h, p(x), p(v), float("nan"), 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update(h, p(x), p(v), -1.0, 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update(h, p(x), None, 0.1, 100, None) == lib.E_INVAL
+    assert r.s3gd_step(h, p(g), 2, 100, 10, None, 0.1, p(w), p(c), None, None, None) == lib.E_INVAL
+    torch.cuda.synchronize()
+    assert int(w.abs().sum()) == 0 and int(c.abs().sum()) == 0
