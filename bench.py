@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of one S3GD-MV step (encode -> majority vote -> update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5]
+
+A "step" is one pass of the whole hot path over one batch of synthetic gradients: the fused
+C-ABI call s3gd_step on a resident [M, N] fp32 tensor.  Inputs are generated on the host from
+the seeded recipes in paper_2302_07475_amd/datagen.py and are resident in HBM before the timed
+region starts.  Prints ONE JSON line:
+
+  value        M*N / t   gradient elements per second through one step
+  roofline     the dominant kernel's algorithmic bytes per launch over its mean duration, measured
+               with HIP events on the launch stream inside the timed region, against 8 TB/s
+  cpu_baseline the CPU oracle timed on this machine's host cores on a bounded sample of the workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
+
+# algorithmic bytes one launch of a kernel moves, per gradient element (4 = one fp32 read of G)
+FULL_READ_KERNELS = {"hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "filter"}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def upload(cfg, datagen, torch, dev, step=0):
+    """[M, N] gradients generated chunk by chunk on host threads and copied straight to HBM."""
+    g = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
+    x = torch.empty((cfg.N,), dtype=torch.float32, device=dev)
+    nch = datagen.n_chunks(cfg.N)
+
+    def gjob(m, j):
+        lo = j * datagen.CHUNK
+        c = datagen.grad_chunk(cfg, step, m, j)
+        g[m, lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
+
+    def xjob(j):
+        lo = j * datagen.CHUNK
+        c = datagen.x0_chunk(cfg, j)
+        x[lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
+
+    with ThreadPoolExecutor(datagen.default_threads()) as ex:
+        futs = [ex.submit(gjob, m, j) for m in range(cfg.M) for j in range(nch)]
+        futs += [ex.submit(xjob, j) for j in range(nch)]
+        for f in futs:
+            f.result()
+    torch.cuda.synchronize()
+    return g, x
+
+
+def cpu_baseline(cfg, datagen):
+    """The oracle, as it stands, on a bounded sample: all M workers, the first N_s coordinates,
+    K scaled to keep K/N.  Sorting is O(N log N), so the per-element rate at the full N is lower."""
+    from oracle import s3gd_oracle as O
+    n_s = min(cfg.N, max(1 << 16, (120_000_000 // cfg.M)))
+    k_s = max(1, round(cfg.K * n_s / cfg.N))
+    small = cfg.scaled(N=n_s, K=k_s)
+    G = datagen.gradients(small)
+    x = datagen.params(small)
+    t0 = time.perf_counter()
+    O.step(G, small.K, x, datagen.lr32(small))
+    dt = time.perf_counter() - t0
+    return {"value": cfg.M * n_s / dt, "unit": "gradient elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"all {cfg.M} workers, first {n_s} coordinates of {cfg.name}, K={k_s}, one step, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--three-calls", action="store_true", help="time encode, vote, update as separate calls")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (all M workers are rows of one tensor); --gpus must be 1")
+        sys.exit(2)
+
+    import torch
+
+    from paper_2302_07475_amd import costs, datagen, s3gd
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    cfg = datagen.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    t0 = time.perf_counter()
+    g, x = upload(cfg, datagen, torch, dev)
+    log(f"[bench] {cfg.name}: M={cfg.M} N={cfg.N} K={cfg.K} generated and uploaded in {time.perf_counter() - t0:.1f} s")
+    M, N, K = cfg.M, cfg.N, cfg.K
+    lr = float(datagen.lr32(cfg))
+    ctx = s3gd.Context(M, N, K, device=0)
+    words = torch.empty((M, K), dtype=torch.int32, device=dev)
+    counts = torch.empty((M,), dtype=torch.int32, device=dev)
+    tally = votes = None
+    if args.three_calls:
+        votes = torch.empty((N,), dtype=torch.int8, device=dev)
+
+    def one_step():
+        if args.three_calls:
+            ctx.topk_sign_encode(g, K, words, counts)
+            ctx.majority_vote(words, counts, N, None, votes)
+            ctx.apply_update(x, votes, lr)
+        else:
+            ctx.step(g, K, x, lr, words, counts, None, None)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    general_rows = ctx.last_encode_info()[1]
+    ctx.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    log(f"[bench] timed {args.steps} steps in {dt * 1e3:.2f} ms")
+
+    ms_step = dt * 1e3 / args.steps
+    kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / args.steps} for k, v in prof.items()}
+    for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
+        log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}")
+    dom = max(kern, key=lambda k: kern[k]["ms_avg"])
+    if dom in FULL_READ_KERNELS:
+        alg_bytes = 4.0 * M * N
+    else:  # the vote kernel dominates only when the gradient passes are cheaper than it
+        alg_bytes = 8.0 * M * K + 8.0 * N
+    achieved = alg_bytes / (kern[dom]["ms_avg"] * 1e-3)
+    floor_bytes = 4.0 * M * N + 8.0 * M * K + 8.0 * N
+    full_reads = sum(v["launches_per_step"] for k, v in kern.items() if k in FULL_READ_KERNELS)
+    out = {
+        "metric": "gradient elements/sec per S3GD-MV step (M*N/t)",
+        "value": M * N / (ms_step * 1e-3),
+        "unit": "gradient elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
+                   "entry": "three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)",
+                   "rows_on_general_path": general_rows},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK, "traffic": None},
+        "step_roofline": {"full_reads_of_G_per_step": full_reads,
+                          "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
+                          "floor_bytes": floor_bytes,
+                          "step_bytes_as_built": 4.0 * M * N * full_reads + 8.0 * M * K,
+                          "f_step": (4.0 * M * N * full_reads + 8.0 * M * K) / (ms_step * 1e-3) / HBM_PEAK},
+        "kernels_ms": {k: round(v["ms_avg"] * v["launches_per_step"], 5) for k, v in kern.items()},
+        "paper_bits_per_step": {"s3gd_uplink": costs.s3gd_uplink(M, N, K), "s3gd_total": costs.s3gd_mv(M, N, K),
+                                "signsgd": costs.signsgd_mv(M, N), "packed_words": costs.packed_words_bits(M, K)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, datagen)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -138,6 +138,19 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
  * single-pass candidate filter did not apply to them.  `out` is host memory, 2 entries. */
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
+/*
+ * Optional per-kernel timing for benchmarks.  When enabled, every kernel launch made through the
+ * context is bracketed by a HIP event pair recorded on the call's own stream (no host
+ * synchronisation is added).  s3gd_profile_read synchronises `stream`, adds the elapsed time of
+ * every recorded pair to ms_sum[kernel id] and its launch count to launches[kernel id] (host
+ * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
+ * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
+ */
+#define S3GD_PROFILE_KERNELS 17
+S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
+S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
+S3GD_API const char* s3gd_profile_kernel_name(int id);
+
 /* hipError_t value of the last failed HIP call made through this context (0 if none). */
 S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx);
 

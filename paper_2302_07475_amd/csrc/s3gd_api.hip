@@ -7,6 +7,8 @@
 
 using namespace s3gd;
 
+static_assert(KID_COUNT == S3GD_PROFILE_KERNELS, "header and kernel id list disagree");
+
 struct s3gd_ctx {
   int device;
   u32 M_max;
@@ -14,6 +16,7 @@ struct s3gd_ctx {
   void* base;
   size_t bytes;
   Workspace ws;
+  Profiler prof;
   int last_hip;
 };
 
@@ -109,6 +112,7 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.hist = reinterpret_cast<u32*>(b + l.hist);
   c->ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
   c->ws.seg = reinterpret_cast<u32*>(b + l.seg);
+  c->ws.prof = &c->prof;
   *out = c;
   return S3GD_OK;
 }
@@ -116,6 +120,10 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
 S3GD_API int s3gd_destroy(s3gd_ctx* ctx) {
   if (!ctx) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
+  if (ctx->prof.ev) {
+    for (int i = 0; i < 2 * Profiler::kPairs; ++i) (void)hipEventDestroy(ctx->prof.ev[i]);
+    delete[] ctx->prof.ev;
+  }
   const hipError_t e = hipFree(ctx->base);
   delete ctx;
   return e == hipSuccess ? S3GD_OK : S3GD_E_HIP;
@@ -153,7 +161,7 @@ S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, flo
   if (!aligned(x, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
-  const hipError_t e = launch_update(x, votes, lr, N, static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_update(ctx->ws, x, votes, lr, N, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
@@ -196,6 +204,47 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
   out[0] = st[2];
   out[1] = st[1];
   return S3GD_OK;
+}
+
+S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on) {
+  if (!ctx) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (on && !ctx->prof.ev) {
+    ctx->prof.ev = new (std::nothrow) hipEvent_t[2 * Profiler::kPairs];
+    if (!ctx->prof.ev) return S3GD_E_NOMEM;
+    for (int i = 0; i < 2 * Profiler::kPairs; ++i) {
+      const hipError_t e = hipEventCreate(&ctx->prof.ev[i]);
+      if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+  }
+  ctx->prof.enabled = on != 0;
+  ctx->prof.used = 0;
+  return S3GD_OK;
+}
+
+S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n) {
+  if (!ctx || !ms_sum || !launches || n < S3GD_PROFILE_KERNELS) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  for (int i = 0; i < n; ++i) { ms_sum[i] = 0.0f; launches[i] = 0; }
+  const hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  for (int i = 0; i < ctx->prof.used; ++i) {
+    float ms = 0.0f;
+    const hipError_t e2 = hipEventElapsedTime(&ms, ctx->prof.ev[2 * i], ctx->prof.ev[2 * i + 1]);
+    if (e2 != hipSuccess) return hip_fail(ctx, e2);
+    ms_sum[ctx->prof.kid[i]] += ms;
+    launches[ctx->prof.kid[i]] += 1;
+  }
+  ctx->prof.used = 0;
+  return S3GD_OK;
+}
+
+S3GD_API const char* s3gd_profile_kernel_name(int id) {
+  static const char* names[KID_COUNT] = {
+      "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
+      "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
+      "apply_update"};
+  return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 
 S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx) { return ctx ? ctx->last_hip : 0; }

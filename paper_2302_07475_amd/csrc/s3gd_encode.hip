@@ -265,19 +265,22 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
   if (gx > n_tiles) gx = n_tiles;
   if (gx < 1) gx = 1;
   const dim3 grid(gx, M);
-  k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, (u32)K, kModeGeneral);
-  k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status);
-  k_resolve<0><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K);
-  k_hist_rows<1><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status);
-  k_resolve<1><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K);
-  k_hist_rows<2><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status);
-  k_resolve<2><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K);
-  k_tile_count<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.tile_cnt, n_tiles, stride);
-  k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride);
-  k_emit_rows<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words);
+  Profiler& P = *ws.prof;
+#define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
+  S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, (u32)K, kModeGeneral)));
+  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
+  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride)));
+  S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words)));
   u32 fx = (u32)((K + 4095) / 4096);
   if (fx > 64) fx = 64;
-  k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status);
+  S3GD_LAUNCH(KID_FINISH, (k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status)));
+#undef S3GD_LAUNCH
   return hipGetLastError();
 }
 

@@ -10,7 +10,32 @@ inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  /
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
 inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
 
+// Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
+enum KernelId : int {
+  KID_ENCODE_INIT = 0,
+  KID_HIST0, KID_HIST1, KID_HIST2, KID_RESOLVE, KID_TILE_COUNT, KID_SCAN_TILES, KID_EMIT, KID_FINISH,
+  KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
+  KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
+  KID_COUNT
+};
+
+// Records a start/stop event pair around a launch when profiling is on.
+struct Profiler {
+  static constexpr int kPairs = 4096;
+  bool enabled = false;
+  int used = 0;
+  hipEvent_t* ev = nullptr;  // 2 * kPairs events, created when profiling is first enabled
+  int kid[kPairs];
+  void begin(int k, hipStream_t s) {
+    if (enabled && used < kPairs) { kid[used] = k; (void)hipEventRecord(ev[2 * used], s); }
+  }
+  void end(hipStream_t s) {
+    if (enabled && used < kPairs) { (void)hipEventRecord(ev[2 * used + 1], s); ++used; }
+  }
+};
+
 struct Workspace {
+  Profiler* prof;
   RowState* rs;   // [M]
   u32* status;    // [4]: 0 = NaN seen, 1 = rows on the general path
   u32* hist;      // [M][kHistBins]
@@ -22,6 +47,6 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
                          hipStream_t s);
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
-hipError_t launch_update(float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);
+hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);
 
 }  // namespace s3gd

@@ -162,21 +162,30 @@ hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts,
                        int8_t* votes, float* x, float lr, hipStream_t s) {
   const u32 n_vt = vote_tiles(N);
   const u32 stride = n_vt + 1;
+  Profiler& P = *ws.prof;
+  P.begin(KID_SEG_BOUNDS, s);
   k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, ws.seg);
+  P.end(s);
   if (tally || votes) {
+    P.begin(KID_VOTE_DENSE, s);
     k_vote_dense<<<n_vt, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, tally, votes, x, lr);
+    P.end(s);
   } else {
     const u32 g = n_vt < 256u * 8u ? n_vt : 256u * 8u;
+    P.begin(KID_VOTE_SPARSE, s);
     k_vote_sparse<<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
+    P.end(s);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_update(float* x, const int8_t* votes, float lr, u64 N, hipStream_t s) {
+hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s) {
   u64 blocks = (N / 16 + kBlock - 1) / kBlock;
   if (blocks > 256u * 32u) blocks = 256u * 32u;
   if (blocks < 1) blocks = 1;
+  ws.prof->begin(KID_UPDATE, s);
   k_apply_update<<<(u32)blocks, kBlock, 0, s>>>(x, votes, lr, N);
+  ws.prof->end(s);
   return hipGetLastError();
 }
 

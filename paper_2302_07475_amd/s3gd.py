@@ -21,8 +21,9 @@ N_LIMIT = (1 << 31) - 2
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
     "s3gd_apply_update", "s3gd_step", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
-    "s3gd_strerror",
+    "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
+PROFILE_KERNELS = 17
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -52,6 +53,13 @@ _lib.s3gd_last_hip_error.restype = _int
 _lib.s3gd_last_hip_error.argtypes = [_vp]
 _lib.s3gd_strerror.restype = ctypes.c_char_p
 _lib.s3gd_strerror.argtypes = [_int]
+
+_lib.s3gd_profile_enable.restype = _int
+_lib.s3gd_profile_enable.argtypes = [_vp, _int]
+_lib.s3gd_profile_read.restype = _int
+_lib.s3gd_profile_read.argtypes = [_vp, _vp, ctypes.POINTER(_f32), ctypes.POINTER(_u32), _int]
+_lib.s3gd_profile_kernel_name.restype = ctypes.c_char_p
+_lib.s3gd_profile_kernel_name.argtypes = [_int]
 
 raw = _lib  # for tests that call the C ABI with hand-made arguments
 
@@ -149,3 +157,14 @@ class Context:
         out = (_u32 * 2)()
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
         return int(out[0]), int(out[1])
+
+    def profile_enable(self, on: bool = True):
+        self._check(_lib.s3gd_profile_enable(self._h, int(on)), "s3gd_profile_enable")
+
+    def profile_read(self, stream=None) -> dict[str, tuple[float, int]]:
+        """{kernel name: (summed milliseconds, launches)} since the last read."""
+        ms = (_f32 * PROFILE_KERNELS)()
+        cnt = (_u32 * PROFILE_KERNELS)()
+        self._check(_lib.s3gd_profile_read(self._h, _stream(stream), ms, cnt, PROFILE_KERNELS), "s3gd_profile_read")
+        return {_lib.s3gd_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i]))
+                for i in range(PROFILE_KERNELS) if cnt[i]}
