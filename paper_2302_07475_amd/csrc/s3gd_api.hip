@@ -27,10 +27,11 @@ constexpr u32 kMaxRows = 65535;  // rows map to gridDim.y
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t rs, status, hist, tile_cnt, seg, total;
+  size_t rs, status, hist, tile_cnt, seg, chunk, blk_sum, cand, total;
+  u64 cand_pool;
 };
 
-Layout layout(u32 M, u64 N, u64 /*K*/) {
+Layout layout(u32 M, u64 N, u64 K) {
   Layout l{};
   size_t off = 0;
   l.rs = off;       off = align_up(off + sizeof(RowState) * (size_t)M, 256);
@@ -38,6 +39,10 @@ Layout layout(u32 M, u64 N, u64 /*K*/) {
   l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
   l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * (vote_tiles(N) + 1), 256);
+  l.chunk = off;    off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
+  l.blk_sum = off;  off = align_up(off + sizeof(u64) * (size_t)M * blk_stride(N), 256);
+  l.cand_pool = candidate_pool_entries(M, N, K);
+  l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);
   l.total = off;
   return l;
 }
@@ -112,6 +117,10 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.hist = reinterpret_cast<u32*>(b + l.hist);
   c->ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
   c->ws.seg = reinterpret_cast<u32*>(b + l.seg);
+  c->ws.chunk = reinterpret_cast<u64*>(b + l.chunk);
+  c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
+  c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
+  c->ws.cand_pool = l.cand_pool;
   c->ws.prof = &c->prof;
   *out = c;
   return S3GD_OK;

@@ -31,16 +31,23 @@ struct RowState {
   u32 q;          // entries with key == T that are selected (lowest indices first); 0 when T == 0
   u32 c_gt;       // entries with key > T
   u32 count;      // words the row emits = c_gt + q
-  u32 mode;       // kModeFast / kModeGeneral
-  u32 n_cand;     // candidates collected by the filter pass
-  u32 L;          // candidate lower bound on the key
-  u32 cand_ok;    // 1 when K <= n_cand <= capacity
-  u32 pad[6];
+  u32 mode;       // kModeCandidates or kModeGeneral
+  u32 L;          // candidate path: lower bound on the key of a candidate, a multiple of 1024
+  u32 n_cand;     // candidate path: candidates collected by the filter pass
+  u32 n_alloc;    // candidate path: candidate slots handed out to blocks (slab allocator)
+  u32 overflow;   // candidate path: a block found no room for its candidates
+  u32 pad[5];
 };
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
 
-constexpr u32 kModeGeneral = 0;
-constexpr u32 kModeFast = 1;
+constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
+constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, select among candidates
+
+constexpr int kSlab = 512;          // candidate slots a block reserves at a time
+constexpr int kGroup = 8;           // lanes that share one tile in the candidate kernels
+constexpr int kTilesPerBlock = 256; // tiles per block in the candidate count / emit kernels
+constexpr int kSampleUnit = 16;     // consecutive entries per sample unit (one 64-byte line)
+constexpr int kSamplePerBlock = 4096;
 
 // ---- wave / block primitives ----------------------------------------------------------------
 __device__ __forceinline__ u32 lane_id() {

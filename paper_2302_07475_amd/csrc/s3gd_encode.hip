@@ -5,6 +5,18 @@
 // select over the key's digits; the row then emits, in ascending index, every entry with
 // key > T and the first q = K - #{key > T} entries with key == T (Section 2.1 eq. "topk": the
 // threshold lies between the K-th and (K+1)-th magnitude; ties go to the lowest index).
+//
+// Two routes reach the same T, q and words:
+//   candidate route  a strided sample of the row gives a lower bound L with, very likely,
+//                    K <= #{key >= L} <= capacity.  ONE pass over the row copies those candidates
+//                    (index, bits) into per-tile chunks and histograms them; T is then resolved
+//                    and the words are emitted from the candidates alone.
+//   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
+//                    pass and an emit pass.  Any row for which the candidate route's checks fail
+//                    (too few or too many candidates, heavy ties, tiny rows) takes it; the choice
+//                    is made on the device, per row, with no host synchronisation.
+#include <math.h>
+
 #include "s3gd_common.h"
 #include "s3gd_kernels.h"
 
@@ -12,13 +24,13 @@ namespace s3gd {
 
 // ------------------------------------------------------------------------------------------------
 // state reset (a kernel rather than a memset so that callers may capture the call into a graph)
-__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 K, u32 mode) {
+__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode) {
   const u32 m = blockIdx.y;
   for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x)
     hist[(size_t)m * kHistBins + i] = 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     RowState s{};
-    s.k_rem = K;
+    s.k_rem = first_rank;  // K on the general route, the sample rank on the candidate route
     s.mode = mode;
     rs[m] = s;
     if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; }
@@ -64,13 +76,20 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
 }
 
 // Picks the digit that holds the sought rank, narrows the prefix and clears the histogram.
-template <int LEVEL>
+//   kResolveGeneral    levels 0..2 of the general route
+//   kResolveSample     levels 0..1 over the sample: ends with L = 21-bit prefix << 10
+//   kResolveFilter     2048 bins of (key - L) >> 10 filled by the filter pass: checks the candidate
+//                      route and either fixes the 21-bit prefix or hands the row to the general route
+//   kResolveCandidates last 10 bits among the candidates
+enum { kResolveGeneral = 0, kResolveSample = 1, kResolveFilter = 2, kResolveCandidates = 3 };
+
+template <int LEVEL, int WHAT>
 __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K) {
-  constexpr int NB = 1 << digit_bits(LEVEL);
+  constexpr int NB = WHAT == kResolveFilter ? kHistBins : (1 << digit_bits(LEVEL));
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
   RowState st = rs[m];
-  if (st.mode != kModeGeneral) return;
+  if ((WHAT == kResolveGeneral) != (st.mode == kModeGeneral)) return;
   __shared__ u32 lds[kWaves];
   u32* h = hist + (size_t)m * kHistBins;
   // thread 0 owns the highest bins
@@ -81,14 +100,39 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
   for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
   u32 total;
   const u32 above = block_excl_scan<u32>(s, &total, lds);
-  const u32 k = st.k_rem;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) h[top - i] = 0;
+  const u32 k = WHAT == kResolveFilter ? K : st.k_rem;
+  if (WHAT == kResolveFilter) {
+    // The candidate route stands only if no block ran out of room, the K-th largest key is among
+    // the candidates, and it does not sit in the open-ended top bin (thread 0's c[0]).
+    __shared__ u32 verdict;
+    if (threadIdx.x == 0) verdict = !st.overflow && st.n_cand >= K && total == st.n_cand && c[0] < K;
+    __syncthreads();
+    if (!verdict) {
+      if (threadIdx.x == 0) {
+        st.mode = kModeGeneral;
+        st.prefix = 0;
+        st.k_rem = K;
+        rs[m] = st;
+      }
+      return;
+    }
+  }
   if (above < k && k <= above + s) {
     u32 acc = above;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       if (acc < k && k <= acc + c[i]) {
-        st.prefix = (st.prefix << digit_bits(LEVEL)) | (u32)(top - i);
+        const u32 digit = (u32)(top - i);
+        if (WHAT == kResolveFilter) st.prefix = (st.L >> 10) + digit;
+        else st.prefix = (st.prefix << digit_bits(LEVEL)) | digit;
         st.k_rem = k - acc;
+        if (WHAT == kResolveSample && LEVEL == 1) {
+          st.L = st.prefix << 10;
+          st.prefix = 0;
+          st.k_rem = K;
+        }
         if (LEVEL == 2) {
           st.T = st.prefix;
           st.q = st.T == 0 ? 0u : st.k_rem;
@@ -100,8 +144,6 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
       acc += c[i];
     }
   }
-#pragma unroll
-  for (int i = 0; i < PER; ++i) h[top - i] = 0;
 }
 
 // Per tile: entries above the threshold and entries equal to it, packed as (eq << 32) | gt.
@@ -142,7 +184,9 @@ __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__
 }
 
 // In-place exclusive scan of a row's packed tile counts; entry n_tiles receives the row total.
-__global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride) {
+__global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
+                                                           const RowState* __restrict__ rs, u32 mode) {
+  if (rs[blockIdx.x].mode != mode) return;
   __shared__ u64 lds[kScanBlock / 64];
   u64* t = tile_cnt + (size_t)blockIdx.x * tile_stride;
   u64 carry = 0;
@@ -233,6 +277,243 @@ __global__ __launch_bounds__(kBlock) void k_emit_rows(const float* __restrict__ 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Candidate route.
+
+// Position of sample unit u of a row: one unit per stride window, at a hashed offset inside it,
+// so that a periodic pattern in the row cannot line up with the sample.
+__device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
+  u32 h = u * 0x9E3779B1u;
+  h ^= h >> 15; h *= 0x85EBCA77u; h ^= h >> 13;
+  return (u64)u * stride + (u64)h % (stride - (kSampleUnit - 1));
+}
+
+// Histogram of one radix level over the sample of each row (gathered straight from the row).
+template <int LEVEL>
+__global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
+                                                        u32* __restrict__ hist, u32 n_units, u64 unit_stride) {
+  constexpr int NB = 1 << digit_bits(LEVEL);
+  constexpr int SH = digit_shift(LEVEL);
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 h[NB];
+  for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
+  __syncthreads();
+  const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
+  const u32 n_samples = n_units * kSampleUnit;
+#pragma unroll 4
+  for (u32 i = blockIdx.x * kSamplePerBlock + threadIdx.x; i < (blockIdx.x + 1) * kSamplePerBlock && i < n_samples; i += kBlock) {
+    const u32 u = i / kSampleUnit, e = i % kSampleUnit;
+    const u32 key = row[sample_unit_start(u, unit_stride) + e] & 0x7FFFFFFFu;
+    if (LEVEL == 0 || (key >> (SH + digit_bits(LEVEL))) == st.prefix) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < NB; i += kBlock) {
+    const u32 c = h[i];
+    if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
+  }
+}
+
+// The one pass over the gradients: every entry with key >= L becomes a candidate (index, bits).
+// A tile's candidates form one contiguous chunk in ascending index; chunks are placed in slabs that
+// the block reserves with one atomic per kSlab candidates.  The block also histograms
+// (key - L) >> 10 into 2048 bins, the last of which is open-ended.
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs,
+                                                   u32* __restrict__ hist, uint2* __restrict__ cand, u32 cand_stride,
+                                                   u64* __restrict__ chunk, u32 n_tiles, u32 tile_stride,
+                                                   u32* __restrict__ status) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 h[kHistBins];
+  __shared__ u32 rank_lds[kLoads * kWaves];
+  __shared__ u32 slab_base;
+  for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
+  __syncthreads();
+  const float* row = grads + (size_t)m * N;
+  const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
+  const u32* rowv = reinterpret_cast<const u32*>(row) - a;
+  const u64 vend = N + a;
+  const u32 L = st.L, Lq = st.L >> 10;
+  uint2* out = cand + (size_t)m * cand_stride;
+  u64* ch = chunk + (size_t)m * tile_stride;
+  u32 cur = 0, end = 0, block_total = 0;  // block-uniform
+  bool nan = false, overflow = false;
+  for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    TileRegs r;
+    load_tile(rowv, a, vend, (u64)tile * kTile, r);
+    u32 cmask = 0;
+#pragma unroll
+    for (int i = 0; i < kLoads * 4; ++i) {
+      const u32 key = r.b[i] & 0x7FFFFFFFu;
+      const bool ok = ((r.valid >> i) & 1u) && key >= L;
+      cmask |= (u32)ok << i;
+      if (ok) {
+        nan |= key > 0x7F800000u;
+        const u32 bin = (key >> 10) - Lq;
+        atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
+      }
+    }
+    u32 base[kLoads], total;
+    tile_rank(cmask, base, &total, rank_lds);
+    if (total == 0) {  // block-uniform
+      if (threadIdx.x == 0) ch[tile] = 0;
+      continue;
+    }
+    if (cur + total > end) {
+      const u32 need = (total + kSlab - 1) / kSlab * kSlab;
+      if (threadIdx.x == 0) slab_base = atomicAdd(&rs[m].n_alloc, need);
+      __syncthreads();  // the next write of slab_base is behind the barriers of the next tile_rank
+      cur = slab_base;
+      end = cur + need;
+    }
+    if (end > cand_stride) {
+      overflow = true;
+    } else {
+      const u64 v0 = (u64)tile * kTile + (u64)threadIdx.x * 4 - a;
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        u32 o = cur + base[j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * j + e;
+          if ((cmask >> i) & 1u) out[o++] = make_uint2((u32)(v0 + (u64)j * (kBlock * 4) + e), r.b[i]);
+        }
+      }
+    }
+    if (threadIdx.x == 0) ch[tile] = ((u64)cur << 32) | total;
+    cur += total;
+    block_total += total;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
+    const u32 c = h[i];
+    if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
+  }
+  if (threadIdx.x == 0) {
+    if (block_total) atomicAdd(&rs[m].n_cand, block_total);
+    if (overflow) rs[m].overflow = 1;
+  }
+  if (nan) status[0] = 1;
+}
+
+// max of a value over the wave
+__device__ __forceinline__ u32 wave_max(u32 v) {
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) { const u32 o = __shfl_xor(v, d, 64); v = o > v ? o : v; }
+  return v;
+}
+
+// Last radix level among the candidates: histogram of key & 1023 where key >> 10 == prefix.
+// kGroup lanes share a tile; only the few hundred candidates of the target bin touch memory.
+__global__ __launch_bounds__(kBlock) void k_cand_hist(const RowState* __restrict__ rs, u32* __restrict__ hist,
+                                                      const uint2* __restrict__ cand, u32 cand_stride,
+                                                      const u64* __restrict__ chunk, u32 n_tiles, u32 tile_stride) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  const u32 g = (blockIdx.x * kBlock + threadIdx.x) / kGroup, sub = threadIdx.x % kGroup;
+  const u64 c = g < n_tiles ? chunk[(size_t)m * tile_stride + g] : 0;
+  const u32 base = (u32)(c >> 32), cnt = (u32)c;
+  const uint2* in = cand + (size_t)m * cand_stride + base;
+  for (u32 i = sub; i < cnt; i += kGroup) {
+    const u32 key = in[i].y & 0x7FFFFFFFu;
+    if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
+  }
+}
+
+// Per tile (gt, eq) against the final threshold, from the candidates; plus one sum per block of
+// kTilesPerBlock tiles so that the scan over tiles has only n_tiles / 256 entries.
+__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
+                                                       const u64* __restrict__ chunk, u64* __restrict__ tile_cnt, u32 n_tiles,
+                                                       u32 tile_stride, u64* __restrict__ blk_sum, u32 blk_stride) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 sum_gt, sum_eq;
+  if (threadIdx.x == 0) { sum_gt = 0; sum_eq = 0; }
+  __syncthreads();
+  const u32 sub = threadIdx.x % kGroup;
+  const uint2* in = cand + (size_t)m * cand_stride;
+  constexpr int kPerIter = kBlock / kGroup;
+  for (int it = 0; it < kTilesPerBlock / kPerIter; ++it) {
+    const u32 tile = blockIdx.x * kTilesPerBlock + it * kPerIter + threadIdx.x / kGroup;
+    const u64 c = tile < n_tiles ? chunk[(size_t)m * tile_stride + tile] : 0;
+    const u32 base = (u32)(c >> 32), cnt = (u32)c;
+    u32 gt = 0, eq = 0;
+    for (u32 i = sub; i < cnt; i += kGroup) {
+      const u32 key = in[base + i].y & 0x7FFFFFFFu;
+      gt += key > st.T;
+      eq += key == st.T;
+    }
+    // all 64 lanes take part in the shuffles; lanes whose loop was shorter hold their partial sums
+#pragma unroll
+    for (int d = kGroup / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    if (sub == 0 && tile < n_tiles) {
+      tile_cnt[(size_t)m * tile_stride + tile] = ((u64)eq << 32) | gt;
+      if (gt) atomicAdd(&sum_gt, gt);
+      if (eq) atomicAdd(&sum_eq, eq);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) blk_sum[(size_t)m * blk_stride + blockIdx.x] = ((u64)sum_eq << 32) | sum_gt;
+}
+
+// Emits the words of 256 tiles per block from their candidate chunks, in ascending index.
+__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
+                                                      const u64* __restrict__ chunk, const u64* __restrict__ tile_cnt, u32 n_tiles,
+                                                      u32 tile_stride, const u64* __restrict__ blk_sum, u32 blk_stride, u64 K,
+                                                      u32* __restrict__ words) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u64 pre[kTilesPerBlock];
+  __shared__ u64 scan_lds[kWaves];
+  {
+    const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
+    const u64 c = tile < n_tiles ? tile_cnt[(size_t)m * tile_stride + tile] : 0;
+    u64 total;
+    const u64 ex = block_excl_scan<u64>(c, &total, scan_lds);
+    pre[threadIdx.x] = blk_sum[(size_t)m * blk_stride + blockIdx.x] + ex;
+  }
+  __syncthreads();
+  const u32 lane = lane_id(), sub = threadIdx.x % kGroup;
+  const u32 gshift = lane & ~(u32)(kGroup - 1);
+  const uint2* in = cand + (size_t)m * cand_stride;
+  u32* out = words + (size_t)m * K;
+  constexpr int kPerIter = kBlock / kGroup;
+  for (int it = 0; it < kTilesPerBlock / kPerIter; ++it) {
+    const u32 slot = it * kPerIter + threadIdx.x / kGroup;
+    const u32 tile = blockIdx.x * kTilesPerBlock + slot;
+    const u64 c = tile < n_tiles ? chunk[(size_t)m * tile_stride + tile] : 0;
+    const u32 base = (u32)(c >> 32), cnt = (u32)c;
+    const u64 p = pre[slot];
+    const u32 gt_before = (u32)p;
+    u32 eq_seen = (u32)(p >> 32);
+    u32 o = gt_before + (eq_seen < st.q ? eq_seen : st.q);
+    const u32 rounds = wave_max((cnt + kGroup - 1) / kGroup);  // wave-uniform trip count for the ballots
+    for (u32 rd = 0; rd < rounds; ++rd) {
+      const u32 i = rd * kGroup + sub;
+      const bool ok = i < cnt;
+      uint2 cd = make_uint2(0, 0);
+      if (ok) cd = in[base + i];
+      const u32 key = cd.y & 0x7FFFFFFFu;
+      const bool is_eq = ok && key == st.T;
+      const u32 eq_bits = (u32)(ballot(is_eq) >> gshift) & ((1u << kGroup) - 1u);
+      const u32 eq_rank = eq_seen + __popc(eq_bits & ((1u << sub) - 1u));
+      const bool sel = ok && (key > st.T || (is_eq && eq_rank < st.q));
+      const u32 sel_bits = (u32)(ballot(sel) >> gshift) & ((1u << kGroup) - 1u);
+      if (sel) {
+        const u32 pos = o + __popc(sel_bits & ((1u << sub) - 1u));
+        if (pos < K) out[pos] = (cd.x << 1) | (cd.y >> 31);  // pos < K by construction
+      }
+      o += __popc(sel_bits);
+      eq_seen += __popc(eq_bits);
+    }
+  }
+}
+
 // counts[m] and the pad words of rows that selected zeros.
 __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __restrict__ words, u32* __restrict__ counts,
                               u32* __restrict__ status) {
@@ -253,29 +534,95 @@ __global__ void k_zero_counts(u32* counts, u32 M) {
 }
 
 // ------------------------------------------------------------------------------------------------
+static u32 blocks_per_row(u32 M, u32 n_tiles) {
+  u32 gx = (kTargetBlocks + M - 1) / M;
+  if (gx > n_tiles) gx = n_tiles;
+  return gx < 1 ? 1 : gx;
+}
+
+// Upper estimate of the candidates per row when the sample rank is r and the sample fraction f:
+// the count of keys above the r-th largest sample key is about r / f with deviation sqrt(r) / f.
+static double candidate_bound(double r, double f) { return 1.25 * (r + 6.0 * sqrt(r) + 8.0) / f; }
+
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool) {
+  EncodePlan p{};
+  p.n_tiles = encode_tiles(N);
+  p.gx = blocks_per_row(M, p.n_tiles);
+  p.candidates = false;
+  if (K == 0 || N < (1ull << 17) || K * 16 > N) return p;
+  // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
+  // and never more than a quarter of the row
+  u64 s = 1ull << 15;
+  while (s < (1ull << 18) && s * 8 <= N && (double)s * (double)K < 256.0 * (double)N) s <<= 1;
+  const double f = (double)s / (double)N, kf = (double)K * f;
+  const double r = ceil(kf + 6.0 * sqrt(kf) + 8.0);
+  if (r >= (double)s) return p;
+  const double need = candidate_bound(r, f) + (double)p.gx * kSlab + kTile;
+  if (need * M > (double)cand_pool || need > 4.0e9) return p;
+  p.candidates = true;
+  p.n_units = (u32)(s / kSampleUnit);
+  p.unit_stride = N / p.n_units;
+  p.sample_rank = (u32)r;
+  p.cand_stride = (u32)need;
+  return p;
+}
+
+u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
+  u64 best = 0;
+  // the bound is not monotone in K (the sample size changes in powers of two): take the largest
+  // need over K_max and the sparsities below it down to 1e-5
+  for (double k = (double)(K_max < N_max / 16 ? K_max : N_max / 16); k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
+    EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull);
+    if (p.candidates && p.cand_stride > best) best = p.cand_stride;
+  }
+  if (best == 0) return 0;
+  return (u64)M_max * best + (u64)(kTargetBlocks + M_max) * kSlab;
+}
+
 hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
                          hipStream_t s) {
   if (K == 0) {
     k_zero_counts<<<(M + 255) / 256, 256, 0, s>>>(counts, M);
     return hipGetLastError();
   }
-  const u32 n_tiles = encode_tiles(N);
+  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool);
+  const u32 n_tiles = p.n_tiles;
   const u32 stride = tile_stride(N);
-  u32 gx = (kTargetBlocks + M - 1) / M;
-  if (gx > n_tiles) gx = n_tiles;
-  if (gx < 1) gx = 1;
-  const dim3 grid(gx, M);
+  const dim3 grid(p.gx, M);
+  const u32 k32 = (u32)K;
   Profiler& P = *ws.prof;
 #define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
-  S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, (u32)K, kModeGeneral)));
+  S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
+                                                                         p.candidates ? kModeCandidates : kModeGeneral)));
+  if (p.candidates) {
+    const u32 n_blk = (n_tiles + kTilesPerBlock - 1) / kTilesPerBlock;
+    const u32 bstride = blk_stride(N);
+    const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_tiles, stride,
+                                                              ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<dim3((n_tiles * kGroup + kBlock - 1) / kBlock, M), kBlock, 0, s>>>(
+                                     ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_tiles, stride)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, ws.tile_cnt,
+                                                                                n_tiles, stride, ws.blk_sum, bstride)));
+    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.blk_sum, n_blk, bstride, ws.rs, kModeCandidates)));
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, ws.tile_cnt, n_tiles,
+                                                                             stride, ws.blk_sum, bstride, K, words)));
+  }
+  // General route: every kernel returns at once for rows the candidate route has served.
   S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
   S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
   S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, (u32)K)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
   S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
-  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride)));
+  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, kModeGeneral)));
   S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words)));
   u32 fx = (u32)((K + 4095) / 4096);
   if (fx > 64) fx = 64;

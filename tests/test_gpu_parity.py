@@ -193,3 +193,57 @@ def test_argument_errors_enqueue_nothing(ctx, lib):
     assert r.s3gd_step(h, p(g), 2, 100, 10, None, 0.1, p(w), p(c), None, None, None) == lib.E_INVAL
     torch.cuda.synchronize()
     assert int(w.abs().sum()) == 0 and int(c.abs().sum()) == 0
+
+
+# ---------------------------------------------------------------- candidate route and its fallback
+def _encode_only(ctx, G, K):
+    g = torch.from_numpy(G).cuda()
+    words, counts = ctx.topk_sign_encode(g, K)
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    rows, general = ctx.last_encode_info()
+    return words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32), rows, general
+
+
+@pytest.mark.parametrize("N,K", [(131_072, 131), (200_003, 2_000), (1_000_000, 1_000), (2_000_001, 20_000), (2_097_152, 100_000)])
+def test_candidate_route_is_taken_and_exact(ctx, N, K):
+    from oracle import s3gd_oracle as O
+    rng = np.random.default_rng(N + K)
+    M = 3
+    G = (rng.standard_normal((M, N)) * np.exp(rng.standard_normal((M, 1)))).astype(np.float32)
+    words, counts, rows, general = _encode_only(ctx, G, K)
+    w, c = O.topk_sign_encode(G, K)
+    assert np.array_equal(words, w) and np.array_equal(counts, c)
+    assert rows == M and general == 0, "ordinary data must not need the general route"
+
+
+def test_rows_fall_back_independently(ctx):
+    """Row 0 ordinary, row 1 all equal (every entry ties: too many candidates), row 2 mostly zero
+    (lower bound 0), row 3 two-valued with the tie straddling K."""
+    from oracle import s3gd_oracle as O
+    rng = np.random.default_rng(5)
+    N, K = 500_000, 5_000
+    G = np.empty((4, N), dtype=np.float32)
+    G[0] = rng.standard_normal(N)
+    G[1] = -2.0
+    G[2] = np.where(rng.random(N) < 0.001, rng.standard_normal(N), 0.0)
+    G[3] = rng.choice([1.0, -1.0, 3.0], N, p=[0.5, 0.495, 0.005])
+    words, counts, rows, general = _encode_only(ctx, G, K)
+    w, c = O.topk_sign_encode(G, K)
+    assert np.array_equal(counts, c)
+    assert np.array_equal(words, w)
+    assert general == 3
+
+
+def test_threshold_ties_on_candidate_route(ctx):
+    """Values on a coarse grid: hundreds of entries share the K-th magnitude; the lowest indices win."""
+    from oracle import s3gd_oracle as O
+    cfg = datagen.C4.scaled(M=4, N=1_500_000, K=15_000)
+    G = (np.rint(datagen.gradients(cfg) * 64.0) / 64.0).astype(np.float32)  # grid 2^-6 at this small N
+    words, counts, rows, general = _encode_only(ctx, G, cfg.K)
+    w, c = O.topk_sign_encode(G, cfg.K)
+    assert np.array_equal(words, w) and np.array_equal(counts, c)
+    mag = np.abs(G[0])
+    t = mag[(w[0] >> 1).astype(np.int64)].min()
+    assert np.count_nonzero(mag == t) > 10, "the recipe is meant to produce ties at the threshold"
+    assert general == 0
