@@ -316,19 +316,19 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 }
 
 // The one pass over the gradients: every entry with key >= L becomes a candidate (index, bits).
-// A tile's candidates form one contiguous chunk in ascending index; chunks are placed in slabs that
-// the block reserves with one atomic per kSlab candidates.  The block also histograms
+// Waves work independently (no block barrier inside the loop): a wave owns a contiguous run of
+// wave tiles (1024 entries each), the candidates of a tile form one contiguous chunk in ascending
+// index, and chunks are placed in slabs that the wave reserves with one atomic per kSlab
+// candidates.  Consecutive tiles therefore have consecutive chunks.  The block also histograms
 // (key - L) >> 10 into 2048 bins, the last of which is open-ended.
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs,
                                                    u32* __restrict__ hist, uint2* __restrict__ cand, u32 cand_stride,
-                                                   u64* __restrict__ chunk, u32 n_tiles, u32 tile_stride,
+                                                   u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride, u32 tiles_per_wave,
                                                    u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u32 h[kHistBins];
-  __shared__ u32 rank_lds[kLoads * kWaves];
-  __shared__ u32 slab_base;
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const float* row = grads + (size_t)m * N;
@@ -336,180 +336,144 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
   const u64 vend = N + a;
   const u32 L = st.L, Lq = st.L >> 10;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
-  u64* ch = chunk + (size_t)m * tile_stride;
-  u32 cur = 0, end = 0, block_total = 0;  // block-uniform
+  u64* ch = chunk + (size_t)m * wt_stride;
+  u32 cur = 0, end = 0, wave_total = 0;  // wave-uniform
   bool nan = false, overflow = false;
-  for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
+  const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
+  for (u32 tile = t0; tile < t1; ++tile) {
     TileRegs r;
-    load_tile(rowv, a, vend, (u64)tile * kTile, r);
+    load_wave_tile(rowv, a, vend, (u64)tile * kWaveTile, lane, r);
     u32 cmask = 0;
 #pragma unroll
     for (int i = 0; i < kLoads * 4; ++i) {
       const u32 key = r.b[i] & 0x7FFFFFFFu;
-      const bool ok = ((r.valid >> i) & 1u) && key >= L;
-      cmask |= (u32)ok << i;
-      if (ok) {
-        nan |= key > 0x7F800000u;
-        const u32 bin = (key >> 10) - Lq;
-        atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
-      }
+      cmask |= (u32)(((r.valid >> i) & 1u) && key >= L) << i;
     }
-    u32 base[kLoads], total;
-    tile_rank(cmask, base, &total, rank_lds);
-    if (total == 0) {  // block-uniform
-      if (threadIdx.x == 0) ch[tile] = 0;
+    if (ballot(cmask != 0) == 0) {  // wave-uniform
+      if (lane == 0) ch[tile] = 0;
       continue;
     }
+    u32 base[kLoads];
+    const u32 total = wave_rank(cmask, base);
     if (cur + total > end) {
       const u32 need = (total + kSlab - 1) / kSlab * kSlab;
-      if (threadIdx.x == 0) slab_base = atomicAdd(&rs[m].n_alloc, need);
-      __syncthreads();  // the next write of slab_base is behind the barriers of the next tile_rank
-      cur = slab_base;
+      u32 b = 0;
+      if (lane == 0) b = atomicAdd(&rs[m].n_alloc, need);
+      cur = __builtin_amdgcn_readfirstlane(b);
       end = cur + need;
     }
     if (end > cand_stride) {
       overflow = true;
-    } else {
-      const u64 v0 = (u64)tile * kTile + (u64)threadIdx.x * 4 - a;
+    } else if (cmask) {
+      const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
         u32 o = cur + base[j];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * j + e;
-          if ((cmask >> i) & 1u) out[o++] = make_uint2((u32)(v0 + (u64)j * (kBlock * 4) + e), r.b[i]);
+          if ((cmask >> i) & 1u) {
+            const u32 key = r.b[i] & 0x7FFFFFFFu;
+            out[o++] = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
+            nan |= key > 0x7F800000u;
+            const u32 bin = (key >> 10) - Lq;
+            atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
+          }
         }
       }
     }
-    if (threadIdx.x == 0) ch[tile] = ((u64)cur << 32) | total;
+    if (lane == 0) ch[tile] = ((u64)cur << 32) | total;
     cur += total;
-    block_total += total;
+    wave_total += total;
   }
+  if (lane == 0) {
+    if (wave_total) atomicAdd(&rs[m].n_cand, wave_total);
+    if (overflow) rs[m].overflow = 1;
+  }
+  if (nan) status[0] = 1;
   __syncthreads();
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
     if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
   }
-  if (threadIdx.x == 0) {
-    if (block_total) atomicAdd(&rs[m].n_cand, block_total);
-    if (overflow) rs[m].overflow = 1;
-  }
-  if (nan) status[0] = 1;
-}
-
-// max of a value over the wave
-__device__ __forceinline__ u32 wave_max(u32 v) {
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) { const u32 o = __shfl_xor(v, d, 64); v = o > v ? o : v; }
-  return v;
 }
 
 // Last radix level among the candidates: histogram of key & 1023 where key >> 10 == prefix.
-// kGroup lanes share a tile; only the few hundred candidates of the target bin touch memory.
+// One thread per wave tile; only the few hundred candidates of the target bin touch the histogram.
 __global__ __launch_bounds__(kBlock) void k_cand_hist(const RowState* __restrict__ rs, u32* __restrict__ hist,
                                                       const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ chunk, u32 n_tiles, u32 tile_stride) {
+                                                      const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  const u32 g = (blockIdx.x * kBlock + threadIdx.x) / kGroup, sub = threadIdx.x % kGroup;
-  const u64 c = g < n_tiles ? chunk[(size_t)m * tile_stride + g] : 0;
-  const u32 base = (u32)(c >> 32), cnt = (u32)c;
-  const uint2* in = cand + (size_t)m * cand_stride + base;
-  for (u32 i = sub; i < cnt; i += kGroup) {
+  const u32 tile = blockIdx.x * kBlock + threadIdx.x;
+  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
+  const u32 cnt = (u32)c;
+  const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
+  for (u32 i = 0; i < cnt; ++i) {
     const u32 key = in[i].y & 0x7FFFFFFFu;
     if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
   }
 }
 
-// Per tile (gt, eq) against the final threshold, from the candidates; plus one sum per block of
-// kTilesPerBlock tiles so that the scan over tiles has only n_tiles / 256 entries.
-__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                       const u64* __restrict__ chunk, u64* __restrict__ tile_cnt, u32 n_tiles,
-                                                       u32 tile_stride, u64* __restrict__ blk_sum, u32 blk_stride) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
-  __shared__ u32 sum_gt, sum_eq;
-  if (threadIdx.x == 0) { sum_gt = 0; sum_eq = 0; }
-  __syncthreads();
-  const u32 sub = threadIdx.x % kGroup;
-  const uint2* in = cand + (size_t)m * cand_stride;
-  constexpr int kPerIter = kBlock / kGroup;
-  for (int it = 0; it < kTilesPerBlock / kPerIter; ++it) {
-    const u32 tile = blockIdx.x * kTilesPerBlock + it * kPerIter + threadIdx.x / kGroup;
-    const u64 c = tile < n_tiles ? chunk[(size_t)m * tile_stride + tile] : 0;
-    const u32 base = (u32)(c >> 32), cnt = (u32)c;
-    u32 gt = 0, eq = 0;
-    for (u32 i = sub; i < cnt; i += kGroup) {
-      const u32 key = in[base + i].y & 0x7FFFFFFFu;
-      gt += key > st.T;
-      eq += key == st.T;
-    }
-    // all 64 lanes take part in the shuffles; lanes whose loop was shorter hold their partial sums
-#pragma unroll
-    for (int d = kGroup / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
-    if (sub == 0 && tile < n_tiles) {
-      tile_cnt[(size_t)m * tile_stride + tile] = ((u64)eq << 32) | gt;
-      if (gt) atomicAdd(&sum_gt, gt);
-      if (eq) atomicAdd(&sum_eq, eq);
-    }
+// (gt, eq) of one wave tile against the final threshold, from its candidates.
+__device__ __forceinline__ u64 count_chunk(const uint2* __restrict__ in, u32 cnt, u32 T) {
+  u32 gt = 0, eq = 0;
+  for (u32 i = 0; i < cnt; ++i) {
+    const u32 key = in[i].y & 0x7FFFFFFFu;
+    gt += key > T;
+    eq += key == T;
   }
-  __syncthreads();
-  if (threadIdx.x == 0) blk_sum[(size_t)m * blk_stride + blockIdx.x] = ((u64)sum_eq << 32) | sum_gt;
+  return ((u64)eq << 32) | gt;
 }
 
-// Emits the words of 256 tiles per block from their candidate chunks, in ascending index.
-__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ chunk, const u64* __restrict__ tile_cnt, u32 n_tiles,
-                                                      u32 tile_stride, const u64* __restrict__ blk_sum, u32 blk_stride, u64 K,
-                                                      u32* __restrict__ words) {
+// Sum of (gt, eq) over each block of kTilesPerBlock wave tiles; scanned afterwards, so that the
+// emit kernel only needs a block-local scan.
+__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
+                                                       const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
+                                                       u64* __restrict__ blk_sum, u32 blk_stride) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  __shared__ u64 pre[kTilesPerBlock];
-  __shared__ u64 scan_lds[kWaves];
-  {
-    const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
-    const u64 c = tile < n_tiles ? tile_cnt[(size_t)m * tile_stride + tile] : 0;
-    u64 total;
-    const u64 ex = block_excl_scan<u64>(c, &total, scan_lds);
-    pre[threadIdx.x] = blk_sum[(size_t)m * blk_stride + blockIdx.x] + ex;
-  }
-  __syncthreads();
-  const u32 lane = lane_id(), sub = threadIdx.x % kGroup;
-  const u32 gshift = lane & ~(u32)(kGroup - 1);
-  const uint2* in = cand + (size_t)m * cand_stride;
+  __shared__ u64 lds[kWaves];
+  const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
+  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
+  const u64 mine = count_chunk(cand + (size_t)m * cand_stride + (u32)(c >> 32), (u32)c, st.T);
+  u64 total;
+  (void)block_excl_scan<u64>(mine, &total, lds);
+  if (threadIdx.x == 0) blk_sum[(size_t)m * blk_stride + blockIdx.x] = total;
+}
+
+// Emits the words of kTilesPerBlock wave tiles per block from their candidate chunks, in ascending index.
+__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
+                                                      const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
+                                                      const u64* __restrict__ blk_sum, u32 blk_stride, u64 K, u32* __restrict__ words) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u64 lds[kWaves];
+  const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
+  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
+  const u32 cnt = (u32)c;
+  const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
+  const u64 mine = count_chunk(in, cnt, st.T);
+  u64 total;
+  const u64 before = blk_sum[(size_t)m * blk_stride + blockIdx.x] + block_excl_scan<u64>(mine, &total, lds);
+  if (mine == 0) return;
+  u32 eq_seen = (u32)(before >> 32);
+  u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
   u32* out = words + (size_t)m * K;
-  constexpr int kPerIter = kBlock / kGroup;
-  for (int it = 0; it < kTilesPerBlock / kPerIter; ++it) {
-    const u32 slot = it * kPerIter + threadIdx.x / kGroup;
-    const u32 tile = blockIdx.x * kTilesPerBlock + slot;
-    const u64 c = tile < n_tiles ? chunk[(size_t)m * tile_stride + tile] : 0;
-    const u32 base = (u32)(c >> 32), cnt = (u32)c;
-    const u64 p = pre[slot];
-    const u32 gt_before = (u32)p;
-    u32 eq_seen = (u32)(p >> 32);
-    u32 o = gt_before + (eq_seen < st.q ? eq_seen : st.q);
-    const u32 rounds = wave_max((cnt + kGroup - 1) / kGroup);  // wave-uniform trip count for the ballots
-    for (u32 rd = 0; rd < rounds; ++rd) {
-      const u32 i = rd * kGroup + sub;
-      const bool ok = i < cnt;
-      uint2 cd = make_uint2(0, 0);
-      if (ok) cd = in[base + i];
-      const u32 key = cd.y & 0x7FFFFFFFu;
-      const bool is_eq = ok && key == st.T;
-      const u32 eq_bits = (u32)(ballot(is_eq) >> gshift) & ((1u << kGroup) - 1u);
-      const u32 eq_rank = eq_seen + __popc(eq_bits & ((1u << sub) - 1u));
-      const bool sel = ok && (key > st.T || (is_eq && eq_rank < st.q));
-      const u32 sel_bits = (u32)(ballot(sel) >> gshift) & ((1u << kGroup) - 1u);
-      if (sel) {
-        const u32 pos = o + __popc(sel_bits & ((1u << sub) - 1u));
-        if (pos < K) out[pos] = (cd.x << 1) | (cd.y >> 31);  // pos < K by construction
-      }
-      o += __popc(sel_bits);
-      eq_seen += __popc(eq_bits);
+  for (u32 i = 0; i < cnt; ++i) {
+    const uint2 cd = in[i];
+    const u32 key = cd.y & 0x7FFFFFFFu;
+    bool sel = key > st.T;
+    if (key == st.T) { sel = eq_seen < st.q; ++eq_seen; }
+    if (sel) {
+      if (o < K) out[o] = (cd.x << 1) | (cd.y >> 31);  // o < K by construction
+      ++o;
     }
   }
 }
@@ -557,7 +521,9 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool) {
   const double f = (double)s / (double)N, kf = (double)K * f;
   const double r = ceil(kf + 6.0 * sqrt(kf) + 8.0);
   if (r >= (double)s) return p;
-  const double need = candidate_bound(r, f) + (double)p.gx * kSlab + kTile;
+  p.n_wtiles = (u32)((N + 3 + kWaveTile - 1) / kWaveTile);
+  p.tiles_per_wave = (p.n_wtiles + p.gx * kWaves - 1) / (p.gx * kWaves);
+  const double need = candidate_bound(r, f) + (double)p.gx * kWaves * kSlab + kWaveTile;
   if (need * M > (double)cand_pool || need > 4.0e9) return p;
   p.candidates = true;
   p.n_units = (u32)(s / kSampleUnit);
@@ -576,7 +542,7 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
     if (p.candidates && p.cand_stride > best) best = p.cand_stride;
   }
   if (best == 0) return 0;
-  return (u64)M_max * best + (u64)(kTargetBlocks + M_max) * kSlab;
+  return (u64)M_max * best + (u64)(kTargetBlocks + M_max) * kWaves * kSlab;
 }
 
 hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
@@ -595,24 +561,25 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
                                                                          p.candidates ? kModeCandidates : kModeGeneral)));
   if (p.candidates) {
-    const u32 n_blk = (n_tiles + kTilesPerBlock - 1) / kTilesPerBlock;
+    const u32 n_wt = p.n_wtiles, wstride = wt_stride(N);
+    const u32 n_blk = (n_wt + kTilesPerBlock - 1) / kTilesPerBlock;
     const u32 bstride = blk_stride(N);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_tiles, stride,
-                                                              ws.status)));
+    S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
+                                                              p.tiles_per_wave, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<dim3((n_tiles * kGroup + kBlock - 1) / kBlock, M), kBlock, 0, s>>>(
-                                     ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_tiles, stride)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<dim3((n_wt + kBlock - 1) / kBlock, M), kBlock, 0, s>>>(ws.rs, ws.hist, ws.cand, p.cand_stride,
+                                                                                                      ws.chunk, n_wt, wstride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, ws.tile_cnt,
-                                                                                n_tiles, stride, ws.blk_sum, bstride)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
+                                                                                ws.blk_sum, bstride)));
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.blk_sum, n_blk, bstride, ws.rs, kModeCandidates)));
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, ws.tile_cnt, n_tiles,
-                                                                             stride, ws.blk_sum, bstride, K, words)));
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
+                                                                             ws.blk_sum, bstride, K, words)));
   }
   // General route: every kernel returns at once for rows the candidate route has served.
   S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));

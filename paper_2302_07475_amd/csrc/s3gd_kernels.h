@@ -8,7 +8,9 @@ constexpr u32 kTargetBlocks = 256 * 16;  // blocks of a streaming launch: 16 per
 
 inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  // rows may start up to 3 slots late
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
-inline u32 blk_stride(u64 N) { return ((encode_tiles(N) + kTilesPerBlock - 1) / kTilesPerBlock + 1 + 3) & ~3u; }
+inline u32 wave_tiles(u64 N) { return (u32)((N + 3 + kWaveTile - 1) / kWaveTile); }
+inline u32 wt_stride(u64 N) { return (wave_tiles(N) + 3) & ~3u; }
+inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + kTilesPerBlock - 1) / kTilesPerBlock + 1 + 3) & ~3u; }
 inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
 
 // Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
@@ -42,8 +44,8 @@ struct Workspace {
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]
   u32* seg;       // [M][vote_tiles + 1]
-  u64* chunk;     // [M][tile_stride]  candidate route: (first slot << 32) | candidates of each tile
-  u64* blk_sum;   // [M][blk_stride]   candidate route: counts per 256 tiles, scanned in place
+  u64* chunk;     // [M][wt_stride]    candidate route: (first slot << 32) | candidates of each wave tile
+  u64* blk_sum;   // [M][blk_stride]   candidate route: (eq << 32 | gt) per 256 wave tiles, scanned in place
   uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
   u64 cand_pool;  // entries of `cand`
 };
@@ -51,7 +53,8 @@ struct Workspace {
 // What one encode call launches; a pure function of the shapes and the pool size.
 struct EncodePlan {
   bool candidates;   // try the candidate route first
-  u32 n_tiles, gx;   // tiles per row, streaming blocks per row
+  u32 n_tiles, gx;   // 4096-entry tiles per row, streaming blocks per row
+  u32 n_wtiles, tiles_per_wave;  // candidate route: 1024-entry wave tiles per row, and per wave of the filter
   u32 n_units;       // sample units (16 entries each) per row
   u64 unit_stride;   // row entries per sample unit window
   u32 sample_rank;   // rank, among the sample, of the key that becomes the lower bound L
