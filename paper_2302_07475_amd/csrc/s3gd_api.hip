@@ -121,6 +121,7 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
   c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
   c->ws.cand_pool = l.cand_pool;
+  c->ws.stream_blocks = resident_stream_blocks(device);
   c->ws.prof = &c->prof;
   *out = c;
   return S3GD_OK;

@@ -109,54 +109,56 @@ __device__ __forceinline__ uint4 load_stream16(const u32* p) {
   return make_uint4(q.x, q.y, q.z, q.w);
 }
 
-__device__ __forceinline__ void load_tile(const u32* __restrict__ rowv /* row start minus a slots */,
-                                          u32 a, u64 vend /* N + a */, u64 vbase, TileRegs& r) {
-  r.valid = 0;
+// Careful path of one 16-byte group that may straddle the ends of the row.
+__device__ __forceinline__ void load_edge4(const u32* __restrict__ rowv, u32 a, u64 vend, u64 v, int j, TileRegs& r) {
+  if (v >= a && v + 4 <= vend) {
+    const uint4 q = load_stream16(rowv + v);
+    r.b[4 * j + 0] = q.x; r.b[4 * j + 1] = q.y; r.b[4 * j + 2] = q.z; r.b[4 * j + 3] = q.w;
+    r.valid |= 0xFu << (4 * j);
+  } else {
 #pragma unroll
-  for (int j = 0; j < kLoads; ++j) {
-    const u64 v = vbase + (u64)j * (kBlock * 4) + (u64)threadIdx.x * 4;
-    if (v >= a && v + 4 <= vend) {
-      const uint4 q = load_stream16(rowv + v);
-      r.b[4 * j + 0] = q.x; r.b[4 * j + 1] = q.y; r.b[4 * j + 2] = q.z; r.b[4 * j + 3] = q.w;
-      r.valid |= 0xFu << (4 * j);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const u64 ve = v + e;
-        if (ve >= a && ve < vend) {
-          r.b[4 * j + e] = rowv[ve];
-          r.valid |= 1u << (4 * j + e);
-        } else {
-          r.b[4 * j + e] = 0;
-        }
+    for (int e = 0; e < 4; ++e) {
+      const u64 ve = v + e;
+      if (ve >= a && ve < vend) {
+        r.b[4 * j + e] = rowv[ve];
+        r.valid |= 1u << (4 * j + e);
+      } else {
+        r.b[4 * j + e] = 0;
       }
     }
   }
 }
 
+// Loads `span` entries starting at vbase; thread/lane `t` owns entries vbase + j*span/kLoads + t*4 + e.
+// Tiles that lie wholly inside the row (all but the first and last of a row) take a branch-free
+// path so that the four loads are in flight together.
+template <int SPAN>
+__device__ __forceinline__ void load_span(const u32* __restrict__ rowv, u32 a, u64 vend, u64 vbase, u32 t, TileRegs& r) {
+  constexpr int STEP = SPAN / kLoads;
+  if (vbase >= a && vbase + SPAN <= vend) {  // uniform over the block (SPAN = kTile) or wave (SPAN = kWaveTile)
+    uint4 q[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) q[j] = load_stream16(rowv + vbase + (u64)j * STEP + (u64)t * 4);
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      r.b[4 * j + 0] = q[j].x; r.b[4 * j + 1] = q[j].y; r.b[4 * j + 2] = q[j].z; r.b[4 * j + 3] = q[j].w;
+    }
+    r.valid = 0xFFFFu;
+  } else {
+    r.valid = 0;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) load_edge4(rowv, a, vend, vbase + (u64)j * STEP + (u64)t * 4, j, r);
+  }
+}
+
+__device__ __forceinline__ void load_tile(const u32* __restrict__ rowv /* row start minus a slots */,
+                                          u32 a, u64 vend /* N + a */, u64 vbase, TileRegs& r) {
+  load_span<kTile>(rowv, a, vend, vbase, threadIdx.x, r);
+}
+
 // The same for a wave tile: entry (j, e) of lane l is v = vbase + j*256 + l*4 + e.
 __device__ __forceinline__ void load_wave_tile(const u32* __restrict__ rowv, u32 a, u64 vend, u64 vbase, u32 lane, TileRegs& r) {
-  r.valid = 0;
-#pragma unroll
-  for (int j = 0; j < kLoads; ++j) {
-    const u64 v = vbase + (u64)j * 256 + (u64)lane * 4;
-    if (v >= a && v + 4 <= vend) {
-      const uint4 q = load_stream16(rowv + v);
-      r.b[4 * j + 0] = q.x; r.b[4 * j + 1] = q.y; r.b[4 * j + 2] = q.z; r.b[4 * j + 3] = q.w;
-      r.valid |= 0xFu << (4 * j);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const u64 ve = v + e;
-        if (ve >= a && ve < vend) {
-          r.b[4 * j + e] = rowv[ve];
-          r.valid |= 1u << (4 * j + e);
-        } else {
-          r.b[4 * j + e] = 0;
-        }
-      }
-    }
-  }
+  load_span<kWaveTile>(rowv, a, vend, vbase, lane, r);
 }
 
 // Ranks of flagged entries of a wave tile in ascending index order (j, lane, e); no LDS, no barrier.

@@ -16,6 +16,7 @@
 //                    (too few or too many candidates, heavy ties, tiny rows) takes it; the choice
 //                    is made on the device, per row, with no host synchronisation.
 #include <math.h>
+#include <stdlib.h>
 
 #include "s3gd_common.h"
 #include "s3gd_kernels.h"
@@ -321,6 +322,130 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 // index, and chunks are placed in slabs that the wave reserves with one atomic per kSlab
 // candidates.  Consecutive tiles therefore have consecutive chunks.  The block also histograms
 // (key - L) >> 10 into 2048 bins, the last of which is open-ended.
+//
+// Stores are batched: single 8-byte stores scattered through the stream cost far more than their
+// bytes (each becomes a partial-line write to HBM), so candidates are staged in LDS and written
+// 64 or more at a time, and the per-tile chunk table is kept in registers, one tile per lane, and
+// written every 64 tiles.
+constexpr int kStage = 192;  // staged candidates per wave
+
+struct FilterWave {
+  u32 cur, end, total;  // slab cursor, slab end, candidates so far (wave-uniform)
+  u32 fill;             // candidates staged in LDS; they belong to out[cur - fill, cur)
+  u64 entry;            // this lane's pending chunk-table entry
+  bool overflow, nan;
+};
+
+__device__ __forceinline__ void flush_stage(FilterWave& w, const uint2* stage, uint2* __restrict__ out, u32 lane) {
+  __builtin_amdgcn_wave_barrier();
+  const u32 g0 = w.cur - w.fill;
+  for (u32 i = lane; i < w.fill; i += 64) out[g0 + i] = stage[i];
+  __builtin_amdgcn_wave_barrier();
+  w.fill = 0;
+}
+
+// Writes the candidates of one tile, in ascending index, to the LDS stage or (DIRECT) to memory.
+template <bool DIRECT>
+__device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (&pr)[kLoads * 4], const u64 (&mk)[kLoads * 4],
+                                                 const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u32 L, u32* h,
+                                                 uint2* __restrict__ dst_global, uint2* dst_stage, bool& nan) {
+  const u32 Lq = L >> 10;
+  u32 run = first_slot;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    if (tot[j] == 0) continue;  // wave-uniform
+    // candidates of load j in lower lanes, then this lane's own in ascending e
+    u32 o = run + ballot_rank(mk[4 * j]) + ballot_rank(mk[4 * j + 1]) + ballot_rank(mk[4 * j + 2]) + ballot_rank(mk[4 * j + 3]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = 4 * j + e;
+      if (pr[i]) {
+        const u32 key = r.b[i] & 0x7FFFFFFFu;
+        const uint2 cd = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
+        if (DIRECT) dst_global[o] = cd; else dst_stage[o] = cd;
+        ++o;
+        nan |= key > 0x7F800000u;
+        const u32 bin = (key >> 10) - Lq;
+        atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
+      }
+    }
+    run += tot[j];
+  }
+}
+
+// INTERIOR tiles lie wholly inside the row: their loads are branch-free.
+template <bool INTERIOR>
+__device__ __forceinline__ void load_filter_tile(const u32* __restrict__ rowv, u32 a, u64 vend, u32 tile, u32 lane, TileRegs& r) {
+  const u64 vbase = (u64)tile * kWaveTile;
+  if (INTERIOR) {
+    uint4 q[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) q[j] = load_stream16(rowv + vbase + (u64)j * 256 + (u64)lane * 4);
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      r.b[4 * j + 0] = q[j].x; r.b[4 * j + 1] = q[j].y; r.b[4 * j + 2] = q[j].z; r.b[4 * j + 3] = q[j].w;
+    }
+    r.valid = 0xFFFFu;
+  } else {
+    r.valid = 0;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) load_edge4(rowv, a, vend, vbase + (u64)j * 256 + (u64)lane * 4, j, r);
+  }
+}
+
+template <bool INTERIOR>
+__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, uint2* stage,
+                                            u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, FilterWave& w) {
+  // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
+  // candidates below is scalar work plus a few mbcnt.
+  bool pr[kLoads * 4];
+  u64 mk[kLoads * 4];
+  u64 any = 0;
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) {
+    const u32 key = r.b[i] & 0x7FFFFFFFu;
+    pr[i] = key >= L;
+    if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
+    mk[i] = ballot(pr[i]);
+    any |= mk[i];
+  }
+  if (any == 0) {  // wave-uniform
+    if (lane == slot) w.entry = 0;
+    return;
+  }
+  u32 tot[kLoads], total = 0;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    tot[j] = (u32)__popcll(mk[4 * j]) + (u32)__popcll(mk[4 * j + 1]) + (u32)__popcll(mk[4 * j + 2]) + (u32)__popcll(mk[4 * j + 3]);
+    total += tot[j];
+  }
+  if (w.cur + total > w.end) {
+    flush_stage(w, stage, out, lane);  // staged candidates belong to the old slab
+    const u32 need = (total + kSlab - 1) / kSlab * kSlab;
+    u32 b = 0;
+    if (lane == 0) b = atomicAdd(n_alloc, need);
+    w.cur = __builtin_amdgcn_readfirstlane(b);
+    w.end = w.cur + need;
+  }
+  if (w.end > cand_stride) {
+    w.overflow = true;
+    w.fill = 0;
+  } else {
+    if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane);
+    const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
+    if (total > (u32)kStage) {  // a tile too dense to stage writes straight to memory (stage is empty here)
+      place_candidates<true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
+    } else {
+      place_candidates<false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
+      w.fill += total;
+    }
+  }
+  if (lane == slot) w.entry = ((u64)w.cur << 32) | total;
+  w.cur += total;
+  w.total += total;
+  if (w.fill >= 64) flush_stage(w, stage, out, lane);
+}
+
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs,
                                                    u32* __restrict__ hist, uint2* __restrict__ cand, u32 cand_stride,
                                                    u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride, u32 tiles_per_wave,
@@ -329,71 +454,48 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u32 h[kHistBins];
+  __shared__ uint2 stage_all[kWaves][kStage];
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
   const u64 vend = N + a;
-  const u32 L = st.L, Lq = st.L >> 10;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
   u64* ch = chunk + (size_t)m * wt_stride;
-  u32 cur = 0, end = 0, wave_total = 0;  // wave-uniform
-  bool nan = false, overflow = false;
+  uint2* stage = stage_all[wave];
+  FilterWave w{0, 0, 0, 0, 0, false, false};
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
+  // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
+  const u32 first = a ? 1u : 0u;
+  const u32 last = (u32)(vend / kWaveTile);  // tiles below this index end inside the row
+  // Software pipeline: the loads of tile t+1 are in flight while tile t is processed.
+  TileRegs nxt;
+  if (t0 < t1) {
+    if (t0 >= first && t0 < last) load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
+    else load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
+  }
   for (u32 tile = t0; tile < t1; ++tile) {
-    TileRegs r;
-    load_wave_tile(rowv, a, vend, (u64)tile * kWaveTile, lane, r);
-    u32 cmask = 0;
-#pragma unroll
-    for (int i = 0; i < kLoads * 4; ++i) {
-      const u32 key = r.b[i] & 0x7FFFFFFFu;
-      cmask |= (u32)(((r.valid >> i) & 1u) && key >= L) << i;
+    const TileRegs r = nxt;
+    if (tile + 1 < t1) {
+      if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
+      else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
-    if (ballot(cmask != 0) == 0) {  // wave-uniform
-      if (lane == 0) ch[tile] = 0;
-      continue;
+    const u32 slot = (tile - t0) & 63u;
+    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, w);
+    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, w);
+    if (slot == 63u || tile + 1 == t1) {  // wave-uniform: write up to 64 chunk-table entries at once
+      if (lane <= slot) ch[tile - slot + lane] = w.entry;
     }
-    u32 base[kLoads];
-    const u32 total = wave_rank(cmask, base);
-    if (cur + total > end) {
-      const u32 need = (total + kSlab - 1) / kSlab * kSlab;
-      u32 b = 0;
-      if (lane == 0) b = atomicAdd(&rs[m].n_alloc, need);
-      cur = __builtin_amdgcn_readfirstlane(b);
-      end = cur + need;
-    }
-    if (end > cand_stride) {
-      overflow = true;
-    } else if (cmask) {
-      const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-#pragma unroll
-      for (int j = 0; j < kLoads; ++j) {
-        u32 o = cur + base[j];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * j + e;
-          if ((cmask >> i) & 1u) {
-            const u32 key = r.b[i] & 0x7FFFFFFFu;
-            out[o++] = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
-            nan |= key > 0x7F800000u;
-            const u32 bin = (key >> 10) - Lq;
-            atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
-          }
-        }
-      }
-    }
-    if (lane == 0) ch[tile] = ((u64)cur << 32) | total;
-    cur += total;
-    wave_total += total;
   }
+  if (!w.overflow) flush_stage(w, stage, out, lane);
   if (lane == 0) {
-    if (wave_total) atomicAdd(&rs[m].n_cand, wave_total);
-    if (overflow) rs[m].overflow = 1;
+    if (w.total) atomicAdd(&rs[m].n_cand, w.total);
+    if (w.overflow) rs[m].overflow = 1;
   }
-  if (nan) status[0] = 1;
+  if (w.nan) status[0] = 1;
   __syncthreads();
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
@@ -498,20 +600,33 @@ __global__ void k_zero_counts(u32* counts, u32 M) {
 }
 
 // ------------------------------------------------------------------------------------------------
-static u32 blocks_per_row(u32 M, u32 n_tiles) {
-  u32 gx = (kTargetBlocks + M - 1) / M;
+// Streaming launches use one round of resident blocks, split evenly over the rows.
+static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
+  u32 gx = stream_blocks / M;
   if (gx > n_tiles) gx = n_tiles;
   return gx < 1 ? 1 : gx;
+}
+
+u32 resident_stream_blocks(int device) {
+  int cus = 0, per_cu = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0) != hipSuccess || per_cu <= 0) per_cu = 4;
+  u32 n = (u32)cus * (u32)per_cu;
+  if (const char* e = getenv("S3GD_STREAM_BLOCKS")) {  // tuning knob for experiments
+    const long v = atol(e);
+    if (v > 0) n = (u32)v;
+  }
+  return n > kMaxStreamBlocks ? kMaxStreamBlocks : n;
 }
 
 // Upper estimate of the candidates per row when the sample rank is r and the sample fraction f:
 // the count of keys above the r-th largest sample key is about r / f with deviation sqrt(r) / f.
 static double candidate_bound(double r, double f) { return 1.25 * (r + 6.0 * sqrt(r) + 8.0) / f; }
 
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool) {
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
   EncodePlan p{};
   p.n_tiles = encode_tiles(N);
-  p.gx = blocks_per_row(M, p.n_tiles);
+  p.gx = blocks_per_row(M, p.n_tiles, stream_blocks);
   p.candidates = false;
   if (K == 0 || N < (1ull << 17) || K * 16 > N) return p;
   // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
@@ -538,11 +653,11 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
   // the bound is not monotone in K (the sample size changes in powers of two): take the largest
   // need over K_max and the sparsities below it down to 1e-5
   for (double k = (double)(K_max < N_max / 16 ? K_max : N_max / 16); k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
-    EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull);
+    EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, kMaxStreamBlocks);
     if (p.candidates && p.cand_stride > best) best = p.cand_stride;
   }
   if (best == 0) return 0;
-  return (u64)M_max * best + (u64)(kTargetBlocks + M_max) * kWaves * kSlab;
+  return (u64)M_max * best + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlab;
 }
 
 hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
@@ -551,7 +666,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
     k_zero_counts<<<(M + 255) / 256, 256, 0, s>>>(counts, M);
     return hipGetLastError();
   }
-  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool);
+  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, ws.stream_blocks);
   const u32 n_tiles = p.n_tiles;
   const u32 stride = tile_stride(N);
   const dim3 grid(p.gx, M);

@@ -4,7 +4,7 @@
 
 namespace s3gd {
 
-constexpr u32 kTargetBlocks = 256 * 16;  // blocks of a streaming launch: 16 per compute unit
+constexpr u32 kMaxStreamBlocks = 256 * 64;  // upper bound on the blocks of one streaming launch (256 CUs x 8 resident blocks)
 
 inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  // rows may start up to 3 slots late
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
@@ -48,6 +48,7 @@ struct Workspace {
   u64* blk_sum;   // [M][blk_stride]   candidate route: (eq << 32 | gt) per 256 wave tiles, scanned in place
   uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
   u64 cand_pool;  // entries of `cand`
+  u32 stream_blocks;  // blocks of a streaming launch = blocks resident on the device at once (one round, no tail)
 };
 
 // What one encode call launches; a pure function of the shapes and the pool size.
@@ -60,7 +61,8 @@ struct EncodePlan {
   u32 sample_rank;   // rank, among the sample, of the key that becomes the lower bound L
   u32 cand_stride;   // candidate slots per row
 };
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool);
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks);
+u32 resident_stream_blocks(int device);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 
 hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
