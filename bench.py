@@ -18,7 +18,6 @@ import json
 import os
 import sys
 import time
-from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -34,31 +33,6 @@ FULL_READ_KERNELS = {"hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
-
-
-def upload(cfg, datagen, torch, dev, step=0):
-    """[M, N] gradients generated chunk by chunk on host threads and copied straight to HBM."""
-    g = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
-    x = torch.empty((cfg.N,), dtype=torch.float32, device=dev)
-    nch = datagen.n_chunks(cfg.N)
-
-    def gjob(m, j):
-        lo = j * datagen.CHUNK
-        c = datagen.grad_chunk(cfg, step, m, j)
-        g[m, lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
-
-    def xjob(j):
-        lo = j * datagen.CHUNK
-        c = datagen.x0_chunk(cfg, j)
-        x[lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
-
-    with ThreadPoolExecutor(datagen.default_threads()) as ex:
-        futs = [ex.submit(gjob, m, j) for m in range(cfg.M) for j in range(nch)]
-        futs += [ex.submit(xjob, j) for j in range(nch)]
-        for f in futs:
-            f.result()
-    torch.cuda.synchronize()
-    return g, x
 
 
 def cpu_baseline(cfg, datagen):
@@ -100,7 +74,7 @@ def main():
     cfg = datagen.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()
-    g, x = upload(cfg, datagen, torch, dev)
+    g, x = datagen.to_device(cfg, device="cuda:0")
     log(f"[bench] {cfg.name}: M={cfg.M} N={cfg.N} K={cfg.K} generated and uploaded in {time.perf_counter() - t0:.1f} s")
     M, N, K = cfg.M, cfg.N, cfg.K
     lr = float(datagen.lr32(cfg))

@@ -174,3 +174,48 @@ def step_dense(G: np.ndarray, K: int, x: np.ndarray, lr) -> dict:
     tally = T.sum(axis=0, dtype=np.int32)
     votes = sgn(tally)
     return dict(tally=tally, votes=votes, x=apply_update(x, votes, lr))
+
+
+# ---------------------------------------------------------------------------------------------
+# Checks that hold at any size (used where a full sort of the row is too slow to run in a test)
+
+def check_message_row(g: np.ndarray, K: int, words: np.ndarray, count: int) -> None:
+    """Raises AssertionError unless (words, count) is exactly TopKSign(g) in the message format.
+
+    Written from the definition, without sorting.  Let S be the selected index set and t the
+    smallest selected magnitude.  S is the top-K set under (|g| descending, index ascending) iff
+      (1) |S| = K;
+      (2) every index with |g| > t is in S;
+      (3) the members of S with |g| == t are the lowest-indexed entries of that magnitude.
+    The message lists S minus its zero-valued members, ascending, with the sign bit of each.
+    """
+    g = _check_row(g, K)
+    N = g.shape[0]
+    words = np.asarray(words, dtype=np.uint32)
+    assert words.shape == (K,), "row has K slots"
+    assert 0 <= count <= K
+    assert (words[count:] == PAD).all(), "slots past count hold the pad word"
+    idx = (words[:count] >> np.uint32(1)).astype(np.int64)
+    assert (idx < N).all(), "index out of range"
+    assert (np.diff(idx) > 0).all(), "indices ascending and distinct"
+    assert np.array_equal(words[:count] & np.uint32(1), (g[idx] < 0).astype(np.uint32)), "sign bits"
+    assert not (g[idx] == 0).any(), "zero entries send nothing"
+    mag = np.abs(g)
+    if count < K:
+        # the K selected entries include zeros: every non-zero entry must have been sent
+        assert count == int(np.count_nonzero(mag)), "a non-zero entry is missing although zeros were selected"
+        return
+    if K == 0:
+        return
+    t = mag[idx].min()
+    assert t > 0
+    n_gt = int(np.count_nonzero(mag > t))
+    sel_mag = mag[idx]
+    assert int(np.count_nonzero(sel_mag > t)) == n_gt, "an entry above the threshold was left out"
+    q = K - n_gt
+    ties_sel = idx[sel_mag == t]
+    assert ties_sel.shape[0] == q
+    # lowest-indexed q entries of magnitude t: find them without touching the whole row twice
+    hi = int(ties_sel[-1]) + 1
+    first_q = np.nonzero(mag[:hi] == t)[0]
+    assert np.array_equal(first_q, ties_sel), "ties at the threshold must go to the lowest indices"

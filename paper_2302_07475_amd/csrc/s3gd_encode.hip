@@ -638,7 +638,8 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
   if (r >= (double)s) return p;
   p.n_wtiles = (u32)((N + 3 + kWaveTile - 1) / kWaveTile);
   p.tiles_per_wave = (p.n_wtiles + p.gx * kWaves - 1) / (p.gx * kWaves);
-  const double need = candidate_bound(r, f) + (double)p.gx * kWaves * kSlab + kWaveTile;
+  p.bound = candidate_bound(r, f);
+  const double need = p.bound + (double)p.gx * kWaves * kSlab + kWaveTile;
   if (need * M > (double)cand_pool || need > 4.0e9) return p;
   p.candidates = true;
   p.n_units = (u32)(s / kSampleUnit);
@@ -649,15 +650,16 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
 }
 
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
-  u64 best = 0;
+  double best = 0;
   // the bound is not monotone in K (the sample size changes in powers of two): take the largest
-  // need over K_max and the sparsities below it down to 1e-5
+  // over K_max and the sparsities below it down to 1e-5
   for (double k = (double)(K_max < N_max / 16 ? K_max : N_max / 16); k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
-    EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, kMaxStreamBlocks);
-    if (p.candidates && p.cand_stride > best) best = p.cand_stride;
+    const EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, 1);
+    if (p.candidates && p.bound > best) best = p.bound;
   }
   if (best == 0) return 0;
-  return (u64)M_max * best + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlab;
+  // per row: the bound and one tile of slack; once: a partly filled slab per wave of a streaming launch
+  return (u64)M_max * ((u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlab;
 }
 
 hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,

@@ -4,7 +4,7 @@
 
 namespace s3gd {
 
-constexpr u32 kMaxStreamBlocks = 256 * 64;  // upper bound on the blocks of one streaming launch (256 CUs x 8 resident blocks)
+constexpr u32 kMaxStreamBlocks = 256 * 16;  // upper bound on the blocks of one streaming launch (256 CUs x 8 resident blocks)
 
 inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  // rows may start up to 3 slots late
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
@@ -60,6 +60,7 @@ struct EncodePlan {
   u64 unit_stride;   // row entries per sample unit window
   u32 sample_rank;   // rank, among the sample, of the key that becomes the lower bound L
   u32 cand_stride;   // candidate slots per row
+  double bound;      // upper estimate of the candidates per row, without slab slack
 };
 EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks);
 u32 resident_stream_blocks(int device);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks

@@ -182,3 +182,30 @@ def params(cfg: Config, out: np.ndarray | None = None, threads: int | None = Non
 
 def lr32(cfg: Config) -> np.float32:
     return np.float32(cfg.lr)
+
+
+def to_device(cfg: Config, step: int = 0, device: str = "cuda:0", threads: int | None = None, want_x: bool = True):
+    """(g, x): the [M, N] gradients of one step and x^0 as device tensors, generated chunk by
+    chunk on host threads and copied straight into device memory (the host never holds the whole
+    tensor).  The bytes are those of gradients() / params()."""
+    import torch
+
+    g = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=device)
+    x = torch.empty((cfg.N,), dtype=torch.float32, device=device) if want_x else None
+
+    def gjob(m, j):
+        lo = j * CHUNK
+        c = grad_chunk(cfg, step, m, j)
+        g[m, lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
+
+    def xjob(j):
+        lo = j * CHUNK
+        c = x0_chunk(cfg, j)
+        x[lo:lo + c.shape[0]].copy_(torch.from_numpy(c))
+
+    jobs = [(lambda m=m, j=j: gjob(m, j)) for m in range(cfg.M) for j in range(n_chunks(cfg.N))]
+    if want_x:
+        jobs += [(lambda j=j: xjob(j)) for j in range(n_chunks(cfg.N))]
+    _run(jobs, threads)
+    torch.cuda.synchronize()
+    return g, x

@@ -298,3 +298,38 @@ def test_planted_mistakes_fail_a_pin(monkeypatch):
     # (e) update with the wrong sign
     r = O.step(np.array([[2.0]], dtype=np.float32), 1, np.array([1.0], dtype=np.float32), 0.5)
     assert r["x"][0] == 0.5
+
+
+# ---------------------------------------------------------------- the any-size checker is itself pinned
+def test_row_checker_accepts_the_sorted_answer_and_rejects_neighbours():
+    """check_message_row is what full-size GPU tests rely on, so it is pinned against the sort
+    on small inputs: it accepts the oracle's message and rejects every single-word perturbation."""
+    rng = np.random.default_rng(12)
+    for name, g in _tiny_cases() + [("grid", (np.rint(rng.standard_normal(300) * 4) / 4).astype(np.float32))]:
+        N = g.shape[0]
+        for K in sorted({0, 1, 2, N // 3, N // 2, N - 1, N}):
+            words, count = O.encode_row(g, K)
+            O.check_message_row(g, K, words, count)  # accepts
+            sel = set((words[:count] >> 1).tolist())
+            others = [n for n in range(N) if n not in sel and g[n] != 0]
+            if count and others:
+                # swap one selected index for an unselected one: must be rejected
+                for victim in (0, count - 1):
+                    bad = words.copy()
+                    keep = [int(w) >> 1 for w in bad[:count]]
+                    keep[victim] = others[0]
+                    keep = sorted(set(keep))
+                    if len(keep) != count:
+                        continue
+                    bad[:count] = np.array([(n << 1) | int(g[n] < 0) for n in keep], dtype=np.uint32)
+                    with pytest.raises(AssertionError):
+                        O.check_message_row(g, K, bad, count)
+            if count:
+                bad = words.copy()
+                bad[0] ^= 1  # wrong sign
+                with pytest.raises(AssertionError):
+                    O.check_message_row(g, K, bad, count)
+                bad = words.copy()
+                bad[count - 1] = 0xFFFFFFFF  # dropped word
+                with pytest.raises(AssertionError):
+                    O.check_message_row(g, K, bad, count - 1)
