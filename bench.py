@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--three-calls", action="store_true", help="time encode, vote, update as separate calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GiB",
+                    help="instead of the benchmark, run three plain device copies of this size; run it under "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE to get the factor between counter units and bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (all M workers are rows of one tensor); --gpus must be 1")
@@ -71,6 +74,15 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(3)
+    if args.calibrate_copy > 0:
+        n = int(args.calibrate_copy * (1 << 30)) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "plain copy", "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n}))
+        return
     cfg = datagen.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()

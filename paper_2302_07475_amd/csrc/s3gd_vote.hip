@@ -12,14 +12,14 @@ namespace s3gd {
 
 constexpr int kRowChunk = 256;  // rows whose segment bounds sit in LDS at once
 
-// seg[m][t] = first position of row m whose index is >= t * kVoteTile (t = 0 .. n_vt).
+// seg[m][t] = first position of row m whose index is >= t * tile_coords (t = 0 .. n_vt).
 __global__ void k_seg_bounds(const u32* __restrict__ words, const u32* __restrict__ counts, u64 K, u32 n_vt, u32 seg_stride,
-                             u32* __restrict__ seg) {
+                             u32 tile_coords, u32* __restrict__ seg) {
   const u32 m = blockIdx.y;
   const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t > n_vt) return;
   const u32* w = words + (size_t)m * K;
-  const u64 target = ((u64)t * kVoteTile) << 1;
+  const u64 target = ((u64)t * tile_coords) << 1;
   u32 lo = 0, hi = counts[m];
   if ((u64)hi > K) hi = (u32)K;  // a count above the row length is a caller error; stay in bounds
   while (lo < hi) {
@@ -91,42 +91,86 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
   }
 }
 
-// Sparse variant: only x is produced.  Work is proportional to the number of messages: the LDS
-// tile is zeroed once, every vote is added, then every message's coordinate is claimed with an
-// exchange that hands the tally to exactly one thread and leaves the slot zero for the next tile.
-__global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
-                                                        u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x, float lr) {
-  __shared__ __attribute__((aligned(16))) int32_t t[kVoteTile];
-  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
+// Sparse variant: only x is produced, and only where somebody voted.
+//
+// The tally of a coordinate lives in an FB-bit field of an LDS word (FB = 8 while M <= 63, 16 while
+// M <= 16383, else 32), so one block covers 32768 / 16384 / 8192 coordinates: at the sparsities of
+// interest a tile holds few messages and the cost of a tile is a chain of memory latencies, so
+// fewer, larger tiles are what counts.  A field holds BIAS + tally, which stays inside
+// [BIAS - M, BIAS + M] and so never carries into its neighbour; its top bit is a "claimed" flag.
+// Per tile: fill the fields with BIAS; add every vote; then every message tries to set the flag
+// of its coordinate, and the one that finds it clear owns the coordinate and applies the update.
+constexpr int kVoteWords = 8192;  // LDS words of the packed tally (32 KB)
+
+template <int FB>
+struct VoteField {
+  static constexpr int kPer = 32 / FB;
+  static constexpr u32 kFlag = 1u << (FB - 1);
+  static constexpr u32 kBias = 1u << (FB - 2);
+  static constexpr u32 kFill = FB == 8 ? 0x40404040u : (FB == 16 ? 0x40004000u : 0x40000000u);
+  static constexpr u32 kTile = kVoteWords * kPer;
+};
+
+template <int FB, int PHASE>
+__device__ __forceinline__ void vote_rows(const u32* __restrict__ words, u64 K, u32 m0, u32 rows, const u32* lo, const u32* hi,
+                                          u32* t, u64 base, u64 N, float* __restrict__ x, float lr) {
+  typedef VoteField<FB> F;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x * 4; i < kVoteTile; i += kBlock * 4) *reinterpret_cast<int4*>(&t[i]) = make_int4(0, 0, 0, 0);
-  for (u32 tile = blockIdx.x; tile < n_vt; tile += gridDim.x) {
-    const u64 base = (u64)tile * kVoteTile;
-    for (int phase = 0; phase < 2; ++phase) {
-      for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
-        __syncthreads();
-        load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
-        __syncthreads();
-        const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
-        for (u32 r = wave; r < rows; r += kWaves) {
-          const u32* w = words + (size_t)(m0 + r) * K;
-          for (u32 i = lo[r] + lane; i < hi[r]; i += 64) {
-            const u32 wd = w[i];
-            const u32 c = (u32)((u64)(wd >> 1) - base);
-            if (c >= (u32)kVoteTile || base + c >= N) continue;  // never true for sorted rows with indices < N
-            if (phase == 0) {
-              atomicAdd(&t[c], (wd & 1u) ? -1 : 1);
-            } else {
-              const int s = atomicExch(&t[c], 0);
-              if (s != 0) {
-                float* p = x + (base + c);
-                *p = *p - lr * (float)((s > 0) - (s < 0));
-              }
-            }
+  for (u32 r = wave; r < rows; r += kWaves) {
+    const u32* w = words + (size_t)(m0 + r) * K;
+    for (u32 i = lo[r] + lane; i < hi[r]; i += 64) {
+      const u32 wd = w[i];
+      const u32 c = (u32)((u64)(wd >> 1) - base);
+      if (c >= F::kTile || base + c >= N) continue;  // never true for sorted rows with indices < N
+      const u32 sh = (c % F::kPer) * FB;
+      if (PHASE == 0) {
+        atomicAdd(&t[c / F::kPer], (wd & 1u) ? (0u - (1u << sh)) : (1u << sh));
+      } else {
+        const u32 old = atomicOr(&t[c / F::kPer], F::kFlag << sh) >> sh;
+        if (!(old & F::kFlag)) {
+          const int s = (int)(old & (F::kFlag - 1u)) - (int)F::kBias;
+          if (s != 0) {
+            float* p = x + (base + c);
+            *p = *p - lr * (float)((s > 0) - (s < 0));
           }
         }
       }
     }
+  }
+}
+
+template <int FB>
+__global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
+                                                        u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x, float lr) {
+  typedef VoteField<FB> F;
+  __shared__ __attribute__((aligned(16))) u32 t[kVoteWords];
+  __shared__ u32 lo[2][kRowChunk], hi[2][kRowChunk];
+  const bool one_chunk = M <= (u32)kRowChunk;  // bounds of the next tile are then fetched a tile ahead
+  u32 buf = 0;
+  if (one_chunk && blockIdx.x < n_vt) load_bounds(seg, seg_stride, 0, M, blockIdx.x, lo[0], hi[0]);
+  for (u32 tile = blockIdx.x; tile < n_vt; tile += gridDim.x) {
+    const u64 base = (u64)tile * F::kTile;
+    for (int i = threadIdx.x * 4; i < kVoteWords; i += kBlock * 4) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
+    __syncthreads();
+    if (one_chunk) {
+      if (tile + gridDim.x < n_vt) load_bounds(seg, seg_stride, 0, M, tile + gridDim.x, lo[buf ^ 1], hi[buf ^ 1]);
+      vote_rows<FB, 0>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
+      __syncthreads();
+      vote_rows<FB, 1>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
+      buf ^= 1;
+    } else {
+      for (int phase = 0; phase < 2; ++phase) {
+        for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
+          __syncthreads();
+          load_bounds(seg, seg_stride, m0, M, tile, lo[0], hi[0]);
+          __syncthreads();
+          const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
+          if (phase == 0) vote_rows<FB, 0>(words, K, m0, rows, lo[0], hi[0], t, base, N, x, lr);
+          else vote_rows<FB, 1>(words, K, m0, rows, lo[0], hi[0], t, base, N, x, lr);
+        }
+      }
+    }
+    __syncthreads();  // all claims made before the fields are refilled
   }
 }
 
@@ -160,20 +204,25 @@ __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, 
 
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s) {
-  const u32 n_vt = vote_tiles(N);
-  const u32 stride = n_vt + 1;
   Profiler& P = *ws.prof;
+  const bool dense = tally || votes;
+  const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
+  const u32 tile_coords = dense ? (u32)kVoteTile : (u32)kVoteWords * (32u / fb);
+  const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);  // at most vote_tiles(N): the scratch row fits
+  const u32 stride = n_vt + 1;
   P.begin(KID_SEG_BOUNDS, s);
-  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, ws.seg);
+  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, tile_coords, ws.seg);
   P.end(s);
-  if (tally || votes) {
+  if (dense) {
     P.begin(KID_VOTE_DENSE, s);
     k_vote_dense<<<n_vt, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, tally, votes, x, lr);
     P.end(s);
   } else {
-    const u32 g = n_vt < 256u * 8u ? n_vt : 256u * 8u;
+    const u32 g = n_vt < ws.stream_blocks ? n_vt : ws.stream_blocks;
     P.begin(KID_VOTE_SPARSE, s);
-    k_vote_sparse<<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
+    if (fb == 8) k_vote_sparse<8><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
+    else if (fb == 16) k_vote_sparse<16><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
+    else k_vote_sparse<32><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, lr);
     P.end(s);
   }
   return hipGetLastError();

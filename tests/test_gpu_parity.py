@@ -247,3 +247,24 @@ def test_threshold_ties_on_candidate_route(ctx):
     t = mag[(w[0] >> 1).astype(np.int64)].min()
     assert np.count_nonzero(mag == t) > 10, "the recipe is meant to produce ties at the threshold"
     assert general == 0
+
+
+@pytest.mark.parametrize("M", [63, 64, 257, 300, 16500])
+def test_many_workers_every_tally_width(lib, M):
+    """The fused step packs tallies into 8-, 16- or 32-bit LDS fields depending on M, and walks the
+    rows in chunks of 256; all workers agree on some coordinates so that |tally| reaches M."""
+    rng = np.random.default_rng(M)
+    N, K = 3000, 12
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    G[:, 7] = 50.0      # everyone votes +1 here
+    G[:, 11] = -60.0    # everyone votes -1 here
+    G[::2, 13] = 70.0   # half vote +1 ...
+    G[1::2, 13] = -70.0  # ... half vote -1: a tie when M is even
+    x = rng.standard_normal(N).astype(np.float32)
+    want = oracle_step(G, K, x, 0.5)
+    assert abs(int(want["tally"][7])) == M and abs(int(want["tally"][11])) == M
+    with lib.Context(M, N, K, device=0) as c:
+        got = gpu_step(c, G, K, x, 0.5, fused=True, dense_outputs=False)
+        assert_same(got, want, keys=("words", "counts", "x"), what=f"sparse M={M}")
+        got = gpu_step(c, G, K, x, 0.5, fused=True, dense_outputs=True)
+        assert_same(got, want, what=f"dense M={M}")
