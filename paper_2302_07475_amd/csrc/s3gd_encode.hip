@@ -323,23 +323,27 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 // candidates.  Consecutive tiles therefore have consecutive chunks.  The block also histograms
 // (key - L) >> 10 into 2048 bins, the last of which is open-ended.
 //
-// Stores are batched: single 8-byte stores scattered through the stream cost far more than their
-// bytes (each becomes a partial-line write to HBM), so candidates are staged in LDS and written
-// 64 or more at a time, and the per-tile chunk table is kept in registers, one tile per lane, and
-// written every 64 tiles.
-constexpr int kStage = 192;  // staged candidates per wave
+// Stores are rare and non-temporal: on this memory system ANY store traffic mixed into the read
+// stream costs several per cent of read bandwidth, whatever its volume (measured: one 8-byte store
+// per 4 KB read, or one 512-byte store per 256 KB read, both cost 9 %; non-temporal stores issued
+// every 2 MB read cost 2.5 %).  So candidates are staged in LDS and written a few hundred at a
+// time, and the per-tile chunk table is staged in LDS and written every 256 tiles.
+constexpr int kStage = 512;        // staged candidates per wave
+constexpr int kStageFlush = 384;   // flush once this many are staged
+constexpr int kEntryStage = 256;   // staged chunk-table entries per wave
 
 struct FilterWave {
   u32 cur, end, total;  // slab cursor, slab end, candidates so far (wave-uniform)
   u32 fill;             // candidates staged in LDS; they belong to out[cur - fill, cur)
-  u64 entry;            // this lane's pending chunk-table entry
   bool overflow, nan;
 };
 
-__device__ __forceinline__ void flush_stage(FilterWave& w, const uint2* stage, uint2* __restrict__ out, u32 lane) {
+__device__ __forceinline__ void store_stream8(u64* p, u64 v) { __builtin_nontemporal_store(v, p); }
+
+__device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, uint2* __restrict__ out, u32 lane) {
   __builtin_amdgcn_wave_barrier();
-  const u32 g0 = w.cur - w.fill;
-  for (u32 i = lane; i < w.fill; i += 64) out[g0 + i] = stage[i];
+  u64* dst = reinterpret_cast<u64*>(out) + (w.cur - w.fill);
+  for (u32 i = lane; i < w.fill; i += 64) store_stream8(dst + i, stage[i]);
   __builtin_amdgcn_wave_barrier();
   w.fill = 0;
 }
@@ -348,7 +352,7 @@ __device__ __forceinline__ void flush_stage(FilterWave& w, const uint2* stage, u
 template <bool DIRECT>
 __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (&pr)[kLoads * 4], const u64 (&mk)[kLoads * 4],
                                                  const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u32 L, u32* h,
-                                                 uint2* __restrict__ dst_global, uint2* dst_stage, bool& nan) {
+                                                 uint2* __restrict__ dst_global, u64* dst_stage, bool& nan) {
   const u32 Lq = L >> 10;
   u32 run = first_slot;
 #pragma unroll
@@ -362,7 +366,7 @@ __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (
       if (pr[i]) {
         const u32 key = r.b[i] & 0x7FFFFFFFu;
         const uint2 cd = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
-        if (DIRECT) dst_global[o] = cd; else dst_stage[o] = cd;
+        if (DIRECT) dst_global[o] = cd; else dst_stage[o] = ((u64)cd.y << 32) | cd.x;
         ++o;
         nan |= key > 0x7F800000u;
         const u32 bin = (key >> 10) - Lq;
@@ -394,8 +398,8 @@ __device__ __forceinline__ void load_filter_tile(const u32* __restrict__ rowv, u
 }
 
 template <bool INTERIOR>
-__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, uint2* stage,
-                                            u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, FilterWave& w) {
+__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, u64* stage,
+                                            u64* entries, u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, FilterWave& w) {
   // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
   // candidates below is scalar work plus a few mbcnt.
   bool pr[kLoads * 4];
@@ -410,7 +414,7 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     any |= mk[i];
   }
   if (any == 0) {  // wave-uniform
-    if (lane == slot) w.entry = 0;
+    if (lane == 0) entries[slot] = 0;
     return;
   }
   u32 tot[kLoads], total = 0;
@@ -440,10 +444,10 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
       w.fill += total;
     }
   }
-  if (lane == slot) w.entry = ((u64)w.cur << 32) | total;
+  if (lane == 0) entries[slot] = ((u64)w.cur << 32) | total;
   w.cur += total;
   w.total += total;
-  if (w.fill >= 64) flush_stage(w, stage, out, lane);
+  if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane);
 }
 
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs,
@@ -454,7 +458,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u32 h[kHistBins];
-  __shared__ uint2 stage_all[kWaves][kStage];
+  __shared__ u64 stage_all[kWaves][kStage];
+  __shared__ u64 entry_all[kWaves][kEntryStage];
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const float* row = grads + (size_t)m * N;
@@ -464,8 +469,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
   u64* ch = chunk + (size_t)m * wt_stride;
-  uint2* stage = stage_all[wave];
-  FilterWave w{0, 0, 0, 0, 0, false, false};
+  u64* stage = stage_all[wave];
+  u64* entries = entry_all[wave];
+  FilterWave w{0, 0, 0, 0, false, false};
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
   // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
@@ -483,11 +489,13 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
       else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
-    const u32 slot = (tile - t0) & 63u;
-    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, w);
-    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, w);
-    if (slot == 63u || tile + 1 == t1) {  // wave-uniform: write up to 64 chunk-table entries at once
-      if (lane <= slot) ch[tile - slot + lane] = w.entry;
+    const u32 slot = (tile - t0) & (u32)(kEntryStage - 1);
+    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, w);
+    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, w);
+    if (slot == (u32)(kEntryStage - 1) || tile + 1 == t1) {  // wave-uniform: write the staged chunk-table entries
+      __builtin_amdgcn_wave_barrier();
+      for (u32 i = lane; i <= slot; i += 64) store_stream8(&ch[tile - slot + i], entries[i]);
+      __builtin_amdgcn_wave_barrier();
     }
   }
   if (!w.overflow) flush_stage(w, stage, out, lane);
