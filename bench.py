@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
 
+# HBM bytes per launch (read + written) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the factors a
+# plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE); figures and commands are in
+# profiles/s3gd_step_C5_hbm_traffic.md.  Reported only for the workload and kernel they were taken on.
+MEASURED_TRAFFIC_BYTES = {("C5", "filter"): 19.2002e9 + 0.1017e9}
+
 # algorithmic bytes one launch of a kernel moves, per gradient element (4 = one fp32 read of G)
 FULL_READ_KERNELS = {"hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "filter"}
 
@@ -144,7 +149,8 @@ def main():
                    "entry": "three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)",
                    "rows_on_general_path": general_rows},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK, "traffic": None},
+                     "frac": achieved / HBM_PEAK,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not args.three_calls else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,
