@@ -511,28 +511,47 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
 }
 
+// The kernels below walk the candidates tile by tile.  G lanes share a wave tile (G = 1, 4 or 16,
+// chosen on the host from the expected candidates per tile), so that a thread's loop stays a few
+// iterations long and the lanes of a group read consecutive candidates.
+template <int G>
+struct TileGroup {
+  static constexpr int kTiles = kBlock / G;  // tiles per block
+  u32 tile, sub;
+  __device__ TileGroup() : tile(blockIdx.x * kTiles + threadIdx.x / G), sub(threadIdx.x % G) {}
+};
+
+template <int G>
+__device__ __forceinline__ u64 group_sum(u64 v) {
+#pragma unroll
+  for (int d = G / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
 // Last radix level among the candidates: histogram of key & 1023 where key >> 10 == prefix.
-// One thread per wave tile; only the few hundred candidates of the target bin touch the histogram.
+// Only the few hundred candidates of the target bin touch the histogram.
+template <int G>
 __global__ __launch_bounds__(kBlock) void k_cand_hist(const RowState* __restrict__ rs, u32* __restrict__ hist,
                                                       const uint2* __restrict__ cand, u32 cand_stride,
                                                       const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  const u32 tile = blockIdx.x * kBlock + threadIdx.x;
-  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
+  const TileGroup<G> g;
+  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
   const u32 cnt = (u32)c;
   const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
-  for (u32 i = 0; i < cnt; ++i) {
+  for (u32 i = g.sub; i < cnt; i += G) {
     const u32 key = in[i].y & 0x7FFFFFFFu;
     if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
   }
 }
 
-// (gt, eq) of one wave tile against the final threshold, from its candidates.
-__device__ __forceinline__ u64 count_chunk(const uint2* __restrict__ in, u32 cnt, u32 T) {
+// (gt, eq) of the candidates i = sub, sub + G, ... of a chunk against the final threshold.
+template <int G>
+__device__ __forceinline__ u64 count_chunk(const uint2* __restrict__ in, u32 cnt, u32 sub, u32 T) {
   u32 gt = 0, eq = 0;
-  for (u32 i = 0; i < cnt; ++i) {
+  for (u32 i = sub; i < cnt; i += G) {
     const u32 key = in[i].y & 0x7FFFFFFFu;
     gt += key > T;
     eq += key == T;
@@ -540,8 +559,9 @@ __device__ __forceinline__ u64 count_chunk(const uint2* __restrict__ in, u32 cnt
   return ((u64)eq << 32) | gt;
 }
 
-// Sum of (gt, eq) over each block of kTilesPerBlock wave tiles; scanned afterwards, so that the
-// emit kernel only needs a block-local scan.
+// Sum of (gt, eq) over the tiles of each block; scanned afterwards, so that the emit kernel only
+// needs a block-local scan.
+template <int G>
 __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                        const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
                                                        u64* __restrict__ blk_sum, u32 blk_stride) {
@@ -549,15 +569,16 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u64 lds[kWaves];
-  const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
-  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
-  const u64 mine = count_chunk(cand + (size_t)m * cand_stride + (u32)(c >> 32), (u32)c, st.T);
+  const TileGroup<G> g;
+  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
+  const u64 mine = count_chunk<G>(cand + (size_t)m * cand_stride + (u32)(c >> 32), (u32)c, g.sub, st.T);
   u64 total;
   (void)block_excl_scan<u64>(mine, &total, lds);
   if (threadIdx.x == 0) blk_sum[(size_t)m * blk_stride + blockIdx.x] = total;
 }
 
-// Emits the words of kTilesPerBlock wave tiles per block from their candidate chunks, in ascending index.
+// Emits the words of the block's tiles from their candidate chunks, in ascending index.
+template <int G>
 __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                       const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
                                                       const u64* __restrict__ blk_sum, u32 blk_stride, u64 K, u32* __restrict__ words) {
@@ -565,25 +586,54 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u64 lds[kWaves];
-  const u32 tile = blockIdx.x * kTilesPerBlock + threadIdx.x;
-  const u64 c = tile < n_wtiles ? chunk[(size_t)m * wt_stride + tile] : 0;
+  const TileGroup<G> g;
+  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
   const u32 cnt = (u32)c;
   const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
-  const u64 mine = count_chunk(in, cnt, st.T);
+  const u64 part = count_chunk<G>(in, cnt, g.sub, st.T);
+  const u64 mine = group_sum<G>(part);  // the whole tile's (gt, eq), in every lane of the group
   u64 total;
-  const u64 before = blk_sum[(size_t)m * blk_stride + blockIdx.x] + block_excl_scan<u64>(mine, &total, lds);
-  if (mine == 0) return;
+  // scan over tiles: only lane 0 of a group contributes, then the group shares its prefix
+  u64 before = block_excl_scan<u64>(g.sub == 0 ? mine : 0, &total, lds);
+  before = __shfl(before, (int)(lane_id() & ~(u32)(G - 1)), 64) + blk_sum[(size_t)m * blk_stride + blockIdx.x];
   u32 eq_seen = (u32)(before >> 32);
   u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
   u32* out = words + (size_t)m * K;
-  for (u32 i = 0; i < cnt; ++i) {
-    const uint2 cd = in[i];
-    const u32 key = cd.y & 0x7FFFFFFFu;
-    bool sel = key > st.T;
-    if (key == st.T) { sel = eq_seen < st.q; ++eq_seen; }
-    if (sel) {
-      if (o < K) out[o] = (cd.x << 1) | (cd.y >> 31);  // o < K by construction
-      ++o;
+  if (G == 1) {
+    for (u32 i = 0; i < cnt; ++i) {
+      const uint2 cd = in[i];
+      const u32 key = cd.y & 0x7FFFFFFFu;
+      bool sel = key > st.T;
+      if (key == st.T) { sel = eq_seen < st.q; ++eq_seen; }
+      if (sel) {
+        if (o < K) out[o] = (cd.x << 1) | (cd.y >> 31);  // o < K by construction
+        ++o;
+      }
+    }
+  } else {
+    // G candidates per round; ranks inside the group come from wave ballots, so every lane of the
+    // wave runs the same number of rounds
+    u32 rounds = (cnt + G - 1) / G;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) { const u32 other = __shfl_xor(rounds, d, 64); rounds = other > rounds ? other : rounds; }
+    const u32 gshift = lane_id() & ~(u32)(G - 1);
+    const u32 gmask = (1u << G) - 1u, below = (1u << g.sub) - 1u;
+    for (u32 rd = 0; rd < rounds; ++rd) {
+      const u32 i = rd * G + g.sub;
+      const bool ok = i < cnt;
+      uint2 cd = make_uint2(0, 0);
+      if (ok) cd = in[i];
+      const u32 key = cd.y & 0x7FFFFFFFu;
+      const bool is_eq = ok && key == st.T;
+      const u32 eq_bits = (u32)(ballot(is_eq) >> gshift) & gmask;
+      const bool sel = ok && (key > st.T || (is_eq && eq_seen + __popc(eq_bits & below) < st.q));
+      const u32 sel_bits = (u32)(ballot(sel) >> gshift) & gmask;
+      if (sel) {
+        const u32 pos = o + __popc(sel_bits & below);
+        if (pos < K) out[pos] = (cd.x << 1) | (cd.y >> 31);  // pos < K by construction
+      }
+      o += __popc(sel_bits);
+      eq_seen += __popc(eq_bits);
     }
   }
 }
@@ -687,7 +737,6 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
                                                                          p.candidates ? kModeCandidates : kModeGeneral)));
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles, wstride = wt_stride(N);
-    const u32 n_blk = (n_wt + kTilesPerBlock - 1) / kTilesPerBlock;
     const u32 bstride = blk_stride(N);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
@@ -697,14 +746,23 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
     S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
                                                               p.tiles_per_wave, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<dim3((n_wt + kBlock - 1) / kBlock, M), kBlock, 0, s>>>(ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                                                      ws.chunk, n_wt, wstride)));
+    // lanes per tile in the candidate kernels, from the expected candidates per tile
+    const double per_tile = p.bound / (double)n_wt;
+    const int G = per_tile <= 3.0 ? 1 : (per_tile <= 12.0 ? 4 : 16);
+    const u32 n_blk = (n_wt + (kBlock / G) - 1) / (kBlock / G);
+    const dim3 cgrid(n_blk, M);
+#define S3GD_CAND(KID, KERNEL, ...)                                                          \
+  do {                                                                                       \
+    if (G == 1) S3GD_LAUNCH(KID, (KERNEL<1><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));          \
+    else if (G == 4) S3GD_LAUNCH(KID, (KERNEL<4><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));     \
+    else S3GD_LAUNCH(KID, (KERNEL<16><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));                \
+  } while (0)
+    S3GD_CAND(KID_CAND_SELECT, k_cand_hist, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride);
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
-                                                                                ws.blk_sum, bstride)));
+    S3GD_CAND(KID_CAND_SELECT, k_cand_count, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride);
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.blk_sum, n_blk, bstride, ws.rs, kModeCandidates)));
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(n_blk, M), kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
-                                                                             ws.blk_sum, bstride, K, words)));
+    S3GD_CAND(KID_CAND_EMIT, k_cand_emit, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride, K, words);
+#undef S3GD_CAND
   }
   // General route: every kernel returns at once for rows the candidate route has served.
   S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));

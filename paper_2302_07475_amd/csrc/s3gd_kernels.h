@@ -10,7 +10,7 @@ inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  /
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
 inline u32 wave_tiles(u64 N) { return (u32)((N + 3 + kWaveTile - 1) / kWaveTile); }
 inline u32 wt_stride(u64 N) { return (wave_tiles(N) + 3) & ~3u; }
-inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + kTilesPerBlock - 1) / kTilesPerBlock + 1 + 3) & ~3u; }
+inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + 15) / 16 + 1 + 3) & ~3u; }  // blocks of the candidate kernels hold >= 16 tiles
 inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
 
 // Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
