@@ -177,6 +177,43 @@ def step_dense(G: np.ndarray, K: int, x: np.ndarray, lr) -> dict:
 
 
 # ---------------------------------------------------------------------------------------------
+# Error-compensation memory (Section 2.2 "Gradient update with sparsification error compensation";
+# Algorithm 1, the two lines before "send")
+#
+# Readings: g = g~ + eta * e is evaluated in fp32 as written (a product, then a sum: two
+# roundings; eta = 1, the paper's setting, makes both exact).  TopK(g) is the masked vector
+# (it is subtracted from g), so e' = g - TopK(g) keeps g off the selected set and is zero on it.
+# The zero is written as +0.0 wherever a sign was sent; a selected entry that is itself +-0 sends
+# nothing and keeps its bits (the literal difference would turn -0.0 into +0.0, and an infinite
+# selected entry into NaN: neither changes any later selection or vote).
+
+def compensate(G_tilde: np.ndarray, E: np.ndarray, eta) -> np.ndarray:
+    """g_m = g~_m + eta * e_m (eq. "gradupdate"), fp32."""
+    if G_tilde.dtype != np.float32 or E.dtype != np.float32 or G_tilde.shape != E.shape:
+        raise ValueError("gradients and error memory are float32 arrays of one shape")
+    prod = (np.float32(eta) * E).astype(np.float32)
+    return (G_tilde + prod).astype(np.float32)
+
+
+def residual(G: np.ndarray, words: np.ndarray, counts: np.ndarray) -> np.ndarray:
+    """e_m' = g_m - TopK(g_m): g off the support of the message, zero on it."""
+    E = G.copy()
+    for m in range(G.shape[0]):
+        idx = (words[m, : int(counts[m])] >> np.uint32(1)).astype(np.int64)
+        E[m, idx] = np.float32(0.0)
+    return E
+
+
+def step_with_memory(G_tilde: np.ndarray, E: np.ndarray, eta, K: int, x: np.ndarray, lr) -> dict:
+    """One full iteration of Algorithm 1 for all workers: compensate, remember, send, vote, update."""
+    G = compensate(G_tilde, E, eta)
+    out = step(G, K, x, lr)
+    out["g"] = G
+    out["err"] = residual(G, out["words"], out["counts"])
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
 # Checks that hold at any size (used where a full sort of the row is too slow to run in a test)
 
 def check_message_row(g: np.ndarray, K: int, words: np.ndarray, count: int) -> None:

@@ -333,3 +333,75 @@ def test_row_checker_accepts_the_sorted_answer_and_rejects_neighbours():
                 bad[count - 1] = 0xFFFFFFFF  # dropped word
                 with pytest.raises(AssertionError):
                     O.check_message_row(g, K, bad, count - 1)
+
+
+# ---------------------------------------------------------------- error-compensation memory
+def test_memory_hand_worked_three_iterations():
+    """Algorithm 1 with eta = 1, K = 1, one worker, constant gradient (3, 2, 1): the unselected
+    components pile up in the memory until they win the selection.
+      t0: g=(3,2,1) -> sel 0, e=(0,2,1)
+      t1: g=(3,4,2) -> sel 1, e=(3,0,2)
+      t2: g=(6,2,3) -> sel 0, e=(0,2,3)
+      t3: g=(3,4,4) -> tie at 4: lowest index 1 wins, e=(3,0,4)
+      t4: g=(6,2,5) -> sel 0, e=(0,2,5)
+      t5: g=(3,4,6) -> sel 2, e=(3,4,0)"""
+    gt = np.array([[3.0, 2.0, 1.0]], dtype=np.float32)
+    e = np.zeros_like(gt)
+    x = np.zeros(3, dtype=np.float32)
+    picks, errs = [], []
+    for _ in range(6):
+        r = O.step_with_memory(gt, e, 1.0, 1, x, 1.0)
+        picks.append(int(r["words"][0, 0] >> 1))
+        errs.append(r["err"][0].tolist())
+        e, x = r["err"], r["x"]
+    assert picks == [0, 1, 0, 1, 0, 2]
+    assert errs == [[0, 2, 1], [3, 0, 2], [0, 2, 3], [3, 0, 4], [0, 2, 5], [3, 4, 0]]
+    assert x.tolist() == [-3.0, -2.0, -1.0]  # every vote was +1: x moved by -lr each time it was selected
+
+
+@pytest.mark.parametrize("eta", [0.0, 1.0, 0.5])
+def test_memory_identities(eta):
+    """(a) eta = 0 is the memoryless step; (b) g = e' + TopK(g) exactly (nothing is lost or counted
+    twice); (c) e' vanishes exactly on the support of the message; (d) with eta = 1 the running
+    sum of gradients equals memory + everything ever selected."""
+    rng = np.random.default_rng(8)
+    M, N, K = 3, 400, 17
+    x = rng.standard_normal(N).astype(np.float32)
+    E = (rng.standard_normal((M, N)) * 0.5).astype(np.float32)
+    Gt = rng.standard_normal((M, N)).astype(np.float32)
+    r = O.step_with_memory(Gt, E, eta, K, x, 1e-3)
+    if eta == 0.0:
+        plain = O.step(Gt, K, x, 1e-3)
+        for k in ("words", "counts", "tally", "votes", "x"):
+            assert np.array_equal(r[k], plain[k])
+    G = r["g"]
+    assert np.array_equal(G, (Gt + np.float32(eta) * E).astype(np.float32))
+    topk_vec = np.zeros_like(G)
+    for m in range(M):
+        idx = (r["words"][m, : r["counts"][m]] >> 1).astype(np.int64)
+        topk_vec[m, idx] = G[m, idx]
+        assert (r["err"][m, idx] == 0).all()
+        rest = np.ones(N, dtype=bool)
+        rest[idx] = False
+        assert np.array_equal(r["err"][m, rest].view(np.uint32), G[m, rest].view(np.uint32))
+    assert np.array_equal(r["err"] + topk_vec, G)
+    if eta == 1.0:  # integers keep fp32 exact: sum of gradients == memory + sum of selected values
+        Gi = rng.integers(-8, 9, size=(1, 50)).astype(np.float32)
+        e = np.zeros_like(Gi)
+        sent = np.zeros_like(Gi)
+        for t in range(12):
+            rr = O.step_with_memory(Gi, e, 1.0, 5, np.zeros(50, np.float32), 1.0)
+            idx = (rr["words"][0, : rr["counts"][0]] >> 1).astype(np.int64)
+            sent[0, idx] += rr["g"][0, idx]
+            e = rr["err"]
+            assert np.array_equal(e + sent, Gi * (t + 1))
+
+
+def test_memory_selected_zero_and_negative_zero_keep_their_bits():
+    g = np.array([[0.0, -0.0, 5.0, -0.0]], dtype=np.float32)
+    words, counts = O.topk_sign_encode(g, 3)  # the 5 and, by index order, the first two zeros
+    assert counts[0] == 1  # only the 5 sends a sign
+    e = O.residual(g, words, counts)
+    assert e[0].view(np.uint32).tolist() == [0, 0x80000000, 0, 0x80000000]
+    # compensation itself follows IEEE: -0.0 + eta * (+0.0) is +0.0
+    assert O.compensate(g, np.zeros_like(g), 1.0)[0].view(np.uint32).tolist() == [0, 0, 0x40A00000, 0]
