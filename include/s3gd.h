@@ -58,7 +58,8 @@ extern "C" {
 
 #define S3GD_OK 0
 #define S3GD_E_INVAL (-1) /* NULL pointer, M == 0, N == 0, K > N, size above the context's maxima,  */
-                          /* misaligned buffer, lr negative or not finite, both vote outputs NULL   */
+                          /* misaligned buffer, lr or eta negative or not finite, both vote outputs */
+                          /* NULL, memory buffer at another 16-byte phase than the gradients       */
 #define S3GD_E_RANGE (-2) /* N > S3GD_N_LIMIT: index, sign bit and pad word must fit 32 bits         */
 #define S3GD_E_HIP (-3)   /* a HIP runtime call failed; s3gd_last_hip_error() has its code           */
 #define S3GD_E_NOMEM (-4) /* scratch allocation failed                                               */
@@ -129,6 +130,35 @@ S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N
               float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
               s3gd_stream_t stream);
 
+/*
+ * Worker side of Algorithm 1 WITH the error-compensation memory (Section 2.2 "Gradient update with
+ * sparsification error compensation", eqs. "gradupdate" and "errupdate"; Algorithm 1, the two
+ * lines before "send"):
+ *
+ *     g_m   = g~_m + eta * e_m          evaluated in fp32 as written: a rounded product, then a
+ *                                       rounded sum (eta = 1, the paper's setting, makes it one sum)
+ *     words = TopKSign(g_m)             exactly as s3gd_topk_sign_encode would encode g_m
+ *     e_m  <- g_m - TopK(g_m)           g_m off the selected set; +0.0 where a sign was sent; a
+ *                                       selected entry that is +-0 sends nothing and keeps its bits
+ *
+ *   grads   dev, const   [M, N] fp32: the fresh stochastic gradients g~.  Never modified.
+ *   err     dev, in/out  [M, N] fp32: e_m on entry, the new memory on return.  Must start at the same
+ *                        16-byte phase as grads ((grads - err) a multiple of 16 bytes) and must not
+ *                        overlap it.  Zero-fill it before the first iteration (e^0 = 0).
+ *   eta     weight of the memory, finite and >= 0.
+ *   words, counts, K     as in s3gd_topk_sign_encode.  K == 0 still folds the gradient into the
+ *                        memory (err <- g~ + eta * err).
+ * NaN in g (from the inputs, or from Inf - Inf) is reported through s3gd_last_async_status.
+ */
+S3GD_API int s3gd_topk_sign_encode_ec(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N,
+                             uint64_t K, uint32_t* words, uint32_t* counts, s3gd_stream_t stream);
+
+/* One whole iteration of Algorithm 1 for all workers: s3gd_topk_sign_encode_ec, then the vote and
+ * the update as in s3gd_step (tally and votes nullable in the same way). */
+S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N, uint64_t K,
+                 float* x, float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
+                 s3gd_stream_t stream);
+
 /* Synchronises `stream`, then returns 0, or S3GD_E_NAN if the last encode on this context saw a
  * NaN, or S3GD_E_HIP. */
 S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
@@ -146,7 +176,7 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 17
+#define S3GD_PROFILE_KERNELS 19
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);

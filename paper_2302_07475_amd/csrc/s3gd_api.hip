@@ -121,7 +121,8 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
   c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
   c->ws.cand_pool = l.cand_pool;
-  c->ws.stream_blocks = resident_stream_blocks(device);
+  c->ws.stream_blocks = resident_stream_blocks(device, false);
+  c->ws.stream_blocks_mem = resident_stream_blocks(device, true);
   c->ws.prof = &c->prof;
   *out = c;
   return S3GD_OK;
@@ -147,7 +148,7 @@ S3GD_API int s3gd_topk_sign_encode(s3gd_ctx* ctx, const float* grads, uint32_t M
   if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
-  const hipError_t e = launch_encode(ctx->ws, grads, M, N, K, words, counts, static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_encode(ctx->ws, grads, nullptr, 0.0f, M, N, K, words, counts, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
@@ -187,7 +188,50 @@ S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = launch_encode(ctx->ws, grads, M, N, K, words, counts, s);
+  hipError_t e = launch_encode(ctx->ws, grads, nullptr, 0.0f, M, N, K, words, counts, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
+  e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+namespace {
+int check_memory_args(const float* grads, const float* err, float eta, u32 M, u64 N) {
+  if (!grads || !err) return S3GD_E_INVAL;
+  if (!(eta >= 0.0f) || isinf(eta)) return S3GD_E_INVAL;
+  const uintptr_t g = reinterpret_cast<uintptr_t>(grads), e = reinterpret_cast<uintptr_t>(err);
+  if ((g & 3) || (e & 3) || ((g ^ e) & 15)) return S3GD_E_INVAL;
+  const uintptr_t bytes = (uintptr_t)M * N * 4;
+  if (g < e + bytes && e < g + bytes) return S3GD_E_INVAL;  // overlap
+  return S3GD_OK;
+}
+}  // namespace
+
+S3GD_API int s3gd_topk_sign_encode_ec(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N, uint64_t K,
+                             uint32_t* words, uint32_t* counts, s3gd_stream_t stream) {
+  int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if ((rc = check_memory_args(grads, err, eta, M, N))) return rc;
+  if (!counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_encode(ctx->ws, grads, err, eta, M, N, K, words, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N, uint64_t K, float* x,
+                 float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes, s3gd_stream_t stream) {
+  int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if ((rc = check_memory_args(grads, err, eta, M, N))) return rc;
+  if (!x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_encode(ctx->ws, grads, err, eta, M, N, K, words, counts, s);
   if (e != hipSuccess) return hip_fail(ctx, e);
   if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
   e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
@@ -253,7 +297,7 @@ S3GD_API const char* s3gd_profile_kernel_name(int id) {
   static const char* names[KID_COUNT] = {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
       "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
-      "apply_update"};
+      "apply_update", "compensate", "filter_mem"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 

@@ -24,6 +24,45 @@
 namespace s3gd {
 
 // ------------------------------------------------------------------------------------------------
+// Error-compensation memory (Section 2.2 "Gradient update with sparsification error compensation";
+// Algorithm 1, the two lines before "send"): the row that is compressed is g = g~ + eta * e, and the
+// memory becomes e' = g - TopK(g), i.e. g off the selected set and zero on it.  With a memory the
+// encode keeps g IN the memory buffer: the single pass over the row writes e <- g while it filters,
+// and the emit kernels write +0.0 over every entry whose sign they send.  The general route then
+// simply reads the memory buffer as its gradient row.
+//
+// g is evaluated in fp32 as written: a rounded product, then a rounded sum (no fused multiply-add).
+__device__ __forceinline__ u32 compensate_bits(u32 g_tilde, u32 e, float eta) {
+  return __float_as_uint(__fadd_rn(__uint_as_float(g_tilde), __fmul_rn(eta, __uint_as_float(e))));
+}
+
+__device__ __forceinline__ void store_stream16(u32* p, u32 a, u32 b, u32 c, u32 d) {
+  u32x4 q; q.x = a; q.y = b; q.z = c; q.w = d;
+  __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(p));
+}
+
+// e <- g~ + eta * e over the flat [M * N] array (rows are contiguous).  Used when no row of the call
+// goes through the filter pass (tiny rows, dense K, K = 0).  `head` = elements before the first
+// 16-byte boundary, the same for both arrays.
+__global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__ g_tilde, float* __restrict__ err, float eta, u64 total,
+                                                       u32 head) {
+  const u32* gt = reinterpret_cast<const u32*>(g_tilde);
+  u32* e = reinterpret_cast<u32*>(err);
+  const u64 tid = (u64)blockIdx.x * blockDim.x + threadIdx.x, nthr = (u64)gridDim.x * blockDim.x;
+  const u64 h = head < total ? head : total;
+  const u64 n4 = (total - h) / 4;
+  for (u64 i = tid; i < n4; i += nthr) {
+    const u64 o = h + i * 4;
+    const uint4 a = load_stream16(gt + o), b = load_stream16(e + o);
+    store_stream16(e + o, compensate_bits(a.x, b.x, eta), compensate_bits(a.y, b.y, eta), compensate_bits(a.z, b.z, eta),
+                   compensate_bits(a.w, b.w, eta));
+  }
+  if (tid < h) e[tid] = compensate_bits(gt[tid], e[tid], eta);
+  const u64 t0 = h + n4 * 4;
+  if (t0 + tid < total) e[t0 + tid] = compensate_bits(gt[t0 + tid], e[t0 + tid], eta);
+}
+
+// ------------------------------------------------------------------------------------------------
 // state reset (a kernel rather than a memset so that callers may capture the call into a graph)
 __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode) {
   const u32 m = blockIdx.y;
@@ -210,9 +249,11 @@ __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ til
 }
 
 // Emits the words of every tile at its scanned offset, in ascending index.
-__global__ __launch_bounds__(kBlock) void k_emit_rows(const float* __restrict__ grads, u64 N, u64 K, const RowState* __restrict__ rs,
+// With a memory (`err` non-NULL) `grads` IS the memory buffer holding g, and every entry whose sign
+// is sent is overwritten with +0.0; a tile is read and rewritten by the same block only.
+__global__ __launch_bounds__(kBlock) void k_emit_rows(const float* grads, u64 N, u64 K, const RowState* __restrict__ rs,
                                                       const u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
-                                                      u32* __restrict__ words) {
+                                                      u32* __restrict__ words, float* err) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeGeneral) return;
@@ -270,7 +311,10 @@ __global__ __launch_bounds__(kBlock) void k_emit_rows(const float* __restrict__ 
         const int i = 4 * j + e;
         if ((sel >> i) & 1u) {
           const u32 n = (u32)(v0 + (u64)j * (kBlock * 4) + e);
-          if (o < K) out[o] = (n << 1) | (r.b[i] >> 31);  // o < K by construction; guards a racing writer of grads
+          if (o < K) {  // o < K by construction; guards a racing writer of grads
+            out[o] = (n << 1) | (r.b[i] >> 31);
+            if (err) err[(size_t)m * N + n] = 0.0f;
+          }
           ++o;
         }
       }
@@ -290,9 +334,11 @@ __device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
 }
 
 // Histogram of one radix level over the sample of each row (gathered straight from the row).
+// With a memory (`err` non-NULL) the sampled value is g~ + eta * e.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
-                                                        u32* __restrict__ hist, u32 n_units, u64 unit_stride) {
+__global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict__ grads, const float* __restrict__ err, float eta, u64 N,
+                                                        const RowState* __restrict__ rs, u32* __restrict__ hist, u32 n_units,
+                                                        u64 unit_stride) {
   constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int SH = digit_shift(LEVEL);
   const u32 m = blockIdx.y;
@@ -302,11 +348,15 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
   for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
   __syncthreads();
   const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
+  const u32* erow = err ? reinterpret_cast<const u32*>(err + (size_t)m * N) : nullptr;
   const u32 n_samples = n_units * kSampleUnit;
 #pragma unroll 4
   for (u32 i = blockIdx.x * kSamplePerBlock + threadIdx.x; i < (blockIdx.x + 1) * kSamplePerBlock && i < n_samples; i += kBlock) {
     const u32 u = i / kSampleUnit, e = i % kSampleUnit;
-    const u32 key = row[sample_unit_start(u, unit_stride) + e] & 0x7FFFFFFFu;
+    const u64 pos = sample_unit_start(u, unit_stride) + e;
+    u32 bits = row[pos];
+    if (erow) bits = compensate_bits(bits, erow[pos], eta);
+    const u32 key = bits & 0x7FFFFFFFu;
     if (LEVEL == 0 || (key >> (SH + digit_bits(LEVEL))) == st.prefix) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
   }
   __syncthreads();
@@ -397,6 +447,23 @@ __device__ __forceinline__ void load_filter_tile(const u32* __restrict__ rowv, u
   }
 }
 
+// Writes a wave tile back over the row it was loaded from (the memory row receiving g).
+template <bool INTERIOR>
+__device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 tile, u32 lane, const TileRegs& r) {
+  const u64 vbase = (u64)tile * kWaveTile;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    u32* p = rowv + vbase + (u64)j * 256 + (u64)lane * 4;
+    if (INTERIOR || ((r.valid >> (4 * j)) & 0xFu) == 0xFu) {
+      store_stream16(p, r.b[4 * j], r.b[4 * j + 1], r.b[4 * j + 2], r.b[4 * j + 3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if ((r.valid >> (4 * j + e)) & 1u) p[e] = r.b[4 * j + e];
+    }
+  }
+}
+
 template <bool INTERIOR>
 __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, u64* stage,
                                             u64* entries, u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, FilterWave& w) {
@@ -450,10 +517,13 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
   if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane);
 }
 
-__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs,
-                                                   u32* __restrict__ hist, uint2* __restrict__ cand, u32 cand_stride,
-                                                   u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride, u32 tiles_per_wave,
-                                                   u32* __restrict__ status) {
+// EC: the row is g = grads + eta * err, and g is written over err tile by tile as it is filtered
+// (grads and err rows start at the same 16-byte phase, checked by the caller).
+template <bool EC>
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
+                                                   RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
+                                                   u32 cand_stride, u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
+                                                   u32 tiles_per_wave, u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
@@ -465,6 +535,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
+  u32* errv = EC ? reinterpret_cast<u32*>(err + (size_t)m * N) - a : nullptr;
   const u64 vend = N + a;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
@@ -478,16 +549,34 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u32 first = a ? 1u : 0u;
   const u32 last = (u32)(vend / kWaveTile);  // tiles below this index end inside the row
   // Software pipeline: the loads of tile t+1 are in flight while tile t is processed.
-  TileRegs nxt;
+  TileRegs nxt, nxe;
   if (t0 < t1) {
-    if (t0 >= first && t0 < last) load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
-    else load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
+    if (t0 >= first && t0 < last) {
+      load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
+      if (EC) load_filter_tile<true>(errv, a, vend, t0, lane, nxe);
+    } else {
+      load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
+      if (EC) load_filter_tile<false>(errv, a, vend, t0, lane, nxe);
+    }
   }
   for (u32 tile = t0; tile < t1; ++tile) {
-    const TileRegs r = nxt;
+    TileRegs r = nxt;
+    TileRegs re;
+    if (EC) re = nxe;
     if (tile + 1 < t1) {
-      if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
-      else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
+      if (tile + 1 >= first && tile + 1 < last) {
+        load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
+        if (EC) load_filter_tile<true>(errv, a, vend, tile + 1, lane, nxe);
+      } else {
+        load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
+        if (EC) load_filter_tile<false>(errv, a, vend, tile + 1, lane, nxe);
+      }
+    }
+    if (EC) {
+#pragma unroll
+      for (int i = 0; i < kLoads * 4; ++i) r.b[i] = compensate_bits(r.b[i], re.b[i], eta);
+      if (tile >= first && tile < last) store_filter_tile<true>(errv, tile, lane, r);
+      else store_filter_tile<false>(errv, tile, lane, r);
     }
     const u32 slot = (tile - t0) & (u32)(kEntryStage - 1);
     if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, w);
@@ -581,11 +670,13 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                       const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
-                                                      const u64* __restrict__ blk_sum, u32 blk_stride, u64 K, u32* __restrict__ words) {
+                                                      const u64* __restrict__ blk_sum, u32 blk_stride, u64 K, u32* __restrict__ words,
+                                                      float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u64 lds[kWaves];
+  float* erow = err ? err + (size_t)m * N : nullptr;  // memory row: +0.0 goes over every entry whose sign is sent
   const TileGroup<G> g;
   const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
   const u32 cnt = (u32)c;
@@ -606,7 +697,10 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
       bool sel = key > st.T;
       if (key == st.T) { sel = eq_seen < st.q; ++eq_seen; }
       if (sel) {
-        if (o < K) out[o] = (cd.x << 1) | (cd.y >> 31);  // o < K by construction
+        if (o < K) {  // o < K by construction
+          out[o] = (cd.x << 1) | (cd.y >> 31);
+          if (erow) erow[cd.x] = 0.0f;
+        }
         ++o;
       }
     }
@@ -630,7 +724,10 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
       const u32 sel_bits = (u32)(ballot(sel) >> gshift) & gmask;
       if (sel) {
         const u32 pos = o + __popc(sel_bits & below);
-        if (pos < K) out[pos] = (cd.x << 1) | (cd.y >> 31);  // pos < K by construction
+        if (pos < K) {  // pos < K by construction
+          out[pos] = (cd.x << 1) | (cd.y >> 31);
+          if (erow) erow[cd.x] = 0.0f;
+        }
       }
       o += __popc(sel_bits);
       eq_seen += __popc(eq_bits);
@@ -665,10 +762,12 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
   return gx < 1 ? 1 : gx;
 }
 
-u32 resident_stream_blocks(int device) {
+u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0) != hipSuccess || per_cu <= 0) per_cu = 4;
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<true>, kBlock, 0)
+                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
+  if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   u32 n = (u32)cus * (u32)per_cu;
   if (const char* e = getenv("S3GD_STREAM_BLOCKS")) {  // tuning knob for experiments
     const long v = atol(e);
@@ -720,31 +819,46 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
   return (u64)M_max * ((u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlab;
 }
 
-hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
-                         hipStream_t s) {
+// `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
+// g = grads + eta * err, and on return err holds the new memory g - TopK(g).
+hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
+                         u32* counts, hipStream_t s) {
+  Profiler& P = *ws.prof;
+#define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
+  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, err ? ws.stream_blocks_mem : ws.stream_blocks);
+  if (err && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
+    const u64 total = (u64)M * N;
+    const u32 head = (u32)((4 - ((reinterpret_cast<uintptr_t>(err) >> 2) & 3u)) & 3u);
+    u64 blocks = (total / 4 + kBlock - 1) / kBlock;
+    if (blocks > ws.stream_blocks_mem) blocks = ws.stream_blocks_mem;
+    if (blocks < 1) blocks = 1;
+    S3GD_LAUNCH(KID_COMPENSATE, (k_compensate<<<(u32)blocks, kBlock, 0, s>>>(grads, err, eta, total, head)));
+  }
   if (K == 0) {
     k_zero_counts<<<(M + 255) / 256, 256, 0, s>>>(counts, M);
     return hipGetLastError();
   }
-  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, ws.stream_blocks);
+  const float* src = err ? err : grads;  // what the general route reads: with a memory, g sits in err by then
   const u32 n_tiles = p.n_tiles;
   const u32 stride = tile_stride(N);
   const dim3 grid(p.gx, M);
   const u32 k32 = (u32)K;
-  Profiler& P = *ws.prof;
-#define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
                                                                          p.candidates ? kModeCandidates : kModeGeneral)));
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles, wstride = wt_stride(N);
     const u32 bstride = blk_stride(N);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride,
-                                                              p.tiles_per_wave, ws.status)));
+    if (err)
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
+                                                                         ws.chunk, n_wt, wstride, p.tiles_per_wave, ws.status)));
+    else
+      S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, nullptr, 0.0f, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
+                                                                      ws.chunk, n_wt, wstride, p.tiles_per_wave, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     // lanes per tile in the candidate kernels, from the expected candidates per tile
     const double per_tile = p.bound / (double)n_wt;
@@ -761,19 +875,19 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, 
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     S3GD_CAND(KID_CAND_SELECT, k_cand_count, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride);
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.blk_sum, n_blk, bstride, ws.rs, kModeCandidates)));
-    S3GD_CAND(KID_CAND_EMIT, k_cand_emit, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride, K, words);
+    S3GD_CAND(KID_CAND_EMIT, k_cand_emit, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride, K, words, err, N);
 #undef S3GD_CAND
   }
   // General route: every kernel returns at once for rows the candidate route has served.
-  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
   S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
   S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, n_tiles, ws.status)));
+  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
   S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
+  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
   S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, kModeGeneral)));
-  S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words)));
+  S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words, err)));
   u32 fx = (u32)((K + 4095) / 4096);
   if (fx > 64) fx = 64;
   S3GD_LAUNCH(KID_FINISH, (k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status)));

@@ -19,6 +19,7 @@ enum KernelId : int {
   KID_HIST0, KID_HIST1, KID_HIST2, KID_RESOLVE, KID_TILE_COUNT, KID_SCAN_TILES, KID_EMIT, KID_FINISH,
   KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
+  KID_COMPENSATE, KID_FILTER_MEM,
   KID_COUNT
 };
 
@@ -49,6 +50,7 @@ struct Workspace {
   uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
   u64 cand_pool;  // entries of `cand`
   u32 stream_blocks;  // blocks of a streaming launch = blocks resident on the device at once (one round, no tail)
+  u32 stream_blocks_mem;  // the same for the filter pass that also carries the error-compensation memory
 };
 
 // What one encode call launches; a pure function of the shapes and the pool size.
@@ -63,11 +65,11 @@ struct EncodePlan {
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
 EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks);
-u32 resident_stream_blocks(int device);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
+u32 resident_stream_blocks(int device, bool with_memory);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 
-hipError_t launch_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u32* words, u32* counts,
-                         hipStream_t s);
+hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
+                         u32* counts, hipStream_t s);
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);

@@ -20,10 +20,10 @@ N_LIMIT = (1 << 31) - 2
 
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
-    "s3gd_apply_update", "s3gd_step", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
+    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
-PROFILE_KERNELS = 17
+PROFILE_KERNELS = 19
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -45,6 +45,10 @@ _lib.s3gd_apply_update.restype = _int
 _lib.s3gd_apply_update.argtypes = [_vp, _vp, _vp, _f32, _u64, _vp]
 _lib.s3gd_step.restype = _int
 _lib.s3gd_step.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.s3gd_topk_sign_encode_ec.restype = _int
+_lib.s3gd_topk_sign_encode_ec.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_step_ec.restype = _int
+_lib.s3gd_step_ec.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
 _lib.s3gd_last_async_status.restype = _int
 _lib.s3gd_last_async_status.argtypes = [_vp, _vp]
 _lib.s3gd_last_encode_info.restype = _int
@@ -147,6 +151,27 @@ class Context:
         M, N = grads.shape
         self._check(_lib.s3gd_step(self._h, _ptr(grads), M, N, K, _ptr(x), float(lr), _ptr(words), _ptr(counts),
                                    _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step")
+        return x
+
+    # -- the same with the error-compensation memory ------------------------------------------
+    def topk_sign_encode_ec(self, grads: torch.Tensor, err: torch.Tensor, eta: float, K: int,
+                            words: torch.Tensor | None = None, counts: torch.Tensor | None = None, stream=None):
+        """Encodes g = grads + eta * err and leaves the new memory g - TopK(g) in err."""
+        M, N = grads.shape
+        if words is None:
+            words = torch.empty((M, K), dtype=torch.int32, device=grads.device)
+        if counts is None:
+            counts = torch.empty((M,), dtype=torch.int32, device=grads.device)
+        self._check(_lib.s3gd_topk_sign_encode_ec(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(words),
+                                                  _ptr(counts), _stream(stream)), "s3gd_topk_sign_encode_ec")
+        return words, counts
+
+    def step_ec(self, grads: torch.Tensor, err: torch.Tensor, eta: float, K: int, x: torch.Tensor, lr: float,
+                words: torch.Tensor, counts: torch.Tensor, tally: torch.Tensor | None = None,
+                votes: torch.Tensor | None = None, stream=None):
+        M, N = grads.shape
+        self._check(_lib.s3gd_step_ec(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), float(lr),
+                                      _ptr(words), _ptr(counts), _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step_ec")
         return x
 
     # -- diagnostics ---------------------------------------------------------------------------

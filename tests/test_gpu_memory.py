@@ -1,0 +1,218 @@
+"""Error-compensation memory on the HIP path vs the CPU oracle (Algorithm 1 with the two memory
+lines): words, counts, the new memory, tally, votes and parameters, bit for bit.  Tolerance 0: the
+compensation is one rounded product and one rounded sum on both sides, everything else is
+integer work or the exact x -/+ lr."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s3gd_oracle as O
+from paper_2302_07475_amd import datagen
+from tests.helpers import assert_same
+
+pytestmark = pytest.mark.gpu
+
+KEYS = ("words", "counts", "err", "tally", "votes", "x")
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(64, 1 << 21, 1 << 21, device=0)
+    yield c
+    c.close()
+
+
+def gpu_step_ec(ctx, Gt, E, eta, K, x0, lr, fused, dense_outputs=True, gt_dev=None, e_dev=None):
+    dev = torch.device("cuda:0")
+    M, N = Gt.shape
+    g = torch.from_numpy(np.ascontiguousarray(Gt)).to(dev) if gt_dev is None else gt_dev
+    e = torch.from_numpy(np.ascontiguousarray(E).copy()).to(dev) if e_dev is None else e_dev
+    x = torch.from_numpy(np.ascontiguousarray(x0).copy()).to(dev)
+    words = torch.full((M, K), 0x55555555, dtype=torch.int32, device=dev)
+    counts = torch.full((M,), 0x55555555, dtype=torch.int32, device=dev)
+    tally = votes = None
+    if dense_outputs:
+        tally = torch.full((N,), 0x55555555, dtype=torch.int32, device=dev)
+        votes = torch.full((N,), 0x55, dtype=torch.int8, device=dev)
+    if fused:
+        ctx.step_ec(g, e, eta, K, x, float(lr), words, counts, tally, votes)
+    else:
+        ctx.topk_sign_encode_ec(g, e, eta, K, words, counts)
+        ctx.majority_vote(words, counts, N, tally, votes)
+        ctx.apply_update(x, votes, float(lr))
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    out = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+               err=e.cpu().numpy(), x=x.cpu().numpy(), g_dev=g)
+    if dense_outputs:
+        out["tally"] = tally.cpu().numpy()
+        out["votes"] = votes.cpu().numpy()
+    return out
+
+
+SCALED = [
+    datagen.C1,
+    datagen.C2.scaled(M=4, N=60_001, K=600),
+    datagen.C3.scaled(M=5, N=50_002, K=50, steps=3),
+    datagen.C4.scaled(M=3, N=40_003, K=400),
+    datagen.C5.scaled(M=4, N=270_001, K=270),       # candidate route, odd N
+    datagen.C2.scaled(M=16, N=300_000, K=3_000),    # candidate route
+    datagen.C4.scaled(M=8, N=1_000_000, K=10_000),  # candidate route with ties at the threshold
+]
+
+
+@pytest.mark.parametrize("cfg", SCALED, ids=lambda c: f"{c.name}-M{c.M}-N{c.N}-K{c.K}")
+@pytest.mark.parametrize("eta", [1.0, 0.5])
+def test_iterations_with_memory_match_oracle(ctx, cfg, eta):
+    """Three iterations of Algorithm 1 with the memory and the parameters carried along."""
+    x = datagen.params(cfg)
+    lr = datagen.lr32(cfg)
+    E = np.zeros((cfg.M, cfg.N), dtype=np.float32)  # e^0 = 0
+    for t in range(3):
+        Gt = datagen.gradients(cfg, step=t)
+        want = O.step_with_memory(Gt, E, eta, cfg.K, x, lr)
+        got = gpu_step_ec(ctx, Gt, E, eta, cfg.K, x, lr, fused=bool(t & 1))
+        assert_same(got, want, keys=KEYS, what=f"{cfg.name} eta={eta} iteration {t}")
+        assert np.array_equal(got["g_dev"].cpu().numpy().view(np.uint32), Gt.view(np.uint32)), "fresh gradients untouched"
+        E, x = want["err"], want["x"]
+
+
+def test_eta_zero_is_the_memoryless_encode(ctx):
+    cfg = SCALED[5]
+    Gt = datagen.gradients(cfg)
+    E = (np.random.default_rng(1).standard_normal(Gt.shape) * 100).astype(np.float32)  # must be ignored
+    x = datagen.params(cfg)
+    want = O.step(Gt, cfg.K, x, 1e-3)
+    got = gpu_step_ec(ctx, Gt, E, 0.0, cfg.K, x, 1e-3, fused=True)
+    assert_same(got, want, keys=("words", "counts", "tally", "votes", "x"), what="eta=0")
+    assert_same(got, dict(err=O.residual(O.compensate(Gt, E, 0.0), want["words"], want["counts"])), keys=("err",), what="eta=0 err")
+
+
+def test_sparse_fused_step_with_memory(ctx):
+    for cfg in (SCALED[1], SCALED[4], SCALED[6]):
+        Gt = datagen.gradients(cfg)
+        E = datagen.gradients(cfg, step=7) * np.float32(0.25)
+        x = datagen.params(cfg)
+        want = O.step_with_memory(Gt, E, 1.0, cfg.K, x, 1e-3)
+        got = gpu_step_ec(ctx, Gt, E, 1.0, cfg.K, x, 1e-3, fused=True, dense_outputs=False)
+        assert_same(got, want, keys=("words", "counts", "err", "x"), what=cfg.name)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 63, 64, 65, 1023, 1024, 1025, 4095, 4096, 4097, 8193, 12289, 131_073, 140_001])
+def test_ragged_sizes_every_alignment(ctx, N):
+    """Odd N puts the five rows at different 16-byte phases; the last two sizes take the filter pass."""
+    rng = np.random.default_rng(N)
+    M = 5
+    Gt = (np.rint(rng.standard_normal((M, N)) * 8) / 8).astype(np.float32)
+    E = (np.rint(rng.standard_normal((M, N)) * 4) / 16).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    for K in sorted({0, 1, min(N, 7), N // 200, N // 2, N}):
+        want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+        got = gpu_step_ec(ctx, Gt, E, 1.0, K, x, 1e-3, fused=False)
+        assert_same(got, want, keys=KEYS, what=f"N={N} K={K}")
+
+
+def test_unaligned_base_pointers_same_phase(ctx, lib):
+    rng = np.random.default_rng(19)
+    M, N, K = 3, 150_001, 1_500
+    for off in (1, 2, 3):
+        fg = rng.standard_normal(M * N + 4).astype(np.float32)
+        fe = rng.standard_normal(M * N + 4).astype(np.float32)
+        bg, be = torch.from_numpy(fg).cuda(), torch.from_numpy(fe).cuda()
+        gt_dev = bg[off:off + M * N].view(M, N)
+        e_dev = be[off:off + M * N].view(M, N)
+        Gt = fg[off:off + M * N].reshape(M, N)
+        E = fe[off:off + M * N].reshape(M, N)
+        x = rng.standard_normal(N).astype(np.float32)
+        want = O.step_with_memory(np.ascontiguousarray(Gt), np.ascontiguousarray(E), 1.0, K, x, 1e-3)
+        got = gpu_step_ec(ctx, Gt, E, 1.0, K, x, 1e-3, fused=True, gt_dev=gt_dev, e_dev=e_dev)
+        assert_same(got, want, keys=KEYS, what=f"offset {off}")
+        # elements around the views are not touched
+        back = be.cpu().numpy()
+        assert np.array_equal(back[:off].view(np.uint32), fe[:off].view(np.uint32))
+        assert np.array_equal(back[off + M * N:].view(np.uint32), fe[off + M * N:].view(np.uint32))
+        # another phase than the gradients is an argument error
+        other = be[(off + 1) % 4:(off + 1) % 4 + M * N].view(M, N)
+        w = torch.zeros((M, K), dtype=torch.int32, device="cuda")
+        c = torch.zeros((M,), dtype=torch.int32, device="cuda")
+        with pytest.raises(lib.S3GDError):
+            ctx.topk_sign_encode_ec(gt_dev, other, 1.0, K, w, c)
+
+
+def test_rows_fall_back_independently_with_memory(ctx):
+    """Rows whose candidate checks fail are served by the general route reading g from the memory."""
+    rng = np.random.default_rng(5)
+    N, K = 500_000, 5_000
+    Gt = np.empty((4, N), dtype=np.float32)
+    Gt[0] = rng.standard_normal(N)
+    Gt[1] = -2.0
+    Gt[2] = np.where(rng.random(N) < 0.001, rng.standard_normal(N), 0.0)
+    Gt[3] = rng.choice([1.0, -1.0, 3.0], N, p=[0.5, 0.495, 0.005])
+    E = np.zeros_like(Gt)
+    E[0] = rng.standard_normal(N) * 0.1
+    E[3] = rng.choice([0.0, 1.0], N)  # g takes the values 1, -1, 3, 2, 0, 4
+    x = rng.standard_normal(N).astype(np.float32)
+    want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+    got = gpu_step_ec(ctx, Gt, E, 1.0, K, x, 1e-3, fused=True)
+    assert_same(got, want, keys=KEYS, what="fallback rows")
+    assert ctx.last_encode_info()[1] == 3
+
+
+def test_special_values(ctx):
+    """Denormals stay denormal in g~ + eta * e; -0.0 and +0.0; infinities are selected and replaced
+    by +0.0 in the memory; selected zeros keep their bits."""
+    rng = np.random.default_rng(3)
+    N = 9000
+    tiny = np.float32(1e-45)
+    Gt = np.stack([
+        rng.integers(-50, 50, N).astype(np.float32) * tiny,
+        np.where(rng.random(N) < 0.01, rng.standard_normal(N), rng.choice([0.0, -0.0], N)).astype(np.float32),
+        np.where(rng.random(N) < 0.002, np.inf, rng.standard_normal(N)).astype(np.float32) * rng.choice([1, -1], N).astype(np.float32),
+        (rng.standard_normal(N) * 10.0 ** rng.integers(-30, 30, N)).astype(np.float32),
+    ])
+    E = np.stack([
+        rng.integers(-50, 50, N).astype(np.float32) * tiny,
+        rng.choice([0.0, -0.0], N).astype(np.float32),
+        rng.standard_normal(N).astype(np.float32),
+        (rng.standard_normal(N) * 10.0 ** rng.integers(-30, 30, N)).astype(np.float32),
+    ])
+    x = rng.standard_normal(N).astype(np.float32)
+    for eta in (1.0, 0.3):
+        for K in (1, 64, 100, 4500, N):
+            want = O.step_with_memory(Gt, E, eta, K, x, 0.25)
+            got = gpu_step_ec(ctx, Gt, E, eta, K, x, 0.25, fused=(K % 2 == 0))
+            assert_same(got, want, keys=KEYS, what=f"eta={eta} K={K}")
+
+
+def test_nan_from_inf_minus_inf_is_reported(ctx, lib):
+    Gt = np.ones((2, 200_000), dtype=np.float32)
+    E = np.zeros_like(Gt)
+    Gt[1, 123_456] = np.inf
+    E[1, 123_456] = -np.inf
+    g, e = torch.from_numpy(Gt).cuda(), torch.from_numpy(E).cuda()
+    ctx.topk_sign_encode_ec(g, e, 1.0, 100)
+    assert ctx.last_async_status() == lib.E_NAN
+
+
+def test_argument_errors(ctx, lib):
+    dev = torch.device("cuda:0")
+    g = torch.zeros((2, 100), dtype=torch.float32, device=dev)
+    e = torch.zeros((2, 100), dtype=torch.float32, device=dev)
+    w = torch.zeros((2, 10), dtype=torch.int32, device=dev)
+    c = torch.zeros((2,), dtype=torch.int32, device=dev)
+    x = torch.zeros((100,), dtype=torch.float32, device=dev)
+    r, h = lib.raw, ctx._h
+    p = lambda z: ctypes.c_void_p(z.data_ptr())
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), None, 1.0, 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode_ec(h, None, p(e), 1.0, 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), p(e), -0.5, 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), p(e), float("nan"), 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), p(e), float("inf"), 2, 100, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), p(g), 1.0, 2, 100, 10, p(w), p(c), None) == lib.E_INVAL  # overlap
+    assert r.s3gd_topk_sign_encode_ec(h, p(g), ctypes.c_void_p(e.data_ptr() + 4), 1.0, 2, 90, 10, p(w), p(c), None) == lib.E_INVAL
+    assert r.s3gd_step_ec(h, p(g), p(e), 1.0, 2, 100, 10, None, 0.1, p(w), p(c), None, None, None) == lib.E_INVAL
+    assert r.s3gd_step_ec(h, p(g), p(e), 1.0, 2, 100, 101, p(x), 0.1, p(w), p(c), None, None, None) == lib.E_INVAL
+    torch.cuda.synchronize()
+    assert int(w.abs().sum()) == 0 and int(c.abs().sum()) == 0 and float(e.abs().sum()) == 0.0
