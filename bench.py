@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--three-calls", action="store_true", help="time encode, vote, update as separate calls")
+    ap.add_argument("--memory", action="store_true",
+                    help="time s3gd_step_ec: the step with the error-compensation memory (eta = 1), a second "
+                         "[M, N] fp32 tensor read and rewritten every step (not the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run three plain device copies of this size; run it under "
@@ -101,9 +104,12 @@ def main():
     tally = votes = None
     if args.three_calls:
         votes = torch.empty((N,), dtype=torch.int8, device=dev)
+    err = torch.zeros((M, N), dtype=torch.float32, device=dev) if args.memory else None
 
     def one_step():
-        if args.three_calls:
+        if args.memory:
+            ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
+        elif args.three_calls:
             ctx.topk_sign_encode(g, K, words, counts)
             ctx.majority_vote(words, counts, N, None, votes)
             ctx.apply_update(x, votes, lr)
@@ -131,13 +137,18 @@ def main():
     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
         log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}")
     dom = max(kern, key=lambda k: kern[k]["ms_avg"])
-    if dom in FULL_READ_KERNELS:
+    if dom == "filter_mem":  # reads g~ and e, writes the new memory
+        alg_bytes = 12.0 * M * N
+    elif dom in FULL_READ_KERNELS:
         alg_bytes = 4.0 * M * N
     else:  # the vote kernel dominates only when the gradient passes are cheaper than it
         alg_bytes = 8.0 * M * K + 8.0 * N
     achieved = alg_bytes / (kern[dom]["ms_avg"] * 1e-3)
-    floor_bytes = 4.0 * M * N + 8.0 * M * K + 8.0 * N
-    full_reads = sum(v["launches_per_step"] for k, v in kern.items() if k in FULL_READ_KERNELS)
+    per_pass = 12.0 if args.memory else 4.0  # with the memory a pass reads g~ and e and writes e
+    floor_bytes = per_pass * M * N + 8.0 * M * K + 8.0 * N
+    # the general route's kernels are always enqueued and return at once unless a row needs them
+    full_reads = sum(v["launches_per_step"] for k, v in kern.items()
+                     if k in ("filter", "filter_mem") or (k in FULL_READ_KERNELS and general_rows > 0))
     out = {
         "metric": "gradient elements/sec per S3GD-MV step (M*N/t)",
         "value": M * N / (ms_step * 1e-3),
@@ -146,16 +157,17 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
-                   "entry": "three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)",
+                   "entry": "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
+                            ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not args.three_calls else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,
-                          "step_bytes_as_built": 4.0 * M * N * full_reads + 8.0 * M * K,
-                          "f_step": (4.0 * M * N * full_reads + 8.0 * M * K) / (ms_step * 1e-3) / HBM_PEAK},
+                          "step_bytes_as_built": per_pass * M * N * full_reads + 8.0 * M * K,
+                          "f_step": (per_pass * M * N * full_reads + 8.0 * M * K) / (ms_step * 1e-3) / HBM_PEAK},
         "kernels_ms": {k: round(v["ms_avg"] * v["launches_per_step"], 5) for k, v in kern.items()},
         "paper_bits_per_step": {"s3gd_uplink": costs.s3gd_uplink(M, N, K), "s3gd_total": costs.s3gd_mv(M, N, K),
                                 "signsgd": costs.signsgd_mv(M, N), "packed_words": costs.packed_words_bits(M, K)},

@@ -131,3 +131,48 @@ def test_c3_ten_steps_parameters_carried(lib):
         del g, G_rows
         _say(f"C3 step {step}: {len(rows)} rows and all parameters checked ({time.time() - t0:.1f} s)")
     ctx.close()
+
+
+# ---------------------------------------------------------------- with the error-compensation memory
+def _memory_case(lib, cfg, iterations, eta=1.0):
+    """Full-size iterations of Algorithm 1 through s3gd_step_ec, memory and parameters carried on the
+    device.  Per row the oracle forms g = g~ + eta * e from the device's previous memory (itself
+    checked in the previous iteration), checks the message against the definition and the new
+    memory against g - TopK(g), bit for bit on every coordinate."""
+    dev = torch.device("cuda:0")
+    ctx = lib.Context(cfg.M, cfg.N, cfg.K, device=0)
+    x = torch.from_numpy(datagen.params(cfg)).to(dev)
+    e = torch.zeros((cfg.M, cfg.N), dtype=torch.float32, device=dev)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device=dev)
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device=dev)
+    t0 = time.time()
+    for it in range(iterations):
+        g, _ = datagen.to_device(cfg, step=it, want_x=False)
+        e_before = [e[m].cpu().numpy() for m in range(cfg.M)]
+        x0 = x.cpu().numpy()
+        ctx.step_ec(g, e, eta, cfg.K, x, float(datagen.lr32(cfg)), words, counts, None, None)
+        torch.cuda.synchronize()
+        assert ctx.last_async_status() == 0
+        assert ctx.last_encode_info() == (cfg.M, 0), "every row should be served by the single-pass candidate route"
+        w, c = words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32)
+        for m in range(cfg.M):
+            row = O.compensate(g[m].cpu().numpy()[None, :], e_before[m][None, :], eta)
+            e_before[m] = None
+            O.check_message_row(row[0], cfg.K, w[m], int(c[m]))
+            want = O.residual(row, w[m:m + 1], c[m:m + 1])
+            got = e[m].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want[0].view(np.uint32)), f"memory of row {m} differs"
+            del row, want, got
+            _say(f"{cfg.name} iteration {it} row {m}: message and memory checked ({time.time() - t0:.1f} s)")
+        _check_vote_and_update(cfg, w, c, x0, x)
+        _say(f"{cfg.name} iteration {it}: vote and update checked ({time.time() - t0:.1f} s)")
+        del g
+    ctx.close()
+
+
+def test_c4_with_memory_ties(lib):
+    _memory_case(lib, datagen.C4, iterations=2)
+
+
+def test_c5_with_memory(lib):
+    _memory_case(lib, datagen.C5, iterations=2)
