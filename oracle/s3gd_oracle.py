@@ -214,6 +214,32 @@ def step_with_memory(G_tilde: np.ndarray, E: np.ndarray, eta, K: int, x: np.ndar
 
 
 # ---------------------------------------------------------------------------------------------
+# Momentum variant of the update (Section 4 "Effects of optimization hyper-parameters"):
+#   v^t = mu * v^{t-1} + sgn[sum_m TopKSign(g_m^t)],   x^{t+1} = x^t - delta * v^t.
+#
+# Readings: fp32, evaluated as written with every operation rounded once: a product mu*v, a sum with
+# the vote (the vote converted exactly to -1.0, 0.0 or +1.0), a product delta*v^t, a difference.
+# v^{-1} = 0.  mu = 0 gives back eq. "s3gd" bit for bit.
+
+def momentum_update(x: np.ndarray, v: np.ndarray, votes: np.ndarray, lr, mu) -> tuple[np.ndarray, np.ndarray]:
+    """(x^{t+1}, v^t) from (x^t, v^{t-1}) and the vote of iteration t."""
+    if x.dtype != np.float32 or v.dtype != np.float32 or x.shape != v.shape:
+        raise ValueError("parameters and momentum are float32 arrays of one shape")
+    decayed = (np.float32(mu) * v).astype(np.float32)
+    v_new = (decayed + votes.astype(np.float32)).astype(np.float32)
+    move = (np.float32(lr) * v_new).astype(np.float32)
+    return (x - move).astype(np.float32), v_new
+
+
+def step_with_momentum(G: np.ndarray, K: int, x: np.ndarray, v: np.ndarray, lr, mu) -> dict:
+    """One iteration: encode and vote as in Algorithm 1, then the momentum form of the update."""
+    words, counts = topk_sign_encode(G, K)
+    tally, votes = majority_vote(words, counts, G.shape[1])
+    x_new, v_new = momentum_update(x, v, votes, lr, mu)
+    return dict(words=words, counts=counts, tally=tally, votes=votes, x=x_new, v=v_new)
+
+
+# ---------------------------------------------------------------------------------------------
 # Checks that hold at any size (used where a full sort of the row is too slow to run in a test)
 
 def check_message_row(g: np.ndarray, K: int, words: np.ndarray, count: int) -> None:

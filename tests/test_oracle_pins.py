@@ -405,3 +405,46 @@ def test_memory_selected_zero_and_negative_zero_keep_their_bits():
     assert e[0].view(np.uint32).tolist() == [0, 0x80000000, 0, 0x80000000]
     # compensation itself follows IEEE: -0.0 + eta * (+0.0) is +0.0
     assert O.compensate(g, np.zeros_like(g), 1.0)[0].view(np.uint32).tolist() == [0, 0, 0x40A00000, 0]
+
+
+# ---------------------------------------------------------------- momentum form of the update
+def test_momentum_hand_worked_geometric_series():
+    """mu = 1/2, delta = 1/4, a coordinate voted +1 at every iteration, one voted -1 once, one never:
+    v = 1, 3/2, 7/4, 15/8 (partial sums of the geometric series), x = -(1/4) * running sum of v.
+    All values are dyadic, so fp32 is exact and the expected numbers are written out by hand."""
+    x = np.zeros(3, dtype=np.float32)
+    v = np.zeros(3, dtype=np.float32)
+    seen_v, seen_x = [], []
+    for t in range(4):
+        votes = np.array([1, -1 if t == 0 else 0, 0], dtype=np.int8)
+        x, v = O.momentum_update(x, v, votes, 0.25, 0.5)
+        seen_v.append(v.tolist())
+        seen_x.append(x.tolist())
+    assert seen_v == [[1.0, -1.0, 0.0], [1.5, -0.5, 0.0], [1.75, -0.25, 0.0], [1.875, -0.125, 0.0]]
+    assert seen_x == [[-0.25, 0.25, 0.0], [-0.625, 0.375, 0.0], [-1.0625, 0.4375, 0.0], [-1.53125, 0.46875, 0.0]]
+
+
+def test_momentum_zero_is_the_plain_update_and_fp64_agrees():
+    rng = np.random.default_rng(12)
+    M, N, K = 4, 500, 40
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    x[3] = -0.0
+    v_prev = rng.standard_normal(N).astype(np.float32)  # must be forgotten when mu = 0
+    plain = O.step(G, K, x, 1e-3)
+    mom = O.step_with_momentum(G, K, x, v_prev, 1e-3, 0.0)
+    assert np.array_equal(mom["x"].view(np.uint32), plain["x"].view(np.uint32))
+    assert np.array_equal(mom["v"], plain["votes"].astype(np.float32))
+    # against the real-valued formula in fp64: three roundings of relative size 2^-24 each
+    mu, lr = 0.9, np.float32(1e-3)
+    r = O.step_with_momentum(G, K, x, v_prev, lr, mu)
+    v64 = float(np.float32(mu)) * v_prev.astype(np.float64) + r["votes"]
+    x64 = x.astype(np.float64) - float(lr) * v64
+    assert np.allclose(r["v"], v64, rtol=2 ** -22, atol=0)
+    assert np.allclose(r["x"], x64, rtol=0, atol=2 ** -22 * (np.abs(x64).max() + 1))
+    # a planted mistake (momentum added after the step instead of before) fails the series pin
+    xb, vb = np.zeros(1, np.float32), np.zeros(1, np.float32)
+    for _ in range(2):
+        xb = xb - np.float32(0.25) * vb  # wrong: uses v^{t-1}
+        vb = np.float32(0.5) * vb + np.float32(1)
+    assert xb.tolist() != [-0.625]
