@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run three plain device copies of this size; run it under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE to get the factor between counter units and bytes")
+    ap.add_argument("--momentum", action="store_true",
+                    help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (all M workers are rows of one tensor); --gpus must be 1")
@@ -106,8 +108,12 @@ def main():
         votes = torch.empty((N,), dtype=torch.int8, device=dev)
     err = torch.zeros((M, N), dtype=torch.float32, device=dev) if args.memory else None
 
+    mom = torch.zeros((N,), dtype=torch.float32, device=dev) if args.momentum else None
+
     def one_step():
-        if args.memory:
+        if args.momentum:
+            ctx.step_momentum(g, K, x, mom, lr, 0.9, words, counts, err=err, eta=1.0)
+        elif args.memory:
             ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
         elif args.three_calls:
             ctx.topk_sign_encode(g, K, words, counts)
@@ -157,12 +163,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
-                   "entry": "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
+                   "entry": ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
+                            "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory) else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,

@@ -159,6 +159,29 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
                  float* x, float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
                  s3gd_stream_t stream);
 
+/*
+ * Momentum form of the update (Section 4 "Effects of optimization hyper-parameters"):
+ *     v[n] <- fp32(fp32(mu * v[n]) + votes[n]),   x[n] <- fp32(x[n] - fp32(lr * v[n]))
+ * with the new v in the second formula; every operation is rounded once.  mu == 0 gives the same x
+ * as s3gd_apply_update, bit for bit.
+ *
+ *   x, v   dev, in/out  [N] fp32, 16-byte aligned.  v is the momentum state; zero-fill it before
+ *                       the first iteration.
+ *   votes  dev, const   [N] int8 in {-1, 0, +1}, 16-byte aligned.
+ *   lr, mu finite and >= 0.
+ */
+S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const int8_t* votes, float lr, float mu,
+                               uint64_t N, s3gd_stream_t stream);
+
+/*
+ * One whole iteration with the momentum form of the update: encode (with the error-compensation
+ * memory when err is non-NULL, exactly as s3gd_topk_sign_encode_ec; err == NULL ignores eta and
+ * encodes grads as they are), majority vote, momentum update.  The vote is not materialised.
+ */
+S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N,
+                       uint64_t K, float* x, float* v, float lr, float mu, uint32_t* words, uint32_t* counts,
+                       s3gd_stream_t stream);
+
 /* Synchronises `stream`, then returns 0, or S3GD_E_NAN if the last encode on this context saw a
  * NaN, or S3GD_E_HIP. */
 S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
@@ -176,7 +199,7 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 19
+#define S3GD_PROFILE_KERNELS 21
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);

@@ -238,6 +238,40 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
+S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const int8_t* votes, float lr, float mu, uint64_t N,
+                               s3gd_stream_t stream) {
+  if (!ctx || !x || !v || !votes || N == 0) return S3GD_E_INVAL;
+  if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (N > ctx->N_max) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr) || !(mu >= 0.0f) || isinf(mu)) return S3GD_E_INVAL;
+  if (!aligned(x, 16) || !aligned(v, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_update_momentum(ctx->ws, x, v, votes, lr, mu, N, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N, uint64_t K,
+                       float* x, float* v, float lr, float mu, uint32_t* words, uint32_t* counts, s3gd_stream_t stream) {
+  int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (err) {
+    if ((rc = check_memory_args(grads, err, eta, M, N))) return rc;
+  } else if (!grads || !aligned(grads, 4)) {
+    return S3GD_E_INVAL;
+  }
+  if (!x || !v || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr) || !(mu >= 0.0f) || isinf(mu)) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(v, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_encode(ctx->ws, grads, err, err ? eta : 0.0f, M, N, K, words, counts, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  e = launch_vote_momentum(ctx->ws, words, counts, M, N, K, x, v, lr, mu, s);  // also with K == 0: the momentum still moves x
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
 S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream) {
   if (!ctx) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
@@ -297,7 +331,7 @@ S3GD_API const char* s3gd_profile_kernel_name(int id) {
   static const char* names[KID_COUNT] = {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
       "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
-      "apply_update", "compensate", "filter_mem"};
+      "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 

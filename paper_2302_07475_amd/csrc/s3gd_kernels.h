@@ -19,7 +19,7 @@ enum KernelId : int {
   KID_HIST0, KID_HIST1, KID_HIST2, KID_RESOLVE, KID_TILE_COUNT, KID_SCAN_TILES, KID_EMIT, KID_FINISH,
   KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
-  KID_COMPENSATE, KID_FILTER_MEM,
+  KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,
   KID_COUNT
 };
 
@@ -73,5 +73,9 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);
+hipError_t launch_vote_momentum(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, float* x, float* v,
+                                float lr, float mu, hipStream_t s);
+hipError_t launch_update_momentum(const Workspace& ws, float* x, float* v, const int8_t* votes, float lr, float mu, u64 N,
+                                  hipStream_t s);
 
 }  // namespace s3gd

@@ -202,6 +202,124 @@ __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Momentum form of the update (Section 4 "Effects of optimization hyper-parameters"):
+//   v <- mu * v + vote,  x <- x - lr * v,
+// every operation rounded once in fp32 (no fused multiply-add).  Unlike the plain update this one
+// moves every coordinate whose momentum is non-zero, so v is streamed in full; x is read and both
+// are written only for groups of four coordinates that hold a vote or a non-zero momentum (a group
+// of +0.0 momenta without votes stays exactly as it is: mu * 0 + 0 = 0 and x - lr * 0 = x).
+__device__ __forceinline__ void momentum_apply(float& x, float& v, int s, float lr, float mu) {
+  v = __fadd_rn(__fmul_rn(mu, v), (float)s);
+  x = __fsub_rn(x, __fmul_rn(lr, v));
+}
+
+__device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __restrict__ v, u64 n, u64 N, const int (&s)[4],
+                                               float lr, float mu) {
+  if (n + 4 <= N) {
+    float4 vv = *reinterpret_cast<const float4*>(v + n);
+    const u32 any = __float_as_uint(vv.x) | __float_as_uint(vv.y) | __float_as_uint(vv.z) | __float_as_uint(vv.w) |
+                    (u32)(s[0] | s[1] | s[2] | s[3]);
+    if (any == 0) return;
+    float4 xv = *reinterpret_cast<const float4*>(x + n);
+    momentum_apply(xv.x, vv.x, s[0], lr, mu);
+    momentum_apply(xv.y, vv.y, s[1], lr, mu);
+    momentum_apply(xv.z, vv.z, s[2], lr, mu);
+    momentum_apply(xv.w, vv.w, s[3], lr, mu);
+    *reinterpret_cast<float4*>(v + n) = vv;
+    *reinterpret_cast<float4*>(x + n) = xv;
+  } else {
+    for (int e = 0; e < 4 && n + e < N; ++e) {
+      float xe = x[n + e], ve = v[n + e];
+      momentum_apply(xe, ve, s[e], lr, mu);
+      v[n + e] = ve;
+      x[n + e] = xe;
+    }
+  }
+}
+
+// Tally in packed LDS fields as in k_vote_sparse, then one dense sweep over the tile.
+template <int FB>
+__global__ __launch_bounds__(kBlock) void k_vote_momentum(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
+                                                          u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x,
+                                                          float* __restrict__ v, float lr, float mu) {
+  typedef VoteField<FB> F;
+  __shared__ __attribute__((aligned(16))) u32 t[kVoteWords];
+  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
+  for (u32 tile = blockIdx.x; tile < n_vt; tile += gridDim.x) {
+    const u64 base = (u64)tile * F::kTile;
+    for (int i = threadIdx.x * 4; i < kVoteWords; i += kBlock * 4) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
+    for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
+      __syncthreads();
+      load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
+      __syncthreads();
+      const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
+      vote_rows<FB, 0>(words, K, m0, rows, lo, hi, t, base, N, x, lr);
+    }
+    __syncthreads();
+    for (u32 c = threadIdx.x * 4; c < F::kTile; c += kBlock * 4) {
+      const u64 n = base + c;
+      if (n >= N) break;
+      int s[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const u32 f = (t[(c + e) / F::kPer] >> (((c + e) % F::kPer) * FB)) & (F::kFlag - 1u);
+        const int d = (int)f - (int)F::kBias;
+        s[e] = (d > 0) - (d < 0);
+      }
+      momentum_group(x, v, n, N, s, lr, mu);
+    }
+    __syncthreads();  // the sweep has read every field before they are refilled
+  }
+}
+
+// The same from a materialised vote vector.
+__global__ __launch_bounds__(kBlock) void k_apply_momentum(float* __restrict__ x, float* __restrict__ v, const int8_t* __restrict__ votes,
+                                                           float lr, float mu, u64 N) {
+  const u64 n4 = (N + 3) / 4;
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (u64)gridDim.x * blockDim.x) {
+    const u64 n = i * 4;
+    int s[4] = {0, 0, 0, 0};
+    if (n + 4 <= N) {
+      const u32 w = *reinterpret_cast<const u32*>(votes + n);
+      s[0] = (int8_t)(w & 0xFF); s[1] = (int8_t)((w >> 8) & 0xFF); s[2] = (int8_t)((w >> 16) & 0xFF); s[3] = (int8_t)(w >> 24);
+    } else {
+      for (int e = 0; e < 4 && n + e < N; ++e) s[e] = votes[n + e];
+    }
+    momentum_group(x, v, n, N, s, lr, mu);
+  }
+}
+
+hipError_t launch_vote_momentum(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, float* x, float* v,
+                                float lr, float mu, hipStream_t s) {
+  Profiler& P = *ws.prof;
+  const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
+  const u32 tile_coords = (u32)kVoteWords * (32u / fb);
+  const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);
+  const u32 stride = n_vt + 1;
+  P.begin(KID_SEG_BOUNDS, s);
+  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, tile_coords, ws.seg);
+  P.end(s);
+  const u32 g = n_vt < ws.stream_blocks ? n_vt : ws.stream_blocks;
+  P.begin(KID_VOTE_MOMENTUM, s);
+  if (fb == 8) k_vote_momentum<8><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, v, lr, mu);
+  else if (fb == 16) k_vote_momentum<16><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, v, lr, mu);
+  else k_vote_momentum<32><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, v, lr, mu);
+  P.end(s);
+  return hipGetLastError();
+}
+
+hipError_t launch_update_momentum(const Workspace& ws, float* x, float* v, const int8_t* votes, float lr, float mu, u64 N,
+                                  hipStream_t s) {
+  u64 blocks = ((N + 3) / 4 + kBlock - 1) / kBlock;
+  if (blocks > ws.stream_blocks * 4ull) blocks = ws.stream_blocks * 4ull;
+  if (blocks < 1) blocks = 1;
+  ws.prof->begin(KID_UPDATE_MOMENTUM, s);
+  k_apply_momentum<<<(u32)blocks, kBlock, 0, s>>>(x, v, votes, lr, mu, N);
+  ws.prof->end(s);
+  return hipGetLastError();
+}
+
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s) {
   Profiler& P = *ws.prof;

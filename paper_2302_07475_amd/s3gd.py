@@ -20,10 +20,11 @@ N_LIMIT = (1 << 31) - 2
 
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
-    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
+    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec",
+    "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
-PROFILE_KERNELS = 19
+PROFILE_KERNELS = 21
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -49,6 +50,10 @@ _lib.s3gd_topk_sign_encode_ec.restype = _int
 _lib.s3gd_topk_sign_encode_ec.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _vp, _vp]
 _lib.s3gd_step_ec.restype = _int
 _lib.s3gd_step_ec.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.s3gd_apply_update_momentum.restype = _int
+_lib.s3gd_apply_update_momentum.argtypes = [_vp, _vp, _vp, _vp, _f32, _f32, _u64, _vp]
+_lib.s3gd_step_momentum.restype = _int
+_lib.s3gd_step_momentum.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _vp, _f32, _f32, _vp, _vp, _vp]
 _lib.s3gd_last_async_status.restype = _int
 _lib.s3gd_last_async_status.argtypes = [_vp, _vp]
 _lib.s3gd_last_encode_info.restype = _int
@@ -173,6 +178,19 @@ class Context:
         self._check(_lib.s3gd_step_ec(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), float(lr),
                                       _ptr(words), _ptr(counts), _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step_ec")
         return x
+
+    # -- momentum form of the update -----------------------------------------------------------
+    def apply_update_momentum(self, x: torch.Tensor, v: torch.Tensor, votes: torch.Tensor, lr: float, mu: float, stream=None):
+        self._check(_lib.s3gd_apply_update_momentum(self._h, _ptr(x), _ptr(v), _ptr(votes), float(lr), float(mu), x.numel(),
+                                                    _stream(stream)), "s3gd_apply_update_momentum")
+        return x, v
+
+    def step_momentum(self, grads: torch.Tensor, K: int, x: torch.Tensor, v: torch.Tensor, lr: float, mu: float,
+                      words: torch.Tensor, counts: torch.Tensor, err: torch.Tensor | None = None, eta: float = 1.0, stream=None):
+        M, N = grads.shape
+        self._check(_lib.s3gd_step_momentum(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), _ptr(v), float(lr),
+                                            float(mu), _ptr(words), _ptr(counts), _stream(stream)), "s3gd_step_momentum")
+        return x, v
 
     # -- diagnostics ---------------------------------------------------------------------------
     def last_async_status(self, stream=None) -> int:

@@ -176,3 +176,32 @@ def test_c4_with_memory_ties(lib):
 
 def test_c5_with_memory(lib):
     _memory_case(lib, datagen.C5, iterations=2)
+
+
+def test_c5_with_momentum(lib):
+    """Two full-size iterations of s3gd_step_momentum (mu = 0.9), x and v carried on the device: one
+    row's message checked against the definition per iteration, then the vote and the momentum update
+    recomputed by the oracle from the messages and compared on every coordinate."""
+    cfg = datagen.C5
+    dev = torch.device("cuda:0")
+    ctx = lib.Context(cfg.M, cfg.N, cfg.K, device=0)
+    x = torch.from_numpy(datagen.params(cfg)).to(dev)
+    v = torch.zeros((cfg.N,), dtype=torch.float32, device=dev)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device=dev)
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device=dev)
+    t0 = time.time()
+    for it in range(2):
+        g, _ = datagen.to_device(cfg, step=it, want_x=False)
+        x0, v0 = x.cpu().numpy(), v.cpu().numpy()
+        ctx.step_momentum(g, cfg.K, x, v, float(datagen.lr32(cfg)), 0.9, words, counts)
+        torch.cuda.synchronize()
+        assert ctx.last_async_status() == 0
+        w, c = words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32)
+        O.check_message_row(g[it].cpu().numpy(), cfg.K, w[it], int(c[it]))
+        _, votes = O.majority_vote(w, c, cfg.N)
+        want_x, want_v = O.momentum_update(x0, v0, votes, datagen.lr32(cfg), 0.9)
+        assert np.array_equal(v.cpu().numpy().view(np.uint32), want_v.view(np.uint32)), "momentum differs"
+        assert np.array_equal(x.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), "parameters differ"
+        _say(f"C5 momentum iteration {it}: x and v checked on all coordinates ({time.time() - t0:.1f} s)")
+        del g
+    ctx.close()

@@ -1,0 +1,157 @@
+"""Momentum form of the update on the HIP path vs the CPU oracle, bit for bit (tolerance 0: both
+sides evaluate mu*v, + vote, lr*v, x - . with one fp32 rounding each and no fused multiply-add)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s3gd_oracle as O
+from paper_2302_07475_amd import datagen
+from tests.helpers import assert_same
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(300, 1 << 21, 1 << 21, device=0)
+    yield c
+    c.close()
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a).copy()).cuda()
+
+
+SCALED = [
+    datagen.C1,
+    datagen.C2.scaled(M=4, N=60_001, K=600),
+    datagen.C3.scaled(M=5, N=50_002, K=50),
+    datagen.C4.scaled(M=3, N=40_003, K=400),
+    datagen.C5.scaled(M=4, N=270_001, K=270),
+    datagen.C2.scaled(M=16, N=300_000, K=3_000),
+]
+
+
+@pytest.mark.parametrize("cfg", SCALED, ids=lambda c: f"{c.name}-M{c.M}-N{c.N}-K{c.K}")
+@pytest.mark.parametrize("mu", [0.9, 0.5])
+def test_iterations_with_momentum_match_oracle(ctx, cfg, mu):
+    """Four iterations, x and v carried; iterations alternate between the fused call and the
+    separate calls (encode, vote, momentum update from the materialised vote)."""
+    x = datagen.params(cfg)
+    v = np.zeros(cfg.N, dtype=np.float32)
+    lr = datagen.lr32(cfg)
+    xd, vd = _dev(x), _dev(v)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device="cuda")
+    votes = torch.empty((cfg.N,), dtype=torch.int8, device="cuda")
+    for t in range(4):
+        G = datagen.gradients(cfg, step=t)
+        want = O.step_with_momentum(G, cfg.K, x, v, lr, mu)
+        g = _dev(G)
+        if t & 1:
+            ctx.topk_sign_encode(g, cfg.K, words, counts)
+            ctx.majority_vote(words, counts, cfg.N, None, votes)
+            ctx.apply_update_momentum(xd, vd, votes, float(lr), mu)
+        else:
+            ctx.step_momentum(g, cfg.K, xd, vd, float(lr), mu, words, counts)
+        torch.cuda.synchronize()
+        got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+                   x=xd.cpu().numpy(), v=vd.cpu().numpy())
+        assert_same(got, want, keys=("words", "counts", "x", "v"), what=f"{cfg.name} mu={mu} iteration {t}")
+        x, v = want["x"], want["v"]
+
+
+def test_momentum_zero_equals_plain_step(ctx):
+    cfg = SCALED[5]
+    G = datagen.gradients(cfg)
+    x = datagen.params(cfg)
+    x[5] = -0.0
+    v_prev = np.random.default_rng(0).standard_normal(cfg.N).astype(np.float32)
+    want = O.step(G, cfg.K, x, 1e-3)
+    xd, vd = _dev(x), _dev(v_prev)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device="cuda")
+    ctx.step_momentum(_dev(G), cfg.K, xd, vd, 1e-3, 0.0, words, counts)
+    torch.cuda.synchronize()
+    assert np.array_equal(xd.cpu().numpy().view(np.uint32), want["x"].view(np.uint32))
+    assert np.array_equal(vd.cpu().numpy(), want["votes"].astype(np.float32))
+
+
+def test_momentum_with_memory_full_iteration(ctx):
+    """Algorithm 1 with memory (eta = 1) and momentum together, three iterations."""
+    cfg = SCALED[4]
+    x = datagen.params(cfg)
+    v = np.zeros(cfg.N, dtype=np.float32)
+    E = np.zeros((cfg.M, cfg.N), dtype=np.float32)
+    xd, vd, ed = _dev(x), _dev(v), _dev(E)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device="cuda")
+    for t in range(3):
+        Gt = datagen.gradients(cfg, step=t)
+        G = O.compensate(Gt, E, 1.0)
+        want = O.step_with_momentum(G, cfg.K, x, v, 1e-3, 0.9)
+        E = O.residual(G, want["words"], want["counts"])
+        ctx.step_momentum(_dev(Gt), cfg.K, xd, vd, 1e-3, 0.9, words, counts, err=ed, eta=1.0)
+        torch.cuda.synchronize()
+        got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+                   x=xd.cpu().numpy(), v=vd.cpu().numpy(), err=ed.cpu().numpy())
+        want["err"] = E
+        assert_same(got, want, keys=("words", "counts", "x", "v", "err"), what=f"iteration {t}")
+        x, v = want["x"], want["v"]
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 63, 65, 1023, 4097, 32767, 32768, 32769, 65537])
+def test_ragged_sizes_and_special_momenta(ctx, N):
+    """Tails that are not a multiple of four; momenta of -0.0, denormals and huge values; K = 0."""
+    rng = np.random.default_rng(N)
+    M = 3
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    v = np.where(rng.random(N) < 0.5, 0.0, rng.standard_normal(N)).astype(np.float32)
+    v[::7] = -0.0
+    v[::11] = np.float32(3e-45)
+    v[::13] = np.float32(1e38)
+    for K in sorted({0, 1, N // 2, N}):
+        want = O.step_with_momentum(G, K, x, v, 0.01, 0.75)
+        xd, vd = _dev(x), _dev(v)
+        counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+        w2 = torch.empty((M, K), dtype=torch.int32, device="cuda")
+        ctx.step_momentum(_dev(G), K, xd, vd, 0.01, 0.75, w2, counts)
+        torch.cuda.synchronize()
+        got = dict(x=xd.cpu().numpy(), v=vd.cpu().numpy())
+        assert_same(got, want, keys=("x", "v"), what=f"N={N} K={K}")
+
+
+@pytest.mark.parametrize("M", [64, 257])
+def test_many_workers_tally_widths(ctx, M):
+    rng = np.random.default_rng(M)
+    N, K = 40_000, 12
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    G[:, 7] = 50.0
+    G[::2, 13] = 70.0
+    G[1::2, 13] = -70.0
+    x = rng.standard_normal(N).astype(np.float32)
+    v = rng.standard_normal(N).astype(np.float32)
+    want = O.step_with_momentum(G, K, x, v, 0.5, 0.5)
+    xd, vd = _dev(x), _dev(v)
+    words = torch.empty((M, K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+    ctx.step_momentum(_dev(G), K, xd, vd, 0.5, 0.5, words, counts)
+    torch.cuda.synchronize()
+    assert_same(dict(x=xd.cpu().numpy(), v=vd.cpu().numpy()), want, keys=("x", "v"), what=f"M={M}")
+
+
+def test_argument_errors(ctx, lib):
+    x = torch.zeros(100, dtype=torch.float32, device="cuda")
+    v = torch.zeros(100, dtype=torch.float32, device="cuda")
+    votes = torch.ones(112, dtype=torch.int8, device="cuda")
+    r, h = lib.raw, ctx._h
+    p = lambda z: ctypes.c_void_p(z.data_ptr())
+    assert r.s3gd_apply_update_momentum(h, p(x), None, p(votes), 0.1, 0.9, 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), 0.1, -0.1, 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), 0.1, float("nan"), 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update_momentum(h, p(x), ctypes.c_void_p(v.data_ptr() + 4), p(votes), 0.1, 0.9, 90, None) == lib.E_INVAL
+    torch.cuda.synchronize()
+    assert float(x.abs().sum()) == 0.0 and float(v.abs().sum()) == 0.0
