@@ -64,6 +64,9 @@ extern "C" {
 #define S3GD_E_HIP (-3)   /* a HIP runtime call failed; s3gd_last_hip_error() has its code           */
 #define S3GD_E_NOMEM (-4) /* scratch allocation failed                                               */
 #define S3GD_E_NAN (-5)   /* reported by s3gd_last_async_status(): a NaN was seen in grads           */
+#define S3GD_E_FORMAT (-6)   /* reported by s3gd_last_async_status(): a packed vector did not decode */
+#define S3GD_E_CAPACITY (-7) /* reported by s3gd_last_async_status(): an output buffer of the coding */
+                             /* calls was too small for the vector it had to hold                    */
 
 #define S3GD_PAD 0xFFFFFFFFu
 #define S3GD_N_LIMIT 2147483646ull /* 2^31 - 2 */
@@ -182,8 +185,65 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
                        uint64_t K, float* x, float* v, float lr, float mu, uint32_t* words, uint32_t* counts,
                        s3gd_stream_t stream);
 
+/*
+ * Server side and update in one call, from messages that are already there (for instance after
+ * the workers' messages were gathered): the fused tail of s3gd_step.  Only the cache lines of x
+ * that hold a voted coordinate are touched.  Arguments as in s3gd_majority_vote / s3gd_apply_update.
+ */
+S3GD_API int s3gd_vote_update(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N,
+                     uint64_t K, float* x, float lr, s3gd_stream_t stream);
+
+/*
+ * Compact wire format.  The paper prices a worker's message at about K + K*log2(N/K) bits (K signs
+ * plus the support pattern; Section 2.2 "Gradient compression") and the server's answer at the
+ * same expression in the size of the voted support (Section 2.2 "Model update").  These calls
+ * convert between the 32-bit message words and an Elias-Fano code of the ascending index set plus
+ * one sign bit per entry, n*(L+2) + ((N-1) >> L) + 1 bits for n entries with L = floor(log2(N/n)):
+ * less than n*(4 + log2(N/n)).
+ *
+ * A packed vector is a sequence of 32-bit little-endian words:
+ *     word 0        n, the number of entries
+ *     word 1        L (0 when n == 0)
+ *     sign section  ceil(n/64) groups of 64 bits: bit l of group g = entry 64g+l is negative
+ *     low section   ceil(n/64)*L groups of 64 bits: group g*L+b holds bit b of the low L index
+ *                   bits of entries 64g..64g+63, one entry per bit position
+ *     high section  n + ((N-1) >> L) + 1 bits (none when n == 0), padded to a word: bit
+ *                   (index_i >> L) + i is set for the i-th entry in ascending order
+ * Unused bits of the sections are 0.  s3gd_packed_row_words(N, K) is an even number of words that
+ * holds any vector of at most K entries; words of a row past the vector's own length are left as
+ * they were.
+ *
+ *   words, counts  dev        message rows as written by s3gd_topk_sign_encode ([M, K], [M])
+ *   packed         dev        [M, row_words] uint32, 8-byte aligned; row_words even and at least
+ *                             s3gd_packed_row_words(N, K)
+ * s3gd_unpack_messages writes every slot of words (S3GD_PAD past the count).  A row that does not
+ * decode (header that does not fit N, K or row_words; more ones than entries; an index >= N)
+ * yields S3GD_E_FORMAT from s3gd_last_async_status; such a row's count is 0 or its bad entries
+ * are S3GD_PAD, and every access stays in bounds.
+ */
+S3GD_API uint64_t s3gd_packed_row_words(uint64_t N, uint64_t K);
+S3GD_API int s3gd_pack_messages(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N,
+                       uint64_t K, uint32_t* packed, uint64_t row_words, s3gd_stream_t stream);
+S3GD_API int s3gd_unpack_messages(s3gd_ctx* ctx, const uint32_t* packed, uint64_t row_words, uint32_t M, uint64_t N,
+                         uint64_t K, uint32_t* words, uint32_t* counts, s3gd_stream_t stream);
+
+/*
+ * The server's answer as one message: a word (n << 1) | (votes[n] < 0) for every n with
+ * votes[n] != 0, ascending, S3GD_PAD in the slots after them (Section 2.2: the downlink carries the
+ * voted support and its signs).  It can then be packed like a worker's message (M = 1).
+ *
+ *   votes  dev, const  [N] int8, 16-byte aligned
+ *   words  dev, out    [capacity] uint32
+ *   count  dev, out    [1] uint32: the number of non-zero votes.  If it exceeds capacity only the
+ *                      first `capacity` words are written and s3gd_last_async_status reports
+ *                      S3GD_E_CAPACITY.
+ */
+S3GD_API int s3gd_votes_to_message(s3gd_ctx* ctx, const int8_t* votes, uint64_t N, uint64_t capacity, uint32_t* words,
+                          uint32_t* count, s3gd_stream_t stream);
+
 /* Synchronises `stream`, then returns 0, or S3GD_E_NAN if the last encode on this context saw a
- * NaN, or S3GD_E_HIP. */
+ * NaN, or S3GD_E_FORMAT / S3GD_E_CAPACITY if the last coding call flagged its input, or
+ * S3GD_E_HIP. */
 S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
 
 /* Diagnostics of the last encode on this context, read back after synchronising `stream`:
@@ -199,7 +259,7 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 21
+#define S3GD_PROFILE_KERNELS 24
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);

@@ -17,8 +17,9 @@ word p // 32).  Shared with the library's interface as a format, not as code:
                   negative; unused bits are 0
     low section   G * L groups of 64 bits; group g*L + b holds bit b of (index & (2^L - 1)) of the
                   entries 64*g .. 64*g + 63, entry 64*g + l in bit l ("bit planes"); unused bits 0
-    high section  H = n + ((N - 1) >> L) + 1 bits; bit (index_i >> L) + i is 1 for the i-th entry
-                  (i = 0 .. n-1 in ascending index), all others 0; padded with 0 to a whole word
+    high section  H = n + ((N - 1) >> L) + 1 bits (H = 0 when n = 0); bit (index_i >> L) + i is 1 for
+                  the i-th entry (i = 0 .. n-1 in ascending index), all others 0; padded with 0 to a
+                  whole word
 
 This file is written from the definition of the code; the decoder recovers an entry from the
 position and rank of its 1 in the high section and never calls the encoder.
@@ -42,6 +43,8 @@ def low_bits(N: int, n: int) -> int:
 
 
 def high_bits_len(N: int, n: int) -> int:
+    if n == 0:
+        return 0  # an empty vector is its header alone
     return n + ((N - 1) >> low_bits(N, n)) + 1
 
 

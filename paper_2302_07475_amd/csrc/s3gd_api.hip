@@ -272,14 +272,74 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
+S3GD_API int s3gd_vote_update(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N, uint64_t K,
+                     float* x, float lr, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!counts || (K > 0 && !words) || !x) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16)) return S3GD_E_INVAL;
+  if (K == 0) return S3GD_OK;  // nobody votes, nothing moves
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_vote(ctx->ws, words, counts, M, N, K, nullptr, nullptr, x, lr, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API uint64_t s3gd_packed_row_words(uint64_t N, uint64_t K) {
+  if (N == 0 || N > S3GD_N_LIMIT) return 0;
+  return packed_row_capacity(N, K);
+}
+
+S3GD_API int s3gd_pack_messages(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N, uint64_t K,
+                       uint32_t* packed, uint64_t row_words, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!counts || (K > 0 && !words) || !packed) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(packed, 8)) return S3GD_E_INVAL;
+  if ((row_words & 1) || row_words < packed_row_capacity(N, K)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_pack(ctx->ws, words, counts, M, N, K, packed, row_words, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_unpack_messages(s3gd_ctx* ctx, const uint32_t* packed, uint64_t row_words, uint32_t M, uint64_t N, uint64_t K,
+                         uint32_t* words, uint32_t* counts, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!counts || (K > 0 && !words) || !packed) return S3GD_E_INVAL;
+  if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(packed, 8)) return S3GD_E_INVAL;
+  if ((row_words & 1) || row_words < 2) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_unpack(ctx->ws, packed, row_words, M, N, K, words, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_votes_to_message(s3gd_ctx* ctx, const int8_t* votes, uint64_t N, uint64_t capacity, uint32_t* words,
+                          uint32_t* count, s3gd_stream_t stream) {
+  if (!ctx || !votes || !count || (capacity > 0 && !words) || N == 0) return S3GD_E_INVAL;
+  if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (N > ctx->N_max) return S3GD_E_INVAL;
+  if (!aligned(votes, 16) || !aligned(words, 4) || !aligned(count, 4)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_votes_to_message(ctx->ws, votes, N, capacity, words, count, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
 S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream) {
   if (!ctx) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
-  u32 st[2] = {0, 0};
+  u32 st[4] = {0, 0, 0, 0};
   hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
   if (e == hipSuccess) e = hipMemcpy(st, ctx->ws.status, sizeof(st), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_fail(ctx, e);
-  return st[0] ? S3GD_E_NAN : S3GD_OK;
+  if (st[0]) return S3GD_E_NAN;
+  if (st[3] & kCodingFormat) return S3GD_E_FORMAT;
+  if (st[3] & kCodingCapacity) return S3GD_E_CAPACITY;
+  return S3GD_OK;
 }
 
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out) {
@@ -331,7 +391,8 @@ S3GD_API const char* s3gd_profile_kernel_name(int id) {
   static const char* names[KID_COUNT] = {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
       "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
-      "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum"};
+      "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum", "pack", "unpack",
+      "votes_to_message"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 
@@ -345,6 +406,8 @@ S3GD_API const char* s3gd_strerror(int code) {
     case S3GD_E_HIP: return "HIP runtime error";
     case S3GD_E_NOMEM: return "out of device memory";
     case S3GD_E_NAN: return "NaN in gradients";
+    case S3GD_E_FORMAT: return "packed vector does not decode";
+    case S3GD_E_CAPACITY: return "output buffer too small";
     default: return "unknown error";
   }
 }

@@ -11,6 +11,7 @@ inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
 inline u32 wave_tiles(u64 N) { return (u32)((N + 3 + kWaveTile - 1) / kWaveTile); }
 inline u32 wt_stride(u64 N) { return (wave_tiles(N) + 3) & ~3u; }
 inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + 15) / 16 + 1 + 3) & ~3u; }  // blocks of the candidate kernels hold >= 16 tiles
+inline u32 coding_blk_stride(u64 N) { return 2 * tile_stride(N); }  // u32 entries per row when tile_cnt serves the coding kernels
 inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
 
 // Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
@@ -20,6 +21,7 @@ enum KernelId : int {
   KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
   KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,
+  KID_PACK, KID_UNPACK, KID_VOTES_TO_MESSAGE,
   KID_COUNT
 };
 
@@ -38,12 +40,16 @@ struct Profiler {
   }
 };
 
+// bits of status[3], set by the coding kernels
+constexpr u32 kCodingFormat = 1;    // a packed vector did not decode (bad header, too many ones, index >= N)
+constexpr u32 kCodingCapacity = 2;  // an output buffer was too small for the vector
+
 struct Workspace {
   Profiler* prof;
   RowState* rs;   // [M]
-  u32* status;    // [4]: 0 = NaN seen, 1 = rows on the general path
+  u32* status;    // [4]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags
   u32* hist;      // [M][kHistBins]
-  u64* tile_cnt;  // [M][tile_stride]
+  u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][vote_tiles + 1]
   u64* chunk;     // [M][wt_stride]    candidate route: (first slot << 32) | candidates of each wave tile
   u64* blk_sum;   // [M][blk_stride]   candidate route: (eq << 32 | gt) per 256 wave tiles, scanned in place
@@ -73,6 +79,12 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);
+u64 packed_row_capacity(u64 N, u64 K);
+hipError_t launch_pack(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, u32* packed, u64 row_words,
+                       hipStream_t s);
+hipError_t launch_unpack(const Workspace& ws, const u32* packed, u64 row_words, u32 M, u64 N, u64 K, u32* words, u32* counts,
+                         hipStream_t s);
+hipError_t launch_votes_to_message(const Workspace& ws, const int8_t* votes, u64 N, u64 cap, u32* words, u32* count, hipStream_t s);
 hipError_t launch_vote_momentum(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, float* x, float* v,
                                 float lr, float mu, hipStream_t s);
 hipError_t launch_update_momentum(const Workspace& ws, float* x, float* v, const int8_t* votes, float lr, float mu, u64 N,

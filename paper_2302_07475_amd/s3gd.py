@@ -14,17 +14,18 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libs3gd.so")
 
-OK, E_INVAL, E_RANGE, E_HIP, E_NOMEM, E_NAN = 0, -1, -2, -3, -4, -5
+OK, E_INVAL, E_RANGE, E_HIP, E_NOMEM, E_NAN, E_FORMAT, E_CAPACITY = 0, -1, -2, -3, -4, -5, -6, -7
 PAD = 0xFFFFFFFF
 N_LIMIT = (1 << 31) - 2
 
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
     "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec",
-    "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
+    "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
+    "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
-PROFILE_KERNELS = 21
+PROFILE_KERNELS = 24
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -54,6 +55,16 @@ _lib.s3gd_apply_update_momentum.restype = _int
 _lib.s3gd_apply_update_momentum.argtypes = [_vp, _vp, _vp, _vp, _f32, _f32, _u64, _vp]
 _lib.s3gd_step_momentum.restype = _int
 _lib.s3gd_step_momentum.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _vp, _f32, _f32, _vp, _vp, _vp]
+_lib.s3gd_vote_update.restype = _int
+_lib.s3gd_vote_update.argtypes = [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp]
+_lib.s3gd_packed_row_words.restype = _u64
+_lib.s3gd_packed_row_words.argtypes = [_u64, _u64]
+_lib.s3gd_pack_messages.restype = _int
+_lib.s3gd_pack_messages.argtypes = [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _u64, _vp]
+_lib.s3gd_unpack_messages.restype = _int
+_lib.s3gd_unpack_messages.argtypes = [_vp, _vp, _u64, _u32, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_votes_to_message.restype = _int
+_lib.s3gd_votes_to_message.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp]
 _lib.s3gd_last_async_status.restype = _int
 _lib.s3gd_last_async_status.argtypes = [_vp, _vp]
 _lib.s3gd_last_encode_info.restype = _int
@@ -86,6 +97,11 @@ def strerror(code: int) -> str:
 
 def workspace_bytes(M_max: int, N_max: int, K_max: int) -> int:
     return int(_lib.s3gd_workspace_bytes(M_max, N_max, K_max))
+
+
+def packed_row_words(N: int, K: int) -> int:
+    """32-bit words (an even number) that hold the packed form of any message of at most K entries."""
+    return int(_lib.s3gd_packed_row_words(N, K))
 
 
 def _ptr(t: torch.Tensor | None) -> int | None:
@@ -191,6 +207,42 @@ class Context:
         self._check(_lib.s3gd_step_momentum(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), _ptr(v), float(lr),
                                             float(mu), _ptr(words), _ptr(counts), _stream(stream)), "s3gd_step_momentum")
         return x, v
+
+    # -- messages that are already there, and the compact wire format -------------------------------
+    def vote_update(self, words: torch.Tensor, counts: torch.Tensor, N: int, x: torch.Tensor, lr: float, stream=None):
+        M, K = words.shape
+        self._check(_lib.s3gd_vote_update(self._h, _ptr(words), _ptr(counts), M, N, K, _ptr(x), float(lr), _stream(stream)),
+                    "s3gd_vote_update")
+        return x
+
+    def pack_messages(self, words: torch.Tensor, counts: torch.Tensor, N: int, packed: torch.Tensor | None = None, stream=None):
+        M, K = words.shape
+        if packed is None:
+            packed = torch.empty((M, packed_row_words(N, K)), dtype=torch.int32, device=words.device)
+        self._check(_lib.s3gd_pack_messages(self._h, _ptr(words), _ptr(counts), M, N, K, _ptr(packed), packed.shape[1],
+                                            _stream(stream)), "s3gd_pack_messages")
+        return packed
+
+    def unpack_messages(self, packed: torch.Tensor, N: int, K: int, words: torch.Tensor | None = None,
+                        counts: torch.Tensor | None = None, stream=None):
+        M = packed.shape[0]
+        if words is None:
+            words = torch.empty((M, K), dtype=torch.int32, device=packed.device)
+        if counts is None:
+            counts = torch.empty((M,), dtype=torch.int32, device=packed.device)
+        self._check(_lib.s3gd_unpack_messages(self._h, _ptr(packed), packed.shape[1], M, N, K, _ptr(words), _ptr(counts),
+                                              _stream(stream)), "s3gd_unpack_messages")
+        return words, counts
+
+    def votes_to_message(self, votes: torch.Tensor, capacity: int, words: torch.Tensor | None = None,
+                         count: torch.Tensor | None = None, stream=None):
+        if words is None:
+            words = torch.empty((capacity,), dtype=torch.int32, device=votes.device)
+        if count is None:
+            count = torch.empty((1,), dtype=torch.int32, device=votes.device)
+        self._check(_lib.s3gd_votes_to_message(self._h, _ptr(votes), votes.numel(), capacity, _ptr(words), _ptr(count),
+                                               _stream(stream)), "s3gd_votes_to_message")
+        return words, count
 
     # -- diagnostics ---------------------------------------------------------------------------
     def last_async_status(self, stream=None) -> int:
