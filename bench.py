@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run three plain device copies of this size; run it under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE to get the factor between counter units and bytes")
+    ap.add_argument("--wire", action="store_true",
+                    help="time encode -> pack -> unpack -> vote+update: the step with the messages passed through the "
+                         "compact wire format, as they would be around an exchange (not the headline workload)")
     ap.add_argument("--momentum", action="store_true",
                     help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
     args = ap.parse_args()
@@ -110,8 +113,18 @@ def main():
 
     mom = torch.zeros((N,), dtype=torch.float32, device=dev) if args.momentum else None
 
+    packed = w2 = c2 = None
+    if args.wire:
+        packed = torch.empty((M, s3gd.packed_row_words(N, K)), dtype=torch.int32, device=dev)
+        w2, c2 = torch.empty_like(words), torch.empty_like(counts)
+
     def one_step():
-        if args.momentum:
+        if args.wire:
+            ctx.topk_sign_encode(g, K, words, counts)
+            ctx.pack_messages(words, counts, N, packed)
+            ctx.unpack_messages(packed, N, K, w2, c2)
+            ctx.vote_update(w2, c2, N, x, lr)
+        elif args.momentum:
             ctx.step_momentum(g, K, x, mom, lr, 0.9, words, counts, err=err, eta=1.0)
         elif args.memory:
             ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
@@ -163,13 +176,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
-                   "entry": ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
+                   "entry": "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
+                            ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
                             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum) else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum or args.wire) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,

@@ -20,7 +20,8 @@
 namespace s3gd {
 
 constexpr u32 kHeaderWords = 2;
-constexpr u32 kHighWordsPerBlock = kBlock * 4;  // 1024 words = 32768 bits of a high section per block
+constexpr int kHighPerThread = 1;                               // high-section words per thread
+constexpr u32 kHighWordsPerBlock = kBlock * kHighPerThread;      // 8192 bits of a high section per block
 
 __host__ __device__ inline u32 ef_low_bits(u64 N, u64 n) {
   if (n == 0) return 0;
@@ -143,8 +144,8 @@ __global__ __launch_bounds__(kBlock) void k_ef_count(const u32* __restrict__ pac
   for (u64 b = blockIdx.x; b * kHighWordsPerBlock < e.high_words; b += gridDim.x) {
     u32 c = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const u64 i = b * kHighWordsPerBlock + (u64)threadIdx.x * 4 + k;
+    for (int k = 0; k < kHighPerThread; ++k) {
+      const u64 i = b * kHighWordsPerBlock + (u64)threadIdx.x * kHighPerThread + k;
       if (i < e.high_words) c += __popc(high[i]);
     }
     u32 total;
@@ -193,17 +194,17 @@ __global__ __launch_bounds__(kBlock) void k_ef_decode(const u32* __restrict__ pa
   const u32* high = row + e.high_off;
   bool bad = false;
   for (u64 b = blockIdx.x; b * kHighWordsPerBlock < e.high_words; b += gridDim.x) {
-    u32 hw[4], c = 0;
-    const u64 w0 = b * kHighWordsPerBlock + (u64)threadIdx.x * 4;
+    u32 hw[kHighPerThread], c = 0;
+    const u64 w0 = b * kHighWordsPerBlock + (u64)threadIdx.x * kHighPerThread;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kHighPerThread; ++k) {
       hw[k] = w0 + k < e.high_words ? high[w0 + k] : 0u;
       c += __popc(hw[k]);
     }
     u32 total;
     u32 rank = blk[(size_t)m * blk_stride + b] + block_excl_scan<u32>(c, &total, lds);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kHighPerThread; ++k) {
       u32 bits = hw[k];
       while (bits) {
         const u32 bit = __ffs(bits) - 1;

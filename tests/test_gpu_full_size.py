@@ -13,6 +13,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import s3gd_coding as C
 from oracle import s3gd_oracle as O
 from paper_2302_07475_amd import datagen
 
@@ -204,4 +205,48 @@ def test_c5_with_momentum(lib):
         assert np.array_equal(x.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), "parameters differ"
         _say(f"C5 momentum iteration {it}: x and v checked on all coordinates ({time.time() - t0:.1f} s)")
         del g
+    ctx.close()
+
+
+def test_c5_messages_through_the_wire_format(lib):
+    """Full-size C5: encode -> pack -> unpack -> vote+update.  Every packed row equals the coding
+    oracle's bits, the unpacked words equal the encoded ones, x equals the fused step's x, and the
+    server's answer (vote -> message -> packed) equals the oracle's."""
+    cfg = datagen.C5
+    g, x = datagen.to_device(cfg)
+    x_fused = x.clone()
+    ctx = lib.Context(cfg.M, cfg.N, cfg.M * cfg.K, device=0)
+    lr = float(datagen.lr32(cfg))
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device=g.device)
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device=g.device)
+    ctx.step(g, cfg.K, x_fused, lr, words, counts, None, None)
+    packed = ctx.pack_messages(words, counts, cfg.N)
+    w2, c2 = ctx.unpack_messages(packed, cfg.N, cfg.K)
+    ctx.vote_update(w2, c2, cfg.N, x, lr)
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    assert torch.equal(w2, words) and torch.equal(c2, counts)
+    assert torch.equal(x.view(torch.int32), x_fused.view(torch.int32))
+    w, c, p = words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32), packed.cpu().numpy().view(np.uint32)
+    for m in range(cfg.M):
+        ref = C.pack_row_fast(w[m], int(c[m]), cfg.N)
+        assert np.array_equal(p[m, : ref.shape[0]], ref), f"packed row {m}"
+    _say(f"C5 uplink: {C.information_bits(cfg.N, cfg.K) / cfg.K:.2f} bits per entry packed, "
+         f"{1 + np.log2(cfg.N / cfg.K):.2f} by the paper's expression, 32 as words")
+    # downlink
+    del g
+    votes = torch.empty((cfg.N,), dtype=torch.int8, device=x.device)
+    ctx.majority_vote(words, counts, cfg.N, None, votes)
+    cap = cfg.M * cfg.K
+    vw, vc = ctx.votes_to_message(votes, cap)
+    vp = ctx.pack_messages(vw.view(1, cap), vc, cfg.N)
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    _, ovotes = O.majority_vote(w, c, cfg.N)
+    ow, on = C.votes_to_message(ovotes)
+    assert int(vc.cpu().numpy().view(np.uint32)[0]) == on
+    assert np.array_equal(vw.cpu().numpy().view(np.uint32)[:on], ow)
+    ref = C.pack_row_fast(ow, on, cfg.N)
+    assert np.array_equal(vp.cpu().numpy().view(np.uint32)[0, : ref.shape[0]], ref)
+    _say(f"C5 downlink: {on} voted coordinates, {C.information_bits(cfg.N, on)} bits packed (N = {cfg.N})")
     ctx.close()
