@@ -186,6 +186,33 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
                        s3gd_stream_t stream);
 
 /*
+ * Worker side of Algorithm 2 (Section 3.3 "Effect of the random-K sparsification"):
+ * words[m, :] = RandKSign(g_m) = sgn(RandK(g_m)) in the message format above: K coordinates drawn at
+ * random instead of the K largest; there is no error memory in this variant.
+ *
+ * The paper leaves the sampling law open.  Worker m at iteration t selects {pi(0), ..., pi(K-1)},
+ * pi a pseudo-random permutation of [0, N) keyed by (seed, t, m): exactly K distinct coordinates,
+ * each with probability K/N over the keys, independent across workers (what Assumption 4 and
+ * Lemma 3 ask for).  pi: with b = max(2, bit length of N-1) and h = ceil(b/2), a value below 4^h is
+ * split into halves of h bits and goes through 6 Feistel rounds
+ * (left, right) <- (right, left ^ (F(right ^ key_r) & (2^h - 1))), where
+ * F(z): z ^= z>>16; z *= 0x85EBCA6B; z ^= z>>13; z *= 0xC2B2AE35; z ^= z>>16 (mod 2^32),
+ * k0 = F(lo32(seed) + 0x9E3779B9*(t+1)), k1 = F(k0 ^ hi32(seed)), k2 = F(k1 ^ 0x85EBCA77*(m+1)),
+ * key_r = F(k2 + 0xC2B2AE3D*(r+1)), r = 0..5; the network is applied again while the value is >= N.
+ *
+ * Only the K selected entries of each row of grads are read.  Arguments as in
+ * s3gd_topk_sign_encode; a selected entry that is +-0 sends nothing (counts[m] < K).
+ */
+S3GD_API int s3gd_randk_sign_encode(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, uint64_t seed,
+                           uint32_t t, uint32_t* words, uint32_t* counts, s3gd_stream_t stream);
+
+/* One whole iteration of Algorithm 2: s3gd_randk_sign_encode, then the vote and the update as in
+ * s3gd_step (tally and votes nullable in the same way). */
+S3GD_API int s3gd_step_randk(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, uint64_t seed,
+                    uint32_t t, float* x, float lr, uint32_t* words, uint32_t* counts, int32_t* tally,
+                    int8_t* votes, s3gd_stream_t stream);
+
+/*
  * Server side and update in one call, from messages that are already there (for instance after
  * the workers' messages were gathered): the fused tail of s3gd_step.  Only the cache lines of x
  * that hold a voted coordinate are touched.  Arguments as in s3gd_majority_vote / s3gd_apply_update.
@@ -259,7 +286,7 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 24
+#define S3GD_PROFILE_KERNELS 25
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);

@@ -272,6 +272,38 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
+S3GD_API int s3gd_randk_sign_encode(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, uint64_t seed, uint32_t t,
+                           uint32_t* words, uint32_t* counts, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!grads || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_randk_encode(ctx->ws, grads, M, N, K, seed, t, words, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_step_randk(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, uint64_t seed, uint32_t t,
+                    float* x, float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
+                    s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!grads || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) ||
+      !aligned(votes, 16))
+    return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_randk_encode(ctx->ws, grads, M, N, K, seed, t, words, counts, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (K == 0 && !tally && !votes) return S3GD_OK;
+  e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
 S3GD_API int s3gd_vote_update(s3gd_ctx* ctx, const uint32_t* words, const uint32_t* counts, uint32_t M, uint64_t N, uint64_t K,
                      float* x, float lr, s3gd_stream_t stream) {
   const int rc = check_shape(ctx, M, N, K);
@@ -392,7 +424,7 @@ S3GD_API const char* s3gd_profile_kernel_name(int id) {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
       "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
       "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum", "pack", "unpack",
-      "votes_to_message"};
+      "votes_to_message", "randk"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 

@@ -21,7 +21,7 @@ enum KernelId : int {
   KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
   KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,
-  KID_PACK, KID_UNPACK, KID_VOTES_TO_MESSAGE,
+  KID_PACK, KID_UNPACK, KID_VOTES_TO_MESSAGE, KID_RANDK,
   KID_COUNT
 };
 
@@ -85,6 +85,8 @@ hipError_t launch_pack(const Workspace& ws, const u32* words, const u32* counts,
 hipError_t launch_unpack(const Workspace& ws, const u32* packed, u64 row_words, u32 M, u64 N, u64 K, u32* words, u32* counts,
                          hipStream_t s);
 hipError_t launch_votes_to_message(const Workspace& ws, const int8_t* votes, u64 N, u64 cap, u32* words, u32* count, hipStream_t s);
+hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u64 seed, u32 t, u32* words,
+                               u32* counts, hipStream_t s);
 hipError_t launch_vote_momentum(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, float* x, float* v,
                                 float lr, float mu, hipStream_t s);
 hipError_t launch_update_momentum(const Workspace& ws, float* x, float* v, const int8_t* votes, float lr, float mu, u64 N,

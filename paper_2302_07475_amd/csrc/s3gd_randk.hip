@@ -1,0 +1,197 @@
+// RandKSign, the worker side of Algorithm 2 (Section 3.3 "Effect of the random-K sparsification"):
+// K coordinates drawn at random instead of the K largest, their signs sent, no error memory.
+//
+// The paper leaves the sampling law open.  Here worker m at iteration t selects
+// {pi(0), ..., pi(K-1)} for a pseudo-random permutation pi of [0, N) keyed by (seed, t, m): exactly
+// K distinct coordinates, each selected with probability K/N over the keys.  pi is a counter-based
+// generator, so the work is O(K) per worker and never touches the other N - K gradient entries:
+//   - b = bit length of N - 1 (at least 2), h = ceil(b / 2); a value below 4^h is split into a
+//     left half (high h bits) and a right half (low h bits);
+//   - 6 Feistel rounds (left, right) <- (right, left ^ (F(right ^ key_r) & (2^h - 1)));
+//   - F(z): z ^= z >> 16; z *= 0x85EBCA6B; z ^= z >> 13; z *= 0xC2B2AE35; z ^= z >> 16 (mod 2^32);
+//   - k0 = F(lo32(seed) + 0x9E3779B9 (t+1)); k1 = F(k0 ^ hi32(seed)); k2 = F(k1 ^ 0x85EBCA77 (m+1));
+//     key_r = F(k2 + 0xC2B2AE3D (r+1));
+//   - the network is applied again while the value is >= N (cycle walking; it is a bijection of
+//     [0, 4^h), so the walk from a value below N comes back below N, and 4^h < 4N keeps it short).
+//
+// The message must list the selected coordinates in ascending order.  They arrive in the order of
+// the permutation, so they are bucket-sorted: a bucket is 2048 consecutive coordinates (it can hold
+// at most 2048 distinct entries, which fit the LDS of one wave whatever the data), a count pass and
+// a scan give every bucket its slot range in the row, a second pass drops each word into its
+// bucket, and one wave per bucket orders it with a bitonic network in LDS.
+#include "s3gd_common.h"
+#include "s3gd_kernels.h"
+
+namespace s3gd {
+
+// Orders the LDS accesses of the lanes of one wave: what a lane wrote before is visible to every
+// lane after (a wave executes its LDS instructions in order; the fences only bind the compiler).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr int kRounds = 6;
+constexpr u32 kBucketShift = 11;
+constexpr u32 kBucket = 1u << kBucketShift;  // coordinates per bucket
+
+struct PermKey {
+  u32 k[kRounds];
+  u32 h, mask;
+};
+
+__host__ __device__ inline u32 fmix32(u32 z) {
+  z ^= z >> 16; z *= 0x85EBCA6Bu; z ^= z >> 13; z *= 0xC2B2AE35u; z ^= z >> 16;
+  return z;
+}
+
+__device__ __forceinline__ PermKey perm_key(u64 seed, u32 t, u32 m, u64 N) {
+  PermKey p;
+  const u32 k0 = fmix32((u32)seed + 0x9E3779B9u * (t + 1u));
+  const u32 k1 = fmix32(k0 ^ (u32)(seed >> 32));
+  const u32 k2 = fmix32(k1 ^ (0x85EBCA77u * (m + 1u)));
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) p.k[r] = fmix32(k2 + 0xC2B2AE3Du * (u32)(r + 1));
+  u32 b = 64u - (u32)__clzll((unsigned long long)(N - 1) | 2ull);  // bit length of N - 1, at least 2
+  p.h = (b + 1) / 2;
+  p.mask = (1u << p.h) - 1u;  // h <= 16 because N < 2^31
+  return p;
+}
+
+__device__ __forceinline__ u32 permute(u32 i, u64 N, const PermKey& p) {
+  u32 v = i;
+  do {
+    u32 left = v >> p.h, right = v & p.mask;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const u32 nr = left ^ (fmix32(right ^ p.k[r]) & p.mask);
+      left = right;
+      right = nr;
+    }
+    v = (left << p.h) | right;
+  } while ((u64)v >= N);
+  return v;
+}
+
+__global__ void k_randk_clear(u32* __restrict__ bucket, u32 nb, u32 bstride, u32* __restrict__ status, u32 M) {
+  const u32 m = blockIdx.y;
+  for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += gridDim.x * blockDim.x) bucket[(size_t)m * bstride + i] = 0;
+  if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { status[0] = 0; status[1] = 0; status[2] = M; }
+}
+
+// SCATTER = false: count the non-zero selected entries of each bucket.
+// SCATTER = true:  bucket[] holds the first slot of each bucket; every entry takes the next slot of
+//                  its bucket (afterwards bucket[b] is the end of bucket b).
+template <bool SCATTER>
+__global__ __launch_bounds__(kBlock) void k_randk_pass(const float* __restrict__ grads, u64 N, u64 K, u64 seed, u32 t,
+                                                       u32* __restrict__ bucket, u32 bstride, u32* __restrict__ words,
+                                                       u32* __restrict__ status) {
+  const u32 m = blockIdx.y;
+  const PermKey p = perm_key(seed, t, m, N);
+  const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
+  u32* bk = bucket + (size_t)m * bstride;
+  u32* out = words + (size_t)m * K;
+  bool nan = false;
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x) {
+    const u32 n = permute((u32)i, N, p);
+    const u32 bits = row[n];
+    const u32 key = bits & 0x7FFFFFFFu;
+    if (key == 0) continue;  // sgn(0) = 0: nothing to send
+    nan |= key > 0x7F800000u;
+    if (SCATTER) {
+      const u32 pos = atomicAdd(&bk[n >> kBucketShift], 1u);
+      if ((u64)pos < K) out[pos] = (n << 1) | (bits >> 31);  // pos < K by construction
+    } else {
+      atomicAdd(&bk[n >> kBucketShift], 1u);
+    }
+  }
+  if (!SCATTER && nan) status[0] = 1;
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_randk_scan(u32* __restrict__ bucket, u32 nb, u32 bstride, u32* __restrict__ counts) {
+  __shared__ u32 lds[kScanBlock / 64];
+  u32* t = bucket + (size_t)blockIdx.x * bstride;
+  u32 carry = 0;
+  for (u32 base = 0; base < nb; base += kScanBlock) {
+    const u32 i = base + threadIdx.x;
+    const u32 v = i < nb ? t[i] : 0;
+    u32 total;
+    const u32 ex = carry + block_excl_scan<u32>(v, &total, lds);
+    if (i < nb) t[i] = ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) counts[blockIdx.x] = carry;
+}
+
+// One wave per bucket: the bucket's words (at most kBucket of them, all distinct) are ordered by a
+// bitonic network in the wave's LDS slice and written back over their slots.
+__global__ __launch_bounds__(kBlock) void k_randk_sort(const u32* __restrict__ bucket, u32 nb, u32 bstride, u64 K,
+                                                       u32* __restrict__ words) {
+  __shared__ u32 lds_all[kWaves][kBucket];
+  const u32 m = blockIdx.y;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  u32* a = lds_all[wave];
+  const u32* bk = bucket + (size_t)m * bstride;
+  u32* out = words + (size_t)m * K;
+  for (u32 b = blockIdx.x * kWaves + wave; b < nb; b += gridDim.x * kWaves) {
+    const u32 s = b ? bk[b - 1] : 0u;
+    u32 e = bk[b];
+    if ((u64)e > K) e = (u32)K;
+    if (e <= s + 1) continue;  // wave-uniform: nothing to order
+    u32 n = e - s;
+    if (n > kBucket) n = kBucket;  // cannot happen: a bucket spans kBucket coordinates
+    u32 P = 2;
+    while (P < n) P <<= 1;
+    for (u32 i = lane; i < P; i += 64) a[i] = i < n ? out[s + i] : 0xFFFFFFFFu;
+    wave_sync();
+    for (u32 k = 2; k <= P; k <<= 1) {
+      for (u32 j = k >> 1; j > 0; j >>= 1) {
+        for (u32 i = lane; i < P / 2; i += 64) {
+          // pair (lo, lo + j) of the block of size 2j that holds the i-th comparator
+          const u32 lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+          const u32 hi = lo + j;
+          const bool up = (lo & k) == 0;
+          const u32 x = a[lo], y = a[hi];
+          if ((x > y) == up) { a[lo] = y; a[hi] = x; }
+        }
+        wave_sync();
+      }
+    }
+    for (u32 i = lane; i < n; i += 64) out[s + i] = a[i];
+    wave_sync();
+  }
+}
+
+__global__ void k_randk_pad(const u32* __restrict__ counts, u64 K, u32* __restrict__ words) {
+  const u32 m = blockIdx.y;
+  u32* out = words + (size_t)m * K;
+  for (u64 i = (u64)counts[m] + (u64)blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x) out[i] = S3GD_PAD;
+}
+
+hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u64 N, u64 K, u64 seed, u32 t, u32* words,
+                               u32* counts, hipStream_t s) {
+  Profiler& P = *ws.prof;
+  u32* bucket = reinterpret_cast<u32*>(ws.tile_cnt);
+  const u32 bstride = coding_blk_stride(N);          // >= N / 2048 + 2 entries per row
+  const u32 nb = (u32)((N + kBucket - 1) >> kBucketShift);
+  u32 gk = (u32)((K + kBlock - 1) / kBlock);
+  const u32 cap = ws.stream_blocks * 2 / M ? ws.stream_blocks * 2 / M : 1;
+  if (gk > cap) gk = cap;
+  if (gk < 1) gk = 1;
+  u32 gb = (nb + kWaves - 1) / kWaves;
+  if (gb > cap) gb = cap;
+  P.begin(KID_RANDK, s);
+  k_randk_clear<<<dim3((nb + 255) / 256 < 64 ? (nb + 255) / 256 : 64, M), 256, 0, s>>>(bucket, nb, bstride, ws.status, M);
+  if (K > 0) k_randk_pass<false><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
+  k_randk_scan<<<M, kScanBlock, 0, s>>>(bucket, nb, bstride, counts);
+  if (K > 0) {
+    k_randk_pass<true><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
+    k_randk_sort<<<dim3(gb, M), kBlock, 0, s>>>(bucket, nb, bstride, K, words);
+    k_randk_pad<<<dim3(gk < 64 ? gk : 64, M), 256, 0, s>>>(counts, K, words);
+  }
+  P.end(s);
+  return hipGetLastError();
+}
+
+}  // namespace s3gd

@@ -22,10 +22,10 @@ EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
     "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
-    "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
+    "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
-PROFILE_KERNELS = 24
+PROFILE_KERNELS = 25
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -65,6 +65,10 @@ _lib.s3gd_unpack_messages.restype = _int
 _lib.s3gd_unpack_messages.argtypes = [_vp, _vp, _u64, _u32, _u64, _u64, _vp, _vp, _vp]
 _lib.s3gd_votes_to_message.restype = _int
 _lib.s3gd_votes_to_message.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_randk_sign_encode.restype = _int
+_lib.s3gd_randk_sign_encode.argtypes = [_vp, _vp, _u32, _u64, _u64, _u64, _u32, _vp, _vp, _vp]
+_lib.s3gd_step_randk.restype = _int
+_lib.s3gd_step_randk.argtypes = [_vp, _vp, _u32, _u64, _u64, _u64, _u32, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
 _lib.s3gd_last_async_status.restype = _int
 _lib.s3gd_last_async_status.argtypes = [_vp, _vp]
 _lib.s3gd_last_encode_info.restype = _int
@@ -207,6 +211,25 @@ class Context:
         self._check(_lib.s3gd_step_momentum(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), _ptr(v), float(lr),
                                             float(mu), _ptr(words), _ptr(counts), _stream(stream)), "s3gd_step_momentum")
         return x, v
+
+    # -- Algorithm 2: random-K instead of top-K ------------------------------------------------
+    def randk_sign_encode(self, grads: torch.Tensor, K: int, seed: int, t: int, words: torch.Tensor | None = None,
+                          counts: torch.Tensor | None = None, stream=None):
+        M, N = grads.shape
+        if words is None:
+            words = torch.empty((M, K), dtype=torch.int32, device=grads.device)
+        if counts is None:
+            counts = torch.empty((M,), dtype=torch.int32, device=grads.device)
+        self._check(_lib.s3gd_randk_sign_encode(self._h, _ptr(grads), M, N, K, seed, t, _ptr(words), _ptr(counts),
+                                                _stream(stream)), "s3gd_randk_sign_encode")
+        return words, counts
+
+    def step_randk(self, grads: torch.Tensor, K: int, seed: int, t: int, x: torch.Tensor, lr: float, words: torch.Tensor,
+                   counts: torch.Tensor, tally: torch.Tensor | None = None, votes: torch.Tensor | None = None, stream=None):
+        M, N = grads.shape
+        self._check(_lib.s3gd_step_randk(self._h, _ptr(grads), M, N, K, seed, t, _ptr(x), float(lr), _ptr(words),
+                                         _ptr(counts), _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step_randk")
+        return x
 
     # -- messages that are already there, and the compact wire format -------------------------------
     def vote_update(self, words: torch.Tensor, counts: torch.Tensor, N: int, x: torch.Tensor, lr: float, stream=None):
