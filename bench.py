@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--wire", action="store_true",
                     help="time encode -> pack -> unpack -> vote+update: the step with the messages passed through the "
                          "compact wire format, as they would be around an exchange (not the headline workload)")
+    ap.add_argument("--randk", action="store_true",
+                    help="time s3gd_step_randk (Algorithm 2: random-K instead of top-K; not the headline workload)")
     ap.add_argument("--momentum", action="store_true",
                     help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
     args = ap.parse_args()
@@ -118,8 +120,13 @@ def main():
         packed = torch.empty((M, s3gd.packed_row_words(N, K)), dtype=torch.int32, device=dev)
         w2, c2 = torch.empty_like(words), torch.empty_like(counts)
 
+    step_no = [0]
+
     def one_step():
-        if args.wire:
+        if args.randk:
+            ctx.step_randk(g, K, 0x5EED, step_no[0], x, lr, words, counts, None, None)
+            step_no[0] += 1
+        elif args.wire:
             ctx.topk_sign_encode(g, K, words, counts)
             ctx.pack_messages(words, counts, N, packed)
             ctx.unpack_messages(packed, N, K, w2, c2)
@@ -156,7 +163,9 @@ def main():
     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
         log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}")
     dom = max(kern, key=lambda k: kern[k]["ms_avg"])
-    if dom == "filter_mem":  # reads g~ and e, writes the new memory
+    if dom == "randk":  # K gathered gradient entries and K words per row; nothing else of G is touched
+        alg_bytes = 8.0 * M * K
+    elif dom == "filter_mem":  # reads g~ and e, writes the new memory
         alg_bytes = 12.0 * M * N
     elif dom in FULL_READ_KERNELS:
         alg_bytes = 4.0 * M * N
@@ -176,14 +185,15 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
-                   "entry": "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
+                   "entry": "s3gd_step_randk (Algorithm 2)" if args.randk else
+                            "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
                             ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
                             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum or args.wire) else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum or args.wire or args.randk) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,

@@ -18,7 +18,8 @@
 // the permutation, so they are bucket-sorted: a bucket is 2048 consecutive coordinates (it can hold
 // at most 2048 distinct entries, which fit the LDS of one wave whatever the data), a count pass and
 // a scan give every bucket its slot range in the row, a second pass drops each word into its
-// bucket, and one wave per bucket orders it with a bitonic network in LDS.
+// bucket, and each bucket is ordered in place: a handful of words by one lane in registers, more by
+// one wave with a bitonic network in LDS.
 #include "s3gd_common.h"
 #include "s3gd_kernels.h"
 
@@ -109,23 +110,72 @@ __global__ __launch_bounds__(kBlock) void k_randk_pass(const float* __restrict__
   if (!SCATTER && nan) status[0] = 1;
 }
 
-__global__ __launch_bounds__(kScanBlock) void k_randk_scan(u32* __restrict__ bucket, u32 nb, u32 bstride, u32* __restrict__ counts) {
+// Exclusive scan of a row's bucket counts in three steps, so that many blocks share the work: the
+// sum of every chunk of kScanChunk counts, a scan of those sums by one block per row (which also
+// yields counts[m]), and the scan inside each chunk started from its chunk's offset.
+constexpr int kScanPer = 8;
+constexpr u32 kScanChunk = kScanBlock * kScanPer;
+
+__device__ __forceinline__ u32 load_chunk(const u32* __restrict__ t, u32 nb, u32 i0, u32 (&v)[kScanPer]) {
+  u32 sum = 0;
+#pragma unroll
+  for (int k = 0; k < kScanPer; ++k) { v[k] = i0 + k < nb ? t[i0 + k] : 0; sum += v[k]; }
+  return sum;
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_randk_chunk_sums(const u32* __restrict__ bucket, u32 nb, u32 bstride,
+                                                                 u32* __restrict__ sums, u32 sstride) {
   __shared__ u32 lds[kScanBlock / 64];
-  u32* t = bucket + (size_t)blockIdx.x * bstride;
+  const u32 m = blockIdx.y;
+  u32 v[kScanPer], total;
+  const u32 sum = load_chunk(bucket + (size_t)m * bstride, nb, blockIdx.x * kScanChunk + threadIdx.x * kScanPer, v);
+  (void)block_excl_scan<u32>(sum, &total, lds);
+  if (threadIdx.x == 0) sums[(size_t)m * sstride + blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_randk_scan_sums(u32* __restrict__ sums, u32 n_chunks, u32 sstride,
+                                                                u32* __restrict__ counts) {
+  __shared__ u32 lds[kScanBlock / 64];
+  u32* t = sums + (size_t)blockIdx.x * sstride;
   u32 carry = 0;
-  for (u32 base = 0; base < nb; base += kScanBlock) {
+  for (u32 base = 0; base < n_chunks; base += kScanBlock) {
     const u32 i = base + threadIdx.x;
-    const u32 v = i < nb ? t[i] : 0;
+    const u32 v = i < n_chunks ? t[i] : 0;
     u32 total;
     const u32 ex = carry + block_excl_scan<u32>(v, &total, lds);
-    if (i < nb) t[i] = ex;
+    if (i < n_chunks) t[i] = ex;
     carry += total;
   }
   if (threadIdx.x == 0) counts[blockIdx.x] = carry;
 }
 
-// One wave per bucket: the bucket's words (at most kBucket of them, all distinct) are ordered by a
-// bitonic network in the wave's LDS slice and written back over their slots.
+__global__ __launch_bounds__(kScanBlock) void k_randk_scan_chunks(u32* __restrict__ bucket, u32 nb, u32 bstride,
+                                                                  const u32* __restrict__ sums, u32 sstride) {
+  __shared__ u32 lds[kScanBlock / 64];
+  const u32 m = blockIdx.y;
+  u32* t = bucket + (size_t)m * bstride;
+  const u32 i0 = blockIdx.x * kScanChunk + threadIdx.x * kScanPer;
+  u32 v[kScanPer], total;
+  const u32 sum = load_chunk(t, nb, i0, v);
+  u32 ex = sums[(size_t)m * sstride + blockIdx.x] + block_excl_scan<u32>(sum, &total, lds);
+#pragma unroll
+  for (int k = 0; k < kScanPer; ++k) {
+    if (i0 + k < nb) t[i0 + k] = ex;
+    ex += v[k];
+  }
+}
+
+// Orders every bucket's words in place.  A lane first takes a bucket of its own: buckets of up to
+// kSmall words (the common case at small K/N, where a bucket holds a handful) are ordered in
+// registers by that lane alone.  Larger ones (at most kBucket words, all distinct) are then taken
+// one after the other by the whole wave, with a bitonic network in the wave's LDS slice.
+constexpr int kSmall = 8;
+
+__device__ __forceinline__ void cmp_swap(u32& x, u32& y) {
+  const u32 lo = x < y ? x : y, hi = x < y ? y : x;
+  x = lo; y = hi;
+}
+
 __global__ __launch_bounds__(kBlock) void k_randk_sort(const u32* __restrict__ bucket, u32 nb, u32 bstride, u64 K,
                                                        u32* __restrict__ words) {
   __shared__ u32 lds_all[kWaves][kBucket];
@@ -134,32 +184,58 @@ __global__ __launch_bounds__(kBlock) void k_randk_sort(const u32* __restrict__ b
   u32* a = lds_all[wave];
   const u32* bk = bucket + (size_t)m * bstride;
   u32* out = words + (size_t)m * K;
-  for (u32 b = blockIdx.x * kWaves + wave; b < nb; b += gridDim.x * kWaves) {
-    const u32 s = b ? bk[b - 1] : 0u;
-    u32 e = bk[b];
-    if ((u64)e > K) e = (u32)K;
-    if (e <= s + 1) continue;  // wave-uniform: nothing to order
-    u32 n = e - s;
-    if (n > kBucket) n = kBucket;  // cannot happen: a bucket spans kBucket coordinates
-    u32 P = 2;
-    while (P < n) P <<= 1;
-    for (u32 i = lane; i < P; i += 64) a[i] = i < n ? out[s + i] : 0xFFFFFFFFu;
-    wave_sync();
-    for (u32 k = 2; k <= P; k <<= 1) {
-      for (u32 j = k >> 1; j > 0; j >>= 1) {
-        for (u32 i = lane; i < P / 2; i += 64) {
-          // pair (lo, lo + j) of the block of size 2j that holds the i-th comparator
-          const u32 lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
-          const u32 hi = lo + j;
-          const bool up = (lo & k) == 0;
-          const u32 x = a[lo], y = a[hi];
-          if ((x > y) == up) { a[lo] = y; a[hi] = x; }
-        }
-        wave_sync();
-      }
+  for (u32 base = (blockIdx.x * kWaves + wave) * 64; base < nb; base += gridDim.x * kWaves * 64) {
+    const u32 b = base + lane;
+    u32 s = 0, n = 0;
+    if (b < nb) {
+      s = b ? bk[b - 1] : 0u;
+      u32 e = bk[b];
+      if ((u64)e > K) e = (u32)K;
+      if ((u64)s > K) s = (u32)K;
+      n = e > s ? e - s : 0u;
     }
-    for (u32 i = lane; i < n; i += 64) out[s + i] = a[i];
-    wave_sync();
+    if (n >= 2 && n <= (u32)kSmall) {
+      u32 r[kSmall];
+#pragma unroll
+      for (int i = 0; i < kSmall; ++i) r[i] = (u32)i < n ? out[s + i] : 0xFFFFFFFFu;
+      // odd-even merge sorting network for 8 keys (19 comparators)
+      cmp_swap(r[0], r[1]); cmp_swap(r[2], r[3]); cmp_swap(r[4], r[5]); cmp_swap(r[6], r[7]);
+      cmp_swap(r[0], r[2]); cmp_swap(r[1], r[3]); cmp_swap(r[4], r[6]); cmp_swap(r[5], r[7]);
+      cmp_swap(r[1], r[2]); cmp_swap(r[5], r[6]);
+      cmp_swap(r[0], r[4]); cmp_swap(r[1], r[5]); cmp_swap(r[2], r[6]); cmp_swap(r[3], r[7]);
+      cmp_swap(r[2], r[4]); cmp_swap(r[3], r[5]);
+      cmp_swap(r[1], r[2]); cmp_swap(r[3], r[4]); cmp_swap(r[5], r[6]);
+#pragma unroll
+      for (int i = 0; i < kSmall; ++i)
+        if ((u32)i < n) out[s + i] = r[i];
+    }
+    u64 big = ballot(n > (u32)kSmall);
+    while (big) {  // wave-uniform
+      const int l = __ffsll((unsigned long long)big) - 1;
+      big &= big - 1;
+      const u32 bs = __shfl(s, l, 64);
+      u32 bn = __shfl(n, l, 64);
+      if (bn > kBucket) bn = kBucket;  // cannot happen: a bucket spans kBucket coordinates
+      u32 P = 2;
+      while (P < bn) P <<= 1;
+      for (u32 i = lane; i < P; i += 64) a[i] = i < bn ? out[bs + i] : 0xFFFFFFFFu;
+      wave_sync();
+      for (u32 k = 2; k <= P; k <<= 1) {
+        for (u32 j = k >> 1; j > 0; j >>= 1) {
+          for (u32 i = lane; i < P / 2; i += 64) {
+            // pair (lo, lo + j) of the block of size 2j that holds the i-th comparator
+            const u32 lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+            const u32 hi = lo + j;
+            const bool up = (lo & k) == 0;
+            const u32 x = a[lo], y = a[hi];
+            if ((x > y) == up) { a[lo] = y; a[hi] = x; }
+          }
+          wave_sync();
+        }
+      }
+      for (u32 i = lane; i < bn; i += 64) out[bs + i] = a[i];
+      wave_sync();
+    }
   }
 }
 
@@ -179,12 +255,17 @@ hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u
   const u32 cap = ws.stream_blocks * 2 / M ? ws.stream_blocks * 2 / M : 1;
   if (gk > cap) gk = cap;
   if (gk < 1) gk = 1;
-  u32 gb = (nb + kWaves - 1) / kWaves;
+  u32 gb = (nb + kWaves * 64 - 1) / (kWaves * 64);
   if (gb > cap) gb = cap;
   P.begin(KID_RANDK, s);
   k_randk_clear<<<dim3((nb + 255) / 256 < 64 ? (nb + 255) / 256 : 64, M), 256, 0, s>>>(bucket, nb, bstride, ws.status, M);
   if (K > 0) k_randk_pass<false><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
-  k_randk_scan<<<M, kScanBlock, 0, s>>>(bucket, nb, bstride, counts);
+  u32* sums = reinterpret_cast<u32*>(ws.blk_sum);    // [M][2 * blk_stride] as u32: far more than n_chunks entries per row
+  const u32 sstride = 2 * blk_stride(N);
+  const u32 n_chunks = (nb + kScanChunk - 1) / kScanChunk;
+  k_randk_chunk_sums<<<dim3(n_chunks, M), kScanBlock, 0, s>>>(bucket, nb, bstride, sums, sstride);
+  k_randk_scan_sums<<<M, kScanBlock, 0, s>>>(sums, n_chunks, sstride, counts);
+  k_randk_scan_chunks<<<dim3(n_chunks, M), kScanBlock, 0, s>>>(bucket, nb, bstride, sums, sstride);
   if (K > 0) {
     k_randk_pass<true><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
     k_randk_sort<<<dim3(gb, M), kBlock, 0, s>>>(bucket, nb, bstride, K, words);

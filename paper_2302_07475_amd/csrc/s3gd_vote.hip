@@ -214,29 +214,39 @@ __device__ __forceinline__ void momentum_apply(float& x, float& v, int s, float 
   x = __fsub_rn(x, __fmul_rn(lr, v));
 }
 
-__device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __restrict__ v, u64 n, u64 N, const int (&s)[4],
-                                               float lr, float mu) {
-  if (n + 4 <= N) {
-    float4 vv = *reinterpret_cast<const float4*>(v + n);
-    const u32 any = __float_as_uint(vv.x) | __float_as_uint(vv.y) | __float_as_uint(vv.z) | __float_as_uint(vv.w) |
-                    (u32)(s[0] | s[1] | s[2] | s[3]);
-    if (any == 0) return;
-    float4 xv = *reinterpret_cast<const float4*>(x + n);
-    momentum_apply(xv.x, vv.x, s[0], lr, mu);
-    momentum_apply(xv.y, vv.y, s[1], lr, mu);
-    momentum_apply(xv.z, vv.z, s[2], lr, mu);
-    momentum_apply(xv.w, vv.w, s[3], lr, mu);
-    *reinterpret_cast<float4*>(v + n) = vv;
-    *reinterpret_cast<float4*>(x + n) = xv;
-  } else {
-    for (int e = 0; e < 4 && n + e < N; ++e) {
-      float xe = x[n + e], ve = v[n + e];
-      momentum_apply(xe, ve, s[e], lr, mu);
-      v[n + e] = ve;
-      x[n + e] = xe;
-    }
+// Four consecutive coordinates whose momenta `vv` are already loaded.
+__device__ __forceinline__ void momentum_group4(float* __restrict__ x, float* __restrict__ v, u64 n, float4 vv, const int (&s)[4],
+                                                float lr, float mu) {
+  const u32 any = __float_as_uint(vv.x) | __float_as_uint(vv.y) | __float_as_uint(vv.z) | __float_as_uint(vv.w) |
+                  (u32)(s[0] | s[1] | s[2] | s[3]);
+  if (any == 0) return;
+  float4 xv = *reinterpret_cast<const float4*>(x + n);
+  momentum_apply(xv.x, vv.x, s[0], lr, mu);
+  momentum_apply(xv.y, vv.y, s[1], lr, mu);
+  momentum_apply(xv.z, vv.z, s[2], lr, mu);
+  momentum_apply(xv.w, vv.w, s[3], lr, mu);
+  *reinterpret_cast<float4*>(v + n) = vv;
+  *reinterpret_cast<float4*>(x + n) = xv;
+}
+
+// The last, partial group of the vector.
+__device__ __forceinline__ void momentum_tail(float* __restrict__ x, float* __restrict__ v, u64 n, u64 N, const int (&s)[4], float lr,
+                                              float mu) {
+  for (int e = 0; e < 4 && n + e < N; ++e) {
+    float xe = x[n + e], ve = v[n + e];
+    momentum_apply(xe, ve, s[e], lr, mu);
+    v[n + e] = ve;
+    x[n + e] = xe;
   }
 }
+
+__device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __restrict__ v, u64 n, u64 N, const int (&s)[4],
+                                               float lr, float mu) {
+  if (n + 4 <= N) momentum_group4(x, v, n, *reinterpret_cast<const float4*>(v + n), s, lr, mu);
+  else momentum_tail(x, v, n, N, s, lr, mu);
+}
+
+constexpr int kSweep = 4;  // groups of four coordinates a thread has in flight in the momentum sweep
 
 // Tally in packed LDS fields as in k_vote_sparse, then one dense sweep over the tile.
 template <int FB>
@@ -257,17 +267,29 @@ __global__ __launch_bounds__(kBlock) void k_vote_momentum(const u32* __restrict_
       vote_rows<FB, 0>(words, K, m0, rows, lo, hi, t, base, N, x, lr);
     }
     __syncthreads();
-    for (u32 c = threadIdx.x * 4; c < F::kTile; c += kBlock * 4) {
-      const u64 n = base + c;
-      if (n >= N) break;
-      int s[4];
+    // the sweep: kSweep groups of four coordinates per thread and round, their momenta loaded first
+    for (u32 c0 = threadIdx.x * 4; c0 < F::kTile; c0 += kBlock * 4 * kSweep) {
+      float4 vv[kSweep];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const u32 f = (t[(c + e) / F::kPer] >> (((c + e) % F::kPer) * FB)) & (F::kFlag - 1u);
-        const int d = (int)f - (int)F::kBias;
-        s[e] = (d > 0) - (d < 0);
+      for (int u = 0; u < kSweep; ++u) {
+        const u64 n = base + c0 + (u32)u * kBlock * 4;
+        vv[u] = (c0 + (u32)u * kBlock * 4 < F::kTile && n + 4 <= N) ? *reinterpret_cast<const float4*>(v + n) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-      momentum_group(x, v, n, N, s, lr, mu);
+#pragma unroll
+      for (int u = 0; u < kSweep; ++u) {
+        const u32 c = c0 + (u32)u * kBlock * 4;
+        const u64 n = base + c;
+        if (c >= F::kTile || n >= N) break;
+        int s[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const u32 f = (t[(c + e) / F::kPer] >> (((c + e) % F::kPer) * FB)) & (F::kFlag - 1u);
+          const int d = (int)f - (int)F::kBias;
+          s[e] = (d > 0) - (d < 0);
+        }
+        if (n + 4 <= N) momentum_group4(x, v, n, vv[u], s, lr, mu);
+        else momentum_tail(x, v, n, N, s, lr, mu);
+      }
     }
     __syncthreads();  // the sweep has read every field before they are refilled
   }

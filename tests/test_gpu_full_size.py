@@ -15,6 +15,7 @@ import torch
 
 from oracle import s3gd_coding as C
 from oracle import s3gd_oracle as O
+from oracle import s3gd_randk as R
 from paper_2302_07475_amd import datagen
 
 pytestmark = pytest.mark.gpu
@@ -249,4 +250,29 @@ def test_c5_messages_through_the_wire_format(lib):
     ref = C.pack_row_fast(ow, on, cfg.N)
     assert np.array_equal(vp.cpu().numpy().view(np.uint32)[0, : ref.shape[0]], ref)
     _say(f"C5 downlink: {on} voted coordinates, {C.information_bits(cfg.N, on)} bits packed (N = {cfg.N})")
+    ctx.close()
+
+
+def test_c5_randk(lib):
+    """Algorithm 2 at the full C5 size: words and counts of every row against the oracle's keyed
+    permutation (O(K) on the host too), the vote and update recomputed on every coordinate."""
+    cfg = datagen.C5
+    g, x = datagen.to_device(cfg)
+    x0 = x.cpu().numpy()
+    seed, t = 0xC0FFEE1234567, 11
+    ctx = lib.Context(cfg.M, cfg.N, cfg.K, device=0)
+    words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device=g.device)
+    counts = torch.empty((cfg.M,), dtype=torch.int32, device=g.device)
+    ctx.step_randk(g, cfg.K, seed, t, x, float(datagen.lr32(cfg)), words, counts, None, None)
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    w, c = words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32)
+    for m in range(cfg.M):
+        S = R.randk_index_set(cfg.N, cfg.K, seed, t, m)
+        vals = g[m][torch.from_numpy(S).to(g.device)].cpu().numpy()
+        keep = vals != 0
+        want = ((S[keep].astype(np.uint64) << np.uint64(1)) | (vals[keep] < 0).astype(np.uint64)).astype(np.uint32)
+        assert int(c[m]) == want.shape[0] and np.array_equal(w[m, : c[m]], want), f"row {m}"
+        assert (w[m, c[m]:] == 0xFFFFFFFF).all()
+    _check_vote_and_update(cfg, w, c, x0, x)
     ctx.close()
