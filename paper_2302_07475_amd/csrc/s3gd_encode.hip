@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // state reset (a kernel rather than a memset so that callers may capture the call into a graph)
-__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode) {
+__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode, u32 first_alloc) {
   const u32 m = blockIdx.y;
   for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x)
     hist[(size_t)m * kHistBins + i] = 0;
@@ -72,6 +72,7 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
     RowState s{};
     s.k_rem = first_rank;  // K on the general route, the sample rank on the candidate route
     s.mode = mode;
+    s.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
     rs[m] = s;
     if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; }
   }
@@ -369,9 +370,16 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 // The one pass over the gradients: every entry with key >= L becomes a candidate (index, bits).
 // Waves work independently (no block barrier inside the loop): a wave owns a contiguous run of
 // wave tiles (1024 entries each), the candidates of a tile form one contiguous chunk in ascending
-// index, and chunks are placed in slabs that the wave reserves with one atomic per kSlab
-// candidates.  Consecutive tiles therefore have consecutive chunks.  The block also histograms
-// (key - L) >> 10 into 2048 bins, the last of which is open-ended.
+// index, and chunks are placed in slabs of the row's candidate pool.  Consecutive tiles therefore
+// have consecutive chunks.  The block also histograms (key - L) >> 10 into 2048 bins, the last of
+// which is open-ended.
+//
+// Slabs.  Every wave starts with a slab of its own, assigned by position (no atomic), sized to
+// about twice the candidates a wave expects; only a wave that fills it (skewed rows) reserves
+// another with a returning atomic on the row's counter.  Those atomics are what must stay rare:
+// all waves of a row hit ONE address, a few thousand of them per millisecond queue up behind each
+// other, and a wave waiting for its atomic also waits for its prefetched tile (measured with
+// 256-entry slabs reserved on demand: 26 000 atomics cost 0.4 ms of a 3.2 ms pass).
 //
 // Stores are rare and non-temporal: on this memory system ANY store traffic mixed into the read
 // stream costs several per cent of read bandwidth, whatever its volume (measured: one 8-byte store
@@ -466,7 +474,8 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
 
 template <bool INTERIOR>
 __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, u64* stage,
-                                            u64* entries, u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, FilterWave& w) {
+                                            u64* entries, u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, u32 slab,
+                                            FilterWave& w) {
   // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
   // candidates below is scalar work plus a few mbcnt.
   bool pr[kLoads * 4];
@@ -492,7 +501,7 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
   }
   if (w.cur + total > w.end) {
     flush_stage(w, stage, out, lane);  // staged candidates belong to the old slab
-    const u32 need = (total + kSlab - 1) / kSlab * kSlab;
+    const u32 need = (total + slab - 1) & ~(slab - 1);  // slab is a power of two
     u32 b = 0;
     if (lane == 0) b = atomicAdd(n_alloc, need);
     w.cur = __builtin_amdgcn_readfirstlane(b);
@@ -523,7 +532,7 @@ template <bool EC>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
                                                    RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
                                                    u32 cand_stride, u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
-                                                   u32 tiles_per_wave, u32* __restrict__ status) {
+                                                   u32 tiles_per_wave, u32 slab, u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
@@ -543,6 +552,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   u64* stage = stage_all[wave];
   u64* entries = entry_all[wave];
   FilterWave w{0, 0, 0, 0, false, false};
+  w.cur = (blockIdx.x * kWaves + wave) * slab;  // the wave's first slab; rs[m].n_alloc starts past all of them
+  w.end = w.cur + slab;
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
   // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
@@ -579,8 +590,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       else store_filter_tile<false>(errv, tile, lane, r);
     }
     const u32 slot = (tile - t0) & (u32)(kEntryStage - 1);
-    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, w);
-    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, w);
+    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, slab, w);
+    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, slab, w);
     if (slot == (u32)(kEntryStage - 1) || tile + 1 == t1) {  // wave-uniform: write the staged chunk-table entries
       __builtin_amdgcn_wave_barrier();
       for (u32 i = lane; i <= slot; i += 64) store_stream8(&ch[tile - slot + i], entries[i]);
@@ -796,7 +807,12 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
   p.n_wtiles = (u32)((N + 3 + kWaveTile - 1) / kWaveTile);
   p.tiles_per_wave = (p.n_wtiles + p.gx * kWaves - 1) / (p.gx * kWaves);
   p.bound = candidate_bound(r, f);
-  const double need = p.bound + (double)p.gx * kWaves * kSlab + kWaveTile;
+  // slab: the power of two at or above the candidates expected per wave of the filter pass
+  const double per_wave = p.bound / ((double)p.gx * kWaves);
+  p.slab = kSlabMin;
+  while (p.slab < kSlabMax && (double)p.slab < per_wave) p.slab <<= 1;
+  // a row needs room for its candidates, for the unused part of every wave's last slab, and a tile of slack
+  const double need = p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
   if (need * M > (double)cand_pool || need > 4.0e9) return p;
   p.candidates = true;
   p.n_units = (u32)(s / kSampleUnit);
@@ -815,8 +831,9 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
     if (p.candidates && p.bound > best) best = p.bound;
   }
   if (best == 0) return 0;
-  // per row: the bound and one tile of slack; once: a partly filled slab per wave of a streaming launch
-  return (u64)M_max * ((u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlab;
+  // per row: the bound, as much again (at most twice) in partly filled slabs, one tile of slack;
+  // once: a smallest slab per wave of a streaming launch
+  return (u64)M_max * (3 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
 }
 
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
@@ -844,7 +861,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const dim3 grid(p.gx, M);
   const u32 k32 = (u32)K;
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
-                                                                         p.candidates ? kModeCandidates : kModeGeneral)));
+                                                                         p.candidates ? kModeCandidates : kModeGeneral,
+                                                                         p.candidates ? p.gx * (u32)kWaves * p.slab : 0u)));
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles, wstride = wt_stride(N);
     const u32 bstride = blk_stride(N);
@@ -855,10 +873,10 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     if (err)
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                         ws.chunk, n_wt, wstride, p.tiles_per_wave, ws.status)));
+                                                                         ws.chunk, n_wt, wstride, p.tiles_per_wave, p.slab, ws.status)));
     else
       S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, nullptr, 0.0f, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                      ws.chunk, n_wt, wstride, p.tiles_per_wave, ws.status)));
+                                                                      ws.chunk, n_wt, wstride, p.tiles_per_wave, p.slab, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     // lanes per tile in the candidate kernels, from the expected candidates per tile
     const double per_tile = p.bound / (double)n_wt;

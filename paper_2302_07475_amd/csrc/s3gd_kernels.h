@@ -68,6 +68,7 @@ struct EncodePlan {
   u64 unit_stride;   // row entries per sample unit window
   u32 sample_rank;   // rank, among the sample, of the key that becomes the lower bound L
   u32 cand_stride;   // candidate slots per row
+  u32 slab;          // candidate slots a wave of the filter pass owns at a time (a power of two)
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
 EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks);
