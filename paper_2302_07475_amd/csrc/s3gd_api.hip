@@ -27,7 +27,7 @@ constexpr u32 kMaxRows = 65535;  // rows map to gridDim.y
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t rs, status, hist, tile_cnt, seg, chunk, blk_sum, cand, total;
+  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_nseg, wave_sum, cand, total;
   u64 cand_pool;
 };
 
@@ -39,7 +39,9 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
   l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * (vote_tiles(N) + 1), 256);
-  l.chunk = off;    off = align_up(off + sizeof(u64) * (size_t)M * wt_stride(N), 256);
+  l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M) * kChain, 256);
+  l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M), 256);
+  l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M), 256);
   l.blk_sum = off;  off = align_up(off + sizeof(u64) * (size_t)M * blk_stride(N), 256);
   l.cand_pool = candidate_pool_entries(M, N, K);
   l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);
@@ -117,7 +119,9 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.hist = reinterpret_cast<u32*>(b + l.hist);
   c->ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
   c->ws.seg = reinterpret_cast<u32*>(b + l.seg);
-  c->ws.chunk = reinterpret_cast<u64*>(b + l.chunk);
+  c->ws.wave_seg = reinterpret_cast<u64*>(b + l.wave_seg);
+  c->ws.wave_nseg = reinterpret_cast<u32*>(b + l.wave_nseg);
+  c->ws.wave_sum = reinterpret_cast<u64*>(b + l.wave_sum);
   c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
   c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
   c->ws.cand_pool = l.cand_pool;

@@ -46,7 +46,7 @@ constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, sel
 constexpr int kWaveTile = 64 * 4 * kLoads;  // 1024 entries: the unit of the candidate route (one wave, no barriers)
 constexpr u32 kSlabMin = 256;       // candidate slots a wave reserves at a time: a power of two chosen per call ...
 constexpr u32 kSlabMax = 1u << 16;  // ... between these, from the candidates expected per wave
-constexpr int kTilesPerBlock = 256; // wave tiles per block (one per thread) in the candidate count / emit kernels
+constexpr int kChain = 8;           // segments (slabs) a wave of the filter pass may leave behind
 constexpr int kSampleUnit = 16;     // consecutive entries per sample unit (one 64-byte line)
 constexpr int kSamplePerBlock = 4096;
 

@@ -369,14 +369,18 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 
 // The one pass over the gradients: every entry with key >= L becomes a candidate (index, bits).
 // Waves work independently (no block barrier inside the loop): a wave owns a contiguous run of
-// wave tiles (1024 entries each), the candidates of a tile form one contiguous chunk in ascending
-// index, and chunks are placed in slabs of the row's candidate pool.  Consecutive tiles therefore
-// have consecutive chunks.  The block also histograms (key - L) >> 10 into 2048 bins, the last of
-// which is open-ended.
+// wave tiles (1024 entries each) and appends its candidates, in ascending index, to slabs of the
+// row's candidate pool.  What a wave leaves behind is its SEGMENT LIST: up to kChain pairs
+// (first slot, count), written once when the wave ends.  Waves in order, and each wave's segments
+// in order, list the row's candidates in ascending index; the kernels after the pass walk them
+// that way, one wave per list.  The block also histograms (key - L) >> 10 into 2048 bins, the
+// last of which is open-ended.
 //
 // Slabs.  Every wave starts with a slab of its own, assigned by position (no atomic), sized to
 // about twice the candidates a wave expects; only a wave that fills it (skewed rows) reserves
-// another with a returning atomic on the row's counter.  Those atomics are what must stay rare:
+// another, twice as large each time, with a returning atomic on the row's counter.  A wave that
+// would need more than kChain segments (more than a hundred times its share) marks the row for
+// the general route.  Those atomics are what must stay rare:
 // all waves of a row hit ONE address, a few thousand of them per millisecond queue up behind each
 // other, and a wave waiting for its atomic also waits for its prefetched tile (measured with
 // 256-entry slabs reserved on demand: 26 000 atomics cost 0.4 ms of a 3.2 ms pass).
@@ -384,17 +388,30 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 // Stores are rare and non-temporal: on this memory system ANY store traffic mixed into the read
 // stream costs several per cent of read bandwidth, whatever its volume (measured: one 8-byte store
 // per 4 KB read, or one 512-byte store per 256 KB read, both cost 9 %; non-temporal stores issued
-// every 2 MB read cost 2.5 %).  So candidates are staged in LDS and written a few hundred at a
-// time, and the per-tile chunk table is staged in LDS and written every 256 tiles.
-constexpr int kStage = 512;        // staged candidates per wave
-constexpr int kStageFlush = 384;   // flush once this many are staged
-constexpr int kEntryStage = 256;   // staged chunk-table entries per wave
+// every 2 MB read cost 2.5 %).  So candidates are staged in LDS and written about nine hundred at a
+// time, and nothing else is stored per tile.
+constexpr int kStage = 1024;       // staged candidates per wave
+constexpr int kStageFlush = 896;   // flush once this many are staged
 
 struct FilterWave {
   u32 cur, end, total;  // slab cursor, slab end, candidates so far (wave-uniform)
   u32 fill;             // candidates staged in LDS; they belong to out[cur - fill, cur)
+  u32 seg_base, n_seg;  // first slot of the segment being filled; segments already closed
+  u64* segs;            // the wave's segment list in global memory, kChain entries
   bool overflow, nan;
 };
+
+// Ends the segment being filled: its (first slot, count) goes to the wave's list.
+__device__ __forceinline__ void close_segment(FilterWave& w, u32 lane) {
+  const u32 count = w.cur - w.seg_base;
+  if (count == 0) return;  // wave-uniform
+  if (w.n_seg < (u32)kChain) {
+    if (lane == 0) w.segs[w.n_seg] = ((u64)w.seg_base << 32) | count;
+    ++w.n_seg;
+  } else {
+    w.overflow = true;
+  }
+}
 
 __device__ __forceinline__ void store_stream8(u64* p, u64 v) { __builtin_nontemporal_store(v, p); }
 
@@ -473,9 +490,8 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
 }
 
 template <bool INTERIOR>
-__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 slot, u32 lane, u32 L, u32* h, u64* stage,
-                                            u64* entries, u32* n_alloc, uint2* __restrict__ out, u32 cand_stride, u32 slab,
-                                            FilterWave& w) {
+__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32* h, u64* stage, u32* n_alloc,
+                                            uint2* __restrict__ out, u32 cand_stride, u32 slab, FilterWave& w) {
   // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
   // candidates below is scalar work plus a few mbcnt.
   bool pr[kLoads * 4];
@@ -489,38 +505,41 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     mk[i] = ballot(pr[i]);
     any |= mk[i];
   }
-  if (any == 0) {  // wave-uniform
-    if (lane == 0) entries[slot] = 0;
-    return;
-  }
+  if (any == 0) return;  // wave-uniform
   u32 tot[kLoads], total = 0;
 #pragma unroll
   for (int j = 0; j < kLoads; ++j) {
     tot[j] = (u32)__popcll(mk[4 * j]) + (u32)__popcll(mk[4 * j + 1]) + (u32)__popcll(mk[4 * j + 2]) + (u32)__popcll(mk[4 * j + 3]);
     total += tot[j];
   }
+  if (w.overflow) return;
   if (w.cur + total > w.end) {
     flush_stage(w, stage, out, lane);  // staged candidates belong to the old slab
-    const u32 need = (total + slab - 1) & ~(slab - 1);  // slab is a power of two
+    close_segment(w, lane);
+    // the next slab: twice the previous one (slab, slab, 2 slab, 4 slab, ...), and at least what the tile needs
+    const u32 grown = slab << (w.n_seg > 1 ? w.n_seg - 1 : 0);
+    const u32 fit = (total + slab - 1) & ~(slab - 1);  // slab is a power of two
+    const u32 need = grown > fit ? grown : fit;
     u32 b = 0;
     if (lane == 0) b = atomicAdd(n_alloc, need);
     w.cur = __builtin_amdgcn_readfirstlane(b);
     w.end = w.cur + need;
-  }
-  if (w.end > cand_stride) {
-    w.overflow = true;
-    w.fill = 0;
-  } else {
-    if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane);
-    const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-    if (total > (u32)kStage) {  // a tile too dense to stage writes straight to memory (stage is empty here)
-      place_candidates<true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
-    } else {
-      place_candidates<false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
-      w.fill += total;
+    w.seg_base = w.cur;
+    if (w.end > cand_stride || w.end < w.cur) {  // pool exhausted (or the counter wrapped): nothing more is written
+      w.overflow = true;
+      w.end = w.cur;
+      w.seg_base = w.cur;
     }
   }
-  if (lane == 0) entries[slot] = ((u64)w.cur << 32) | total;
+  if (w.overflow) return;
+  if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane);
+  const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
+  if (total > (u32)kStage) {  // a tile too dense to stage writes straight to memory (stage is empty here)
+    place_candidates<true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
+  } else {
+    place_candidates<false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
+    w.fill += total;
+  }
   w.cur += total;
   w.total += total;
   if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane);
@@ -531,14 +550,14 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
 template <bool EC>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
                                                    RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
-                                                   u32 cand_stride, u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
-                                                   u32 tiles_per_wave, u32 slab, u32* __restrict__ status) {
+                                                   u32 cand_stride, u64* __restrict__ wave_seg, u32* __restrict__ wave_nseg,
+                                                   u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
+                                                   u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u32 h[kHistBins];
   __shared__ u64 stage_all[kWaves][kStage];
-  __shared__ u64 entry_all[kWaves][kEntryStage];
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const float* row = grads + (size_t)m * N;
@@ -548,12 +567,13 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u64 vend = N + a;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
-  u64* ch = chunk + (size_t)m * wt_stride;
   u64* stage = stage_all[wave];
-  u64* entries = entry_all[wave];
-  FilterWave w{0, 0, 0, 0, false, false};
-  w.cur = (blockIdx.x * kWaves + wave) * slab;  // the wave's first slab; rs[m].n_alloc starts past all of them
+  const u32 g = blockIdx.x * kWaves + wave;  // the wave's position among the waves of its row
+  FilterWave w{};
+  w.cur = g * slab;  // the wave's first slab; rs[m].n_alloc starts past all of them
   w.end = w.cur + slab;
+  w.seg_base = w.cur;
+  w.segs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
   // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
@@ -589,17 +609,15 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       if (tile >= first && tile < last) store_filter_tile<true>(errv, tile, lane, r);
       else store_filter_tile<false>(errv, tile, lane, r);
     }
-    const u32 slot = (tile - t0) & (u32)(kEntryStage - 1);
-    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, slab, w);
-    else filter_tile<false>(r, a, tile, slot, lane, st.L, h, stage, entries, &rs[m].n_alloc, out, cand_stride, slab, w);
-    if (slot == (u32)(kEntryStage - 1) || tile + 1 == t1) {  // wave-uniform: write the staged chunk-table entries
-      __builtin_amdgcn_wave_barrier();
-      for (u32 i = lane; i <= slot; i += 64) store_stream8(&ch[tile - slot + i], entries[i]);
-      __builtin_amdgcn_wave_barrier();
-    }
+    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
+    else filter_tile<false>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
   }
-  if (!w.overflow) flush_stage(w, stage, out, lane);
+  if (!w.overflow) {
+    flush_stage(w, stage, out, lane);
+    close_segment(w, lane);
+  }
   if (lane == 0) {
+    wave_nseg[(size_t)m * wave_stride + g] = w.overflow ? 0u : w.n_seg;
     if (w.total) atomicAdd(&rs[m].n_cand, w.total);
     if (w.overflow) rs[m].overflow = 1;
   }
@@ -611,137 +629,106 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
 }
 
-// The kernels below walk the candidates tile by tile.  G lanes share a wave tile (G = 1, 4 or 16,
-// chosen on the host from the expected candidates per tile), so that a thread's loop stays a few
-// iterations long and the lanes of a group read consecutive candidates.
-template <int G>
-struct TileGroup {
-  static constexpr int kTiles = kBlock / G;  // tiles per block
-  u32 tile, sub;
-  __device__ TileGroup() : tile(blockIdx.x * kTiles + threadIdx.x / G), sub(threadIdx.x % G) {}
+// The kernels below walk the candidates of a row in ascending index: one wave per segment list
+// (the list of the filter wave at the same position), segments in order, 64 candidates at a time.
+struct SegmentWalk {
+  const u64* segs;
+  u32 n_seg;
+  const uint2* pool;
+  __device__ SegmentWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
+                         u32 cand_stride, u32 m, u32 g, u32 n_waves)
+      : segs(wave_seg + ((size_t)m * wave_stride + g) * kChain), n_seg(g < n_waves ? wave_nseg[(size_t)m * wave_stride + g] : 0u),
+        pool(cand + (size_t)m * cand_stride) {
+    if (n_seg > (u32)kChain) n_seg = (u32)kChain;
+  }
 };
-
-template <int G>
-__device__ __forceinline__ u64 group_sum(u64 v) {
-#pragma unroll
-  for (int d = G / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
-  return v;
-}
 
 // Last radix level among the candidates: histogram of key & 1023 where key >> 10 == prefix.
 // Only the few hundred candidates of the target bin touch the histogram.
-template <int G>
 __global__ __launch_bounds__(kBlock) void k_cand_hist(const RowState* __restrict__ rs, u32* __restrict__ hist,
                                                       const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride) {
+                                                      const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
+                                                      u32 wave_stride, u32 n_waves) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  const TileGroup<G> g;
-  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
-  const u32 cnt = (u32)c;
-  const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
-  for (u32 i = g.sub; i < cnt; i += G) {
-    const u32 key = in[i].y & 0x7FFFFFFFu;
-    if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
+  const u32 lane = lane_id();
+  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, blockIdx.x * kWaves + (threadIdx.x >> 6), n_waves);
+  for (u32 c = 0; c < sw.n_seg; ++c) {
+    const u64 sg = sw.segs[c];
+    const uint2* in = sw.pool + (u32)(sg >> 32);
+    const u32 cnt = (u32)sg;
+    for (u32 i = lane; i < cnt; i += 64) {
+      const u32 key = in[i].y & 0x7FFFFFFFu;
+      if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
+    }
   }
 }
 
-// (gt, eq) of the candidates i = sub, sub + G, ... of a chunk against the final threshold.
-template <int G>
-__device__ __forceinline__ u64 count_chunk(const uint2* __restrict__ in, u32 cnt, u32 sub, u32 T) {
-  u32 gt = 0, eq = 0;
-  for (u32 i = sub; i < cnt; i += G) {
-    const u32 key = in[i].y & 0x7FFFFFFFu;
-    gt += key > T;
-    eq += key == T;
-  }
-  return ((u64)eq << 32) | gt;
-}
-
-// Sum of (gt, eq) over the tiles of each block; scanned afterwards, so that the emit kernel only
-// needs a block-local scan.
-template <int G>
+// (eq << 32) | gt of each segment list against the final threshold; scanned afterwards.
 __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                       const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
-                                                       u64* __restrict__ blk_sum, u32 blk_stride) {
+                                                       const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
+                                                       u32 wave_stride, u32 n_waves, u64* __restrict__ wave_sum) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  __shared__ u64 lds[kWaves];
-  const TileGroup<G> g;
-  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
-  const u64 mine = count_chunk<G>(cand + (size_t)m * cand_stride + (u32)(c >> 32), (u32)c, g.sub, st.T);
-  u64 total;
-  (void)block_excl_scan<u64>(mine, &total, lds);
-  if (threadIdx.x == 0) blk_sum[(size_t)m * blk_stride + blockIdx.x] = total;
+  const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
+  u32 gt = 0, eq = 0;
+  for (u32 c = 0; c < sw.n_seg; ++c) {
+    const u64 sg = sw.segs[c];
+    const uint2* in = sw.pool + (u32)(sg >> 32);
+    const u32 cnt = (u32)sg;
+    for (u32 i = lane; i < cnt; i += 64) {
+      const u32 key = in[i].y & 0x7FFFFFFFu;
+      gt += key > st.T;
+      eq += key == st.T;
+    }
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+  if (lane == 0 && g < n_waves) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
 }
 
-// Emits the words of the block's tiles from their candidate chunks, in ascending index.
-template <int G>
+// Emits the words of each segment list at its scanned offset, in ascending index, the tie quota
+// applied in index order.  With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
 __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ chunk, u32 n_wtiles, u32 wt_stride,
-                                                      const u64* __restrict__ blk_sum, u32 blk_stride, u64 K, u32* __restrict__ words,
-                                                      float* __restrict__ err, u64 N) {
+                                                      const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
+                                                      u32 wave_stride, u32 n_waves, const u64* __restrict__ wave_sum, u64 K,
+                                                      u32* __restrict__ words, float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  __shared__ u64 lds[kWaves];
-  float* erow = err ? err + (size_t)m * N : nullptr;  // memory row: +0.0 goes over every entry whose sign is sent
-  const TileGroup<G> g;
-  const u64 c = g.tile < n_wtiles ? chunk[(size_t)m * wt_stride + g.tile] : 0;
-  const u32 cnt = (u32)c;
-  const uint2* in = cand + (size_t)m * cand_stride + (u32)(c >> 32);
-  const u64 part = count_chunk<G>(in, cnt, g.sub, st.T);
-  const u64 mine = group_sum<G>(part);  // the whole tile's (gt, eq), in every lane of the group
-  u64 total;
-  // scan over tiles: only lane 0 of a group contributes, then the group shares its prefix
-  u64 before = block_excl_scan<u64>(g.sub == 0 ? mine : 0, &total, lds);
-  before = __shfl(before, (int)(lane_id() & ~(u32)(G - 1)), 64) + blk_sum[(size_t)m * blk_stride + blockIdx.x];
+  const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
+  if (sw.n_seg == 0) return;  // wave-uniform
+  float* erow = err ? err + (size_t)m * N : nullptr;
+  u32* out = words + (size_t)m * K;
+  const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
   u32 eq_seen = (u32)(before >> 32);
   u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-  u32* out = words + (size_t)m * K;
-  if (G == 1) {
-    for (u32 i = 0; i < cnt; ++i) {
-      const uint2 cd = in[i];
-      const u32 key = cd.y & 0x7FFFFFFFu;
-      bool sel = key > st.T;
-      if (key == st.T) { sel = eq_seen < st.q; ++eq_seen; }
-      if (sel) {
-        if (o < K) {  // o < K by construction
-          out[o] = (cd.x << 1) | (cd.y >> 31);
-          if (erow) erow[cd.x] = 0.0f;
-        }
-        ++o;
-      }
-    }
-  } else {
-    // G candidates per round; ranks inside the group come from wave ballots, so every lane of the
-    // wave runs the same number of rounds
-    u32 rounds = (cnt + G - 1) / G;
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) { const u32 other = __shfl_xor(rounds, d, 64); rounds = other > rounds ? other : rounds; }
-    const u32 gshift = lane_id() & ~(u32)(G - 1);
-    const u32 gmask = (1u << G) - 1u, below = (1u << g.sub) - 1u;
-    for (u32 rd = 0; rd < rounds; ++rd) {
-      const u32 i = rd * G + g.sub;
-      const bool ok = i < cnt;
+  for (u32 c = 0; c < sw.n_seg; ++c) {
+    const u64 sg = sw.segs[c];
+    const uint2* in = sw.pool + (u32)(sg >> 32);
+    const u32 cnt = (u32)sg;
+    for (u32 i0 = 0; i0 < cnt; i0 += 64) {  // wave-uniform trip count
+      const bool ok = i0 + lane < cnt;
       uint2 cd = make_uint2(0, 0);
-      if (ok) cd = in[i];
+      if (ok) cd = in[i0 + lane];
       const u32 key = cd.y & 0x7FFFFFFFu;
       const bool is_eq = ok && key == st.T;
-      const u32 eq_bits = (u32)(ballot(is_eq) >> gshift) & gmask;
-      const bool sel = ok && (key > st.T || (is_eq && eq_seen + __popc(eq_bits & below) < st.q));
-      const u32 sel_bits = (u32)(ballot(sel) >> gshift) & gmask;
+      const u64 eq_mask = ballot(is_eq);
+      const bool sel = ok && (key > st.T || (is_eq && eq_seen + ballot_rank(eq_mask) < st.q));
+      const u64 sel_mask = ballot(sel);
       if (sel) {
-        const u32 pos = o + __popc(sel_bits & below);
+        const u32 pos = o + ballot_rank(sel_mask);
         if (pos < K) {  // pos < K by construction
           out[pos] = (cd.x << 1) | (cd.y >> 31);
           if (erow) erow[cd.x] = 0.0f;
         }
       }
-      o += __popc(sel_bits);
-      eq_seen += __popc(eq_bits);
+      o += (u32)__popcll(sel_mask);
+      eq_seen += (u32)__popcll(eq_mask);
     }
   }
 }
@@ -811,8 +798,9 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
   const double per_wave = p.bound / ((double)p.gx * kWaves);
   p.slab = kSlabMin;
   while (p.slab < kSlabMax && (double)p.slab < per_wave) p.slab <<= 1;
-  // a row needs room for its candidates, for the unused part of every wave's last slab, and a tile of slack
-  const double need = p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
+  // a row needs room for its candidates, for the first slab of every wave, for the unused part of the
+  // later (doubling) slabs of waves that overflowed (at most what they hold), and a tile of slack
+  const double need = 2.0 * p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
   if (need * M > (double)cand_pool || need > 4.0e9) return p;
   p.candidates = true;
   p.n_units = (u32)(s / kSampleUnit);
@@ -831,9 +819,9 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
     if (p.candidates && p.bound > best) best = p.bound;
   }
   if (best == 0) return 0;
-  // per row: the bound, as much again (at most twice) in partly filled slabs, one tile of slack;
-  // once: a smallest slab per wave of a streaming launch
-  return (u64)M_max * (3 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
+  // per row: twice the bound, as much again (at most twice the bound) in first slabs, one tile of
+  // slack; once: a smallest slab per wave of a streaming launch
+  return (u64)M_max * (4 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
 }
 
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
@@ -864,8 +852,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                          p.candidates ? kModeCandidates : kModeGeneral,
                                                                          p.candidates ? p.gx * (u32)kWaves * p.slab : 0u)));
   if (p.candidates) {
-    const u32 n_wt = p.n_wtiles, wstride = wt_stride(N);
-    const u32 bstride = blk_stride(N);
+    const u32 n_wt = p.n_wtiles;
+    const u32 n_waves = p.gx * (u32)kWaves, wstride = wave_stride(p.gx);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
@@ -873,28 +861,22 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     if (err)
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                         ws.chunk, n_wt, wstride, p.tiles_per_wave, p.slab, ws.status)));
+                                                                         ws.wave_seg, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
+                                                                         p.slab, ws.status)));
     else
       S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, nullptr, 0.0f, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                      ws.chunk, n_wt, wstride, p.tiles_per_wave, p.slab, ws.status)));
+                                                                      ws.wave_seg, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
+                                                                      p.slab, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    // lanes per tile in the candidate kernels, from the expected candidates per tile
-    const double per_tile = p.bound / (double)n_wt;
-    const int G = per_tile <= 3.0 ? 1 : (per_tile <= 12.0 ? 4 : 16);
-    const u32 n_blk = (n_wt + (kBlock / G) - 1) / (kBlock / G);
-    const dim3 cgrid(n_blk, M);
-#define S3GD_CAND(KID, KERNEL, ...)                                                          \
-  do {                                                                                       \
-    if (G == 1) S3GD_LAUNCH(KID, (KERNEL<1><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));          \
-    else if (G == 4) S3GD_LAUNCH(KID, (KERNEL<4><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));     \
-    else S3GD_LAUNCH(KID, (KERNEL<16><<<cgrid, kBlock, 0, s>>>(__VA_ARGS__)));                \
-  } while (0)
-    S3GD_CAND(KID_CAND_SELECT, k_cand_hist, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride);
+    // one wave per segment list
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<grid, kBlock, 0, s>>>(ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg,
+                                                                     wstride, n_waves)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_CAND(KID_CAND_SELECT, k_cand_count, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride);
-    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.blk_sum, n_blk, bstride, ws.rs, kModeCandidates)));
-    S3GD_CAND(KID_CAND_EMIT, k_cand_emit, ws.rs, ws.cand, p.cand_stride, ws.chunk, n_wt, wstride, ws.blk_sum, bstride, K, words, err, N);
-#undef S3GD_CAND
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
+                                                                      n_waves, ws.wave_sum)));
+    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, kModeCandidates)));
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
+                                                                   n_waves, ws.wave_sum, K, words, err, N)));
   }
   // General route: every kernel returns at once for rows the candidate route has served.
   S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));

@@ -9,8 +9,10 @@ constexpr u32 kMaxStreamBlocks = 256 * 16;  // upper bound on the blocks of one 
 inline u32 encode_tiles(u64 N) { return (u32)((N + 3 + kTile - 1) / kTile); }  // rows may start up to 3 slots late
 inline u32 tile_stride(u64 N) { return (encode_tiles(N) + 1 + 3) & ~3u; }
 inline u32 wave_tiles(u64 N) { return (u32)((N + 3 + kWaveTile - 1) / kWaveTile); }
-inline u32 wt_stride(u64 N) { return (wave_tiles(N) + 3) & ~3u; }
-inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + 15) / 16 + 1 + 3) & ~3u; }  // blocks of the candidate kernels hold >= 16 tiles
+inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + 15) / 16 + 1 + 3) & ~3u; }  // per-row scratch of the random-K scan
+inline u32 wave_stride(u32 gx) { return gx * kWaves + 4; }  // per-row stride of the per-wave tables of a launch with gx blocks per row
+// entries of the per-wave tables: gx * M <= max(resident blocks, M) for every launch
+inline size_t wave_table_entries(u32 M_max) { return (size_t)(kMaxStreamBlocks + M_max) * kWaves + 4 * (size_t)M_max; }
 inline u32 coding_blk_stride(u64 N) { return 2 * tile_stride(N); }  // u32 entries per row when tile_cnt serves the coding kernels
 inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
 
@@ -51,8 +53,10 @@ struct Workspace {
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][vote_tiles + 1]
-  u64* chunk;     // [M][wt_stride]    candidate route: (first slot << 32) | candidates of each wave tile
-  u64* blk_sum;   // [M][blk_stride]   candidate route: (eq << 32 | gt) per 256 wave tiles, scanned in place
+  u64* blk_sum;   // [M][blk_stride]   scratch of the random-K scan
+  u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment a filter wave left
+  u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each wave's list
+  u64* wave_sum;  // [M][wave_stride]  candidate route: (eq << 32 | gt) of each list, scanned in place
   uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
   u64 cand_pool;  // entries of `cand`
   u32 stream_blocks;  // blocks of a streaming launch = blocks resident on the device at once (one round, no tail)

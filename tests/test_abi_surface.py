@@ -39,7 +39,7 @@ def test_workspace_bytes_is_pure_and_monotone(lib):
     assert lib.workspace_bytes(1, (1 << 31) - 1, 1) == 0  # above the index limit
     # scratch stays a small fraction of the gradients it serves
     M, N = 4, 1_200_000_000
-    assert lib.workspace_bytes(M, N, N // 1000) < 0.02 * 4 * M * N
+    assert lib.workspace_bytes(M, N, N // 1000) < 0.025 * 4 * M * N
 
 
 def test_strerror(lib):
