@@ -139,6 +139,51 @@ __device__ __forceinline__ void vote_rows(const u32* __restrict__ words, u64 K, 
   }
 }
 
+// A light tile: at most kKeep rows per wave and at most 64 messages per row (the usual case at small
+// K/N: a tile holds a few dozen messages per worker).  Every lane then holds its messages in
+// registers across both phases, and the parameter of each message is fetched right away, so that
+// a tile costs two memory latencies in a row (messages, parameters) instead of four.
+constexpr int kKeep = 8;
+
+template <int FB>
+__device__ __forceinline__ void vote_tile_light(const u32* __restrict__ words, u64 K, u32 M, const u32* lo, const u32* hi, u32* t,
+                                                u64 base, u64 N, float* __restrict__ x, float lr) {
+  typedef VoteField<FB> F;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  u32 wd[kKeep];
+  float xv[kKeep];
+#pragma unroll
+  for (int k = 0; k < kKeep; ++k) {
+    const u32 r = wave + (u32)k * kWaves;
+    wd[k] = S3GD_PAD;
+    xv[k] = 0.0f;
+    if (r < M) {
+      const u32 i = lo[r] + lane;
+      if (i < hi[r]) wd[k] = words[(size_t)r * K + i];
+    }
+    const u32 c = (u32)((u64)(wd[k] >> 1) - base);
+    if (wd[k] == S3GD_PAD || c >= F::kTile || base + c >= N) {  // the last two never hold for sorted rows with indices < N
+      wd[k] = S3GD_PAD;
+    } else {
+      xv[k] = x[base + c];
+      const u32 sh = (c % F::kPer) * FB;
+      atomicAdd(&t[c / F::kPer], (wd[k] & 1u) ? (0u - (1u << sh)) : (1u << sh));
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kKeep; ++k) {
+    if (wd[k] == S3GD_PAD) continue;
+    const u32 c = (u32)((u64)(wd[k] >> 1) - base);
+    const u32 sh = (c % F::kPer) * FB;
+    const u32 old = atomicOr(&t[c / F::kPer], F::kFlag << sh) >> sh;
+    if (!(old & F::kFlag)) {  // first to claim the coordinate: apply its update
+      const int sgn = (int)(old & (F::kFlag - 1u)) - (int)F::kBias;
+      if (sgn != 0) x[base + c] = xv[k] - lr * (float)((sgn > 0) - (sgn < 0));
+    }
+  }
+}
+
 template <int FB>
 __global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
                                                         u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x, float lr) {
@@ -154,9 +199,14 @@ __global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ 
     __syncthreads();
     if (one_chunk) {
       if (tile + gridDim.x < n_vt) load_bounds(seg, seg_stride, 0, M, tile + gridDim.x, lo[buf ^ 1], hi[buf ^ 1]);
-      vote_rows<FB, 0>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
-      __syncthreads();
-      vote_rows<FB, 1>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
+      const bool heavy = M > (u32)(kWaves * kKeep) || (threadIdx.x < M && hi[buf][threadIdx.x] - lo[buf][threadIdx.x] > 64u);
+      if (!__syncthreads_or(heavy)) {  // block-uniform
+        vote_tile_light<FB>(words, K, M, lo[buf], hi[buf], t, base, N, x, lr);
+      } else {
+        vote_rows<FB, 0>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
+        __syncthreads();
+        vote_rows<FB, 1>(words, K, 0, M, lo[buf], hi[buf], t, base, N, x, lr);
+      }
       buf ^= 1;
     } else {
       for (int phase = 0; phase < 2; ++phase) {
