@@ -30,7 +30,7 @@ HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
 # HBM bytes per launch (read + written) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the factors a
 # plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE); figures and commands are in
 # profiles/s3gd_step_C5_hbm_traffic.md.  Reported only for the workload and kernel they were taken on.
-MEASURED_TRAFFIC_BYTES = {("C5", "filter"): 19.2002e9 + 0.1017e9}
+MEASURED_TRAFFIC_BYTES = {("C5", "filter"): 19.2000e9 + 0.0620e9}
 
 # algorithmic bytes one launch of a kernel moves, per gradient element (4 = one fp32 read of G)
 FULL_READ_KERNELS = {"hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "filter"}
