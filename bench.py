@@ -75,6 +75,8 @@ def main():
                          "compact wire format, as they would be around an exchange (not the headline workload)")
     ap.add_argument("--randk", action="store_true",
                     help="time s3gd_step_randk (Algorithm 2: random-K instead of top-K; not the headline workload)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into a HIP graph once and time replays (the same kernels, fewer launch gaps)")
     ap.add_argument("--momentum", action="store_true",
                     help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
     args = ap.parse_args()
@@ -142,26 +144,47 @@ def main():
         else:
             ctx.step(g, K, x, lr, words, counts, None, None)
 
+    eager_step = one_step
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            eager_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        one_step = graph.replay
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
     assert ctx.last_async_status() == 0
     general_rows = ctx.last_encode_info()[1]
-    ctx.profile_enable(True)
+    # per-kernel breakdown from a short eager pass with an event pair around every launch (not timed: the
+    # hundred events per step it records cost a few per cent)
+    ctx.profile_enable(1)
+    for _ in range(3):
+        eager_step()
+    prof = ctx.profile_read()
+    kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / 3} for k, v in prof.items()}
+    # timed region: only the selection pass (the dominant kernel) carries an event pair
+    ctx.profile_enable(0 if args.graph else 2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    prof = ctx.profile_read()
-    ctx.profile_enable(False)
+    live = {} if args.graph else ctx.profile_read()
+    ctx.profile_enable(0)
     log(f"[bench] timed {args.steps} steps in {dt * 1e3:.2f} ms")
+    for k, v in live.items():  # measured inside the timed region: these replace the figures of the breakdown pass
+        kern[k] = {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / args.steps}
 
     ms_step = dt * 1e3 / args.steps
-    kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / args.steps} for k, v in prof.items()}
     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
-        log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}")
+        log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}" + ("  (timed region)" if k in live else ""))
     dom = max(kern, key=lambda k: kern[k]["ms_avg"])
     if dom == "randk":  # K gathered gradient entries and K words per row; nothing else of G is touched
         alg_bytes = 8.0 * M * K
@@ -190,9 +213,10 @@ def main():
                             ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
                             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
-                   "rows_on_general_path": general_rows},
+                   "rows_on_general_path": general_rows, "launch": "HIP graph replay" if args.graph else "eager"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
+                     "duration_from": "HIP events inside the timed region" if dom in live else "HIP events, eager pass before the timed region",
                      "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum or args.wire or args.randk) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,

@@ -279,9 +279,10 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
 /*
- * Optional per-kernel timing for benchmarks.  When enabled, every kernel launch made through the
- * context is bracketed by a HIP event pair recorded on the call's own stream (no host
- * synchronisation is added).  s3gd_profile_read synchronises `stream`, adds the elapsed time of
+ * Optional per-kernel timing for benchmarks.  When enabled (on = 1), every kernel launch made
+ * through the context is bracketed by a HIP event pair recorded on the call's own stream (no host
+ * synchronisation is added); on = 2 brackets only the passes over the gradients (the dominant
+ * kernel of a step), two events per step.  s3gd_profile_read synchronises `stream`, adds the elapsed time of
  * every recorded pair to ms_sum[kernel id] and its launch count to launches[kernel id] (host
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).

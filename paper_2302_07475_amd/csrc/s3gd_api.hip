@@ -401,7 +401,7 @@ S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on) {
       if (e != hipSuccess) return hip_fail(ctx, e);
     }
   }
-  ctx->prof.enabled = on != 0;
+  ctx->prof.mode = on == 2 ? 2 : (on != 0 ? 1 : 0);
   ctx->prof.used = 0;
   return S3GD_OK;
 }

@@ -157,25 +157,6 @@ __device__ __forceinline__ void load_tile(const u32* __restrict__ rowv /* row st
   load_span<kTile>(rowv, a, vend, vbase, threadIdx.x, r);
 }
 
-// The same for a wave tile: entry (j, e) of lane l is v = vbase + j*256 + l*4 + e.
-__device__ __forceinline__ void load_wave_tile(const u32* __restrict__ rowv, u32 a, u64 vend, u64 vbase, u32 lane, TileRegs& r) {
-  load_span<kWaveTile>(rowv, a, vend, vbase, lane, r);
-}
-
-// Ranks of flagged entries of a wave tile in ascending index order (j, lane, e); no LDS, no barrier.
-// base[j] = flagged entries of the wave before this lane's load j.  Returns the wave's total.
-__device__ __forceinline__ u32 wave_rank(u32 mask, u32 base[kLoads]) {
-  u32 run = 0;
-#pragma unroll
-  for (int j = 0; j < kLoads; ++j) {
-    const u32 c = __popc((mask >> (4 * j)) & 0xFu);  // 0..4
-    const u64 b0 = ballot(c & 1u), b1 = ballot(c & 2u), b2 = ballot(c & 4u);
-    base[j] = run + ballot_rank(b0) + 2u * ballot_rank(b1) + 4u * ballot_rank(b2);
-    run += (u32)__popcll(b0) + 2u * (u32)__popcll(b1) + 4u * (u32)__popcll(b2);
-  }
-  return run;
-}
-
 // Ranks of flagged entries of a tile in ascending index order.
 // mask: bit (4j+e) of this thread's entries.  base[j] = number of flagged entries of the block that
 // precede this thread's load j.  *total = flagged entries in the block.  lds: kLoads*kWaves entries.

@@ -9,8 +9,8 @@
 // Two routes reach the same T, q and words:
 //   candidate route  a strided sample of the row gives a lower bound L with, very likely,
 //                    K <= #{key >= L} <= capacity.  ONE pass over the row copies those candidates
-//                    (index, bits) into per-tile chunks and histograms them; T is then resolved
-//                    and the words are emitted from the candidates alone.
+//                    (index, bits) into per-wave segments of a pool and histograms them; T is then
+//                    resolved and the words are emitted from the candidates alone.
 //   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
 //                    pass and an emit pass.  Any row for which the candidate route's checks fail
 //                    (too few or too many candidates, heavy ties, tiny rows) takes it; the choice

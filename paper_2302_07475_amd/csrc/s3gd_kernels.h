@@ -30,15 +30,17 @@ enum KernelId : int {
 // Records a start/stop event pair around a launch when profiling is on.
 struct Profiler {
   static constexpr int kPairs = 4096;
-  bool enabled = false;
+  int mode = 0;  // 0 off, 1 every kernel, 2 only the selection pass over the gradients (two events per step: next to no overhead)
+  bool open = false;
   int used = 0;
   hipEvent_t* ev = nullptr;  // 2 * kPairs events, created when profiling is first enabled
   int kid[kPairs];
   void begin(int k, hipStream_t s) {
-    if (enabled && used < kPairs) { kid[used] = k; (void)hipEventRecord(ev[2 * used], s); }
+    open = mode != 0 && used < kPairs && (mode == 1 || k == KID_FILTER || k == KID_FILTER_MEM || k == KID_RANDK);
+    if (open) { kid[used] = k; (void)hipEventRecord(ev[2 * used], s); }
   }
   void end(hipStream_t s) {
-    if (enabled && used < kPairs) { (void)hipEventRecord(ev[2 * used + 1], s); ++used; }
+    if (open) { (void)hipEventRecord(ev[2 * used + 1], s); ++used; open = false; }
   }
 };
 

@@ -130,7 +130,7 @@ class Context:
             raise S3GDError(rc, "s3gd_create")
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:  # _lib is None while the interpreter shuts down
             _lib.s3gd_destroy(self._h)
             self._h = None
 
@@ -276,7 +276,8 @@ class Context:
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
         return int(out[0]), int(out[1])
 
-    def profile_enable(self, on: bool = True):
+    def profile_enable(self, on: bool | int = True):
+        """True / 1: time every kernel; 2: only the passes over the gradients; False / 0: off."""
         self._check(_lib.s3gd_profile_enable(self._h, int(on)), "s3gd_profile_enable")
 
     def profile_read(self, stream=None) -> dict[str, tuple[float, int]]:

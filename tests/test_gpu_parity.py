@@ -268,3 +268,18 @@ def test_many_workers_every_tally_width(lib, M):
         assert_same(got, want, keys=("words", "counts", "x"), what=f"sparse M={M}")
         got = gpu_step(c, G, K, x, 0.5, fused=True, dense_outputs=True)
         assert_same(got, want, what=f"dense M={M}")
+
+
+@pytest.mark.parametrize("M,N,K", [(10, 500_000, 500), (100, 500_000, 25_000), (5, 850_000, 8_500), (50, 850_000, 42_500)])
+def test_paper_sized_models(lib, M, N, K):
+    """The paper's own sizes: its CNN (N = 5e5) and ResNet-56 (N = 8.5e5) with the worker counts and
+    sparsities of its cost comparison (Section 4), on the i.i.d. recipe.  Element by element."""
+    cfg = datagen.C1.scaled(M=M, N=N, K=K)
+    G = datagen.gradients(cfg)
+    x = datagen.params(cfg)
+    want = oracle_step(G, K, x, 1e-3)
+    with lib.Context(M, N, K, device=0) as c:
+        got = gpu_step(c, G, K, x, 1e-3, fused=True)
+        assert_same(got, want, what=f"M={M} N={N} K={K}")
+        got = gpu_step(c, G, K, x, 1e-3, fused=True, dense_outputs=False)
+        assert_same(got, want, keys=("words", "counts", "x"), what=f"sparse M={M} N={N} K={K}")
