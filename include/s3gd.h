@@ -275,7 +275,9 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
 
 /* Diagnostics of the last encode on this context, read back after synchronising `stream`:
  * out[0] = number of rows, out[1] = rows that took the general multi-pass path because the
- * single-pass candidate filter did not apply to them.  `out` is host memory, 2 entries. */
+ * single-pass candidate filter did not apply to them, out[2] = rows served by the single pass whose
+ * K-th magnitude lay far above the sampled bound (their radix select ran over all three levels of
+ * the candidates instead of the last).  `out` is host memory, 3 entries. */
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
 /*

@@ -35,7 +35,7 @@ Layout layout(u32 M, u64 N, u64 K) {
   Layout l{};
   size_t off = 0;
   l.rs = off;       off = align_up(off + sizeof(RowState) * (size_t)M, 256);
-  l.status = off;   off = align_up(off + sizeof(u32) * 4, 256);
+  l.status = off;   off = align_up(off + sizeof(u32) * 8, 256);
   l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
   l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * (vote_tiles(N) + 1), 256);
@@ -381,12 +381,13 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream) {
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out) {
   if (!ctx || !out) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
-  u32 st[3] = {0, 0, 0};
+  u32 st[5] = {0, 0, 0, 0, 0};
   hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
   if (e == hipSuccess) e = hipMemcpy(st, ctx->ws.status, sizeof(st), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_fail(ctx, e);
   out[0] = st[2];
   out[1] = st[1];
+  out[2] = st[4];
   return S3GD_OK;
 }
 

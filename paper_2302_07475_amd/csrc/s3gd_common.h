@@ -31,7 +31,7 @@ struct RowState {
   u32 q;          // entries with key == T that are selected (lowest indices first); 0 when T == 0
   u32 c_gt;       // entries with key > T
   u32 count;      // words the row emits = c_gt + q
-  u32 mode;       // kModeCandidates or kModeGeneral
+  u32 mode;       // kModeGeneral, kModeCandidates or kModeCandWide
   u32 L;          // candidate path: lower bound on the key of a candidate, a multiple of 1024
   u32 n_cand;     // candidate path: candidates collected by the filter pass
   u32 n_alloc;    // candidate path: candidate slots handed out to blocks (slab allocator)
@@ -41,7 +41,8 @@ struct RowState {
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
 
 constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
-constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, select among candidates
+constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, last ten key bits resolved among the candidates
+constexpr u32 kModeCandWide = 2;    // as above, but the K-th key lies far above the bound: full radix select among the candidates
 
 constexpr int kWaveTile = 64 * 4 * kLoads;  // 1024 entries: the unit of the candidate route (one wave, no barriers)
 constexpr u32 kSlabMin = 256;       // candidate slots a wave reserves at a time: a power of two chosen per call ...

@@ -11,10 +11,12 @@
 //                    K <= #{key >= L} <= capacity.  ONE pass over the row copies those candidates
 //                    (index, bits) into per-wave segments of a pool and histograms them; T is then
 //                    resolved and the words are emitted from the candidates alone.
+//                    If the K-th key lies far above L (a row whose magnitudes are spread widely
+//                    around the threshold) the radix select simply runs over the candidates.
 //   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
 //                    pass and an emit pass.  Any row for which the candidate route's checks fail
-//                    (too few or too many candidates, heavy ties, tiny rows) takes it; the choice
-//                    is made on the device, per row, with no host synchronisation.
+//                    (too few or too many candidates, tiny rows) takes it; the choice is made on
+//                    the device, per row, with no host synchronisation.
 #include <math.h>
 #include <stdlib.h>
 
@@ -74,38 +76,73 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
     s.mode = mode;
     s.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
     rs[m] = s;
-    if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; }
+    if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// General path, histogram pass of one radix level over the whole row.
+// The candidates of a row, as the filter pass left them: per wave of that pass a list of at most
+// kChain segments (first slot, count) of the row's pool.  Waves in order and segments in order
+// enumerate the candidates in ascending index.
+struct SegmentWalk {
+  const u64* segs;
+  u32 n_seg;
+  const uint2* pool;
+  __device__ SegmentWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
+                         u32 cand_stride, u32 m, u32 g, u32 n_waves)
+      : segs(wave_seg + ((size_t)m * wave_stride + g) * kChain), n_seg(g < n_waves ? wave_nseg[(size_t)m * wave_stride + g] : 0u),
+        pool(cand + (size_t)m * cand_stride) {
+    if (n_seg > (u32)kChain) n_seg = (u32)kChain;
+  }
+};
+
+// Histogram pass of one radix level (11 + 10 + 10 key bits, most significant first).
+//   general rows            over the whole row
+//   wide candidate rows     over the row's candidates, every level
+//   other candidate rows    over the candidates at the last level only: the filter pass has already
+//                           fixed the upper 21 bits
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
-                                                      u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status) {
+                                                      u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status,
+                                                      const uint2* __restrict__ cand, u32 cand_stride, const u64* __restrict__ wave_seg,
+                                                      const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves) {
   constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int SH = digit_shift(LEVEL);
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode != kModeGeneral) return;
+  if (st.mode == kModeCandidates && LEVEL != 2) return;
   __shared__ u32 h[NB];
   for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
   __syncthreads();
-  const float* row = grads + (size_t)m * N;
-  const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
-  const u32* rowv = reinterpret_cast<const u32*>(row) - a;
-  const u64 vend = N + a;
   bool nan = false;
-  for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    TileRegs r;
-    load_tile(rowv, a, vend, (u64)tile * kTile, r);
+  if (st.mode == kModeGeneral) {
+    const float* row = grads + (size_t)m * N;
+    const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
+    const u32* rowv = reinterpret_cast<const u32*>(row) - a;
+    const u64 vend = N + a;
+    for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+      TileRegs r;
+      load_tile(rowv, a, vend, (u64)tile * kTile, r);
 #pragma unroll
-    for (int i = 0; i < kLoads * 4; ++i) {
-      const u32 key = r.b[i] & 0x7FFFFFFFu;
-      bool take = (r.valid >> i) & 1u;
-      if (LEVEL == 0) nan |= take && key > 0x7F800000u;
-      if (LEVEL > 0) take = take && (key >> (SH + digit_bits(LEVEL))) == st.prefix;
-      if (take) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+      for (int i = 0; i < kLoads * 4; ++i) {
+        const u32 key = r.b[i] & 0x7FFFFFFFu;
+        bool take = (r.valid >> i) & 1u;
+        if (LEVEL == 0) nan |= take && key > 0x7F800000u;
+        if (LEVEL > 0) take = take && (key >> (SH + digit_bits(LEVEL))) == st.prefix;
+        if (take) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+      }
+    }
+  } else {  // one wave per segment list (the grid is the filter pass's)
+    const u32 lane = lane_id();
+    const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, blockIdx.x * kWaves + (threadIdx.x >> 6), n_waves);
+    for (u32 c = 0; c < sw.n_seg; ++c) {
+      const u64 sg = sw.segs[c];
+      const uint2* in = sw.pool + (u32)(sg >> 32);
+      const u32 cnt = (u32)sg;
+      for (u32 i = lane; i < cnt; i += 64) {
+        const u32 key = in[i].y & 0x7FFFFFFFu;
+        if (LEVEL == 0 || (key >> (SH + digit_bits(LEVEL))) == st.prefix) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+      }
     }
   }
   __syncthreads();
@@ -117,12 +154,13 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
 }
 
 // Picks the digit that holds the sought rank, narrows the prefix and clears the histogram.
-//   kResolveGeneral    levels 0..2 of the general route
+//   kResolveRadix      a level of the radix select filled by k_hist_rows: every level for general
+//                      and wide candidate rows, the last level for the other candidate rows
 //   kResolveSample     levels 0..1 over the sample: ends with L = 21-bit prefix << 10
 //   kResolveFilter     2048 bins of (key - L) >> 10 filled by the filter pass: checks the candidate
-//                      route and either fixes the 21-bit prefix or hands the row to the general route
-//   kResolveCandidates last 10 bits among the candidates
-enum { kResolveGeneral = 0, kResolveSample = 1, kResolveFilter = 2, kResolveCandidates = 3 };
+//                      route and fixes the 21-bit prefix, or starts a radix select over the
+//                      candidates (K-th key in the open top bin), or hands the row to the general route
+enum { kResolveRadix = 0, kResolveSample = 1, kResolveFilter = 2 };
 
 template <int LEVEL, int WHAT>
 __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K) {
@@ -130,7 +168,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
   RowState st = rs[m];
-  if ((WHAT == kResolveGeneral) != (st.mode == kModeGeneral)) return;
+  if (WHAT == kResolveRadix ? (st.mode == kModeCandidates && LEVEL != 2) : (st.mode != kModeCandidates)) return;
   __shared__ u32 lds[kWaves];
   u32* h = hist + (size_t)m * kHistBins;
   // thread 0 owns the highest bins
@@ -145,14 +183,15 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
   for (int i = 0; i < PER; ++i) h[top - i] = 0;
   const u32 k = WHAT == kResolveFilter ? K : st.k_rem;
   if (WHAT == kResolveFilter) {
-    // The candidate route stands only if no block ran out of room, the K-th largest key is among
-    // the candidates, and it does not sit in the open-ended top bin (thread 0's c[0]).
+    // The candidate route stands only if no wave ran out of room and the K-th largest key is among
+    // the candidates.  If it sits in the open-ended top bin (thread 0's c[0]) the bins say nothing
+    // about it: the radix select then starts over, among the candidates.
     __shared__ u32 verdict;
-    if (threadIdx.x == 0) verdict = !st.overflow && st.n_cand >= K && total == st.n_cand && c[0] < K;
+    if (threadIdx.x == 0) verdict = (!st.overflow && st.n_cand >= K && total == st.n_cand) ? (c[0] < K ? 2u : 1u) : 0u;
     __syncthreads();
-    if (!verdict) {
+    if (verdict != 2u) {
       if (threadIdx.x == 0) {
-        st.mode = kModeGeneral;
+        st.mode = verdict ? kModeCandWide : kModeGeneral;
         st.prefix = 0;
         st.k_rem = K;
         rs[m] = st;
@@ -226,8 +265,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__
 
 // In-place exclusive scan of a row's packed tile counts; entry n_tiles receives the row total.
 __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
-                                                           const RowState* __restrict__ rs, u32 mode) {
-  if (rs[blockIdx.x].mode != mode) return;
+                                                           const RowState* __restrict__ rs, u32 candidate_rows) {
+  if ((rs[blockIdx.x].mode != kModeGeneral) != (candidate_rows != 0)) return;
   __shared__ u64 lds[kScanBlock / 64];
   u64* t = tile_cnt + (size_t)blockIdx.x * tile_stride;
   u64 carry = 0;
@@ -629,49 +668,15 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
 }
 
-// The kernels below walk the candidates of a row in ascending index: one wave per segment list
-// (the list of the filter wave at the same position), segments in order, 64 candidates at a time.
-struct SegmentWalk {
-  const u64* segs;
-  u32 n_seg;
-  const uint2* pool;
-  __device__ SegmentWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
-                         u32 cand_stride, u32 m, u32 g, u32 n_waves)
-      : segs(wave_seg + ((size_t)m * wave_stride + g) * kChain), n_seg(g < n_waves ? wave_nseg[(size_t)m * wave_stride + g] : 0u),
-        pool(cand + (size_t)m * cand_stride) {
-    if (n_seg > (u32)kChain) n_seg = (u32)kChain;
-  }
-};
-
-// Last radix level among the candidates: histogram of key & 1023 where key >> 10 == prefix.
-// Only the few hundred candidates of the target bin touch the histogram.
-__global__ __launch_bounds__(kBlock) void k_cand_hist(const RowState* __restrict__ rs, u32* __restrict__ hist,
-                                                      const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
-                                                      u32 wave_stride, u32 n_waves) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
-  const u32 lane = lane_id();
-  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, blockIdx.x * kWaves + (threadIdx.x >> 6), n_waves);
-  for (u32 c = 0; c < sw.n_seg; ++c) {
-    const u64 sg = sw.segs[c];
-    const uint2* in = sw.pool + (u32)(sg >> 32);
-    const u32 cnt = (u32)sg;
-    for (u32 i = lane; i < cnt; i += 64) {
-      const u32 key = in[i].y & 0x7FFFFFFFu;
-      if ((key >> 10) == st.prefix) atomicAdd(&hist[(size_t)m * kHistBins + (key & 1023u)], 1u);
-    }
-  }
-}
-
+// The kernels below walk the candidates of a row in ascending index (SegmentWalk): one wave per
+// segment list, segments in order, 64 candidates at a time.
 // (eq << 32) | gt of each segment list against the final threshold; scanned afterwards.
 __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                        const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
                                                        u32 wave_stride, u32 n_waves, u64* __restrict__ wave_sum) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
+  if (st.mode == kModeGeneral) return;
   const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
   u32 gt = 0, eq = 0;
@@ -698,7 +703,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
                                                       u32* __restrict__ words, float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
+  if (st.mode == kModeGeneral) return;
   const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
   if (sw.n_seg == 0) return;  // wave-uniform
@@ -741,6 +746,7 @@ __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __res
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     counts[m] = st.count;
     if (st.mode == kModeGeneral) atomicAdd(&status[1], 1u);
+    if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
   }
   u32* out = words + (size_t)m * K;
   for (u64 i = (u64)st.count + blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x)
@@ -853,7 +859,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                          p.candidates ? p.gx * (u32)kWaves * p.slab : 0u)));
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles;
-    const u32 n_waves = p.gx * (u32)kWaves, wstride = wave_stride(p.gx);
+    const u32 wstride = wave_stride(p.gx);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
@@ -868,25 +874,28 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                       ws.wave_seg, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
                                                                       p.slab, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    // one wave per segment list
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_hist<<<grid, kBlock, 0, s>>>(ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg,
-                                                                     wstride, n_waves)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveCandidates><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+  }
+  // Radix select: over the row for general rows, over the candidates for the others (the last level
+  // only, unless the filter's bins could not place the K-th key).
+  const u32 n_waves = p.candidates ? p.gx * (u32)kWaves : 0u, wstride = wave_stride(p.gx);
+#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves
+  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+#undef S3GD_HIST_ARGS
+  if (p.candidates) {  // one wave per segment list
     S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                       n_waves, ws.wave_sum)));
-    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, kModeCandidates)));
+    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, 1u)));
     S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
   }
-  // General route: every kernel returns at once for rows the candidate route has served.
-  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.hist, n_tiles, ws.status)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveGeneral><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+  // General rows: per-tile counts and the emit pass (both return at once for the other rows).
   S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
-  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, kModeGeneral)));
+  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, 0u)));
   S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words, err)));
   u32 fx = (u32)((K + 4095) / 4096);
   if (fx > 64) fx = 64;

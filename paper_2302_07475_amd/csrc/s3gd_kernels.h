@@ -51,7 +51,8 @@ constexpr u32 kCodingCapacity = 2;  // an output buffer was too small for the ve
 struct Workspace {
   Profiler* prof;
   RowState* rs;   // [M]
-  u32* status;    // [4]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags
+  u32* status;    // [8]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags,
+                  //      4 = candidate rows whose radix select ran over all levels
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][vote_tiles + 1]

@@ -78,7 +78,7 @@ __device__ __forceinline__ u32 permute(u32 i, u64 N, const PermKey& p) {
 __global__ void k_randk_clear(u32* __restrict__ bucket, u32 nb, u32 bstride, u32* __restrict__ status, u32 M) {
   const u32 m = blockIdx.y;
   for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += gridDim.x * blockDim.x) bucket[(size_t)m * bstride + i] = 0;
-  if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { status[0] = 0; status[1] = 0; status[2] = M; }
+  if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; }
 }
 
 // SCATTER = false: count the non-zero selected entries of each bucket.

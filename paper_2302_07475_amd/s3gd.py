@@ -272,9 +272,14 @@ class Context:
         return int(_lib.s3gd_last_async_status(self._h, _stream(stream)))
 
     def last_encode_info(self, stream=None) -> tuple[int, int]:
-        out = (_u32 * 2)()
+        """(rows, rows on the general multi-pass route)."""
+        return self.last_encode_details(stream)[:2]
+
+    def last_encode_details(self, stream=None) -> tuple[int, int, int]:
+        """(rows, rows on the general route, single-pass rows that needed the full radix select)."""
+        out = (_u32 * 3)()
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
-        return int(out[0]), int(out[1])
+        return int(out[0]), int(out[1]), int(out[2])
 
     def profile_enable(self, on: bool | int = True):
         """True / 1: time every kernel; 2: only the passes over the gradients; False / 0: off."""

@@ -283,3 +283,44 @@ def test_paper_sized_models(lib, M, N, K):
         assert_same(got, want, what=f"M={M} N={N} K={K}")
         got = gpu_step(c, G, K, x, 1e-3, fused=True, dense_outputs=False)
         assert_same(got, want, keys=("words", "counts", "x"), what=f"sparse M={M} N={N} K={K}")
+
+
+def _banded_rows(N, K, band, rng):
+    """Rows whose K largest magnitudes all sit in one narrow band (a layer with a far larger scale)."""
+    G = (rng.standard_normal((3, N)) * 0.01).astype(np.float32)
+    starts = [0, N // 2 - band // 2, N - band]
+    for m, s in enumerate(starts):
+        G[m, s:s + band] = (rng.standard_normal(band) * 5.0 + np.sign(rng.standard_normal(band)) * 3.0).astype(np.float32)
+    return G
+
+
+def test_skewed_rows_grow_their_segment_lists(ctx):
+    """All candidates of a row come from a few waves of the single pass: those waves fill their first
+    slab and reserve more (twice as large each time); the row stays on the candidate route."""
+    from oracle import s3gd_oracle as O
+    rng = np.random.default_rng(11)
+    N, K, band = 1 << 21, 20_971, 32_768
+    G = _banded_rows(N, K, band, rng)
+    words, counts, rows, general = _encode_only(ctx, G, K)
+    w, c = O.topk_sign_encode(G, K)
+    assert np.array_equal(counts, c) and np.array_equal(words, w)
+    # the magnitudes are spread widely around the threshold: the K-th lies far above the sampled
+    # bound, so the radix select runs over all levels, but over the candidates, not over the row
+    assert ctx.last_encode_details() == (3, 0, 3)
+    idx = (w[1] >> 1).astype(np.int64)
+    assert idx.min() >= N // 2 - band // 2 and idx.max() < N // 2 + band // 2, "the recipe is meant to put every selected entry in the band"
+
+
+def test_few_waves_long_segment_chains(lib, monkeypatch):
+    """With a grid of four blocks a wave covers 131072 entries, so a banded row makes one wave hold
+    thousands of candidates against a first slab of 256: the chain 256, 256, 512, 1024, ... is walked."""
+    from oracle import s3gd_oracle as O
+    monkeypatch.setenv("S3GD_STREAM_BLOCKS", "4")
+    rng = np.random.default_rng(12)
+    N, K, band = 1 << 21, 2_097, 8_192
+    G = _banded_rows(N, K, band, rng)[:1]
+    with lib.Context(1, N, K, device=0) as c:
+        words, counts, rows, general = _encode_only(c, G, K)
+        assert c.last_encode_details()[1] == 0
+    w, cc = O.topk_sign_encode(G, K)
+    assert np.array_equal(counts, cc) and np.array_equal(words, w)
