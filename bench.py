@@ -79,6 +79,10 @@ def main():
                     help="capture the step into a HIP graph once and time replays (the same kernels, fewer launch gaps)")
     ap.add_argument("--momentum", action="store_true",
                     help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
+    ap.add_argument("--dense-state", action="store_true",
+                    help="with --momentum: start from a momentum vector without zeros, as it is after some hundred "
+                         "steps of training (every coordinate is then read, updated and written each step); without "
+                         "this flag the vector starts at zero, as in the first steps, and stays as sparse as the votes")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (all M workers are rows of one tensor); --gpus must be 1")
@@ -116,6 +120,11 @@ def main():
     err = torch.zeros((M, N), dtype=torch.float32, device=dev) if args.memory else None
 
     mom = torch.zeros((N,), dtype=torch.float32, device=dev) if args.momentum else None
+    if args.momentum and args.dense_state:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1234)
+        mom.normal_(0.0, 1.0, generator=gen)
+        mom[mom == 0] = 1.0
 
     packed = w2 = c2 = None
     if args.wire:
@@ -210,7 +219,8 @@ def main():
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
                    "entry": "s3gd_step_randk (Algorithm 2)" if args.randk else
                             "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
-                            ("s3gd_step_momentum (mu=0.9" + (", with memory)" if args.memory else ")")) if args.momentum else
+                            ("s3gd_step_momentum (mu=0.9" + (", with memory" if args.memory else "") +
+                             (", dense momentum state)" if args.dense_state else ", momentum starts at zero)")) if args.momentum else
                             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows, "launch": "HIP graph replay" if args.graph else "eager"},

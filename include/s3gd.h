@@ -119,7 +119,7 @@ S3GD_API int s3gd_majority_vote(s3gd_ctx* ctx, const uint32_t* words, const uint
  *
  *   x      dev, in/out  [N] fp32, 16-byte aligned.
  *   votes  dev, const   [N] int8 in {-1, 0, +1}, 16-byte aligned.
- *   lr     step size delta >= 0, finite.
+ *   lr     step size delta >= 0, finite (negative zero is refused).
  */
 S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, float lr, uint64_t N,
                       s3gd_stream_t stream);
@@ -171,7 +171,7 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
  *   x, v   dev, in/out  [N] fp32, 16-byte aligned.  v is the momentum state; zero-fill it before
  *                       the first iteration.
  *   votes  dev, const   [N] int8 in {-1, 0, +1}, 16-byte aligned.
- *   lr, mu finite and >= 0.
+ *   lr, mu finite and >= 0 (negative zero is refused).
  */
 S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const int8_t* votes, float lr, float mu,
                                uint64_t N, s3gd_stream_t stream);

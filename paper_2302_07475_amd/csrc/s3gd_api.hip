@@ -38,7 +38,7 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.status = off;   off = align_up(off + sizeof(u32) * 8, 256);
   l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
-  l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * (vote_tiles(N) + 1), 256);
+  l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * seg_row_entries(N), 256);
   l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M) * kChain, 256);
   l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M), 256);
   l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M), 256);
@@ -168,11 +168,16 @@ S3GD_API int s3gd_majority_vote(s3gd_ctx* ctx, const uint32_t* words, const uint
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
+// A step size or momentum factor: finite and >= 0.  Negative zero is refused as well: with it
+// lr * 0 is -0.0 and x - (-0.0) turns a parameter of -0.0 into +0.0, so "a coordinate without a
+// vote and without momentum keeps its bits" would no longer hold.
+static bool step_size_ok(float a) { return a >= 0.0f && !std::isinf(a) && !std::signbit(a); }
+
 S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, float lr, uint64_t N, s3gd_stream_t stream) {
   if (!ctx || !x || !votes || N == 0) return S3GD_E_INVAL;
   if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
   if (N > ctx->N_max) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
   if (!aligned(x, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
@@ -185,7 +190,7 @@ S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N
   const int rc = check_shape(ctx, M, N, K);
   if (rc) return rc;
   if (!grads || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
   if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) ||
       !aligned(votes, 16))
     return S3GD_E_INVAL;
@@ -230,7 +235,7 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
   if (rc) return rc;
   if ((rc = check_memory_args(grads, err, eta, M, N))) return rc;
   if (!x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
   if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
@@ -247,7 +252,7 @@ S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const
   if (!ctx || !x || !v || !votes || N == 0) return S3GD_E_INVAL;
   if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
   if (N > ctx->N_max) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr) || !(mu >= 0.0f) || isinf(mu)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr) || !step_size_ok(mu)) return S3GD_E_INVAL;
   if (!aligned(x, 16) || !aligned(v, 16) || !aligned(votes, 16)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
@@ -265,7 +270,7 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
     return S3GD_E_INVAL;
   }
   if (!x || !v || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr) || !(mu >= 0.0f) || isinf(mu)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr) || !step_size_ok(mu)) return S3GD_E_INVAL;
   if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(v, 16)) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
@@ -294,7 +299,7 @@ S3GD_API int s3gd_step_randk(s3gd_ctx* ctx, const float* grads, uint32_t M, uint
   const int rc = check_shape(ctx, M, N, K);
   if (rc) return rc;
   if (!grads || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
   if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) ||
       !aligned(votes, 16))
     return S3GD_E_INVAL;
@@ -313,7 +318,7 @@ S3GD_API int s3gd_vote_update(s3gd_ctx* ctx, const uint32_t* words, const uint32
   const int rc = check_shape(ctx, M, N, K);
   if (rc) return rc;
   if (!counts || (K > 0 && !words) || !x) return S3GD_E_INVAL;
-  if (!(lr >= 0.0f) || isinf(lr)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
   if (!aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16)) return S3GD_E_INVAL;
   if (K == 0) return S3GD_OK;  // nobody votes, nothing moves
   DeviceGuard g(ctx->device);

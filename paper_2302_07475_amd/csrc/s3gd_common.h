@@ -17,6 +17,7 @@ constexpr int kLoads = 4;                   // 16-byte loads per thread and tile
 constexpr int kTile = kBlock * 4 * kLoads;  // 4096 gradient entries per tile
 constexpr int kHistBins = 2048;             // first radix digit: key bits [30:20]
 constexpr int kVoteTile = 8192;             // coordinates tallied in LDS by one block
+constexpr unsigned kMomTile = 4096;         // coordinates one wave of the momentum sweep owns (the finest vote tiling)
 constexpr int kScanBlock = 1024;
 
 // Radix digits of the 31-bit magnitude key, most significant first.
@@ -60,6 +61,14 @@ __device__ __forceinline__ u32 ballot_rank(u64 b) {
   return __builtin_amdgcn_mbcnt_hi((u32)(b >> 32), __builtin_amdgcn_mbcnt_lo((u32)b, 0u));
 }
 __device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// Orders the LDS accesses of the lanes of one wave: what a lane wrote before is visible to every
+// lane after (a wave executes its LDS instructions in order; the fences only bind the compiler).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 template <typename T>
 __device__ __forceinline__ T wave_incl_scan(T v) {

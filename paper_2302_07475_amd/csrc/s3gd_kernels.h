@@ -14,7 +14,8 @@ inline u32 wave_stride(u32 gx) { return gx * kWaves + 4; }  // per-row stride of
 // entries of the per-wave tables: gx * M <= max(resident blocks, M) for every launch
 inline size_t wave_table_entries(u32 M_max) { return (size_t)(kMaxStreamBlocks + M_max) * kWaves + 4 * (size_t)M_max; }
 inline u32 coding_blk_stride(u64 N) { return 2 * tile_stride(N); }  // u32 entries per row when tile_cnt serves the coding kernels
-inline u32 vote_tiles(u64 N) { return (u32)((N + kVoteTile - 1) / kVoteTile); }
+// entries per row of the segment table: one per tile of the finest tiling, plus the end
+inline size_t seg_row_entries(u64 N) { return (size_t)((N + kMomTile - 1) / kMomTile) + 1; }
 
 // Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
 enum KernelId : int {
@@ -55,7 +56,7 @@ struct Workspace {
                   //      4 = candidate rows whose radix select ran over all levels
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
-  u32* seg;       // [M][vote_tiles + 1]
+  u32* seg;       // [M][tiles of the launch's tiling + 1], at most seg_row_entries(N) per row
   u64* blk_sum;   // [M][blk_stride]   scratch of the random-K scan
   u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment a filter wave left
   u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each wave's list

@@ -25,14 +25,6 @@
 
 namespace s3gd {
 
-// Orders the LDS accesses of the lanes of one wave: what a lane wrote before is visible to every
-// lane after (a wave executes its LDS instructions in order; the fences only bind the compiler).
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 constexpr int kRounds = 6;
 constexpr u32 kBucketShift = 11;
 constexpr u32 kBucket = 1u << kBucketShift;  // coordinates per bucket

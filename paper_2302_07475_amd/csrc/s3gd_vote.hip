@@ -257,19 +257,21 @@ __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, 
 //   v <- mu * v + vote,  x <- x - lr * v,
 // every operation rounded once in fp32 (no fused multiply-add).  Unlike the plain update this one
 // moves every coordinate whose momentum is non-zero, so v is streamed in full; x is read and both
-// are written only for groups of four coordinates that hold a vote or a non-zero momentum (a group
-// of +0.0 momenta without votes stays exactly as it is: mu * 0 + 0 = 0 and x - lr * 0 = x).
+// are written only for runs of 16 coordinates (64 bytes) that hold a vote or a non-zero momentum (a
+// coordinate with +0.0 momentum and no vote stays exactly as it is: mu * 0 + 0 = 0, x - lr * 0 = x).
+// Whole 64-byte runs, not the 16 bytes of one lane: memory merges a smaller write by reading first.
 __device__ __forceinline__ void momentum_apply(float& x, float& v, int s, float lr, float mu) {
   v = __fadd_rn(__fmul_rn(mu, v), (float)s);
   x = __fsub_rn(x, __fmul_rn(lr, v));
 }
 
-// Four consecutive coordinates whose momenta `vv` are already loaded.
+// Four consecutive coordinates whose momenta `vv` are already loaded; consecutive lanes hold
+// consecutive groups.
 __device__ __forceinline__ void momentum_group4(float* __restrict__ x, float* __restrict__ v, u64 n, float4 vv, const int (&s)[4],
                                                 float lr, float mu) {
   const u32 any = __float_as_uint(vv.x) | __float_as_uint(vv.y) | __float_as_uint(vv.z) | __float_as_uint(vv.w) |
                   (u32)(s[0] | s[1] | s[2] | s[3]);
-  if (any == 0) return;
+  if (((ballot(any != 0) >> (lane_id() & 60u)) & 0xFull) == 0) return;  // nothing to do in these 64 bytes
   float4 xv = *reinterpret_cast<const float4*>(x + n);
   momentum_apply(xv.x, vv.x, s[0], lr, mu);
   momentum_apply(xv.y, vv.y, s[1], lr, mu);
@@ -296,52 +298,142 @@ __device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __r
   else momentum_tail(x, v, n, N, s, lr, mu);
 }
 
-constexpr int kSweep = 4;  // groups of four coordinates a thread has in flight in the momentum sweep
+// ---- the fused vote + momentum sweep -----------------------------------------------------------
+// One wave owns kMomTile consecutive coordinates and nothing is shared between waves: no block-wide
+// barrier, a block is just four independent waves, and one block per 16384 coordinates is launched
+// in coordinate order, so that the running blocks cover a compact window of x and v (a read-modify-
+// write stream is measurably faster that way than with far-apart persistent streams).  A wave
+//   1. issues the loads of its momenta (nothing depends on them before step 4),
+//   2. fills its slice of the packed LDS tally, fetches the segment bounds of all rows (one row per
+//      lane) and flattens the messages of its tile into one numbering, so that every lane fetches
+//      its messages with independent loads instead of one dependent load per row,
+//   3. adds the messages into the tally,
+//   4. sweeps: per group of four coordinates, skip if all four momenta are +0.0 and nobody voted
+//      (mu * 0 + 0 = 0 and x - lr * 0 = x), else fetch x, update, store both.
+constexpr int kMomRounds = 4;                      // groups of four coordinates a lane has in flight
+constexpr u32 kMomBatch = 256u * kMomRounds;       // coordinates of a wave per batch of rounds
+constexpr int kMomBatches = kMomTile / kMomBatch;  // batches per tile; the momenta of the next are fetched a batch ahead
+constexpr int kMomPass = 4;     // messages a lane fetches before it adds them to the tally
 
-// Tally in packed LDS fields as in k_vote_sparse, then one dense sweep over the tile.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream_f4(const float* p) {
+  const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(q.x, q.y, q.z, q.w);
+}
+__device__ __forceinline__ void store_stream_f4(float* p, float4 a) {
+  f32x4 q;
+  q.x = a.x; q.y = a.y; q.z = a.z; q.w = a.w;
+  __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
+}
+
 template <int FB>
 __global__ __launch_bounds__(kBlock) void k_vote_momentum(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
                                                           u32 seg_stride, u32 M, u64 N, u32 n_vt, float* __restrict__ x,
                                                           float* __restrict__ v, float lr, float mu) {
   typedef VoteField<FB> F;
-  __shared__ __attribute__((aligned(16))) u32 t[kVoteWords];
-  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
-  for (u32 tile = blockIdx.x; tile < n_vt; tile += gridDim.x) {
-    const u64 base = (u64)tile * F::kTile;
-    for (int i = threadIdx.x * 4; i < kVoteWords; i += kBlock * 4) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
-    for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
-      __syncthreads();
-      load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
-      __syncthreads();
-      const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
-      vote_rows<FB, 0>(words, K, m0, rows, lo, hi, t, base, N, x, lr);
+  constexpr u32 kSlice = kMomTile / F::kPer;  // LDS words of one wave's tally
+  __shared__ __attribute__((aligned(16))) u32 lds[kWaves * kSlice];
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 tile = blockIdx.x * kWaves + wave;
+  if (tile >= n_vt) return;  // whole waves leave; nothing below synchronises across waves
+  u32* t = lds + wave * kSlice;
+  const u64 base = (u64)tile * kMomTile;
+
+  float4 vv[kMomRounds];
+#pragma unroll
+  for (int u = 0; u < kMomRounds; ++u) {
+    const u64 n = base + (u32)u * 256u + lane * 4u;
+    vv[u] = n + 4 <= N ? load_stream_f4(v + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (u32 i = lane * 4; i < kSlice; i += 256) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
+  wave_sync();
+
+  for (u32 m0 = 0; m0 < M; m0 += 64) {
+    const u32 rows = M - m0 < 64u ? M - m0 : 64u;
+    u32 lo = 0, cnt = 0;
+    if (lane < rows) {
+      const u32* sg = seg + (size_t)(m0 + lane) * seg_stride + tile;
+      lo = sg[0];
+      const u32 hi = sg[1];
+      cnt = hi > lo ? hi - lo : 0u;
     }
-    __syncthreads();
-    // the sweep: kSweep groups of four coordinates per thread and round, their momenta loaded first
-    for (u32 c0 = threadIdx.x * 4; c0 < F::kTile; c0 += kBlock * 4 * kSweep) {
-      float4 vv[kSweep];
+    const u32 incl = wave_incl_scan(cnt);
+    const u32 first = incl - cnt;  // number of this row's first message in the tile's flat numbering
+    const u32 total = __builtin_amdgcn_readlane(incl, 63);
+    for (u32 j0 = 0; j0 < total; j0 += 64u * kMomPass) {
+      size_t at[kMomPass];
 #pragma unroll
-      for (int u = 0; u < kSweep; ++u) {
-        const u64 n = base + c0 + (u32)u * kBlock * 4;
-        vv[u] = (c0 + (u32)u * kBlock * 4 < F::kTile && n + 4 <= N) ? *reinterpret_cast<const float4*>(v + n) : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
+      for (int p = 0; p < kMomPass; ++p) at[p] = ~(size_t)0;
+      for (u32 r = 0; r < rows; ++r) {  // r is wave-uniform: the three values come from lane r
+        const u32 rf = __builtin_amdgcn_readlane(first, r), rc = __builtin_amdgcn_readlane(cnt, r),
+                  rl = __builtin_amdgcn_readlane(lo, r);
+        if (rc == 0) continue;
 #pragma unroll
-      for (int u = 0; u < kSweep; ++u) {
-        const u32 c = c0 + (u32)u * kBlock * 4;
-        const u64 n = base + c;
-        if (c >= F::kTile || n >= N) break;
-        int s[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const u32 f = (t[(c + e) / F::kPer] >> (((c + e) % F::kPer) * FB)) & (F::kFlag - 1u);
-          const int d = (int)f - (int)F::kBias;
-          s[e] = (d > 0) - (d < 0);
+        for (int p = 0; p < kMomPass; ++p) {
+          const u32 d = j0 + (u32)p * 64u + lane - rf;  // wraps to a huge value for messages of earlier rows
+          if (d < rc) at[p] = (size_t)(m0 + r) * K + rl + d;
         }
-        if (n + 4 <= N) momentum_group4(x, v, n, vv[u], s, lr, mu);
-        else momentum_tail(x, v, n, N, s, lr, mu);
+      }
+      u32 wd[kMomPass];
+#pragma unroll
+      for (int p = 0; p < kMomPass; ++p) wd[p] = at[p] != ~(size_t)0 ? words[at[p]] : S3GD_PAD;
+#pragma unroll
+      for (int p = 0; p < kMomPass; ++p) {
+        const u32 c = (u32)((u64)(wd[p] >> 1) - base);
+        if (wd[p] == S3GD_PAD || c >= kMomTile || base + c >= N) continue;  // the last two never hold for sorted rows
+        const u32 sh = (c % F::kPer) * FB;
+        atomicAdd(&t[c / F::kPer], (wd[p] & 1u) ? (0u - (1u << sh)) : (1u << sh));
       }
     }
-    __syncthreads();  // the sweep has read every field before they are refilled
+  }
+  wave_sync();
+
+  for (int bt = 0; bt < kMomBatches; ++bt) {
+    const u32 c0 = (u32)bt * kMomBatch + lane * 4u;
+    float4 nv[kMomRounds];  // the next batch's momenta, requested before this batch waits for anything
+#pragma unroll
+    for (int u = 0; u < kMomRounds; ++u) {
+      const u64 n = base + c0 + kMomBatch + (u32)u * 256u;
+      nv[u] = (bt + 1 < kMomBatches && n + 4 <= N) ? load_stream_f4(v + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    int sg[kMomRounds][4];
+    bool live[kMomRounds];
+    float4 xv[kMomRounds];
+#pragma unroll
+    for (int u = 0; u < kMomRounds; ++u) {
+      const u32 c = c0 + (u32)u * 256u;
+      const u64 n = base + c;
+      u32 any = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const u32 f = (t[(c + e) / F::kPer] >> (((c + e) % F::kPer) * FB)) & (F::kFlag - 1u);
+        const int d = (int)f - (int)F::kBias;
+        sg[u][e] = (d > 0) - (d < 0);
+        any |= (u32)sg[u][e];
+      }
+      any |= __float_as_uint(vv[u].x) | __float_as_uint(vv[u].y) | __float_as_uint(vv[u].z) | __float_as_uint(vv[u].w);
+      // four lanes share 64 bytes of v and of x: if one of them has work, all four rewrite their part
+      // (the same bits where nothing moves), so that memory sees whole 64-byte writes and not 16-byte
+      // pieces, which it would have to merge by reading first (measured: 10 % to 30 % of the sweep
+      // while the momentum is sparse; groups of 8 lanes do the same, 16 lanes lose)
+      const bool line = ((ballot(any != 0) >> (lane & 60u)) & 0xFull) != 0;
+      live[u] = line && n + 4 <= N;
+      if (live[u]) xv[u] = load_stream_f4(x + n);
+      if (n < N && n + 4 > N) momentum_tail(x, v, n, N, sg[u], lr, mu);  // the one group that straddles the end
+    }
+#pragma unroll
+    for (int u = 0; u < kMomRounds; ++u) {
+      if (live[u]) {
+        const u64 n = base + c0 + (u32)u * 256u;
+        momentum_apply(xv[u].x, vv[u].x, sg[u][0], lr, mu);
+        momentum_apply(xv[u].y, vv[u].y, sg[u][1], lr, mu);
+        momentum_apply(xv[u].z, vv[u].z, sg[u][2], lr, mu);
+        momentum_apply(xv[u].w, vv[u].w, sg[u][3], lr, mu);
+        store_stream_f4(v + n, vv[u]);
+        store_stream_f4(x + n, xv[u]);
+      }
+      vv[u] = nv[u];
+    }
   }
 }
 
@@ -366,13 +458,12 @@ hipError_t launch_vote_momentum(const Workspace& ws, const u32* words, const u32
                                 float lr, float mu, hipStream_t s) {
   Profiler& P = *ws.prof;
   const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
-  const u32 tile_coords = (u32)kVoteWords * (32u / fb);
-  const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);
+  const u32 n_vt = (u32)((N + kMomTile - 1) / kMomTile);
   const u32 stride = n_vt + 1;
   P.begin(KID_SEG_BOUNDS, s);
-  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, tile_coords, ws.seg);
+  k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, kMomTile, ws.seg);
   P.end(s);
-  const u32 g = n_vt < ws.stream_blocks ? n_vt : ws.stream_blocks;
+  const u32 g = (n_vt + kWaves - 1) / kWaves;
   P.begin(KID_VOTE_MOMENTUM, s);
   if (fb == 8) k_vote_momentum<8><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, v, lr, mu);
   else if (fb == 16) k_vote_momentum<16><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, x, v, lr, mu);
@@ -398,7 +489,7 @@ hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts,
   const bool dense = tally || votes;
   const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
   const u32 tile_coords = dense ? (u32)kVoteTile : (u32)kVoteWords * (32u / fb);
-  const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);  // at most vote_tiles(N): the scratch row fits
+  const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);  // a tiling no finer than kMomTile: the table row fits
   const u32 stride = n_vt + 1;
   P.begin(KID_SEG_BOUNDS, s);
   k_seg_bounds<<<dim3((n_vt + 1 + 255) / 256, M), 256, 0, s>>>(words, counts, K, n_vt, stride, tile_coords, ws.seg);

@@ -113,6 +113,7 @@ def test_ragged_sizes_and_special_momenta(ctx, N):
     v[::7] = -0.0
     v[::11] = np.float32(3e-45)
     v[::13] = np.float32(1e38)
+    x[::5] = -0.0  # a parameter of -0.0 keeps its sign where nothing moves it
     for K in sorted({0, 1, N // 2, N}):
         want = O.step_with_momentum(G, K, x, v, 0.01, 0.75)
         xd, vd = _dev(x), _dev(v)
@@ -152,6 +153,8 @@ def test_argument_errors(ctx, lib):
     assert r.s3gd_apply_update_momentum(h, p(x), None, p(votes), 0.1, 0.9, 100, None) == lib.E_INVAL
     assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), 0.1, -0.1, 100, None) == lib.E_INVAL
     assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), 0.1, float("nan"), 100, None) == lib.E_INVAL
+    assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), -0.0, 0.9, 100, None) == lib.E_INVAL  # negative zero
+    assert r.s3gd_apply_update_momentum(h, p(x), p(v), p(votes), 0.1, -0.0, 100, None) == lib.E_INVAL
     assert r.s3gd_apply_update_momentum(h, p(x), ctypes.c_void_p(v.data_ptr() + 4), p(votes), 0.1, 0.9, 90, None) == lib.E_INVAL
     torch.cuda.synchronize()
     assert float(x.abs().sum()) == 0.0 and float(v.abs().sum()) == 0.0
