@@ -39,9 +39,9 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
   l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * seg_row_entries(N), 256);
-  l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M) * kChain, 256);
-  l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M), 256);
-  l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M), 256);
+  l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N) * kChain, 256);
+  l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M, N), 256);
+  l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N), 256);
   l.blk_sum = off;  off = align_up(off + sizeof(u64) * (size_t)M * blk_stride(N), 256);
   l.cand_pool = candidate_pool_entries(M, N, K);
   l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);

@@ -46,6 +46,7 @@ constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, las
 constexpr u32 kModeCandWide = 2;    // as above, but the K-th key lies far above the bound: full radix select among the candidates
 
 constexpr int kWaveTile = 64 * 4 * kLoads;  // 1024 entries: the unit of the candidate route (one wave, no barriers)
+constexpr int kChunkTiles = 2;      // wave tiles a wave of the chunked filter pass holds: a block covers 8192 entries
 constexpr u32 kSlabMin = 256;       // candidate slots a wave reserves at a time: a power of two chosen per call ...
 constexpr u32 kSlabMax = 1u << 16;  // ... between these, from the candidates expected per wave
 constexpr int kChain = 8;           // segments (slabs) a wave of the filter pass may leave behind

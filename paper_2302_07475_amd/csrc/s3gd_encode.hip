@@ -81,20 +81,41 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
 }
 
 // ------------------------------------------------------------------------------------------------
-// The candidates of a row, as the filter pass left them: per wave of that pass a list of at most
-// kChain segments (first slot, count) of the row's pool.  Waves in order and segments in order
-// enumerate the candidates in ascending index.
-struct SegmentWalk {
-  const u64* segs;
-  u32 n_seg;
+// The candidates of a row, as the filter pass left them: a table of segment lists, each of at most
+// kChain segments (first slot, count) of the row's pool.  Lists in order and segments in order
+// enumerate the candidates in ascending index.  A ListWalk numbers the candidates of one list
+// 0 .. total-1 across its segments, so that a wave takes them 64 (or more) at a time whatever the
+// segment lengths are: a list may be two long slabs or eight short runs.
+struct ListWalk {
+  u32 first[kChain], count[kChain], slot[kChain];  // flat number of a segment's first candidate, its length, its first slot
+  u32 total;
   const uint2* pool;
-  __device__ SegmentWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
-                         u32 cand_stride, u32 m, u32 g, u32 n_waves)
-      : segs(wave_seg + ((size_t)m * wave_stride + g) * kChain), n_seg(g < n_waves ? wave_nseg[(size_t)m * wave_stride + g] : 0u),
-        pool(cand + (size_t)m * cand_stride) {
-    if (n_seg > (u32)kChain) n_seg = (u32)kChain;
+  __device__ ListWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
+                      u32 cand_stride, u32 m, u32 g)
+      : total(0), pool(cand + (size_t)m * cand_stride) {
+    const u64* segs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
+    const u32 n_seg = wave_nseg[(size_t)m * wave_stride + g];
+#pragma unroll
+    for (int c = 0; c < kChain; ++c) {
+      const u64 sg = segs[c];  // the whole line is loaded; entries past n_seg are stale
+      slot[c] = (u32)(sg >> 32);
+      count[c] = (u32)c < n_seg ? (u32)sg : 0u;
+      first[c] = total;
+      total += count[c];
+    }
+  }
+  // pool slot of candidate j < total
+  __device__ __forceinline__ u32 locate(u32 j) const {
+    u32 at = 0;
+#pragma unroll
+    for (int c = 0; c < kChain; ++c) {
+      const u32 d = j - first[c];  // wraps to a huge value for candidates of earlier segments
+      if (d < count[c]) at = slot[c] + d;
+    }
+    return at;
   }
 };
+constexpr int kWalk = 4;  // candidates a lane has in flight where their order does not matter
 
 // Histogram pass of one radix level (11 + 10 + 10 key bits, most significant first).
 //   general rows            over the whole row
@@ -132,16 +153,21 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
         if (take) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
       }
     }
-  } else {  // one wave per segment list (the grid is the filter pass's)
+  } else {  // a wave per segment list
     const u32 lane = lane_id();
-    const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, blockIdx.x * kWaves + (threadIdx.x >> 6), n_waves);
-    for (u32 c = 0; c < sw.n_seg; ++c) {
-      const u64 sg = sw.segs[c];
-      const uint2* in = sw.pool + (u32)(sg >> 32);
-      const u32 cnt = (u32)sg;
-      for (u32 i = lane; i < cnt; i += 64) {
-        const u32 key = in[i].y & 0x7FFFFFFFu;
-        if (LEVEL == 0 || (key >> (SH + digit_bits(LEVEL))) == st.prefix) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+    for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {
+      const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+      for (u32 i0 = lane; i0 < lw.total; i0 += 64 * kWalk) {
+        u32 key[kWalk];
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+          const u32 j = i0 + (u32)u * 64u;
+          key[u] = j < lw.total ? (lw.pool[lw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u)
+          if (key[u] != 0xFFFFFFFFu && (LEVEL == 0 || (key[u] >> (SH + digit_bits(LEVEL))) == st.prefix))
+            atomicAdd(&h[(key[u] >> SH) & (NB - 1)], 1u);
       }
     }
   }
@@ -163,7 +189,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
 enum { kResolveRadix = 0, kResolveSample = 1, kResolveFilter = 2 };
 
 template <int LEVEL, int WHAT>
-__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K) {
+__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins) {
   constexpr int NB = WHAT == kResolveFilter ? kHistBins : (1 << digit_bits(LEVEL));
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
@@ -187,7 +213,10 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
     // the candidates.  If it sits in the open-ended top bin (thread 0's c[0]) the bins say nothing
     // about it: the radix select then starts over, among the candidates.
     __shared__ u32 verdict;
-    if (threadIdx.x == 0) verdict = (!st.overflow && st.n_cand >= K && total == st.n_cand) ? (c[0] < K ? 2u : 1u) : 0u;
+    // (A filter pass in chunks fills no bins: its candidates are the slots it handed out.)
+    if (!have_bins) st.n_cand = st.n_alloc;
+    if (threadIdx.x == 0)
+      verdict = (!st.overflow && st.n_cand >= K && (!have_bins || total == st.n_cand)) ? ((have_bins && c[0] < K) ? 2u : 1u) : 0u;
     __syncthreads();
     if (verdict != 2u) {
       if (threadIdx.x == 0) {
@@ -463,7 +492,7 @@ __device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, uin
 }
 
 // Writes the candidates of one tile, in ascending index, to the LDS stage or (DIRECT) to memory.
-template <bool DIRECT>
+template <bool DIRECT, bool BINS = true>
 __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (&pr)[kLoads * 4], const u64 (&mk)[kLoads * 4],
                                                  const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u32 L, u32* h,
                                                  uint2* __restrict__ dst_global, u64* dst_stage, bool& nan) {
@@ -483,8 +512,10 @@ __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (
         if (DIRECT) dst_global[o] = cd; else dst_stage[o] = ((u64)cd.y << 32) | cd.x;
         ++o;
         nan |= key > 0x7F800000u;
-        const u32 bin = (key >> 10) - Lq;
-        atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
+        if (BINS) {
+          const u32 bin = (key >> 10) - Lq;
+          atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
+        }
       }
     }
     run += tot[j];
@@ -584,11 +615,8 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
   if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane);
 }
 
-// EC: the row is g = grads + eta * err, and g is written over err tile by tile as it is filtered
-// (grads and err rows start at the same 16-byte phase, checked by the caller).
-template <bool EC>
-__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
-                                                   RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
+// The filter pass over rows that are read only: persistent waves, each with a range of its own.
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
                                                    u32 cand_stride, u64* __restrict__ wave_seg, u32* __restrict__ wave_nseg,
                                                    u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
                                                    u32* __restrict__ status) {
@@ -602,7 +630,6 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
-  u32* errv = EC ? reinterpret_cast<u32*>(err + (size_t)m * N) - a : nullptr;
   const u64 vend = N + a;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
   uint2* out = cand + (size_t)m * cand_stride;
@@ -619,34 +646,16 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u32 first = a ? 1u : 0u;
   const u32 last = (u32)(vend / kWaveTile);  // tiles below this index end inside the row
   // Software pipeline: the loads of tile t+1 are in flight while tile t is processed.
-  TileRegs nxt, nxe;
+  TileRegs nxt;
   if (t0 < t1) {
-    if (t0 >= first && t0 < last) {
-      load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
-      if (EC) load_filter_tile<true>(errv, a, vend, t0, lane, nxe);
-    } else {
-      load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
-      if (EC) load_filter_tile<false>(errv, a, vend, t0, lane, nxe);
-    }
+    if (t0 >= first && t0 < last) load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
+    else load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
   }
   for (u32 tile = t0; tile < t1; ++tile) {
-    TileRegs r = nxt;
-    TileRegs re;
-    if (EC) re = nxe;
+    const TileRegs r = nxt;
     if (tile + 1 < t1) {
-      if (tile + 1 >= first && tile + 1 < last) {
-        load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
-        if (EC) load_filter_tile<true>(errv, a, vend, tile + 1, lane, nxe);
-      } else {
-        load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
-        if (EC) load_filter_tile<false>(errv, a, vend, tile + 1, lane, nxe);
-      }
-    }
-    if (EC) {
-#pragma unroll
-      for (int i = 0; i < kLoads * 4; ++i) r.b[i] = compensate_bits(r.b[i], re.b[i], eta);
-      if (tile >= first && tile < last) store_filter_tile<true>(errv, tile, lane, r);
-      else store_filter_tile<false>(errv, tile, lane, r);
+      if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
+      else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
     if (tile >= first && tile < last) filter_tile<true>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
     else filter_tile<false>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
@@ -668,8 +677,130 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
 }
 
-// The kernels below walk the candidates of a row in ascending index (SegmentWalk): one wave per
-// segment list, segments in order, 64 candidates at a time.
+// ---- the filter pass with a memory, in chunks --------------------------------------------------
+// The row is g = grads + eta * err, and g is written over err as it is filtered (grads and err rows
+// start at the same 16-byte phase, checked by the caller).  One block per chunk of 8192 consecutive
+// entries, launched in index order; a wave holds its kChunkTiles consecutive wave tiles in
+// registers.  The block counts its candidates, reserves exactly that many slots of the row's pool
+// with one atomic, and its waves write them there in ascending index.  Chunk c leaves the segment
+// (first slot, count) as entry c of the row's segment table, so that list g of the table (kChain
+// entries) is chunks g*kChain .. g*kChain + kChain - 1 in order.  No bins are filled: the radix
+// select then runs over the candidates at every level.
+//
+// Why not persistent waves as in k_filter: this pass reads two rows and writes one, and blocks
+// dispatched in index order keep the running blocks inside a compact window of the three streams,
+// which the memory system rewards (a bare read-modify-write stream: 5.9 TB/s against 5.2 TB/s for
+// waves that each stream a far-apart range).  A read-only pass gains nothing from it, and the one
+// returning atomic per block, harmless next to 96 KB of traffic, would bound it: atomics on one
+// counter (or on the neighbouring counters of a few rows) complete at about 86 per microsecond.
+template <bool INTERIOR>
+__device__ __forceinline__ u32 count_candidates(const TileRegs& r, u32 L) {
+  u32 total = 0;
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) {
+    bool p = (r.b[i] & 0x7FFFFFFFu) >= L;
+    if (!INTERIOR) p = p && ((r.valid >> i) & 1u);
+    total += (u32)__popcll(ballot(p));
+  }
+  return total;
+}
+
+template <bool INTERIOR>
+__device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 first_slot,
+                                                 uint2* __restrict__ out, bool& nan) {
+  bool pr[kLoads * 4];
+  u64 mk[kLoads * 4];
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) {
+    pr[i] = (r.b[i] & 0x7FFFFFFFu) >= L;
+    if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
+    mk[i] = ballot(pr[i]);
+  }
+  u32 tot[kLoads];
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j)
+    tot[j] = (u32)__popcll(mk[4 * j]) + (u32)__popcll(mk[4 * j + 1]) + (u32)__popcll(mk[4 * j + 2]) + (u32)__popcll(mk[4 * j + 3]);
+  const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
+  place_candidates<true, false>(r, pr, mk, tot, first_slot, v0, L, nullptr, out, nullptr, nan);
+}
+
+__global__ __launch_bounds__(kBlock) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
+                                                          RowState* __restrict__ rs, uint2* __restrict__ cand, u32 cand_stride,
+                                                          u64* __restrict__ list_seg, u32* __restrict__ list_nseg, u32 list_stride,
+                                                          u32 n_chunks, u32* __restrict__ status) {
+  static_assert(kChunkTiles == 2, "the two wave tiles of a chunk are held in named registers");
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;  // block-uniform
+  __shared__ u32 wsum[kWaves];
+  __shared__ u32 sbase;
+  const float* row = grads + (size_t)m * N;
+  const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
+  const u32* rowv = reinterpret_cast<const u32*>(row) - a;
+  u32* errv = reinterpret_cast<u32*>(err + (size_t)m * N) - a;
+  const u64 vend = N + a;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 chunk = blockIdx.x;
+  const u32 t0 = (chunk * kWaves + wave) * kChunkTiles, t1 = t0 + 1;
+  const u32 first = a ? 1u : 0u;              // tiles from here on do not start before the row
+  const u32 last = (u32)(vend / kWaveTile);   // tiles below this index end inside the row
+  const bool in0 = t0 >= first && t0 < last, in1 = t1 >= first && t1 < last;  // wave-uniform
+  TileRegs r0, r1, e0, e1;
+  if (in0) { load_filter_tile<true>(rowv, a, vend, t0, lane, r0); load_filter_tile<true>(errv, a, vend, t0, lane, e0); }
+  else { load_filter_tile<false>(rowv, a, vend, t0, lane, r0); load_filter_tile<false>(errv, a, vend, t0, lane, e0); }
+  if (in1) { load_filter_tile<true>(rowv, a, vend, t1, lane, r1); load_filter_tile<true>(errv, a, vend, t1, lane, e1); }
+  else { load_filter_tile<false>(rowv, a, vend, t1, lane, r1); load_filter_tile<false>(errv, a, vend, t1, lane, e1); }
+  // g = grads + eta * err goes over err right away: the stores are under way while the candidates are counted
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) r0.b[i] = compensate_bits(r0.b[i], e0.b[i], eta);
+  if (in0) store_filter_tile<true>(errv, t0, lane, r0); else store_filter_tile<false>(errv, t0, lane, r0);
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
+  if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
+  const u32 c0 = in0 ? count_candidates<true>(r0, st.L) : count_candidates<false>(r0, st.L);
+  const u32 c1 = in1 ? count_candidates<true>(r1, st.L) : count_candidates<false>(r1, st.L);
+  if (lane == 0) wsum[wave] = c0 + c1;
+  __syncthreads();
+  u32 before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const u32 c = wsum[w];
+    if ((u32)w < wave) before += c;
+    total += c;
+  }
+  if (threadIdx.x == 0) {
+    u32 base = 0;
+    bool fits = true;
+    if (total) {
+      base = atomicAdd(&rs[m].n_alloc, total);
+      fits = base + total <= cand_stride && base + total >= base;
+      if (!fits) rs[m].overflow = 1;
+    }
+    sbase = fits ? base : 0xFFFFFFFFu;
+    list_seg[(size_t)m * list_stride * kChain + chunk] = fits ? (((u64)base << 32) | total) : 0ull;
+    if (chunk % kChain == 0) {
+      const u32 left = n_chunks - chunk;
+      list_nseg[(size_t)m * list_stride + chunk / kChain] = left < (u32)kChain ? left : (u32)kChain;
+    }
+  }
+  __syncthreads();
+  const u32 base = sbase;
+  if (total == 0 || base == 0xFFFFFFFFu) return;
+  uint2* out = cand + (size_t)m * cand_stride;
+  bool nan = false;
+  if (c0) {
+    if (in0) place_chunk_tile<true>(r0, a, t0, lane, st.L, base + before, out, nan);
+    else place_chunk_tile<false>(r0, a, t0, lane, st.L, base + before, out, nan);
+  }
+  if (c1) {
+    if (in1) place_chunk_tile<true>(r1, a, t1, lane, st.L, base + before + c0, out, nan);
+    else place_chunk_tile<false>(r1, a, t1, lane, st.L, base + before + c0, out, nan);
+  }
+  if (nan) status[0] = 1;
+}
+
+// The kernels below walk the candidates of a row in ascending index (ListWalk): a wave per segment
+// list.
 // (eq << 32) | gt of each segment list against the final threshold; scanned afterwards.
 __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                        const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
@@ -677,22 +808,27 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode == kModeGeneral) return;
-  const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
-  u32 gt = 0, eq = 0;
-  for (u32 c = 0; c < sw.n_seg; ++c) {
-    const u64 sg = sw.segs[c];
-    const uint2* in = sw.pool + (u32)(sg >> 32);
-    const u32 cnt = (u32)sg;
-    for (u32 i = lane; i < cnt; i += 64) {
-      const u32 key = in[i].y & 0x7FFFFFFFu;
-      gt += key > st.T;
-      eq += key == st.T;
-    }
-  }
+  const u32 lane = lane_id();
+  for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
+    const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+    u32 gt = 0, eq = 0;
+    for (u32 i0 = lane; i0 < lw.total; i0 += 64 * kWalk) {
+      u32 key[kWalk];
 #pragma unroll
-  for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
-  if (lane == 0 && g < n_waves) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
+      for (int u = 0; u < kWalk; ++u) {
+        const u32 j = i0 + (u32)u * 64u;
+        key[u] = j < lw.total ? (lw.pool[lw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+      }
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) {
+        gt += key[u] != 0xFFFFFFFFu && key[u] > st.T;
+        eq += key[u] == st.T;  // T is a key, never the filler
+      }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    if (lane == 0) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
+  }
 }
 
 // Emits the words of each segment list at its scanned offset, in ascending index, the tie quota
@@ -704,22 +840,19 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode == kModeGeneral) return;
-  const u32 lane = lane_id(), g = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const SegmentWalk sw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g, n_waves);
-  if (sw.n_seg == 0) return;  // wave-uniform
+  const u32 lane = lane_id();
   float* erow = err ? err + (size_t)m * N : nullptr;
   u32* out = words + (size_t)m * K;
-  const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
-  u32 eq_seen = (u32)(before >> 32);
-  u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-  for (u32 c = 0; c < sw.n_seg; ++c) {
-    const u64 sg = sw.segs[c];
-    const uint2* in = sw.pool + (u32)(sg >> 32);
-    const u32 cnt = (u32)sg;
-    for (u32 i0 = 0; i0 < cnt; i0 += 64) {  // wave-uniform trip count
-      const bool ok = i0 + lane < cnt;
+  for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
+    const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+    if (lw.total == 0) continue;
+    const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
+    u32 eq_seen = (u32)(before >> 32);
+    u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
+    for (u32 i0 = 0; i0 < lw.total; i0 += 64) {  // wave-uniform trip count
+      const bool ok = i0 + lane < lw.total;
       uint2 cd = make_uint2(0, 0);
-      if (ok) cd = in[i0 + lane];
+      if (ok) cd = lw.pool[lw.locate(i0 + lane)];
       const u32 key = cd.y & 0x7FFFFFFFu;
       const bool is_eq = ok && key == st.T;
       const u64 eq_mask = ballot(is_eq);
@@ -769,8 +902,8 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
 u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<true>, kBlock, 0)
-                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks, kBlock, 0)
+                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   u32 n = (u32)cus * (u32)per_cu;
   if (const char* e = getenv("S3GD_STREAM_BLOCKS")) {  // tuning knob for experiments
@@ -784,7 +917,7 @@ u32 resident_stream_blocks(int device, bool with_memory) {
 // the count of keys above the r-th largest sample key is about r / f with deviation sqrt(r) / f.
 static double candidate_bound(double r, double f) { return 1.25 * (r + 6.0 * sqrt(r) + 8.0) / f; }
 
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bool chunks) {
   EncodePlan p{};
   p.n_tiles = encode_tiles(N);
   p.gx = blocks_per_row(M, p.n_tiles, stream_blocks);
@@ -806,9 +939,15 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks) {
   while (p.slab < kSlabMax && (double)p.slab < per_wave) p.slab <<= 1;
   // a row needs room for its candidates, for the first slab of every wave, for the unused part of the
   // later (doubling) slabs of waves that overflowed (at most what they hold), and a tile of slack
-  const double need = 2.0 * p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
+  double need = 2.0 * p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
+  if (chunks) {  // blocks reserve exactly what they found: no slabs
+    need = 2.0 * p.bound + kWaveTile;
+    p.n_chunks = chunk_count(N);
+    p.n_lists = chunk_lists(N);
+  }
   if (need * M > (double)cand_pool || need > 4.0e9) return p;
   p.candidates = true;
+  p.chunks = chunks;
   p.n_units = (u32)(s / kSampleUnit);
   p.unit_stride = N / p.n_units;
   p.sample_rank = (u32)r;
@@ -821,7 +960,7 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
   // the bound is not monotone in K (the sample size changes in powers of two): take the largest
   // over K_max and the sparsities below it down to 1e-5
   for (double k = (double)(K_max < N_max / 16 ? K_max : N_max / 16); k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
-    const EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, 1);
+    const EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, 1, false);
     if (p.candidates && p.bound > best) best = p.bound;
   }
   if (best == 0) return 0;
@@ -836,7 +975,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                          u32* counts, hipStream_t s) {
   Profiler& P = *ws.prof;
 #define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
-  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, err ? ws.stream_blocks_mem : ws.stream_blocks);
+  // With a memory the filter pass reads two rows and writes one: that mix runs fastest as blocks in index order.
+  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, err ? ws.stream_blocks_mem : ws.stream_blocks, err != nullptr);
   if (err && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
     const u64 total = (u64)M * N;
     const u32 head = (u32)((4 - ((reinterpret_cast<uintptr_t>(err) >> 2) & 3u)) & 3u);
@@ -856,41 +996,45 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const u32 k32 = (u32)K;
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
                                                                          p.candidates ? kModeCandidates : kModeGeneral,
-                                                                         p.candidates ? p.gx * (u32)kWaves * p.slab : 0u)));
+                                                                         p.candidates && !p.chunks ? p.gx * (u32)kWaves * p.slab : 0u)));
+  const u32 n_waves = !p.candidates ? 0u : (p.chunks ? p.n_lists : p.gx * (u32)kWaves);  // segment lists per row
+  const u32 wstride = p.chunks ? p.n_lists + 4 : wave_stride(p.gx);
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles;
-    const u32 wstride = wave_stride(p.gx);
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    if (err)
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                         ws.wave_seg, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
-                                                                         p.slab, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    if (p.chunks)
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
+                                                                                               ws.wave_seg, ws.wave_nseg, wstride,
+                                                                                               p.n_chunks, ws.status)));
     else
-      S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, nullptr, 0.0f, N, ws.rs, ws.hist, ws.cand, p.cand_stride,
-                                                                      ws.wave_seg, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
-                                                                      p.slab, ws.status)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+      S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg,
+                                                               wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
   }
   // Radix select: over the row for general rows, over the candidates for the others (the last level
   // only, unless the filter's bins could not place the K-th key).
-  const u32 n_waves = p.candidates ? p.gx * (u32)kWaves : 0u, wstride = wave_stride(p.gx);
+  // launches that walk segment lists: a wave per list, up to four rounds of resident blocks
+  u32 lx = (n_waves + kWaves - 1) / kWaves;
+  if (lx > 4 * p.gx) lx = 4 * p.gx;
+  if (lx < p.gx) lx = p.gx;
+  const dim3 lgrid(lx, M);
 #define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves
-  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<grid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                       n_waves, ws.wave_sum)));
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, 1u)));
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<grid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).

@@ -12,7 +12,15 @@ inline u32 wave_tiles(u64 N) { return (u32)((N + 3 + kWaveTile - 1) / kWaveTile)
 inline u32 blk_stride(u64 N) { return ((wave_tiles(N) + 15) / 16 + 1 + 3) & ~3u; }  // per-row scratch of the random-K scan
 inline u32 wave_stride(u32 gx) { return gx * kWaves + 4; }  // per-row stride of the per-wave tables of a launch with gx blocks per row
 // entries of the per-wave tables: gx * M <= max(resident blocks, M) for every launch
-inline size_t wave_table_entries(u32 M_max) { return (size_t)(kMaxStreamBlocks + M_max) * kWaves + 4 * (size_t)M_max; }
+// segment lists a row has after a filter pass in chunks: kChain chunks of kWaves * kChunkTiles wave tiles each
+inline u32 chunk_count(u64 N) { return (u32)(((N + 3 + kWaveTile - 1) / kWaveTile + kWaves * kChunkTiles - 1) / (kWaves * kChunkTiles)); }
+inline u32 chunk_lists(u64 N) { return (chunk_count(N) + kChain - 1) / kChain; }
+// entries of the per-list tables: enough for the persistent filter pass (a list per wave) and for the chunked one
+inline size_t wave_table_entries(u32 M_max, u64 N_max) {
+  const size_t waves = (size_t)(kMaxStreamBlocks + M_max) * kWaves + 4 * (size_t)M_max;
+  const size_t lists = (size_t)M_max * ((size_t)chunk_lists(N_max) + 4);
+  return waves > lists ? waves : lists;
+}
 inline u32 coding_blk_stride(u64 N) { return 2 * tile_stride(N); }  // u32 entries per row when tile_cnt serves the coding kernels
 // entries per row of the segment table: one per tile of the finest tiling, plus the end
 inline size_t seg_row_entries(u64 N) { return (size_t)((N + kMomTile - 1) / kMomTile) + 1; }
@@ -70,6 +78,8 @@ struct Workspace {
 // What one encode call launches; a pure function of the shapes and the pool size.
 struct EncodePlan {
   bool candidates;   // try the candidate route first
+  bool chunks;       // the filter pass runs in chunks (one block each, in index order) instead of persistent waves
+  u32 n_chunks, n_lists;  // chunked filter pass: blocks per row, segment lists per row
   u32 n_tiles, gx;   // 4096-entry tiles per row, streaming blocks per row
   u32 n_wtiles, tiles_per_wave;  // candidate route: 1024-entry wave tiles per row, and per wave of the filter
   u32 n_units;       // sample units (16 entries each) per row
@@ -79,7 +89,7 @@ struct EncodePlan {
   u32 slab;          // candidate slots a wave of the filter pass owns at a time (a power of two)
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks);
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bool chunks);
 u32 resident_stream_blocks(int device, bool with_memory);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 

@@ -114,6 +114,25 @@ def test_ragged_sizes_every_alignment(ctx, N):
         assert_same(got, want, keys=KEYS, what=f"N={N} K={K}")
 
 
+@pytest.mark.parametrize("N", [196_607, 196_608, 196_613, 262_147, 589_825, 655_361])
+def test_filter_chunk_boundaries(ctx, N):
+    """Row lengths around multiples of a filter block (8192 entries) and of a segment list (8 blocks),
+    rows at different 16-byte phases, continuous values (few ties) and a stretch of the row without
+    any candidate; every row must be served by the filter pass."""
+    rng = np.random.default_rng(N)
+    M = 3
+    Gt = rng.standard_normal((M, N)).astype(np.float32)
+    E = (rng.standard_normal((M, N)) * 0.25).astype(np.float32)
+    Gt[:, 20_000:90_000] *= 1e-3  # nothing here comes near the threshold: blocks with no candidate
+    E[:, 20_000:90_000] *= 1e-3
+    x = rng.standard_normal(N).astype(np.float32)
+    for K in (N // 1000, N // 64):
+        want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+        got = gpu_step_ec(ctx, Gt, E, 1.0, K, x, 1e-3, fused=True)
+        assert_same(got, want, keys=KEYS, what=f"N={N} K={K}")
+        assert ctx.last_encode_info() == (M, 0)
+
+
 def test_unaligned_base_pointers_same_phase(ctx, lib):
     rng = np.random.default_rng(19)
     M, N, K = 3, 150_001, 1_500
