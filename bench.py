@@ -201,6 +201,10 @@ def main():
         alg_bytes = 12.0 * M * N
     elif dom in FULL_READ_KERNELS:
         alg_bytes = 4.0 * M * N
+    elif dom == "vote_momentum":
+        # the momentum is read in full; where it is non-zero (everywhere, in the dense state) it is written back and
+        # the parameter is read and written too
+        alg_bytes = 4.0 * M * K + (16.0 * N if args.dense_state else 4.0 * N)
     else:  # the vote kernel dominates only when the gradient passes are cheaper than it
         alg_bytes = 8.0 * M * K + 8.0 * N
     achieved = alg_bytes / (kern[dom]["ms_avg"] * 1e-3)
