@@ -16,7 +16,6 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kLoads = 4;                   // 16-byte loads per thread and tile
 constexpr int kTile = kBlock * 4 * kLoads;  // 4096 gradient entries per tile
 constexpr int kHistBins = 2048;             // first radix digit: key bits [30:20]
-constexpr int kVoteTile = 8192;             // coordinates tallied in LDS by one block
 constexpr unsigned kMomTile = 4096;         // coordinates one wave of the momentum sweep owns (the finest vote tiling)
 constexpr int kScanBlock = 1024;
 

@@ -3,8 +3,9 @@
 // model update x <- x - lr * vote (eq. "s3gd").
 //
 // Messages are sorted by index, so each row is cut once into per-tile segments by binary search;
-// a block then owns kVoteTile consecutive coordinates, tallies them with LDS integer atomics and is
-// the only writer of that stretch of the outputs.
+// a block (or, for the dense outputs and the momentum sweep, a wave) then owns a tile of
+// consecutive coordinates, tallies them with LDS integer atomics and is the only writer of that
+// stretch of the outputs.
 #include "s3gd_common.h"
 #include "s3gd_kernels.h"
 
@@ -37,60 +38,6 @@ __device__ __forceinline__ void load_bounds(const u32* __restrict__ seg, u32 seg
   }
 }
 
-// Dense variant: writes every element of tally and/or votes, optionally updates x.
-__global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
-                                                       u32 seg_stride, u32 M, u64 N, int32_t* __restrict__ tally,
-                                                       int8_t* __restrict__ votes, float* __restrict__ x, float lr) {
-  __shared__ __attribute__((aligned(16))) int32_t t[kVoteTile];
-  __shared__ u32 lo[kRowChunk], hi[kRowChunk];
-  const u32 tile = blockIdx.x;
-  const u64 base = (u64)tile * kVoteTile;
-  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x * 4; i < kVoteTile; i += kBlock * 4) *reinterpret_cast<int4*>(&t[i]) = make_int4(0, 0, 0, 0);
-  for (u32 m0 = 0; m0 < M; m0 += kRowChunk) {
-    __syncthreads();
-    load_bounds(seg, seg_stride, m0, M, tile, lo, hi);
-    __syncthreads();
-    const u32 rows = M - m0 < (u32)kRowChunk ? M - m0 : (u32)kRowChunk;
-    for (u32 r = wave; r < rows; r += kWaves) {
-      const u32* w = words + (size_t)(m0 + r) * K;
-      for (u32 i = lo[r] + lane; i < hi[r]; i += 64) {
-        const u32 wd = w[i];
-        const u32 c = (u32)((u64)(wd >> 1) - base);
-        if (c < (u32)kVoteTile) atomicAdd(&t[c], (wd & 1u) ? -1 : 1);  // always true for sorted rows
-      }
-    }
-  }
-  __syncthreads();
-  for (int c = threadIdx.x * 4; c < kVoteTile; c += kBlock * 4) {
-    const u64 n = base + c;
-    if (n >= N) break;
-    const int4 s = *reinterpret_cast<const int4*>(&t[c]);
-    const int v0 = (s.x > 0) - (s.x < 0), v1 = (s.y > 0) - (s.y < 0), v2 = (s.z > 0) - (s.z < 0), v3 = (s.w > 0) - (s.w < 0);
-    if (n + 4 <= N) {
-      if (tally) *reinterpret_cast<int4*>(tally + n) = s;
-      if (votes)
-        *reinterpret_cast<u32*>(votes + n) = (u32)(v0 & 0xFF) | ((u32)(v1 & 0xFF) << 8) | ((u32)(v2 & 0xFF) << 16) | ((u32)(v3 & 0xFF) << 24);
-      if (x && (v0 | v1 | v2 | v3)) {
-        float4 xv = *reinterpret_cast<float4*>(x + n);
-        if (v0) xv.x = xv.x - lr * (float)v0;
-        if (v1) xv.y = xv.y - lr * (float)v1;
-        if (v2) xv.z = xv.z - lr * (float)v2;
-        if (v3) xv.w = xv.w - lr * (float)v3;
-        *reinterpret_cast<float4*>(x + n) = xv;
-      }
-    } else {
-      const int sv[4] = {s.x, s.y, s.z, s.w};
-      const int vv[4] = {v0, v1, v2, v3};
-      for (int e = 0; e < 4 && n + e < N; ++e) {
-        if (tally) tally[n + e] = sv[e];
-        if (votes) votes[n + e] = (int8_t)vv[e];
-        if (x && vv[e]) x[n + e] = x[n + e] - lr * (float)vv[e];
-      }
-    }
-  }
-}
-
 // Sparse variant: only x is produced, and only where somebody voted.
 //
 // The tally of a coordinate lives in an FB-bit field of an LDS word (FB = 8 while M <= 63, 16 while
@@ -110,6 +57,156 @@ struct VoteField {
   static constexpr u32 kFill = FB == 8 ? 0x40404040u : (FB == 16 ? 0x40004000u : 0x40000000u);
   static constexpr u32 kTile = kVoteWords * kPer;
 };
+
+// ---- a wave's own tile ---------------------------------------------------------------------------
+// One wave owns kMomTile consecutive coordinates and a slice of LDS holding their packed tally;
+// nothing is shared between waves, so no block-wide barrier is needed and a block is just four
+// independent waves.  The wave fills its slice, fetches the segment bounds of all rows (one row
+// per lane) and adds the messages in.  Where a row has only a few messages in the tile (small K/N)
+// they are numbered flat across the rows, so that every lane fetches its messages with independent
+// loads instead of one dependent, nearly empty load per row; where rows have dozens each, lanes run
+// over the messages of a row, a few rows at a time.
+constexpr int kMomPass = 4;  // messages a lane fetches before it adds them to the tally
+
+template <int FB>
+__device__ __forceinline__ void tally_wave_tile(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg, u32 seg_stride,
+                                                u32 M, u64 N, u32 tile, u32* t) {
+  typedef VoteField<FB> F;
+  constexpr u32 kSlice = kMomTile / F::kPer;
+  const u32 lane = lane_id();
+  const u64 base = (u64)tile * kMomTile;
+  for (u32 i = lane * 4; i < kSlice; i += 256) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
+  wave_sync();
+
+  for (u32 m0 = 0; m0 < M; m0 += 64) {
+    const u32 rows = M - m0 < 64u ? M - m0 : 64u;
+    u32 lo = 0, cnt = 0;
+    if (lane < rows) {
+      const u32* sg = seg + (size_t)(m0 + lane) * seg_stride + tile;
+      lo = sg[0];
+      const u32 hi = sg[1];
+      cnt = hi > lo ? hi - lo : 0u;
+    }
+    const u32 incl = wave_incl_scan(cnt);
+    const u32 first = incl - cnt;  // number of this row's first message in the tile's flat numbering
+    const u32 total = __builtin_amdgcn_readlane(incl, 63);
+    if (total >= 32u * rows) {
+      // rows with dozens of messages each in this tile: lanes over the messages of a row, kMomPass rows at a time
+      for (u32 r0 = 0; r0 < rows; r0 += kMomPass) {
+        u32 rl[kMomPass], rc[kMomPass], longest = 0;
+#pragma unroll
+        for (int p = 0; p < kMomPass; ++p) {
+          const u32 r = r0 + (u32)p < rows ? r0 + (u32)p : rows - 1;  // r is wave-uniform
+          rl[p] = __builtin_amdgcn_readlane(lo, r);
+          rc[p] = r0 + (u32)p < rows ? __builtin_amdgcn_readlane(cnt, r) : 0u;
+          longest = rc[p] > longest ? rc[p] : longest;
+        }
+        for (u32 i = lane; i < longest + lane; i += 64) {  // the same trip count in every lane
+          u32 wd[kMomPass];
+#pragma unroll
+          for (int p = 0; p < kMomPass; ++p) wd[p] = i < rc[p] ? words[(size_t)(m0 + r0 + (u32)p) * K + rl[p] + i] : S3GD_PAD;
+#pragma unroll
+          for (int p = 0; p < kMomPass; ++p) {
+            const u32 c = (u32)((u64)(wd[p] >> 1) - base);
+            if (wd[p] == S3GD_PAD || c >= kMomTile || base + c >= N) continue;
+            const u32 sh = (c % F::kPer) * FB;
+            atomicAdd(&t[c / F::kPer], (wd[p] & 1u) ? (0u - (1u << sh)) : (1u << sh));
+          }
+        }
+      }
+      continue;
+    }
+    for (u32 j0 = 0; j0 < total; j0 += 64u * kMomPass) {
+      size_t at[kMomPass];
+#pragma unroll
+      for (int p = 0; p < kMomPass; ++p) at[p] = ~(size_t)0;
+      for (u32 r = 0; r < rows; ++r) {  // r is wave-uniform: the three values come from lane r
+        const u32 rf = __builtin_amdgcn_readlane(first, r), rc = __builtin_amdgcn_readlane(cnt, r),
+                  rl = __builtin_amdgcn_readlane(lo, r);
+        if (rc == 0) continue;
+#pragma unroll
+        for (int p = 0; p < kMomPass; ++p) {
+          const u32 d = j0 + (u32)p * 64u + lane - rf;  // wraps to a huge value for messages of earlier rows
+          if (d < rc) at[p] = (size_t)(m0 + r) * K + rl + d;
+        }
+      }
+      u32 wd[kMomPass];
+#pragma unroll
+      for (int p = 0; p < kMomPass; ++p) wd[p] = at[p] != ~(size_t)0 ? words[at[p]] : S3GD_PAD;
+#pragma unroll
+      for (int p = 0; p < kMomPass; ++p) {
+        const u32 c = (u32)((u64)(wd[p] >> 1) - base);
+        if (wd[p] == S3GD_PAD || c >= kMomTile || base + c >= N) continue;  // the last two never hold for sorted rows
+        const u32 sh = (c % F::kPer) * FB;
+        atomicAdd(&t[c / F::kPer], (wd[p] & 1u) ? (0u - (1u << sh)) : (1u << sh));
+      }
+    }
+  }
+  wave_sync();
+}
+
+// Dense variant: writes every element of tally and/or votes, optionally updates x.  A wave per
+// kMomTile coordinates: tally in its own LDS slice, then 16 votes (one 16-byte store) per lane and
+// round, and four tally entries (one 16-byte store) per lane and round.
+template <int FB>
+__global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
+                                                       u32 seg_stride, u32 M, u64 N, u32 n_vt, int32_t* __restrict__ tally,
+                                                       int8_t* __restrict__ votes, float* __restrict__ x, float lr) {
+  typedef VoteField<FB> F;
+  constexpr u32 kSlice = kMomTile / F::kPer;
+  __shared__ __attribute__((aligned(16))) u32 lds[kWaves * kSlice];
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 tile = blockIdx.x * kWaves + wave;
+  if (tile >= n_vt) return;  // whole waves leave; nothing below synchronises across waves
+  u32* t = lds + wave * kSlice;
+  const u64 base = (u64)tile * kMomTile;
+  tally_wave_tile<FB>(words, K, seg, seg_stride, M, N, tile, t);
+  auto tally_of = [&](u32 c) -> int {
+    const u32 f = (t[c / F::kPer] >> ((c % F::kPer) * FB)) & (F::kFlag - 1u);
+    return (int)f - (int)F::kBias;
+  };
+  if (votes) {
+    for (u32 c0 = lane * 16u; c0 < kMomTile; c0 += 1024u) {
+      const u64 n = base + c0;
+      if (n >= N) break;
+      u32 w[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int d = tally_of(c0 + (u32)i);
+        w[i / 4] |= (u32)(((d > 0) - (d < 0)) & 0xFF) << (8 * (i % 4));
+      }
+      if (n + 16 <= N) {
+        *reinterpret_cast<uint4*>(votes + n) = make_uint4(w[0], w[1], w[2], w[3]);
+      } else {
+        for (int i = 0; i < 16 && n + i < N; ++i) votes[n + i] = (int8_t)((w[i / 4] >> (8 * (i % 4))) & 0xFF);
+      }
+    }
+  }
+  if (tally || x) {
+    for (u32 c0 = lane * 4u; c0 < kMomTile; c0 += 256u) {
+      const u64 n = base + c0;
+      if (n >= N) break;
+      const int d[4] = {tally_of(c0), tally_of(c0 + 1), tally_of(c0 + 2), tally_of(c0 + 3)};
+      const int v[4] = {(d[0] > 0) - (d[0] < 0), (d[1] > 0) - (d[1] < 0), (d[2] > 0) - (d[2] < 0), (d[3] > 0) - (d[3] < 0)};
+      if (n + 4 <= N) {
+        if (tally) *reinterpret_cast<int4*>(tally + n) = make_int4(d[0], d[1], d[2], d[3]);
+        if (x && (v[0] | v[1] | v[2] | v[3])) {
+          float4 xv = *reinterpret_cast<float4*>(x + n);
+          if (v[0]) xv.x = xv.x - lr * (float)v[0];
+          if (v[1]) xv.y = xv.y - lr * (float)v[1];
+          if (v[2]) xv.z = xv.z - lr * (float)v[2];
+          if (v[3]) xv.w = xv.w - lr * (float)v[3];
+          *reinterpret_cast<float4*>(x + n) = xv;
+        }
+      } else {
+        for (int e = 0; e < 4 && n + e < N; ++e) {
+          if (tally) tally[n + e] = d[e];
+          if (x && v[e]) x[n + e] = x[n + e] - lr * (float)v[e];
+        }
+      }
+    }
+  }
+}
 
 template <int FB, int PHASE>
 __device__ __forceinline__ void vote_rows(const u32* __restrict__ words, u64 K, u32 m0, u32 rows, const u32* lo, const u32* hi,
@@ -224,24 +321,50 @@ __global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ 
   }
 }
 
-// Standalone update from a materialised vote vector, 16 coordinates per thread and step.
+// Standalone update from a materialised vote vector.  A lane takes 16 consecutive votes (one
+// 16-byte load) at a time, kUpd such groups per round with all their loads in flight together; where
+// a group holds a vote, the lane rewrites the whole 64 bytes of x that belong to it (memory merges a
+// smaller write by reading first).
+constexpr int kUpd = 2;
+
+typedef u32 u32x4v __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, const int8_t* __restrict__ votes, float lr, u64 N) {
   const u64 n16 = N / 16;
-  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) {
-    const uint4 v = *reinterpret_cast<const uint4*>(votes + i * 16);
-    const u32 vw[4] = {v.x, v.y, v.z, v.w};
+  const u64 stride = (u64)gridDim.x * blockDim.x;
+  for (u64 i0 = (u64)blockIdx.x * blockDim.x + threadIdx.x; i0 < n16; i0 += stride * kUpd) {
+    u32x4v v[kUpd];
+    bool live[kUpd];
+    float4 q[kUpd][4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (vw[k] == 0) continue;
-      float4* p = reinterpret_cast<float4*>(x + i * 16 + k * 4);
-      float4 xv = *p;
-      const int a = (int8_t)(vw[k] & 0xFF), b = (int8_t)((vw[k] >> 8) & 0xFF), c = (int8_t)((vw[k] >> 16) & 0xFF),
-                d = (int8_t)(vw[k] >> 24);
-      if (a) xv.x = xv.x - lr * (float)a;
-      if (b) xv.y = xv.y - lr * (float)b;
-      if (c) xv.z = xv.z - lr * (float)c;
-      if (d) xv.w = xv.w - lr * (float)d;
-      *p = xv;
+    for (int u = 0; u < kUpd; ++u) {
+      const u64 i = i0 + (u64)u * stride;
+      v[u] = 0;
+      if (i < n16) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(votes + i * 16));
+    }
+#pragma unroll
+    for (int u = 0; u < kUpd; ++u) {
+      live[u] = (v[u].x | v[u].y | v[u].z | v[u].w) != 0;
+      if (live[u]) {
+        const float4* p = reinterpret_cast<const float4*>(x + (i0 + (u64)u * stride) * 16);
+        q[u][0] = p[0]; q[u][1] = p[1]; q[u][2] = p[2]; q[u][3] = p[3];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUpd; ++u) {
+      if (!live[u]) continue;
+      const u32 vw[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      float4* p = reinterpret_cast<float4*>(x + (i0 + (u64)u * stride) * 16);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int a = (int8_t)(vw[k] & 0xFF), b = (int8_t)((vw[k] >> 8) & 0xFF), c = (int8_t)((vw[k] >> 16) & 0xFF),
+                  d = (int8_t)(vw[k] >> 24);
+        float4 xv = q[u][k];
+        if (a) xv.x = xv.x - lr * (float)a;
+        if (b) xv.y = xv.y - lr * (float)b;
+        if (c) xv.z = xv.z - lr * (float)c;
+        if (d) xv.w = xv.w - lr * (float)d;
+        p[k] = xv;
+      }
     }
   }
   if (blockIdx.x == 0) {
@@ -313,7 +436,6 @@ __device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __r
 constexpr int kMomRounds = 4;                      // groups of four coordinates a lane has in flight
 constexpr u32 kMomBatch = 256u * kMomRounds;       // coordinates of a wave per batch of rounds
 constexpr int kMomBatches = kMomTile / kMomBatch;  // batches per tile; the momenta of the next are fetched a batch ahead
-constexpr int kMomPass = 4;     // messages a lane fetches before it adds them to the tally
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load_stream_f4(const float* p) {
@@ -345,48 +467,7 @@ __global__ __launch_bounds__(kBlock) void k_vote_momentum(const u32* __restrict_
     const u64 n = base + (u32)u * 256u + lane * 4u;
     vv[u] = n + 4 <= N ? load_stream_f4(v + n) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  for (u32 i = lane * 4; i < kSlice; i += 256) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
-  wave_sync();
-
-  for (u32 m0 = 0; m0 < M; m0 += 64) {
-    const u32 rows = M - m0 < 64u ? M - m0 : 64u;
-    u32 lo = 0, cnt = 0;
-    if (lane < rows) {
-      const u32* sg = seg + (size_t)(m0 + lane) * seg_stride + tile;
-      lo = sg[0];
-      const u32 hi = sg[1];
-      cnt = hi > lo ? hi - lo : 0u;
-    }
-    const u32 incl = wave_incl_scan(cnt);
-    const u32 first = incl - cnt;  // number of this row's first message in the tile's flat numbering
-    const u32 total = __builtin_amdgcn_readlane(incl, 63);
-    for (u32 j0 = 0; j0 < total; j0 += 64u * kMomPass) {
-      size_t at[kMomPass];
-#pragma unroll
-      for (int p = 0; p < kMomPass; ++p) at[p] = ~(size_t)0;
-      for (u32 r = 0; r < rows; ++r) {  // r is wave-uniform: the three values come from lane r
-        const u32 rf = __builtin_amdgcn_readlane(first, r), rc = __builtin_amdgcn_readlane(cnt, r),
-                  rl = __builtin_amdgcn_readlane(lo, r);
-        if (rc == 0) continue;
-#pragma unroll
-        for (int p = 0; p < kMomPass; ++p) {
-          const u32 d = j0 + (u32)p * 64u + lane - rf;  // wraps to a huge value for messages of earlier rows
-          if (d < rc) at[p] = (size_t)(m0 + r) * K + rl + d;
-        }
-      }
-      u32 wd[kMomPass];
-#pragma unroll
-      for (int p = 0; p < kMomPass; ++p) wd[p] = at[p] != ~(size_t)0 ? words[at[p]] : S3GD_PAD;
-#pragma unroll
-      for (int p = 0; p < kMomPass; ++p) {
-        const u32 c = (u32)((u64)(wd[p] >> 1) - base);
-        if (wd[p] == S3GD_PAD || c >= kMomTile || base + c >= N) continue;  // the last two never hold for sorted rows
-        const u32 sh = (c % F::kPer) * FB;
-        atomicAdd(&t[c / F::kPer], (wd[p] & 1u) ? (0u - (1u << sh)) : (1u << sh));
-      }
-    }
-  }
-  wave_sync();
+  tally_wave_tile<FB>(words, K, seg, seg_stride, M, N, tile, t);
 
   for (int bt = 0; bt < kMomBatches; ++bt) {
     const u32 c0 = (u32)bt * kMomBatch + lane * 4u;
@@ -488,7 +569,7 @@ hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts,
   Profiler& P = *ws.prof;
   const bool dense = tally || votes;
   const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
-  const u32 tile_coords = dense ? (u32)kVoteTile : (u32)kVoteWords * (32u / fb);
+  const u32 tile_coords = dense ? kMomTile : (u32)kVoteWords * (32u / fb);
   const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);  // a tiling no finer than kMomTile: the table row fits
   const u32 stride = n_vt + 1;
   P.begin(KID_SEG_BOUNDS, s);
@@ -496,7 +577,10 @@ hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts,
   P.end(s);
   if (dense) {
     P.begin(KID_VOTE_DENSE, s);
-    k_vote_dense<<<n_vt, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, tally, votes, x, lr);
+    const u32 g = (n_vt + kWaves - 1) / kWaves;
+    if (fb == 8) k_vote_dense<8><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, tally, votes, x, lr);
+    else if (fb == 16) k_vote_dense<16><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, tally, votes, x, lr);
+    else k_vote_dense<32><<<g, kBlock, 0, s>>>(words, K, ws.seg, stride, M, N, n_vt, tally, votes, x, lr);
     P.end(s);
   } else {
     const u32 g = n_vt < ws.stream_blocks ? n_vt : ws.stream_blocks;
