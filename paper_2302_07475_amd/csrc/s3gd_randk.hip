@@ -73,13 +73,18 @@ __global__ void k_randk_clear(u32* __restrict__ bucket, u32 nb, u32 bstride, u32
   if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; }
 }
 
-// SCATTER = false: count the non-zero selected entries of each bucket.
-// SCATTER = true:  bucket[] holds the first slot of each bucket; every entry takes the next slot of
-//                  its bucket (afterwards bucket[b] is the end of bucket b).
-template <bool SCATTER>
+// The selected entries reach their buckets in two steps around the scan of the bucket counts.
+//   kCount    count the non-zero selected entries of each bucket
+//   kRank     the same, and every entry keeps (word, its arrival number in its bucket) in `tmp`,
+//             so that the second step neither evaluates the permutation nor touches the gradients again
+//   kScatter  second step without `tmp`: bucket[] holds the first slot of each bucket; every entry
+//             takes the next slot of its bucket (afterwards bucket[b] is the end of bucket b)
+enum { kCount = 0, kRank = 1, kScatter = 2 };
+
+template <int STEP>
 __global__ __launch_bounds__(kBlock) void k_randk_pass(const float* __restrict__ grads, u64 N, u64 K, u64 seed, u32 t,
                                                        u32* __restrict__ bucket, u32 bstride, u32* __restrict__ words,
-                                                       u32* __restrict__ status) {
+                                                       uint2* __restrict__ tmp, u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const PermKey p = perm_key(seed, t, m, N);
   const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
@@ -90,16 +95,36 @@ __global__ __launch_bounds__(kBlock) void k_randk_pass(const float* __restrict__
     const u32 n = permute((u32)i, N, p);
     const u32 bits = row[n];
     const u32 key = bits & 0x7FFFFFFFu;
-    if (key == 0) continue;  // sgn(0) = 0: nothing to send
+    if (key == 0) {  // sgn(0) = 0: nothing to send
+      if (STEP == kRank) tmp[(size_t)m * K + i] = make_uint2(S3GD_PAD, 0u);
+      continue;
+    }
     nan |= key > 0x7F800000u;
-    if (SCATTER) {
+    const u32 word = (n << 1) | (bits >> 31);
+    if (STEP == kScatter) {
       const u32 pos = atomicAdd(&bk[n >> kBucketShift], 1u);
-      if ((u64)pos < K) out[pos] = (n << 1) | (bits >> 31);  // pos < K by construction
+      if ((u64)pos < K) out[pos] = word;  // pos < K by construction
+    } else if (STEP == kRank) {
+      tmp[(size_t)m * K + i] = make_uint2(word, atomicAdd(&bk[n >> kBucketShift], 1u));
     } else {
       atomicAdd(&bk[n >> kBucketShift], 1u);
     }
   }
-  if (!SCATTER && nan) status[0] = 1;
+  if (STEP != kScatter && nan) status[0] = 1;
+}
+
+// Second step with `tmp`: bucket[] holds the first slot of each bucket.
+__global__ __launch_bounds__(kBlock) void k_randk_place(const uint2* __restrict__ tmp, u64 K, const u32* __restrict__ bucket, u32 bstride,
+                                                        u32* __restrict__ words) {
+  const u32 m = blockIdx.y;
+  const u32* bk = bucket + (size_t)m * bstride;
+  u32* out = words + (size_t)m * K;
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x) {
+    const uint2 wr = tmp[(size_t)m * K + i];
+    if (wr.x == S3GD_PAD) continue;
+    const u64 pos = (u64)bk[wr.x >> (1 + kBucketShift)] + wr.y;
+    if (pos < K) out[pos] = wr.x;  // pos < K by construction
+  }
 }
 
 // Exclusive scan of a row's bucket counts in three steps, so that many blocks share the work: the
@@ -168,8 +193,10 @@ __device__ __forceinline__ void cmp_swap(u32& x, u32& y) {
   x = lo; y = hi;
 }
 
+// `starts`: bucket[b] is the first slot of bucket b (and counts[m] the end of the last); otherwise
+// bucket[b] is the end of bucket b.
 __global__ __launch_bounds__(kBlock) void k_randk_sort(const u32* __restrict__ bucket, u32 nb, u32 bstride, u64 K,
-                                                       u32* __restrict__ words) {
+                                                       u32* __restrict__ words, const u32* __restrict__ counts, u32 starts) {
   __shared__ u32 lds_all[kWaves][kBucket];
   const u32 m = blockIdx.y;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
@@ -180,8 +207,8 @@ __global__ __launch_bounds__(kBlock) void k_randk_sort(const u32* __restrict__ b
     const u32 b = base + lane;
     u32 s = 0, n = 0;
     if (b < nb) {
-      s = b ? bk[b - 1] : 0u;
-      u32 e = bk[b];
+      s = starts ? bk[b] : (b ? bk[b - 1] : 0u);
+      u32 e = starts ? (b + 1 < nb ? bk[b + 1] : counts[m]) : bk[b];
       if ((u64)e > K) e = (u32)K;
       if ((u64)s > K) s = (u32)K;
       n = e > s ? e - s : 0u;
@@ -249,9 +276,15 @@ hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u
   if (gk < 1) gk = 1;
   u32 gb = (nb + kWaves * 64 - 1) / (kWaves * 64);
   if (gb > cap) gb = cap;
+  // room for (word, arrival number) of every selected entry in the candidate pool, which this call does not use otherwise?
+  const bool ranked = (u64)M * K <= ws.cand_pool;
+  uint2* tmp = ws.cand;
   P.begin(KID_RANDK, s);
   k_randk_clear<<<dim3((nb + 255) / 256 < 64 ? (nb + 255) / 256 : 64, M), 256, 0, s>>>(bucket, nb, bstride, ws.status, M);
-  if (K > 0) k_randk_pass<false><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
+  if (K > 0) {
+    if (ranked) k_randk_pass<kRank><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, tmp, ws.status);
+    else k_randk_pass<kCount><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, tmp, ws.status);
+  }
   u32* sums = reinterpret_cast<u32*>(ws.blk_sum);    // [M][2 * blk_stride] as u32: far more than n_chunks entries per row
   const u32 sstride = 2 * blk_stride(N);
   const u32 n_chunks = (nb + kScanChunk - 1) / kScanChunk;
@@ -259,8 +292,9 @@ hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u
   k_randk_scan_sums<<<M, kScanBlock, 0, s>>>(sums, n_chunks, sstride, counts);
   k_randk_scan_chunks<<<dim3(n_chunks, M), kScanBlock, 0, s>>>(bucket, nb, bstride, sums, sstride);
   if (K > 0) {
-    k_randk_pass<true><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, ws.status);
-    k_randk_sort<<<dim3(gb, M), kBlock, 0, s>>>(bucket, nb, bstride, K, words);
+    if (ranked) k_randk_place<<<dim3(gk, M), kBlock, 0, s>>>(tmp, K, bucket, bstride, words);
+    else k_randk_pass<kScatter><<<dim3(gk, M), kBlock, 0, s>>>(grads, N, K, seed, t, bucket, bstride, words, tmp, ws.status);
+    k_randk_sort<<<dim3(gb, M), kBlock, 0, s>>>(bucket, nb, bstride, K, words, counts, ranked ? 1u : 0u);
     k_randk_pad<<<dim3(gk < 64 ? gk : 64, M), 256, 0, s>>>(counts, K, words);
   }
   P.end(s);
