@@ -128,6 +128,22 @@ def test_many_workers(lib):
     assert_same(got, want, what="M=300")
 
 
+@pytest.mark.parametrize("shape", [(2, 50_000, 5_000), (3, 300_000, 150_000), (3, 300_000, 3_000)],
+                         ids=["no_scratch_pool", "K_beyond_the_pool", "pool_holds_the_records"])
+def test_both_forms_of_the_second_step(lib, shape):
+    """A context of exactly the call's size: small rows and dense K leave no room for the per-entry
+    records, so the second step evaluates the permutation again; the last shape keeps the records."""
+    M, N, K = shape
+    rng = np.random.default_rng(N + K)
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    G[:, ::9] = 0.0
+    x = rng.standard_normal(N).astype(np.float32)
+    want = R.step_randk(G, K, x, 1e-3, SEED, 5)
+    with lib.Context(M, N, K, device=0) as c:
+        got = gpu_step_randk(c, G, K, x, 1e-3, SEED, 5, fused=False)
+    assert_same(got, want, what=f"{shape}")
+
+
 def test_nan_among_the_selected_is_reported(ctx, lib):
     G = np.ones((2, 5000), dtype=np.float32)
     S = R.randk_index_set(5000, 50, SEED, 0, 1)
