@@ -14,6 +14,7 @@ region starts.  Prints ONE JSON line:
   cpu_baseline the CPU oracle timed on this machine's host cores on a bounded sample of the workload
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -83,6 +84,9 @@ def main():
                     help="with --momentum: start from a momentum vector without zeros, as it is after some hundred "
                          "steps of training (every coordinate is then read, updated and written each step); without "
                          "this flag the vector starts at zero, as in the first steps, and stays as sparse as the votes")
+    ap.add_argument("--sparsity", type=float, default=0.0, metavar="GAMMA",
+                    help="override K with GAMMA * N on the chosen workload (the paper sweeps K/N from 1 down to 0.001; "
+                         "not the headline workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (all M workers are rows of one tensor); --gpus must be 1")
@@ -110,6 +114,9 @@ def main():
     g, x = datagen.to_device(cfg, device="cuda:0")
     log(f"[bench] {cfg.name}: M={cfg.M} N={cfg.N} K={cfg.K} generated and uploaded in {time.perf_counter() - t0:.1f} s")
     M, N, K = cfg.M, cfg.N, cfg.K
+    if args.sparsity > 0:
+        K = max(1, min(N, int(round(args.sparsity * N))))
+        cfg = dataclasses.replace(cfg, K=K)
     lr = float(datagen.lr32(cfg))
     ctx = s3gd.Context(M, N, K, device=0)
     words = torch.empty((M, K), dtype=torch.int32, device=dev)

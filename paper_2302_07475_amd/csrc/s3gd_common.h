@@ -36,7 +36,10 @@ struct RowState {
   u32 n_cand;     // candidate path: candidates collected by the filter pass
   u32 n_alloc;    // candidate path: candidate slots handed out to blocks (slab allocator)
   u32 overflow;   // candidate path: a block found no room for its candidates
-  u32 pad[5];
+  u32 bracket;    // candidate path with a bracket: entries at or above L + (kHistBins - 1) * 1024 are counted, not kept
+  u32 n_sure;     // bracket: entries at or above the bracket's upper end (all of them are selected)
+  u32 row_emit;   // bracket: the threshold is known and the row passes (count, emit) serve the row
+  u32 pad[2];
 };
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
 

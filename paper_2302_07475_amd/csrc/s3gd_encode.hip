@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // state reset (a kernel rather than a memset so that callers may capture the call into a graph)
-__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode, u32 first_alloc) {
+__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode, u32 first_alloc, u32 bracket, u32 all_selected) {
   const u32 m = blockIdx.y;
   for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x)
     hist[(size_t)m * kHistBins + i] = 0;
@@ -75,6 +75,8 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
     s.k_rem = first_rank;  // K on the general route, the sample rank on the candidate route
     s.mode = mode;
     s.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
+    s.bracket = bracket;
+    s.row_emit = all_selected ? 2u : 0u;  // K = N: threshold 0, no tie slots (the zero-filled T and q), count from the scan
     rs[m] = s;
     if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; }
   }
@@ -207,7 +209,9 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
   const u32 above = block_excl_scan<u32>(s, &total, lds);
 #pragma unroll
   for (int i = 0; i < PER; ++i) h[top - i] = 0;
-  const u32 k = WHAT == kResolveFilter ? K : st.k_rem;
+  // With a bracket the n_sure entries above it come first in the order: the K-th overall is the
+  // (K - n_sure)-th of the candidates (n_sure is 0 without a bracket).
+  const u32 k = WHAT == kResolveFilter ? (K > st.n_sure ? K - st.n_sure : 0u) : st.k_rem;
   if (WHAT == kResolveFilter) {
     // The candidate route stands only if no wave ran out of room and the K-th largest key is among
     // the candidates.  If it sits in the open-ended top bin (thread 0's c[0]) the bins say nothing
@@ -215,8 +219,11 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
     __shared__ u32 verdict;
     // (A filter pass in chunks fills no bins: its candidates are the slots it handed out.)
     if (!have_bins) st.n_cand = st.n_alloc;
-    if (threadIdx.x == 0)
-      verdict = (!st.overflow && st.n_cand >= K && (!have_bins || total == st.n_cand)) ? ((have_bins && c[0] < K) ? 2u : 1u) : 0u;
+    if (threadIdx.x == 0) {
+      const bool usable = !st.overflow && k >= 1 && st.n_cand >= k && (!have_bins || total == st.n_cand);
+      // a bracket has no way on if the K-th key lies above it (k == 0): those entries were not kept
+      verdict = usable ? ((have_bins && c[0] < k) ? 2u : (st.bracket ? 0u : 1u)) : 0u;
+    }
     __syncthreads();
     if (verdict != 2u) {
       if (threadIdx.x == 0) {
@@ -247,6 +254,10 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
           st.q = st.T == 0 ? 0u : st.k_rem;
           st.c_gt = K - st.k_rem;
           st.count = st.c_gt + st.q;
+          if (st.mode == kModeCandidates && st.bracket) {  // the candidates do not hold every selected entry:
+            st.mode = kModeGeneral;                        // the row passes count and emit with this T
+            st.row_emit = 1;
+          }
         }
         rs[m] = st;
       }
@@ -257,7 +268,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
 
 // Per tile: entries above the threshold and entries equal to it, packed as (eq << 32) | gt.
 __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
-                                                       u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride) {
+                                                       u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
+                                                       u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeGeneral) return;
@@ -271,13 +283,16 @@ __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__
     TileRegs r;
     load_tile(rowv, a, vend, (u64)tile * kTile, r);
     u32 gt = 0, eq = 0;
+    bool nan = false;
 #pragma unroll
     for (int i = 0; i < kLoads * 4; ++i) {
       const u32 key = r.b[i] & 0x7FFFFFFFu;
       const bool ok = (r.valid >> i) & 1u;
       gt += ok && key > st.T;
       eq += ok && key == st.T;
+      nan |= ok && key > 0x7F800000u;
     }
+    if (nan) status[0] = 1;  // the only pass that sees every entry when K = N skips the radix select
     u32 pk = gt | (eq << 16);  // at most 1024 per wave each
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) pk += __shfl_down(pk, d, 64);
@@ -294,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__
 
 // In-place exclusive scan of a row's packed tile counts; entry n_tiles receives the row total.
 __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
-                                                           const RowState* __restrict__ rs, u32 candidate_rows) {
+                                                           RowState* __restrict__ rs, u32 candidate_rows) {
   if ((rs[blockIdx.x].mode != kModeGeneral) != (candidate_rows != 0)) return;
   __shared__ u64 lds[kScanBlock / 64];
   u64* t = tile_cnt + (size_t)blockIdx.x * tile_stride;
@@ -314,7 +329,13 @@ __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ til
     }
     carry += total;
   }
-  if (threadIdx.x == 0) t[n_tiles] = carry;
+  if (threadIdx.x == 0) {
+    t[n_tiles] = carry;
+    if (!candidate_rows && rs[blockIdx.x].row_emit == 2u) {  // K = N: every non-zero entry is sent
+      rs[blockIdx.x].c_gt = (u32)carry;
+      rs[blockIdx.x].count = (u32)carry;
+    }
+  }
 }
 
 // Emits the words of every tile at its scanned offset, in ascending index.
@@ -466,6 +487,7 @@ struct FilterWave {
   u32 fill;             // candidates staged in LDS; they belong to out[cur - fill, cur)
   u32 seg_base, n_seg;  // first slot of the segment being filled; segments already closed
   u64* segs;            // the wave's segment list in global memory, kChain entries
+  u32 sure;  // bracket: entries at or above the bracket's upper end seen by this wave
   bool overflow, nan;
 };
 
@@ -559,11 +581,13 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
   }
 }
 
-template <bool INTERIOR>
+template <bool INTERIOR, bool BRACKET>
 __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32* h, u64* stage, u32* n_alloc,
                                             uint2* __restrict__ out, u32 cand_stride, u32 slab, FilterWave& w) {
   // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
-  // candidates below is scalar work plus a few mbcnt.
+  // candidates below is scalar work plus a few mbcnt.  With a bracket an entry at or above its upper
+  // end U (the start of the open top bin) is only counted: it is selected whatever the threshold.
+  const u32 U = L + ((u32)(kHistBins - 1) << 10);
   bool pr[kLoads * 4];
   u64 mk[kLoads * 4];
   u64 any = 0;
@@ -572,6 +596,12 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     const u32 key = r.b[i] & 0x7FFFFFFFu;
     pr[i] = key >= L;
     if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
+    if (BRACKET) {
+      const bool top = pr[i] && key >= U;
+      w.sure += (u32)__popcll(ballot(top));
+      w.nan |= top && key > 0x7F800000u;
+      pr[i] = pr[i] && !top;
+    }
     mk[i] = ballot(pr[i]);
     any |= mk[i];
   }
@@ -616,6 +646,9 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
 }
 
 // The filter pass over rows that are read only: persistent waves, each with a range of its own.
+// BRACKET (dense K, where keeping every entry at or above L would need a pool as large as the row):
+// only the entries inside the 2047 closed bins above L are kept, the ones above are counted.
+template <bool BRACKET>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
                                                    u32 cand_stride, u64* __restrict__ wave_seg, u32* __restrict__ wave_nseg,
                                                    u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
@@ -657,8 +690,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
       else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
-    if (tile >= first && tile < last) filter_tile<true>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
-    else filter_tile<false>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
+    if (tile >= first && tile < last) filter_tile<true, BRACKET>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
+    else filter_tile<false, BRACKET>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
   }
   if (!w.overflow) {
     flush_stage(w, stage, out, lane);
@@ -667,6 +700,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   if (lane == 0) {
     wave_nseg[(size_t)m * wave_stride + g] = w.overflow ? 0u : w.n_seg;
     if (w.total) atomicAdd(&rs[m].n_cand, w.total);
+    if (BRACKET && w.sure) atomicAdd(&rs[m].n_sure, w.sure);
     if (w.overflow) rs[m].overflow = 1;
   }
   if (w.nan) status[0] = 1;
@@ -880,7 +914,7 @@ __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __res
   const RowState st = rs[m];
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     counts[m] = st.count;
-    if (st.mode == kModeGeneral) atomicAdd(&status[1], 1u);
+    if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
     if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
   }
   u32* out = words + (size_t)m * K;
@@ -905,7 +939,7 @@ u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
   const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks, kBlock, 0)
-                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0);
+                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   u32 n = (u32)cus * (u32)per_cu;
   if (const char* e = getenv("S3GD_STREAM_BLOCKS")) {  // tuning knob for experiments
@@ -924,11 +958,19 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
   p.n_tiles = encode_tiles(N);
   p.gx = blocks_per_row(M, p.n_tiles, stream_blocks);
   p.candidates = false;
-  if (K == 0 || N < (1ull << 17) || K * 16 > N) return p;
+  if (K == 0 || N < (1ull << 17)) return p;
+  // Dense K: keeping every entry at or above L would take a pool as large as the row.  The filter
+  // pass then keeps only the entries inside the bins above L (a bracket around the K-th key), counts
+  // the ones above, and the words come from two more passes over the row (count, emit) once the
+  // threshold is known: three reads instead of the general route's five.  Not with a memory (the
+  // chunked pass fills no bins).
+  p.bracket = K * 16 > N;
+  if (p.bracket && chunks) return p;
   // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
   // and never more than a quarter of the row
+  // (with a bracket the largest sample: the K-th key has to fall inside the bins above L)
   u64 s = 1ull << 15;
-  while (s < (1ull << 18) && s * 8 <= N && (double)s * (double)K < 256.0 * (double)N) s <<= 1;
+  while (s < (1ull << 18) && s * 8 <= N && (p.bracket || (double)s * (double)K < 256.0 * (double)N)) s <<= 1;
   const double f = (double)s / (double)N, kf = (double)K * f;
   const double r = ceil(kf + 6.0 * sqrt(kf) + 8.0);
   if (r >= (double)s) return p;
@@ -942,6 +984,15 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
   // a row needs room for its candidates, for the first slab of every wave, for the unused part of the
   // later (doubling) slabs of waves that overflowed (at most what they hold), and a tile of slack
   double need = 2.0 * p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
+  if (p.bracket) {
+    // how many entries fall inside the bracket depends on the distribution: the row takes its share of
+    // the pool, half of it as first slabs; a row that needs more falls back to the general route
+    need = floor((double)cand_pool / M);
+    if (need > (double)N + 2.0 * kWaveTile) need = (double)N + 2.0 * kWaveTile;
+    p.slab = kSlabMin;
+    while (p.slab < kSlabMax && (double)p.slab * 2.0 * p.gx * kWaves < need / 2.0) p.slab <<= 1;
+    if ((double)p.gx * kWaves * p.slab + kWaveTile > need) return p;
+  }
   if (chunks) {  // blocks reserve exactly what they found: no slabs
     need = 2.0 * p.bound + kWaveTile;
     p.n_chunks = chunk_count(N);
@@ -968,7 +1019,10 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
   if (best == 0) return 0;
   // per row: twice the bound, as much again (at most twice the bound) in first slabs, one tile of
   // slack; once: a smallest slab per wave of a streaming launch
-  return (u64)M_max * (4 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
+  u64 pool = (u64)M_max * (4 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
+  // dense K (bracket): an eighth of the row, 25 % of the gradients' bytes
+  if (K_max * 16 > N_max && pool < (u64)M_max * (N_max / 8)) pool = (u64)M_max * (N_max / 8);
+  return pool;
 }
 
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
@@ -996,9 +1050,11 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const u32 stride = tile_stride(N);
   const dim3 grid(p.gx, M);
   const u32 k32 = (u32)K;
+  const bool all = K == N;  // signSGD with majority vote: every non-zero entry is sent, nothing to select
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
                                                                          p.candidates ? kModeCandidates : kModeGeneral,
-                                                                         p.candidates && !p.chunks ? p.gx * (u32)kWaves * p.slab : 0u)));
+                                                                         p.candidates && !p.chunks ? p.gx * (u32)kWaves * p.slab : 0u,
+                                                                         p.candidates && p.bracket ? 1u : 0u, all ? 1u : 0u)));
   const u32 n_waves = !p.candidates ? 0u : (p.chunks ? p.n_lists : p.gx * (u32)kWaves);  // segment lists per row
   const u32 wstride = p.chunks ? p.n_lists + 4 : wave_stride(p.gx);
   if (p.candidates) {
@@ -1012,9 +1068,12 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
                                                                                                p.n_chunks, ws.status)));
+    else if (p.bracket)
+      S3GD_LAUNCH(KID_FILTER, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
+                                                                     ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
     else
-      S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg,
-                                                               wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
+      S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
+                                                                      ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
   }
   // Radix select: over the row for general rows, over the candidates for the others (the last level
@@ -1025,12 +1084,14 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   if (lx < p.gx) lx = p.gx;
   const dim3 lgrid(lx, M);
 #define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves
-  S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-  S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-  S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-  S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+  if (!all) {
+    S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+  }
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
     S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
@@ -1040,7 +1101,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).
-  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride)));
+  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride, ws.status)));
   S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, 0u)));
   S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words, err)));
   u32 fx = (u32)((K + 4095) / 4096);

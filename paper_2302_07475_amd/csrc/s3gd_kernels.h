@@ -79,6 +79,7 @@ struct Workspace {
 struct EncodePlan {
   bool candidates;   // try the candidate route first
   bool chunks;       // the filter pass runs in chunks (one block each, in index order) instead of persistent waves
+  bool bracket;      // dense K: the filter pass keeps the entries inside a bracket around the K-th key and counts those above
   u32 n_chunks, n_lists;  // chunked filter pass: blocks per row, segment lists per row
   u32 n_tiles, gx;   // 4096-entry tiles per row, streaming blocks per row
   u32 n_wtiles, tiles_per_wave;  // candidate route: 1024-entry wave tiles per row, and per wave of the filter

@@ -567,7 +567,11 @@ hipError_t launch_update_momentum(const Workspace& ws, float* x, float* v, const
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s) {
   Profiler& P = *ws.prof;
-  const bool dense = tally || votes;
+  // The sweep over every coordinate also serves the fused call once there is a message per twenty
+  // coordinates: the sparse kernel walks the messages twice (tally, then claim) and pays per message
+  // (measured crossover between M*K/N = 0.03, where the sparse kernel is 1.4 times faster, and
+  // 0.08, where the sweep is; at one message per coordinate the sweep is 5 times faster).
+  const bool dense = tally || votes || (u64)M * K * 20 >= N;
   const int fb = M <= 63 ? 8 : (M <= 16383 ? 16 : 32);
   const u32 tile_coords = dense ? kMomTile : (u32)kVoteWords * (32u / fb);
   const u32 n_vt = (u32)((N + tile_coords - 1) / tile_coords);  // a tiling no finer than kMomTile: the table row fits

@@ -205,6 +205,34 @@ def _encode_only(ctx, G, K):
     return words.cpu().numpy().view(np.uint32), counts.cpu().numpy().view(np.uint32), rows, general
 
 
+@pytest.mark.parametrize("kind", ["gauss", "ties", "layers"])
+@pytest.mark.parametrize("gamma", [0.07, 0.1, 0.25, 0.5, 0.9, 0.999, 1.0])
+def test_dense_sparsity_levels(ctx, gamma, kind):
+    """K/N from 0.07 to 1 (the paper sweeps the sparsity up to 1, signSGD with majority vote): the
+    filter pass keeps a bracket around the K-th magnitude and counts what lies above; K = N selects
+    nothing.  Whatever route a row ends on, words, votes and parameters are the oracle's; on
+    well-spread data up to K = N/2 no row needs the general route."""
+    from oracle import s3gd_oracle as O
+    rng = np.random.default_rng(int(gamma * 1000))
+    M, N = 3, 300_007
+    if kind == "gauss":
+        G = rng.standard_normal((M, N)).astype(np.float32)
+    elif kind == "ties":  # coarse grid and exact zeros: thousands of entries share the K-th magnitude
+        G = (np.rint(rng.standard_t(3, (M, N)) * 16) / 16).astype(np.float32)
+        G[rng.random((M, N)) < 0.05] = 0.0
+    else:  # magnitudes spread over four decades in contiguous blocks
+        G = (rng.standard_normal((M, N)) * np.repeat(10.0 ** rng.uniform(-4, 0, (M, 60)), N // 60 + 1, axis=1)[:, :N]).astype(np.float32)
+    K = min(N, int(round(gamma * N)))
+    x = rng.standard_normal(N).astype(np.float32)
+    want = O.step(G, K, x, np.float32(1e-3))
+    got = gpu_step(ctx, G, K, x, 1e-3, fused=True, dense_outputs=False)
+    assert_same(got, want, keys=("words", "counts", "x"), what=f"{kind} gamma={gamma}")
+    if kind == "gauss" and gamma <= 0.5:
+        assert ctx.last_encode_info() == (M, 0)
+    if gamma == 1.0:
+        assert ctx.last_encode_info() == (M, 0)  # nothing to select: not a fallback
+
+
 @pytest.mark.parametrize("N,K", [(131_072, 131), (200_003, 2_000), (1_000_000, 1_000), (2_000_001, 20_000), (2_097_152, 100_000)])
 def test_candidate_route_is_taken_and_exact(ctx, N, K):
     from oracle import s3gd_oracle as O
