@@ -222,14 +222,15 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
     if (threadIdx.x == 0) {
       const bool usable = !st.overflow && k >= 1 && st.n_cand >= k && (!have_bins || total == st.n_cand);
       // a bracket has no way on if the K-th key lies above it (k == 0): those entries were not kept
-      verdict = usable ? ((have_bins && c[0] < k) ? 2u : (st.bracket ? 0u : 1u)) : 0u;
+      // (with bins; without them the radix select over the candidates finds the (K - n_sure)-th)
+      verdict = usable ? ((have_bins && c[0] < k) ? 2u : ((st.bracket && have_bins) ? 0u : 1u)) : 0u;
     }
     __syncthreads();
     if (verdict != 2u) {
       if (threadIdx.x == 0) {
         st.mode = verdict ? kModeCandWide : kModeGeneral;
         st.prefix = 0;
-        st.k_rem = K;
+        st.k_rem = verdict ? k : K;
         rs[m] = st;
       }
       return;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
           st.q = st.T == 0 ? 0u : st.k_rem;
           st.c_gt = K - st.k_rem;
           st.count = st.c_gt + st.q;
-          if (st.mode == kModeCandidates && st.bracket) {  // the candidates do not hold every selected entry:
+          if (st.mode != kModeGeneral && st.bracket) {     // the candidates do not hold every selected entry:
             st.mode = kModeGeneral;                        // the row passes count and emit with this T
             st.row_emit = 1;
           }
@@ -401,11 +402,31 @@ __global__ __launch_bounds__(kBlock) void k_emit_rows(const float* grads, u64 N,
         const int i = 4 * j + e;
         if ((sel >> i) & 1u) {
           const u32 n = (u32)(v0 + (u64)j * (kBlock * 4) + e);
-          if (o < K) {  // o < K by construction; guards a racing writer of grads
-            out[o] = (n << 1) | (r.b[i] >> 31);
-            if (err) err[(size_t)m * N + n] = 0.0f;
-          }
+          if (o < K) out[o] = (n << 1) | (r.b[i] >> 31);  // o < K by construction; guards a racing writer of grads
           ++o;
+        }
+      }
+    }
+    if (err) {
+      // +0.0 over every entry whose sign is sent.  Four lanes share 64 bytes of the row: if one of them
+      // has such an entry all four rewrite their 16 bytes (memory merges a smaller write by reading
+      // first; with dense K nearly every run is touched).  Groups that reach outside the row store
+      // their selected entries one by one.
+      u32* erow = reinterpret_cast<u32*>(err + (size_t)m * N) - a;
+      const u32 lane = lane_id();
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        const u32 s4 = (sel >> (4 * j)) & 0xFu, ok4 = (r.valid >> (4 * j)) & 0xFu;
+        const u64 live = ballot(s4 != 0);
+        if (((live >> (lane & 60u)) & 0xFull) == 0) continue;
+        u32* p = erow + (u64)tile * kTile + (u64)j * (kBlock * 4) + (u64)threadIdx.x * 4;
+        if (ok4 == 0xFu) {
+          *reinterpret_cast<uint4*>(p) = make_uint4((s4 & 1u) ? 0u : r.b[4 * j], (s4 & 2u) ? 0u : r.b[4 * j + 1],
+                                                    (s4 & 4u) ? 0u : r.b[4 * j + 2], (s4 & 8u) ? 0u : r.b[4 * j + 3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if ((s4 >> e) & 1u) p[e] = 0u;
         }
       }
     }
@@ -727,26 +748,35 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
 // waves that each stream a far-apart range).  A read-only pass gains nothing from it, and the one
 // returning atomic per block, harmless next to 96 KB of traffic, would bound it: atomics on one
 // counter (or on the neighbouring counters of a few rows) complete at about 86 per microsecond.
-template <bool INTERIOR>
-__device__ __forceinline__ u32 count_candidates(const TileRegs& r, u32 L) {
+// BRACKET: entries at or above U are counted in `sure` and not kept.
+template <bool INTERIOR, bool BRACKET>
+__device__ __forceinline__ u32 count_candidates(const TileRegs& r, u32 L, u32 U, u32& sure, bool& nan) {
   u32 total = 0;
 #pragma unroll
   for (int i = 0; i < kLoads * 4; ++i) {
-    bool p = (r.b[i] & 0x7FFFFFFFu) >= L;
+    const u32 key = r.b[i] & 0x7FFFFFFFu;
+    bool p = key >= L;
     if (!INTERIOR) p = p && ((r.valid >> i) & 1u);
+    if (BRACKET) {
+      const bool top = p && key >= U;
+      sure += (u32)__popcll(ballot(top));
+      nan |= top && key > 0x7F800000u;
+      p = p && !top;
+    }
     total += (u32)__popcll(ballot(p));
   }
   return total;
 }
 
-template <bool INTERIOR>
-__device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 first_slot,
+template <bool INTERIOR, bool BRACKET>
+__device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32 first_slot,
                                                  uint2* __restrict__ out, bool& nan) {
   bool pr[kLoads * 4];
   u64 mk[kLoads * 4];
 #pragma unroll
   for (int i = 0; i < kLoads * 4; ++i) {
-    pr[i] = (r.b[i] & 0x7FFFFFFFu) >= L;
+    const u32 key = r.b[i] & 0x7FFFFFFFu;
+    pr[i] = key >= L && (!BRACKET || key < U);
     if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
     mk[i] = ballot(pr[i]);
   }
@@ -760,6 +790,7 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
 
 // Six waves per SIMD (80 registers, four of them spilled) measured 2 % to 6 % faster than the five the
 // kernel would take by itself; seven lose again, and so do eight waves of one tile each.
+template <bool BRACKET>
 __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
                                                           RowState* __restrict__ rs, uint2* __restrict__ cand, u32 cand_stride,
                                                           u64* __restrict__ list_seg, u32* __restrict__ list_nseg, u32 list_stride,
@@ -793,9 +824,17 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
 #pragma unroll
   for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
   if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
-  const u32 c0 = in0 ? count_candidates<true>(r0, st.L) : count_candidates<false>(r0, st.L);
-  const u32 c1 = in1 ? count_candidates<true>(r1, st.L) : count_candidates<false>(r1, st.L);
-  if (lane == 0) wsum[wave] = c0 + c1;
+  // dense K: a bracket of one binade above L (there are no bins here to tie its width to)
+  const u32 U = st.L + 0x00800000u;
+  u32 sure = 0;
+  bool nan = false;
+  const u32 c0 = in0 ? count_candidates<true, BRACKET>(r0, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r0, st.L, U, sure, nan);
+  const u32 c1 = in1 ? count_candidates<true, BRACKET>(r1, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r1, st.L, U, sure, nan);
+  if (lane == 0) {
+    wsum[wave] = c0 + c1;
+    if (BRACKET && sure) atomicAdd(&rs[m].n_sure, sure);
+  }
+  if (nan) status[0] = 1;
   __syncthreads();
   u32 before = 0, total = 0;
 #pragma unroll
@@ -823,14 +862,13 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
   const u32 base = sbase;
   if (total == 0 || base == 0xFFFFFFFFu) return;
   uint2* out = cand + (size_t)m * cand_stride;
-  bool nan = false;
   if (c0) {
-    if (in0) place_chunk_tile<true>(r0, a, t0, lane, st.L, base + before, out, nan);
-    else place_chunk_tile<false>(r0, a, t0, lane, st.L, base + before, out, nan);
+    if (in0) place_chunk_tile<true, BRACKET>(r0, a, t0, lane, st.L, U, base + before, out, nan);
+    else place_chunk_tile<false, BRACKET>(r0, a, t0, lane, st.L, U, base + before, out, nan);
   }
   if (c1) {
-    if (in1) place_chunk_tile<true>(r1, a, t1, lane, st.L, base + before + c0, out, nan);
-    else place_chunk_tile<false>(r1, a, t1, lane, st.L, base + before + c0, out, nan);
+    if (in1) place_chunk_tile<true, BRACKET>(r1, a, t1, lane, st.L, U, base + before + c0, out, nan);
+    else place_chunk_tile<false, BRACKET>(r1, a, t1, lane, st.L, U, base + before + c0, out, nan);
   }
   if (nan) status[0] = 1;
 }
@@ -938,7 +976,7 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
 u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks, kBlock, 0)
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks<false>, kBlock, 0)
                                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   u32 n = (u32)cus * (u32)per_cu;
@@ -962,10 +1000,9 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
   // Dense K: keeping every entry at or above L would take a pool as large as the row.  The filter
   // pass then keeps only the entries inside the bins above L (a bracket around the K-th key), counts
   // the ones above, and the words come from two more passes over the row (count, emit) once the
-  // threshold is known: three reads instead of the general route's five.  Not with a memory (the
-  // chunked pass fills no bins).
+  // threshold is known: three reads instead of the general route's five.  With a memory the bracket
+  // is one binade wide (the chunked pass fills no bins).
   p.bracket = K * 16 > N;
-  if (p.bracket && chunks) return p;
   // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
   // and never more than a quarter of the row
   // (with a bracket the largest sample: the K-th key has to fall inside the bins above L)
@@ -994,7 +1031,7 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
     if ((double)p.gx * kWaves * p.slab + kWaveTile > need) return p;
   }
   if (chunks) {  // blocks reserve exactly what they found: no slabs
-    need = 2.0 * p.bound + kWaveTile;
+    if (!p.bracket) need = 2.0 * p.bound + kWaveTile;
     p.n_chunks = chunk_count(N);
     p.n_lists = chunk_lists(N);
   }
@@ -1064,10 +1101,14 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-    if (p.chunks)
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
+    if (p.chunks && p.bracket)
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
                                                                                                p.n_chunks, ws.status)));
+    else if (p.chunks)
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
+                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
+                                                                                                p.n_chunks, ws.status)));
     else if (p.bracket)
       S3GD_LAUNCH(KID_FILTER, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
                                                                      ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));

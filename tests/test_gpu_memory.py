@@ -133,6 +133,26 @@ def test_filter_chunk_boundaries(ctx, N):
         assert ctx.last_encode_info() == (M, 0)
 
 
+@pytest.mark.parametrize("gamma", [0.1, 0.3, 0.7, 1.0])
+def test_dense_sparsity_levels_with_memory(ctx, gamma):
+    """K/N up to 1 with the memory: the chunked filter pass keeps a bracket of one binade above the
+    sampled bound; two iterations so that the memory left by the first feeds the second."""
+    rng = np.random.default_rng(int(gamma * 100))
+    M, N = 3, 262_147
+    K = min(N, int(round(gamma * N)))
+    E = (rng.standard_normal((M, N)) * 0.3).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    for t in range(2):
+        Gt = rng.standard_normal((M, N)).astype(np.float32)
+        Gt[:, ::11] = 0.0
+        want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+        got = gpu_step_ec(ctx, Gt, E, 1.0, K, x, 1e-3, fused=(t == 0))
+        assert_same(got, want, keys=KEYS, what=f"gamma={gamma} iteration {t}")
+        E, x = want["err"], want["x"]
+    if gamma <= 0.3 or gamma == 1.0:
+        assert ctx.last_encode_info() == (M, 0)
+
+
 def test_unaligned_base_pointers_same_phase(ctx, lib):
     rng = np.random.default_rng(19)
     M, N, K = 3, 150_001, 1_500
