@@ -114,6 +114,13 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   }
   c->bytes = l.total;
   char* b = static_cast<char*>(c->base);
+  // the status words start clear: each call resets only the flags it can raise itself
+  if (hipMemset(b + l.status, 0, sizeof(u32) * 8) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(c->base);
+    delete c;
+    return S3GD_E_HIP;
+  }
   c->ws.rs = reinterpret_cast<RowState*>(b + l.rs);
   c->ws.status = reinterpret_cast<u32*>(b + l.status);
   c->ws.hist = reinterpret_cast<u32*>(b + l.hist);

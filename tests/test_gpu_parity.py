@@ -352,3 +352,20 @@ def test_few_waves_long_segment_chains(lib, monkeypatch):
         assert c.last_encode_details()[1] == 0
     w, cc = O.topk_sign_encode(G, K)
     assert np.array_equal(counts, cc) and np.array_equal(words, w)
+
+
+def test_fresh_context_has_clear_status(lib):
+    """The status words belong to the workspace, which is not cleared as a whole: a context created
+    over memory that held other data before must still report no stale flag after its first call."""
+    junk = torch.full((64 << 20,), -1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    del junk
+    torch.cuda.empty_cache()
+    for _ in range(4):
+        with lib.Context(2, 50_000, 500, device=0) as c:
+            assert c.last_async_status() == 0
+            g = torch.randn((2, 50_000), device="cuda")
+            c.topk_sign_encode(g, 500)
+            torch.cuda.synchronize()
+            assert c.last_async_status() == 0
+
