@@ -13,6 +13,10 @@
 //                    resolved and the words are emitted from the candidates alone.
 //                    If the K-th key lies far above L (a row whose magnitudes are spread widely
 //                    around the threshold) the radix select simply runs over the candidates.
+//                    At dense sparsity levels (K > N/16) the pass keeps only a bracket of keys above L
+//                    and counts the entries above it; the words then come from the general route's
+//                    count and emit passes with the threshold known (three reads of the row).
+//                    K = N selects nothing: count and emit (two reads).
 //   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
 //                    pass and an emit pass.  Any row for which the candidate route's checks fail
 //                    (too few or too many candidates, tiny rows) takes it; the choice is made on
