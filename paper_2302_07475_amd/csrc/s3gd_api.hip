@@ -27,7 +27,7 @@ constexpr u32 kMaxRows = 65535;  // rows map to gridDim.y
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_nseg, wave_sum, cand, total;
+  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_nseg, wave_sum, wave_sure, cand, total;
   u64 cand_pool;
 };
 
@@ -42,6 +42,7 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N) * kChain, 256);
   l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M, N), 256);
   l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N), 256);
+  l.wave_sure = off; off = align_up(off + sizeof(u32) * wave_table_entries(M, N), 256);
   l.blk_sum = off;  off = align_up(off + sizeof(u64) * (size_t)M * blk_stride(N), 256);
   l.cand_pool = candidate_pool_entries(M, N, K);
   l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);
@@ -129,6 +130,7 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->ws.wave_seg = reinterpret_cast<u64*>(b + l.wave_seg);
   c->ws.wave_nseg = reinterpret_cast<u32*>(b + l.wave_nseg);
   c->ws.wave_sum = reinterpret_cast<u64*>(b + l.wave_sum);
+  c->ws.wave_sure = reinterpret_cast<u32*>(b + l.wave_sure);
   c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
   c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
   c->ws.cand_pool = l.cand_pool;

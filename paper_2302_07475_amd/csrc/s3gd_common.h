@@ -38,7 +38,8 @@ struct RowState {
   u32 overflow;   // candidate path: a block found no room for its candidates
   u32 bracket;    // candidate path with a bracket: entries at or above L + (kHistBins - 1) * 1024 are counted, not kept
   u32 n_sure;     // bracket: entries at or above the bracket's upper end (all of them are selected)
-  u32 row_emit;   // bracket: the threshold is known and the row passes (count, emit) serve the row
+  u32 row_emit;   // the row passes (count, emit) serve the row with a threshold that is already known:
+                  // 1 = from a bracket (chunked filter pass), 2 = K = N (threshold 0, count from the scan)
   u32 pad[2];
 };
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
@@ -46,6 +47,7 @@ static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
 constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
 constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, last ten key bits resolved among the candidates
 constexpr u32 kModeCandWide = 2;    // as above, but the K-th key lies far above the bound: full radix select among the candidates
+constexpr u32 kModeRangeEmit = 3;   // dense K: threshold known from the bracket; a second pass over the waves' ranges emits the words
 
 constexpr int kWaveTile = 64 * 4 * kLoads;  // 1024 entries: the unit of the candidate route (one wave, no barriers)
 constexpr int kChunkTiles = 2;      // wave tiles a wave of the chunked filter pass holds: a block covers 8192 entries

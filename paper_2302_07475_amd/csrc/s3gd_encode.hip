@@ -14,9 +14,8 @@
 //                    If the K-th key lies far above L (a row whose magnitudes are spread widely
 //                    around the threshold) the radix select simply runs over the candidates.
 //                    At dense sparsity levels (K > N/16) the pass keeps only a bracket of keys above L
-//                    and counts the entries above it; the words then come from the general route's
-//                    count and emit passes with the threshold known (three reads of the row).
-//                    K = N selects nothing: count and emit (two reads).
+//                    and counts the entries above it; the words then come from a second pass over the
+//                    row (two reads).  K = N selects nothing: count and emit (two reads).
 //   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
 //                    pass and an emit pass.  Any row for which the candidate route's checks fail
 //                    (too few or too many candidates, tiny rows) takes it; the choice is made on
@@ -259,8 +258,10 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
           st.q = st.T == 0 ? 0u : st.k_rem;
           st.c_gt = K - st.k_rem;
           st.count = st.c_gt + st.q;
-          if (st.mode != kModeGeneral && st.bracket) {     // the candidates do not hold every selected entry:
-            st.mode = kModeGeneral;                        // the row passes count and emit with this T
+          if (st.mode == kModeCandidates && st.bracket) {
+            st.mode = kModeRangeEmit;  // the candidates do not hold every selected entry: a second pass over the waves' ranges emits
+          } else if (st.mode == kModeCandWide && st.bracket) {
+            st.mode = kModeGeneral;    // chunked pass: the row passes count and emit with this T
             st.row_emit = 1;
           }
         }
@@ -677,7 +678,7 @@ template <bool BRACKET>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
                                                    u32 cand_stride, u64* __restrict__ wave_seg, u32* __restrict__ wave_nseg,
                                                    u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
-                                                   u32* __restrict__ status) {
+                                                   u32* __restrict__ status, u32* __restrict__ wave_sure) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
@@ -725,7 +726,10 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   if (lane == 0) {
     wave_nseg[(size_t)m * wave_stride + g] = w.overflow ? 0u : w.n_seg;
     if (w.total) atomicAdd(&rs[m].n_cand, w.total);
-    if (BRACKET && w.sure) atomicAdd(&rs[m].n_sure, w.sure);
+    if (BRACKET) {
+      wave_sure[(size_t)m * wave_stride + g] = w.sure;
+      if (w.sure) atomicAdd(&rs[m].n_sure, w.sure);
+    }
     if (w.overflow) rs[m].overflow = 1;
   }
   if (w.nan) status[0] = 1;
@@ -882,7 +886,8 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
 // (eq << 32) | gt of each segment list against the final threshold; scanned afterwards.
 __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
                                                        const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
-                                                       u32 wave_stride, u32 n_waves, u64* __restrict__ wave_sum) {
+                                                       u32 wave_stride, u32 n_waves, u64* __restrict__ wave_sum,
+                                                       const u32* __restrict__ wave_sure) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode == kModeGeneral) return;
@@ -905,6 +910,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
     }
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    if (st.mode == kModeRangeEmit) gt += wave_sure[(size_t)m * wave_stride + g];  // above the bracket: all greater than T
     if (lane == 0) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
   }
 }
@@ -917,7 +923,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
                                                       u32* __restrict__ words, float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode == kModeGeneral) return;
+  if (st.mode == kModeGeneral || st.mode == kModeRangeEmit) return;
   const u32 lane = lane_id();
   float* erow = err ? err + (size_t)m * N : nullptr;
   u32* out = words + (size_t)m * K;
@@ -946,6 +952,95 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
       o += (u32)__popcll(sel_mask);
       eq_seen += (u32)__popcll(eq_mask);
     }
+  }
+}
+
+// ---- dense K: the words from a second pass over the waves' ranges -------------------------------
+// The filter pass with a bracket kept only the candidates inside it, so the words cannot come from
+// the pool.  Every wave walks the same run of wave tiles as in the filter pass; its first output slot
+// is the scanned count of its predecessors (candidates above T plus the entries above the bracket,
+// and the ties before it), so no count pass over the row is needed.
+template <bool INTERIOR>
+__device__ __forceinline__ void emit_range_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 T, u32 q, u32& o, u32& eq_seen,
+                                                u32* __restrict__ out, u64 K) {
+  bool sel[kLoads * 4], eqb[kLoads * 4];
+  u64 eqm[kLoads * 4];
+  u64 eq_any = 0;
+#pragma unroll
+  for (int i = 0; i < kLoads * 4; ++i) {
+    const u32 key = r.b[i] & 0x7FFFFFFFu;
+    const bool ok = INTERIOR || ((r.valid >> i) & 1u);
+    sel[i] = ok && key > T;
+    eqb[i] = ok && key == T;
+    eqm[i] = ballot(eqb[i]);
+    eq_any |= eqm[i];
+  }
+  if (eq_any) {  // wave-uniform
+    if (eq_seen < q) {  // tie slots are left: they go to the equal entries in ascending index
+      u32 run = eq_seen;
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        u32 rk = run + ballot_rank(eqm[4 * j]) + ballot_rank(eqm[4 * j + 1]) + ballot_rank(eqm[4 * j + 2]) + ballot_rank(eqm[4 * j + 3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (eqb[4 * j + e]) { sel[4 * j + e] = rk < q; ++rk; }
+        }
+        run += (u32)__popcll(eqm[4 * j]) + (u32)__popcll(eqm[4 * j + 1]) + (u32)__popcll(eqm[4 * j + 2]) + (u32)__popcll(eqm[4 * j + 3]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kLoads * 4; ++i) eq_seen += (u32)__popcll(eqm[i]);
+  }
+  const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const u64 m0 = ballot(sel[4 * j]), m1 = ballot(sel[4 * j + 1]), m2 = ballot(sel[4 * j + 2]), m3 = ballot(sel[4 * j + 3]);
+    if ((m0 | m1 | m2 | m3) == 0) continue;  // wave-uniform
+    u32 p = o + ballot_rank(m0) + ballot_rank(m1) + ballot_rank(m2) + ballot_rank(m3);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = 4 * j + e;
+      if (sel[i]) {
+        if (p < K) out[p] = ((u32)(v0 + (u64)j * 256 + e) << 1) | (r.b[i] >> 31);  // p < K by construction
+        ++p;
+      }
+    }
+    o += (u32)__popcll(m0) + (u32)__popcll(m1) + (u32)__popcll(m2) + (u32)__popcll(m3);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_range_emit(const float* __restrict__ grads, u64 N, u64 K, const RowState* __restrict__ rs,
+                                                       const u64* __restrict__ wave_sum, u32 wave_stride, u32 n_wtiles,
+                                                       u32 tiles_per_wave, u32* __restrict__ words) {
+  const u32 m = blockIdx.y;
+  const RowState st = rs[m];
+  if (st.mode != kModeRangeEmit) return;
+  const float* row = grads + (size_t)m * N;
+  const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
+  const u32* rowv = reinterpret_cast<const u32*>(row) - a;
+  const u64 vend = N + a;
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 g = blockIdx.x * kWaves + wave;  // the same wave, the same run of tiles as in the filter pass
+  const u32 t0 = g * tiles_per_wave;
+  const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
+  if (t0 >= t1) return;  // wave-uniform; nothing below synchronises across waves
+  const u64 before = wave_sum[(size_t)m * wave_stride + g];
+  u32 eq_seen = (u32)(before >> 32);
+  u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
+  u32* out = words + (size_t)m * K;
+  const u32 first = a ? 1u : 0u;
+  const u32 last = (u32)(vend / kWaveTile);
+  TileRegs nxt;
+  if (t0 >= first && t0 < last) load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
+  else load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
+  for (u32 tile = t0; tile < t1; ++tile) {
+    const TileRegs r = nxt;
+    if (tile + 1 < t1) {
+      if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
+      else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
+    }
+    if (tile >= first && tile < last) emit_range_tile<true>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K);
+    else emit_range_tile<false>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K);
   }
 }
 
@@ -1003,9 +1098,9 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
   if (K == 0 || N < (1ull << 17)) return p;
   // Dense K: keeping every entry at or above L would take a pool as large as the row.  The filter
   // pass then keeps only the entries inside the bins above L (a bracket around the K-th key), counts
-  // the ones above, and the words come from two more passes over the row (count, emit) once the
-  // threshold is known: three reads instead of the general route's five.  With a memory the bracket
-  // is one binade wide (the chunked pass fills no bins).
+  // the ones above, and the words come from a second pass over the row once the threshold is known:
+  // two reads instead of the general route's five.  With a memory the bracket is one binade wide (the
+  // chunked pass fills no bins) and the row passes count and emit: three reads.
   p.bracket = K * 16 > N;
   // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
   // and never more than a quarter of the row
@@ -1115,10 +1210,11 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                                                 p.n_chunks, ws.status)));
     else if (p.bracket)
       S3GD_LAUNCH(KID_FILTER, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
-                                                                     ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
+                                                                     ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status, ws.wave_sure)));
     else
       S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
-                                                                      ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status)));
+                                                                      ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status,
+                                                                      ws.wave_sure)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
   }
   // Radix select: over the row for general rows, over the candidates for the others (the last level
@@ -1140,10 +1236,13 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
     S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
-                                                                      n_waves, ws.wave_sum)));
+                                                                      n_waves, ws.wave_sum, ws.wave_sure)));
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, 1u)));
     S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
+    if (p.bracket && !p.chunks)
+      S3GD_LAUNCH(KID_EMIT, (k_range_emit<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.wave_sum, wstride, p.n_wtiles, p.tiles_per_wave,
+                                                                 words)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).
   S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride, ws.status)));

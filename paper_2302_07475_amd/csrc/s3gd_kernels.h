@@ -69,6 +69,7 @@ struct Workspace {
   u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment a filter wave left
   u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each wave's list
   u64* wave_sum;  // [M][wave_stride]  candidate route: (eq << 32 | gt) of each list, scanned in place
+  u32* wave_sure; // [M][wave_stride]  bracket: entries at or above the bracket's upper end in each wave's range
   uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
   u64 cand_pool;  // entries of `cand`
   u32 stream_blocks;  // blocks of a streaming launch = blocks resident on the device at once (one round, no tail)
