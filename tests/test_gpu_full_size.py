@@ -6,6 +6,7 @@ against the oracle.  Elsewhere each row's message is checked against the definit
 oracle's any-size checker (exact: it accepts one answer only), membership of sampled coordinates
 is decided one by one from the rank definition, and the vote and the update are recomputed by the
 oracle from the checked messages and compared on every coordinate.  Tolerance: 0 bits."""
+import dataclasses
 import time
 from concurrent.futures import ThreadPoolExecutor
 
@@ -113,6 +114,31 @@ def test_c4_heavy_tails_and_ties(lib):
 
 def test_c5_largest(lib):
     _property_case(lib, datagen.C5, sample_rows=range(datagen.C5.M), samples_per_row=1)
+
+
+def test_c4_at_a_tenth_of_the_coordinates(lib):
+    """K/N = 0.1, the sparsity the paper finds best for ten workers: the filter pass with a bracket
+    and the second pass over the wave ranges, at full size, on the recipe with ties and exact zeros."""
+    cfg = dataclasses.replace(datagen.C4, K=datagen.C4.N // 10)
+    _property_case(lib, cfg, sample_rows=(0, 5), samples_per_row=2)
+
+
+def test_c2_every_coordinate_selected(lib):
+    """K = N (signSGD with majority vote) at full size: every non-zero entry of every row is sent."""
+    cfg = dataclasses.replace(datagen.C2, K=datagen.C2.N)
+    G = datagen.gradients(cfg)
+    x0 = datagen.params(cfg)
+    g = torch.from_numpy(G).cuda()
+    x = torch.from_numpy(x0.copy()).cuda()
+    words, counts, info = _run_step(lib, cfg, g, x)
+    idx = np.arange(cfg.N, dtype=np.uint64)
+    for m in range(cfg.M):
+        nz = G[m] != 0
+        want = ((idx[nz] << np.uint64(1)) | (G[m][nz] < 0).astype(np.uint64)).astype(np.uint32)
+        assert counts[m] == want.size and np.array_equal(words[m, : want.size], want)
+        assert (words[m, want.size:] == 0xFFFFFFFF).all()
+    _check_vote_and_update(cfg, words, counts, x0, x)
+    assert info == (cfg.M, 0)
 
 
 def test_c3_ten_steps_parameters_carried(lib):
