@@ -807,7 +807,7 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;  // block-uniform
-  __shared__ u32 wsum[kWaves];
+  __shared__ u32 wsum[kWaves], wsure[kWaves];
   __shared__ u32 sbase;
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
@@ -832,15 +832,15 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
 #pragma unroll
   for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
   if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
-  // dense K: a bracket of one binade above L (there are no bins here to tie its width to)
-  const u32 U = st.L + 0x00800000u;
+  // dense K: the same bracket as the persistent pass keeps (its 2047 closed bins), though no bins are filled here
+  const u32 U = st.L + ((u32)(kHistBins - 1) << 10);
   u32 sure = 0;
   bool nan = false;
   const u32 c0 = in0 ? count_candidates<true, BRACKET>(r0, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r0, st.L, U, sure, nan);
   const u32 c1 = in1 ? count_candidates<true, BRACKET>(r1, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r1, st.L, U, sure, nan);
   if (lane == 0) {
     wsum[wave] = c0 + c1;
-    if (BRACKET && sure) atomicAdd(&rs[m].n_sure, sure);
+    if (BRACKET) wsure[wave] = sure;
   }
   if (nan) status[0] = 1;
   __syncthreads();
@@ -852,6 +852,11 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
     total += c;
   }
   if (threadIdx.x == 0) {
+    if (BRACKET) {
+      u32 block_sure = 0;
+      for (int w = 0; w < kWaves; ++w) block_sure += wsure[w];
+      if (block_sure) atomicAdd(&rs[m].n_sure, block_sure);
+    }
     u32 base = 0;
     bool fits = true;
     if (total) {
@@ -1099,8 +1104,8 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bo
   // Dense K: keeping every entry at or above L would take a pool as large as the row.  The filter
   // pass then keeps only the entries inside the bins above L (a bracket around the K-th key), counts
   // the ones above, and the words come from a second pass over the row once the threshold is known:
-  // two reads instead of the general route's five.  With a memory the bracket is one binade wide (the
-  // chunked pass fills no bins) and the row passes count and emit: three reads.
+  // two reads instead of the general route's five.  With a memory (the chunked pass fills no bins) the
+  // radix select runs over the bracket's candidates and the row passes count and emit: three reads.
   p.bracket = K * 16 > N;
   // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
   // and never more than a quarter of the row
