@@ -233,6 +233,28 @@ def test_dense_sparsity_levels(ctx, gamma, kind):
         assert ctx.last_encode_info() == (M, 0)  # nothing to select: not a fallback
 
 
+def test_dense_rows_that_do_not_fit_the_bracket(ctx):
+    """K/N = 0.2 on rows whose magnitudes crowd the bracket (all equal, two values, one value plus a
+    sprinkle of larger ones) or leave it empty around the K-th key: each such row ends on the general
+    route, the well-spread row next to them does not."""
+    from oracle import s3gd_oracle as O
+    rng = np.random.default_rng(77)
+    N = 400_000
+    K = N // 5
+    G = np.empty((5, N), dtype=np.float32)
+    G[0] = rng.standard_normal(N)
+    G[1] = 3.0
+    G[2] = rng.choice([1.0, -1.0, 1.0000001], N)
+    G[3] = np.where(rng.random(N) < 0.01, rng.standard_normal(N) * 100, 0.5)
+    G[4] = np.where(rng.random(N) < 0.15, 1e6, 1e-6) * rng.choice([1.0, -1.0], N)  # K-th key far below the ones above it
+    x = rng.standard_normal(N).astype(np.float32)
+    want = O.step(G, K, x, np.float32(1e-3))
+    got = gpu_step(ctx, G, K, x, 1e-3, fused=True, dense_outputs=False)
+    assert_same(got, want, keys=("words", "counts", "x"), what="crowded brackets")
+    rows, general = ctx.last_encode_info()
+    assert rows == 5 and 3 <= general <= 4
+
+
 @pytest.mark.parametrize("N,K", [(131_072, 131), (200_003, 2_000), (1_000_000, 1_000), (2_000_001, 20_000), (2_097_152, 100_000)])
 def test_candidate_route_is_taken_and_exact(ctx, N, K):
     from oracle import s3gd_oracle as O
