@@ -1,5 +1,6 @@
 """A seeded sweep over shapes, sparsity levels and value distributions, each case run through one
-of the entry-point combinations and compared with the CPU oracle bit for bit (tolerance 0).  The
+of the entry-point combinations (fused step, the three calls, with the memory, with momentum, random-K,
+through the wire format) and compared with the CPU oracle bit for bit (tolerance 0).  The
 cases are drawn so that every route of the encode is hit: rows below and above the smallest row the
 single pass serves (2^17 entries), K on both sides of N/16 (where the pass starts to keep a bracket
 instead of every candidate), K = N, K of a handful, ties, zeros, magnitudes spread over decades."""
@@ -9,7 +10,9 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import s3gd_coding as C
 from oracle import s3gd_oracle as O
+from oracle import s3gd_randk as R
 from tests.helpers import assert_same, gpu_step
 from tests.test_gpu_memory import gpu_step_ec
 
@@ -46,12 +49,13 @@ def _case(seed):
     gamma = float(rng.choice([2e-4, 1e-3, 1e-2, 0.05, 1 / 16, 0.0626, 0.1, 0.3, 0.6, 0.95, 1.0]))
     K = max(1, min(N, int(round(gamma * N))))
     kind = int(rng.integers(0, 5))
-    mode = int(rng.integers(0, 4))  # 0 fused, 1 three calls, 2 fused with memory, 3 separate calls with memory
+    # 0 fused, 1 three calls, 2 fused with memory, 3 separate calls with memory, 4 momentum, 5 random-K, 6 wire format
+    mode = int(rng.integers(0, 7))
     return rng, M, N, K, kind, mode
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("S3GD_SWEEP_CASES", "80"))))  # more cases for a longer hunt
-def test_seeded_case(ctx, seed):
+def test_seeded_case(ctx, lib, seed):
     rng, M, N, K, kind, mode = _case(seed)
     what = f"seed {seed}: M={M} N={N} K={K} kind={kind} mode={mode}"
     G = _values(rng, kind, M, N).astype(np.float32)
@@ -61,6 +65,49 @@ def test_seeded_case(ctx, seed):
         want = O.step(G, K, x, lr)
         got = gpu_step(ctx, G, K, x, lr, fused=(mode == 0), dense_outputs=(mode == 1))
         assert_same(got, want, what=what)
+    elif mode == 4:
+        mu = float(rng.choice([0.9, 0.5]))
+        v = np.where(rng.random(N) < 0.5, 0.0, rng.standard_normal(N)).astype(np.float32)
+        xd, vd = torch.from_numpy(x.copy()).cuda(), torch.from_numpy(v.copy()).cuda()
+        words = torch.empty((M, K), dtype=torch.int32, device="cuda")
+        counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+        for t in range(2):
+            want = O.step_with_momentum(G, K, x, v, lr, mu)
+            ctx.step_momentum(torch.from_numpy(G).cuda(), K, xd, vd, float(lr), mu, words, counts)
+            torch.cuda.synchronize()
+            got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+                       x=xd.cpu().numpy(), v=vd.cpu().numpy())
+            assert_same(got, want, keys=("words", "counts", "x", "v"), what=f"{what} iteration {t}")
+            x, v = want["x"], want["v"]
+            G = _values(rng, kind, M, N).astype(np.float32)
+    elif mode == 5:
+        seed, t = int(rng.integers(0, 2**63)), int(rng.integers(0, 1000))
+        want = R.step_randk(G, K, x, lr, seed, t)
+        xd = torch.from_numpy(x.copy()).cuda()
+        words = torch.empty((M, K), dtype=torch.int32, device="cuda")
+        counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+        ctx.step_randk(torch.from_numpy(G).cuda(), K, seed, t, xd, float(lr), words, counts)
+        torch.cuda.synchronize()
+        got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32), x=xd.cpu().numpy())
+        assert_same(got, want, keys=("words", "counts", "x"), what=what)
+    elif mode == 6:
+        want = O.step(G, K, x, lr)
+        g = torch.from_numpy(G).cuda()
+        xd = torch.from_numpy(x.copy()).cuda()
+        words, counts = ctx.topk_sign_encode(g, K)
+        packed = torch.full((M, lib.packed_row_words(N, K)), 0x55555555, dtype=torch.int32, device="cuda")
+        ctx.pack_messages(words, counts, N, packed)
+        w2, c2 = torch.empty_like(words), torch.empty_like(counts)
+        ctx.unpack_messages(packed, N, K, w2, c2)
+        ctx.vote_update(w2, c2, N, xd, float(lr))
+        torch.cuda.synchronize()
+        assert ctx.last_async_status() == 0
+        pk = packed.cpu().numpy().view(np.uint32)
+        for m in range(M):
+            ref = C.pack_row_fast(want["words"][m], int(want["counts"][m]), N)
+            assert np.array_equal(pk[m, : ref.size], ref), f"{what}: packed row {m}"
+        got = dict(words=w2.cpu().numpy().view(np.uint32), counts=c2.cpu().numpy().view(np.uint32), x=xd.cpu().numpy())
+        assert_same(got, want, keys=("words", "counts", "x"), what=what)
     else:
         E = (_values(rng, int(rng.integers(0, 5)), M, N) * 0.5).astype(np.float32)
         eta = float(rng.choice([1.0, 0.5]))
