@@ -176,7 +176,9 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
         w[i / 4] |= (u32)(((d > 0) - (d < 0)) & 0xFF) << (8 * (i % 4));
       }
       if (n + 16 <= N) {
-        *reinterpret_cast<uint4*>(votes + n) = make_uint4(w[0], w[1], w[2], w[3]);
+        u32x4 q;  // streamed out: 1 byte per coordinate is never read back by this kernel
+        q.x = w[0]; q.y = w[1]; q.z = w[2]; q.w = w[3];
+        __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(votes + n));
       } else {
         for (int i = 0; i < 16 && n + i < N; ++i) votes[n + i] = (int8_t)((w[i / 4] >> (8 * (i % 4))) & 0xFF);
       }
