@@ -80,6 +80,9 @@ def main():
                     help="capture the step into a HIP graph once and time replays (the same kernels, fewer launch gaps)")
     ap.add_argument("--momentum", action="store_true",
                     help="time s3gd_step_momentum (mu = 0.9): the update streams a momentum vector (not the headline workload)")
+    ap.add_argument("--memory-acc", action="store_true",
+                    help="time s3gd_step_acc: the error-compensation memory already holds g~ + e when the step starts (the "
+                         "gradients were accumulated into it), so the step reads one tensor (not the headline workload)")
     ap.add_argument("--dense-state", action="store_true",
                     help="with --momentum: start from a momentum vector without zeros, as it is after some hundred "
                          "steps of training (every coordinate is then read, updated and written each step); without "
@@ -151,6 +154,8 @@ def main():
             ctx.vote_update(w2, c2, N, x, lr)
         elif args.momentum:
             ctx.step_momentum(g, K, x, mom, lr, 0.9, words, counts, err=err, eta=1.0)
+        elif args.memory_acc:
+            ctx.step_acc(g, K, x, lr, words, counts, None, None)  # g plays the memory: each step's zeros stay in it
         elif args.memory:
             ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
         elif args.three_calls:
@@ -232,13 +237,14 @@ def main():
                             "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
                             ("s3gd_step_momentum (mu=0.9" + (", with memory" if args.memory else "") +
                              (", dense momentum state)" if args.dense_state else ", momentum starts at zero)")) if args.momentum else
+                            "s3gd_step_acc (fused, the memory already holds the compensated gradients)" if args.memory_acc else
                             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
                             ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
                    "rows_on_general_path": general_rows, "launch": "HIP graph replay" if args.graph else "eager"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
                      "duration_from": "HIP events inside the timed region" if dom in live else "HIP events, eager pass before the timed region",
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.momentum or args.wire or args.randk) else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.memory_acc or args.momentum or args.wire or args.randk) else None},
         "step_roofline": {"full_reads_of_G_per_step": full_reads,
                           "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
                           "floor_bytes": floor_bytes,

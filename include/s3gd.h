@@ -163,6 +163,26 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
                  s3gd_stream_t stream);
 
 /*
+ * The same iteration when the caller has already formed g_m in the memory buffer (Section 2.2, the same
+ * two equations): a backward pass that accumulates its gradients into the buffer leaves
+ * g_m = g~_m + e_m there (eta = 1), and any other eta is a scaling the caller applies before
+ * accumulating.  The encode then reads one tensor instead of two and writes only the zeros:
+ *
+ *     words = TopKSign(acc_m),   acc_m <- acc_m - TopK(acc_m)      (+0.0 where a sign was sent)
+ *
+ *   acc    dev, in/out  [M, N] fp32, row stride N, 4-byte aligned: g_m on entry, the new memory on
+ *                       return.  Only the sent entries are written.
+ *   words, counts, x, lr, tally, votes   as in s3gd_topk_sign_encode / s3gd_step.
+ *
+ * Bit for bit the result of s3gd_topk_sign_encode_ec / s3gd_step_ec called with gradients and memory
+ * whose fp32 sum is acc (for eta = 1).
+ */
+S3GD_API int s3gd_topk_sign_encode_acc(s3gd_ctx* ctx, float* acc, uint32_t M, uint64_t N, uint64_t K, uint32_t* words,
+                              uint32_t* counts, s3gd_stream_t stream);
+S3GD_API int s3gd_step_acc(s3gd_ctx* ctx, float* acc, uint32_t M, uint64_t N, uint64_t K, float* x, float lr, uint32_t* words,
+                  uint32_t* counts, int32_t* tally, int8_t* votes, s3gd_stream_t stream);
+
+/*
  * Momentum form of the update (Section 4 "Effects of optimization hyper-parameters"):
  *     v[n] <- fp32(fp32(mu * v[n]) + votes[n]),   x[n] <- fp32(x[n] - fp32(lr * v[n]))
  * with the new v in the second formula; every operation is rounded once.  mu == 0 gives the same x

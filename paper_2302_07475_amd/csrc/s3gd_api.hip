@@ -256,6 +256,36 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 
+S3GD_API int s3gd_topk_sign_encode_acc(s3gd_ctx* ctx, float* acc, uint32_t M, uint64_t N, uint64_t K, uint32_t* words,
+                              uint32_t* counts, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!acc || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!aligned(acc, 4) || !aligned(words, 4) || !aligned(counts, 4)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_encode(ctx->ws, nullptr, acc, 0.0f, M, N, K, words, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_step_acc(s3gd_ctx* ctx, float* acc, uint32_t M, uint64_t N, uint64_t K, float* x, float lr, uint32_t* words,
+                  uint32_t* counts, int32_t* tally, int8_t* votes, s3gd_stream_t stream) {
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  if (!acc || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
+  if (!aligned(acc, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) || !aligned(votes, 16))
+    return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_encode(ctx->ws, nullptr, acc, 0.0f, M, N, K, words, counts, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
+  e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
 S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const int8_t* votes, float lr, float mu, uint64_t N,
                                s3gd_stream_t stream) {
   if (!ctx || !x || !v || !votes || N == 0) return S3GD_E_INVAL;

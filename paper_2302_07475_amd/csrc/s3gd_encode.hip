@@ -967,7 +967,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
 // and the ties before it), so no count pass over the row is needed.
 template <bool INTERIOR>
 __device__ __forceinline__ void emit_range_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 T, u32 q, u32& o, u32& eq_seen,
-                                                u32* __restrict__ out, u64 K) {
+                                                u32* __restrict__ out, u64 K, u32* zero_row) {
   bool sel[kLoads * 4], eqb[kLoads * 4];
   u64 eqm[kLoads * 4];
   u64 eq_any = 0;
@@ -1011,12 +1011,26 @@ __device__ __forceinline__ void emit_range_tile(const TileRegs& r, u32 a, u32 ti
       }
     }
     o += (u32)__popcll(m0) + (u32)__popcll(m1) + (u32)__popcll(m2) + (u32)__popcll(m3);
+    if (zero_row) {  // the row is a memory: +0.0 over the sent entries, as whole 64-byte runs (see k_emit_rows)
+      const u32 s4 = (u32)sel[4 * j] | ((u32)sel[4 * j + 1] << 1) | ((u32)sel[4 * j + 2] << 2) | ((u32)sel[4 * j + 3] << 3);
+      if (((ballot(s4 != 0) >> (lane & 60u)) & 0xFull) == 0) continue;
+      u32* p = zero_row + (u64)tile * kWaveTile + (u64)j * 256 + (u64)lane * 4;
+      if (INTERIOR) {
+        *reinterpret_cast<uint4*>(p) = make_uint4((s4 & 1u) ? 0u : r.b[4 * j], (s4 & 2u) ? 0u : r.b[4 * j + 1],
+                                                  (s4 & 4u) ? 0u : r.b[4 * j + 2], (s4 & 8u) ? 0u : r.b[4 * j + 3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if ((s4 >> e) & 1u) p[e] = 0u;
+      }
+    }
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_range_emit(const float* __restrict__ grads, u64 N, u64 K, const RowState* __restrict__ rs,
+// `zero` non-NULL: `grads` is a memory holding g (the same buffer): every sent entry becomes +0.0.
+__global__ __launch_bounds__(kBlock) void k_range_emit(const float* grads, u64 N, u64 K, const RowState* __restrict__ rs,
                                                        const u64* __restrict__ wave_sum, u32 wave_stride, u32 n_wtiles,
-                                                       u32 tiles_per_wave, u32* __restrict__ words) {
+                                                       u32 tiles_per_wave, u32* __restrict__ words, float* zero) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeRangeEmit) return;
@@ -1033,6 +1047,7 @@ __global__ __launch_bounds__(kBlock) void k_range_emit(const float* __restrict__
   u32 eq_seen = (u32)(before >> 32);
   u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
   u32* out = words + (size_t)m * K;
+  u32* zero_row = zero ? reinterpret_cast<u32*>(zero + (size_t)m * N) - a : nullptr;
   const u32 first = a ? 1u : 0u;
   const u32 last = (u32)(vend / kWaveTile);
   TileRegs nxt;
@@ -1044,8 +1059,8 @@ __global__ __launch_bounds__(kBlock) void k_range_emit(const float* __restrict__
       if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
       else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
-    if (tile >= first && tile < last) emit_range_tile<true>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K);
-    else emit_range_tile<false>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K);
+    if (tile >= first && tile < last) emit_range_tile<true>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K, zero_row);
+    else emit_range_tile<false>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K, zero_row);
   }
 }
 
@@ -1173,8 +1188,13 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   Profiler& P = *ws.prof;
 #define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
   // With a memory the filter pass reads two rows and writes one: that mix runs fastest as blocks in index order.
-  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, err ? ws.stream_blocks_mem : ws.stream_blocks, err != nullptr);
-  if (err && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
+  // `grads` NULL with `err`: the caller has already formed g in the memory buffer (accumulated into it); the row is
+  // then read like plain gradients, and only the zeros over the sent entries distinguish the call.
+  const bool formed = err && !grads;
+  if (formed) grads = err;
+  float* mem = formed ? nullptr : err;  // the memory to add in, if any
+  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, mem ? ws.stream_blocks_mem : ws.stream_blocks, mem != nullptr);
+  if (mem && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
     const u64 total = (u64)M * N;
     const u32 head = (u32)((4 - ((reinterpret_cast<uintptr_t>(err) >> 2) & 3u)) & 3u);
     u64 blocks = (total / 4 + kBlock - 1) / kBlock;
@@ -1201,9 +1221,9 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles;
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
     if (p.chunks && p.bracket)
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
@@ -1247,7 +1267,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
     if (p.bracket && !p.chunks)
       S3GD_LAUNCH(KID_EMIT, (k_range_emit<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.wave_sum, wstride, p.n_wtiles, p.tiles_per_wave,
-                                                                 words)));
+                                                                 words, err)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).
   S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride, ws.status)));

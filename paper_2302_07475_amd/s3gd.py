@@ -20,7 +20,7 @@ N_LIMIT = (1 << 31) - 2
 
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
-    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec",
+    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
@@ -47,6 +47,10 @@ _lib.s3gd_apply_update.restype = _int
 _lib.s3gd_apply_update.argtypes = [_vp, _vp, _vp, _f32, _u64, _vp]
 _lib.s3gd_step.restype = _int
 _lib.s3gd_step.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.s3gd_topk_sign_encode_acc.restype = _int
+_lib.s3gd_topk_sign_encode_acc.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _vp, _vp]
+_lib.s3gd_step_acc.restype = _int
+_lib.s3gd_step_acc.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
 _lib.s3gd_topk_sign_encode_ec.restype = _int
 _lib.s3gd_topk_sign_encode_ec.argtypes = [_vp, _vp, _vp, _f32, _u32, _u64, _u64, _vp, _vp, _vp]
 _lib.s3gd_step_ec.restype = _int
@@ -197,6 +201,25 @@ class Context:
         M, N = grads.shape
         self._check(_lib.s3gd_step_ec(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), float(lr),
                                       _ptr(words), _ptr(counts), _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step_ec")
+        return x
+
+    def topk_sign_encode_acc(self, acc: torch.Tensor, K: int, words: torch.Tensor | None = None,
+                             counts: torch.Tensor | None = None, stream=None):
+        """The encode when g = g~ + e already sits in the memory buffer `acc`; on return acc is the new memory."""
+        M, N = acc.shape
+        if words is None:
+            words = torch.empty((M, K), dtype=torch.int32, device=acc.device)
+        if counts is None:
+            counts = torch.empty((M,), dtype=torch.int32, device=acc.device)
+        self._check(_lib.s3gd_topk_sign_encode_acc(self._h, _ptr(acc), M, N, K, _ptr(words), _ptr(counts), _stream(stream)),
+                    "s3gd_topk_sign_encode_acc")
+        return words, counts
+
+    def step_acc(self, acc: torch.Tensor, K: int, x: torch.Tensor, lr: float, words: torch.Tensor, counts: torch.Tensor,
+                 tally: torch.Tensor | None = None, votes: torch.Tensor | None = None, stream=None):
+        M, N = acc.shape
+        self._check(_lib.s3gd_step_acc(self._h, _ptr(acc), M, N, K, _ptr(x), float(lr), _ptr(words), _ptr(counts),
+                                       _ptr(tally), _ptr(votes), _stream(stream)), "s3gd_step_acc")
         return x
 
     # -- momentum form of the update -----------------------------------------------------------

@@ -153,6 +153,41 @@ def test_dense_sparsity_levels_with_memory(ctx, gamma):
         assert ctx.last_encode_info() == (M, 0)
 
 
+@pytest.mark.parametrize("shape", [(3, 10_001, 100), (5, 140_001, 1_400), (3, 262_147, 26_214), (2, 300_000, 150_000),
+                                   (2, 131_073, 131_073), (4, 65_537, 0), (4, 500_000, 5_000)],
+                         ids=lambda t: f"M{t[0]}-N{t[1]}-K{t[2]}")
+@pytest.mark.parametrize("fused", [False, True], ids=["encode", "step"])
+def test_memory_already_holding_the_sum(ctx, shape, fused):
+    """s3gd_topk_sign_encode_acc / s3gd_step_acc: the caller has formed g = g~ + e in the buffer.  Words,
+    counts, the new memory and the parameters are those of the two-tensor call on (g~, e); every
+    route of the encode is taken (small rows, single pass, bracket, K = N, K = 0, fallback rows)."""
+    M, N, K = shape
+    rng = np.random.default_rng(N + K)
+    Gt = rng.standard_normal((M, N)).astype(np.float32)
+    E = (rng.standard_normal((M, N)) * 0.4).astype(np.float32)
+    if N == 500_000:  # rows the candidate checks reject
+        Gt[1] = 2.0
+        E[1] = 0.0
+        Gt[2] = np.where(rng.random(N) < 0.001, rng.standard_normal(N), 0.0)
+        E[2] = 0.0
+    x = rng.standard_normal(N).astype(np.float32)
+    want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+    acc = torch.from_numpy(O.compensate(Gt, E, 1.0)).cuda()
+    words = torch.full((M, K), 0x55555555, dtype=torch.int32, device="cuda")
+    counts = torch.full((M,), 0x55555555, dtype=torch.int32, device="cuda")
+    xd = torch.from_numpy(x.copy()).cuda()
+    if fused:
+        ctx.step_acc(acc, K, xd, 1e-3, words, counts)
+    else:
+        ctx.topk_sign_encode_acc(acc, K, words, counts)
+        ctx.vote_update(words, counts, N, xd, 1e-3)
+    torch.cuda.synchronize()
+    assert ctx.last_async_status() == 0
+    got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32), err=acc.cpu().numpy(),
+               x=xd.cpu().numpy())
+    assert_same(got, want, keys=("words", "counts", "err", "x"), what=f"{shape}")
+
+
 def test_unaligned_base_pointers_same_phase(ctx, lib):
     rng = np.random.default_rng(19)
     M, N, K = 3, 150_001, 1_500

@@ -49,8 +49,9 @@ def _case(seed):
     gamma = float(rng.choice([2e-4, 1e-3, 1e-2, 0.05, 1 / 16, 0.0626, 0.1, 0.3, 0.6, 0.95, 1.0]))
     K = max(1, min(N, int(round(gamma * N))))
     kind = int(rng.integers(0, 5))
-    # 0 fused, 1 three calls, 2 fused with memory, 3 separate calls with memory, 4 momentum, 5 random-K, 6 wire format
-    mode = int(rng.integers(0, 7))
+    # 0 fused, 1 three calls, 2 fused with memory, 3 separate calls with memory, 4 momentum, 5 random-K, 6 wire format,
+    # 7 memory that already holds the sum
+    mode = int(rng.integers(0, 8))
     return rng, M, N, K, kind, mode
 
 
@@ -65,6 +66,21 @@ def test_seeded_case(ctx, lib, seed):
         want = O.step(G, K, x, lr)
         got = gpu_step(ctx, G, K, x, lr, fused=(mode == 0), dense_outputs=(mode == 1))
         assert_same(got, want, what=what)
+    elif mode == 7:
+        E = (_values(rng, int(rng.integers(0, 5)), M, N) * 0.5).astype(np.float32)
+        for t in range(2):
+            want = O.step_with_memory(G, E, 1.0, K, x, lr)
+            acc = torch.from_numpy(O.compensate(G, E, 1.0)).cuda()
+            xd = torch.from_numpy(x.copy()).cuda()
+            words = torch.empty((M, K), dtype=torch.int32, device="cuda")
+            counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+            ctx.step_acc(acc, K, xd, float(lr), words, counts)
+            torch.cuda.synchronize()
+            got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+                       err=acc.cpu().numpy(), x=xd.cpu().numpy())
+            assert_same(got, want, keys=("words", "counts", "err", "x"), what=f"{what} iteration {t}")
+            E, x = want["err"], want["x"]
+            G = _values(rng, kind, M, N).astype(np.float32)
     elif mode == 4:
         mu = float(rng.choice([0.9, 0.5]))
         v = np.where(rng.random(N) < 0.5, 0.0, rng.standard_normal(N)).astype(np.float32)
