@@ -199,7 +199,9 @@ S3GD_API int s3gd_apply_update_momentum(s3gd_ctx* ctx, float* x, float* v, const
 /*
  * One whole iteration with the momentum form of the update: encode (with the error-compensation
  * memory when err is non-NULL, exactly as s3gd_topk_sign_encode_ec; err == NULL ignores eta and
- * encodes grads as they are), majority vote, momentum update.  The vote is not materialised.
+ * encodes grads as they are; grads == NULL with err non-NULL treats err as a memory that already
+ * holds the compensated gradients, exactly as s3gd_topk_sign_encode_acc), majority vote, momentum
+ * update.  The vote is not materialised.
  */
 S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, float eta, uint32_t M, uint64_t N,
                        uint64_t K, float* x, float* v, float lr, float mu, uint32_t* words, uint32_t* counts,

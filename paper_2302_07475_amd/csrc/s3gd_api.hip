@@ -303,7 +303,9 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
                        float* x, float* v, float lr, float mu, uint32_t* words, uint32_t* counts, s3gd_stream_t stream) {
   int rc = check_shape(ctx, M, N, K);
   if (rc) return rc;
-  if (err) {
+  if (err && !grads) {  // the memory already holds the compensated gradients (as in s3gd_step_acc)
+    if (!aligned(err, 4)) return S3GD_E_INVAL;
+  } else if (err) {
     if ((rc = check_memory_args(grads, err, eta, M, N))) return rc;
   } else if (!grads || !aligned(grads, 4)) {
     return S3GD_E_INVAL;

@@ -230,7 +230,7 @@ class Context:
 
     def step_momentum(self, grads: torch.Tensor, K: int, x: torch.Tensor, v: torch.Tensor, lr: float, mu: float,
                       words: torch.Tensor, counts: torch.Tensor, err: torch.Tensor | None = None, eta: float = 1.0, stream=None):
-        M, N = grads.shape
+        M, N = (grads if grads is not None else err).shape
         self._check(_lib.s3gd_step_momentum(self._h, _ptr(grads), _ptr(err), float(eta), M, N, K, _ptr(x), _ptr(v), float(lr),
                                             float(mu), _ptr(words), _ptr(counts), _stream(stream)), "s3gd_step_momentum")
         return x, v

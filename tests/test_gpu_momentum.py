@@ -102,6 +102,28 @@ def test_momentum_with_memory_full_iteration(ctx):
         x, v = want["x"], want["v"]
 
 
+def test_momentum_with_a_memory_that_holds_the_sum(ctx):
+    """grads == NULL: err is a memory into which the gradients were already accumulated."""
+    rng = np.random.default_rng(23)
+    M, N, K = 3, 200_003, 2_000
+    Gt = rng.standard_normal((M, N)).astype(np.float32)
+    E = (rng.standard_normal((M, N)) * 0.3).astype(np.float32)
+    x = rng.standard_normal(N).astype(np.float32)
+    v = np.where(rng.random(N) < 0.5, 0.0, rng.standard_normal(N)).astype(np.float32)
+    G = O.compensate(Gt, E, 1.0)
+    want = O.step_with_momentum(G, K, x, v, 0.01, 0.9)
+    want_err = O.residual(G, want["words"], want["counts"])
+    acc, xd, vd = _dev(G), _dev(x), _dev(v)
+    words = torch.empty((M, K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((M,), dtype=torch.int32, device="cuda")
+    ctx.step_momentum(None, K, xd, vd, 0.01, 0.9, words, counts, err=acc)
+    torch.cuda.synchronize()
+    got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32), x=xd.cpu().numpy(),
+               v=vd.cpu().numpy())
+    assert_same(got, want, keys=("words", "counts", "x", "v"), what="memory holds the sum")
+    assert np.array_equal(acc.cpu().numpy().view(np.uint32), want_err.view(np.uint32))
+
+
 @pytest.mark.parametrize("N", [1, 2, 3, 5, 63, 65, 1023, 4097, 32767, 32768, 32769, 65537])
 def test_ragged_sizes_and_special_momenta(ctx, N):
     """Tails that are not a multiple of four; momenta of -0.0, denormals and huge values; K = 0."""
