@@ -531,16 +531,32 @@ __device__ __forceinline__ void close_segment(FilterWave& w, u32 lane) {
 
 __device__ __forceinline__ void store_stream8(u64* p, u64 v) { __builtin_nontemporal_store(v, p); }
 
-__device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, uint2* __restrict__ out, u32 lane) {
+// Writes the staged candidates to the wave's slab and enters them into the block's bins.  Binning
+// here, a candidate per lane, rather than where a candidate is found (a lane or two at a time under
+// its own branch) takes the bin arithmetic and the NaN test out of the per-tile code: a quarter of
+// the pass's instructions once a tile holds ten candidates (K = N / 100).
+__device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, uint2* __restrict__ out, u32 lane, u32 L, u32* h) {
   __builtin_amdgcn_wave_barrier();
   u64* dst = reinterpret_cast<u64*>(out) + (w.cur - w.fill);
-  for (u32 i = lane; i < w.fill; i += 64) store_stream8(dst + i, stage[i]);
+  const u32 Lq = L >> 10;
+  for (u32 i = lane; i < w.fill; i += 64) {
+    const u64 cd = stage[i];
+    store_stream8(dst + i, cd);
+    const u32 key = (u32)(cd >> 32) & 0x7FFFFFFFu;
+    w.nan |= key > 0x7F800000u;
+    const u32 bin = (key >> 10) - Lq;
+    // the open top bin takes most candidates of a heavy-tailed row: one add per wave for those
+    const bool top = bin >= (u32)kHistBins - 1;
+    const u64 tm = ballot(top);
+    if (!top) atomicAdd(&h[bin], 1u);
+    else if (ballot_rank(tm) == 0) atomicAdd(&h[kHistBins - 1], (u32)__popcll(tm));
+  }
   __builtin_amdgcn_wave_barrier();
   w.fill = 0;
 }
 
 // Writes the candidates of one tile, in ascending index, to the LDS stage or (DIRECT) to memory.
-template <bool DIRECT, bool BINS = true>
+template <bool DIRECT, bool BINS, bool NANS>
 __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (&pr)[kLoads * 4], const u64 (&mk)[kLoads * 4],
                                                  const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u32 L, u32* h,
                                                  uint2* __restrict__ dst_global, u64* dst_stage, bool& nan) {
@@ -559,7 +575,7 @@ __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (
         const uint2 cd = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
         if (DIRECT) dst_global[o] = cd; else dst_stage[o] = ((u64)cd.y << 32) | cd.x;
         ++o;
-        nan |= key > 0x7F800000u;
+        if (NANS) nan |= key > 0x7F800000u;
         if (BINS) {
           const u32 bin = (key >> 10) - Lq;
           atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
@@ -640,7 +656,7 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
   }
   if (w.overflow) return;
   if (w.cur + total > w.end) {
-    flush_stage(w, stage, out, lane);  // staged candidates belong to the old slab
+    flush_stage(w, stage, out, lane, L, h);  // staged candidates belong to the old slab
     close_segment(w, lane);
     // the next slab: twice the previous one (slab, slab, 2 slab, 4 slab, ...), and at least what the tile needs
     const u32 grown = slab << (w.n_seg > 1 ? w.n_seg - 1 : 0);
@@ -658,17 +674,17 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     }
   }
   if (w.overflow) return;
-  if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane);
+  if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane, L, h);
   const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
   if (total > (u32)kStage) {  // a tile too dense to stage writes straight to memory (stage is empty here)
-    place_candidates<true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
+    place_candidates<true, true, true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
   } else {
-    place_candidates<false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
+    place_candidates<false, false, false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
     w.fill += total;
   }
   w.cur += total;
   w.total += total;
-  if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane);
+  if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane, L, h);
 }
 
 // The filter pass over rows that are read only: persistent waves, each with a range of its own.
@@ -720,7 +736,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
     else filter_tile<false, BRACKET>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
   }
   if (!w.overflow) {
-    flush_stage(w, stage, out, lane);
+    flush_stage(w, stage, out, lane, st.L, h);
     close_segment(w, lane);
   }
   if (lane == 0) {
@@ -793,7 +809,7 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
   for (int j = 0; j < kLoads; ++j)
     tot[j] = (u32)__popcll(mk[4 * j]) + (u32)__popcll(mk[4 * j + 1]) + (u32)__popcll(mk[4 * j + 2]) + (u32)__popcll(mk[4 * j + 3]);
   const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-  place_candidates<true, false>(r, pr, mk, tot, first_slot, v0, L, nullptr, out, nullptr, nan);
+  place_candidates<true, false, true>(r, pr, mk, tot, first_slot, v0, L, nullptr, out, nullptr, nan);
 }
 
 // Six waves per SIMD (80 registers, four of them spilled) measured 2 % to 6 % faster than the five the
