@@ -94,6 +94,7 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
 struct ListWalk {
   u32 first[kChain], count[kChain], slot[kChain];  // flat number of a segment's first candidate, its length, its first slot
   u32 total;
+  bool single;  // the whole list is one run of the pool (the usual case: the wave's first slab sufficed); wave-uniform
   const uint2* pool;
   __device__ ListWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
                       u32 cand_stride, u32 m, u32 g)
@@ -108,9 +109,11 @@ struct ListWalk {
       first[c] = total;
       total += count[c];
     }
+    single = __builtin_amdgcn_readfirstlane(n_seg <= 1u ? 1 : 0) != 0;
   }
   // pool slot of candidate j < total
   __device__ __forceinline__ u32 locate(u32 j) const {
+    if (single) return slot[0] + j;
     u32 at = 0;
 #pragma unroll
     for (int c = 0; c < kChain; ++c) {
