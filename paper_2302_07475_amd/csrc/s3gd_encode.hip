@@ -957,24 +957,34 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
     const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
     u32 eq_seen = (u32)(before >> 32);
     u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-    for (u32 i0 = 0; i0 < lw.total; i0 += 64) {  // wave-uniform trip count
-      const bool ok = i0 + lane < lw.total;
-      uint2 cd = make_uint2(0, 0);
-      if (ok) cd = lw.pool[lw.locate(i0 + lane)];
-      const u32 key = cd.y & 0x7FFFFFFFu;
-      const bool is_eq = ok && key == st.T;
-      const u64 eq_mask = ballot(is_eq);
-      const bool sel = ok && (key > st.T || (is_eq && eq_seen + ballot_rank(eq_mask) < st.q));
-      const u64 sel_mask = ballot(sel);
-      if (sel) {
-        const u32 pos = o + ballot_rank(sel_mask);
-        if (pos < K) {  // pos < K by construction
-          out[pos] = (cd.x << 1) | (cd.y >> 31);
-          if (erow) erow[cd.x] = 0.0f;
-        }
+    for (u32 i0 = 0; i0 < lw.total; i0 += 64 * kWalk) {  // wave-uniform trip count
+      // kWalk groups of 64 candidates are loaded together, then placed one group after the other
+      uint2 cds[kWalk];
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) {
+        const u32 j = i0 + (u32)u * 64u + lane;
+        cds[u] = j < lw.total ? lw.pool[lw.locate(j)] : make_uint2(0, 0);
       }
-      o += (u32)__popcll(sel_mask);
-      eq_seen += (u32)__popcll(eq_mask);
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) {
+        if (i0 + (u32)u * 64u >= lw.total) break;  // wave-uniform
+        const bool ok = i0 + (u32)u * 64u + lane < lw.total;
+        const uint2 cd = cds[u];
+        const u32 key = cd.y & 0x7FFFFFFFu;
+        const bool is_eq = ok && key == st.T;
+        const u64 eq_mask = ballot(is_eq);
+        const bool sel = ok && (key > st.T || (is_eq && eq_seen + ballot_rank(eq_mask) < st.q));
+        const u64 sel_mask = ballot(sel);
+        if (sel) {
+          const u32 pos = o + ballot_rank(sel_mask);
+          if (pos < K) {  // pos < K by construction
+            out[pos] = (cd.x << 1) | (cd.y >> 31);
+            if (erow) erow[cd.x] = 0.0f;
+          }
+        }
+        o += (u32)__popcll(sel_mask);
+        eq_seen += (u32)__popcll(eq_mask);
+      }
     }
   }
 }
