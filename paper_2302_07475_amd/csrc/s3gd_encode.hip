@@ -134,7 +134,7 @@ template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
                                                       u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status,
                                                       const uint2* __restrict__ cand, u32 cand_stride, const u64* __restrict__ wave_seg,
-                                                      const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves) {
+                                                      const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves, u32 parts) {
   constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int SH = digit_shift(LEVEL);
   const u32 m = blockIdx.y;
@@ -161,16 +161,20 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
         if (take) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
       }
     }
-  } else {  // a wave per segment list
+  } else {  // `parts` waves per segment list, each with a share of its candidates (their order does not matter here)
     const u32 lane = lane_id();
-    for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {
+    for (u32 w = blockIdx.x * kWaves + (threadIdx.x >> 6); w < n_waves * parts; w += gridDim.x * kWaves) {
+      const u32 g = w / parts, part = w - g * parts;
       const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
-      for (u32 i0 = lane; i0 < lw.total; i0 += 64 * kWalk) {
+      const u32 share = ((lw.total + parts - 1) / parts + 63u) & ~63u;
+      const u32 lo = part * share;
+      const u32 hi = lo + share < lw.total ? lo + share : lw.total;
+      for (u32 i0 = lo + lane; i0 < hi; i0 += 64 * kWalk) {
         u32 key[kWalk];
 #pragma unroll
         for (int u = 0; u < kWalk; ++u) {
           const u32 j = i0 + (u32)u * 64u;
-          key[u] = j < lw.total ? (lw.pool[lw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+          key[u] = j < hi ? (lw.pool[lw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
         }
 #pragma unroll
         for (int u = 0; u < kWalk; ++u)
@@ -1278,13 +1282,17 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   if (lx > 4 * p.gx) lx = 4 * p.gx;
   if (lx < p.gx) lx = p.gx;
   const dim3 lgrid(lx, M);
-#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves
+  const dim3 hgrid(p.candidates ? 4 * p.gx : p.gx, M);  // histogram launches
+  // where the candidates' order does not matter a list is shared by as many waves as that grid has for it
+  u32 parts = n_waves ? hgrid.x * (u32)kWaves / n_waves : 1u;
+  parts = parts < 1 ? 1u : (parts > 4 ? 4u : parts);
+#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves, parts
   if (!all) {
-    S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-    S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
-    S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<lgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
+    S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
     S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
   }
 #undef S3GD_HIST_ARGS
