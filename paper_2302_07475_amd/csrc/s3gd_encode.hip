@@ -923,7 +923,28 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
   for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
     const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
     u32 gt = 0, eq = 0;
-    for (u32 i0 = lane; i0 < lw.total; i0 += 64 * kWalk) {
+    u32 done = 0;
+    if (lw.single && (lw.slot[0] & 1u) == 0) {  // wave-uniform: two candidates per lane and load, 16 bytes
+      const uint4* p4 = reinterpret_cast<const uint4*>(lw.pool + lw.slot[0]);
+      const u32 pairs = lw.total >> 1;
+      for (u32 i0 = lane; i0 < pairs; i0 += 64 * kWalk) {
+        uint4 c[kWalk];
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+          const u32 j = i0 + (u32)u * 64u;
+          c[u] = j < pairs ? p4[j] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+          const bool ok = i0 + (u32)u * 64u < pairs;
+          const u32 k0 = c[u].y & 0x7FFFFFFFu, k1 = c[u].w & 0x7FFFFFFFu;
+          gt += (ok && k0 > st.T) + (ok && k1 > st.T);
+          eq += (ok && k0 == st.T) + (ok && k1 == st.T);
+        }
+      }
+      done = pairs << 1;
+    }
+    for (u32 i0 = done + lane; i0 < lw.total; i0 += 64 * kWalk) {
       u32 key[kWalk];
 #pragma unroll
       for (int u = 0; u < kWalk; ++u) {
