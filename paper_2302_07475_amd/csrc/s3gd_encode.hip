@@ -21,7 +21,6 @@
 //                    (too few or too many candidates, tiny rows) takes it; the choice is made on
 //                    the device, per row, with no host synchronisation.
 #include <math.h>
-#include <stdlib.h>
 
 #include "s3gd_common.h"
 #include "s3gd_kernels.h"
@@ -1152,11 +1151,7 @@ u32 resident_stream_blocks(int device, bool with_memory) {
   const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks<false>, kBlock, 0)
                                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
-  u32 n = (u32)cus * (u32)per_cu;
-  if (const char* e = getenv("S3GD_STREAM_BLOCKS")) {  // tuning knob for experiments
-    const long v = atol(e);
-    if (v > 0) n = (u32)v;
-  }
+  const u32 n = (u32)cus * (u32)per_cu;
   return n > kMaxStreamBlocks ? kMaxStreamBlocks : n;
 }
 
