@@ -76,9 +76,11 @@ def test_c2_element_by_element(lib):
     assert info == (cfg.M, 0), "every row should be served by the single-pass candidate route"
 
 
-def _property_case(lib, cfg, sample_rows, samples_per_row):
+def _property_case(lib, cfg, sample_rows, samples_per_row, plant=None):
     t0 = time.time()
     g, x = datagen.to_device(cfg)
+    if plant is not None:
+        plant(g)
     x0 = x.cpu().numpy()
     _say(f"{cfg.name} generated on device in {time.time() - t0:.1f} s")
     words, counts, info = _run_step(lib, cfg, g, x)
@@ -106,6 +108,7 @@ def _property_case(lib, cfg, sample_rows, samples_per_row):
     _check_vote_and_update(cfg, words, counts, x0, x)
     _say(f"{cfg.name} vote and update checked on all {cfg.N} coordinates ({time.time() - t0:.1f} s)")
     assert info == (cfg.M, 0), "every row should be served by the single-pass candidate route"
+    return words, counts
 
 
 def test_c4_heavy_tails_and_ties(lib):
@@ -114,6 +117,26 @@ def test_c4_heavy_tails_and_ties(lib):
 
 def test_c5_largest(lib):
     _property_case(lib, datagen.C5, sample_rows=range(datagen.C5.M), samples_per_row=1)
+
+
+def test_longest_row_the_word_format_allows(lib):
+    """N = 2^31 - 2, the largest the 32-bit words can index (index, sign bit, and a pad word that is
+    no message), on the C5 recipe with two workers.  Entries planted at both ends of the rows must come
+    out as the first and the last words, the last one a single step below the pad word."""
+    N = (1 << 31) - 2
+    cfg = dataclasses.replace(datagen.C5, M=2, N=N, K=1 << 21, name="C5 recipe at the longest row")
+
+    def plant(g):
+        g[:, 0] = -1.0e9
+        g[0, N - 1] = -2.0e9
+        g[1, N - 1] = 3.0e9
+        g[:, N - 2] = 1.0e9
+        torch.cuda.synchronize()
+
+    w, _ = _property_case(lib, cfg, sample_rows=(1,), samples_per_row=1, plant=plant)
+    assert w[0, 0] == 1 and w[1, 0] == 1
+    assert w[0, -1] == (((N - 1) << 1) | 1) == 0xFFFFFFFB and w[0, -2] == ((N - 2) << 1)
+    assert w[1, -1] == ((N - 1) << 1) == 0xFFFFFFFA and w[1, -2] == ((N - 2) << 1)
 
 
 def test_c4_at_a_tenth_of_the_coordinates(lib):
