@@ -229,11 +229,10 @@ def test_c5_with_memory(lib):
     _memory_case(lib, datagen.C5, iterations=2)
 
 
-def test_c5_with_momentum(lib):
-    """Two full-size iterations of s3gd_step_momentum (mu = 0.9), x and v carried on the device: one
+def _momentum_case(lib, cfg, iterations):
+    """Full-size iterations of s3gd_step_momentum (mu = 0.9), x and v carried on the device: one
     row's message checked against the definition per iteration, then the vote and the momentum update
     recomputed by the oracle from the messages and compared on every coordinate."""
-    cfg = datagen.C5
     dev = torch.device("cuda:0")
     ctx = lib.Context(cfg.M, cfg.N, cfg.K, device=0)
     x = torch.from_numpy(datagen.params(cfg)).to(dev)
@@ -241,7 +240,7 @@ def test_c5_with_momentum(lib):
     words = torch.empty((cfg.M, cfg.K), dtype=torch.int32, device=dev)
     counts = torch.empty((cfg.M,), dtype=torch.int32, device=dev)
     t0 = time.time()
-    for it in range(2):
+    for it in range(iterations):
         g, _ = datagen.to_device(cfg, step=it, want_x=False)
         x0, v0 = x.cpu().numpy(), v.cpu().numpy()
         ctx.step_momentum(g, cfg.K, x, v, float(datagen.lr32(cfg)), 0.9, words, counts)
@@ -253,16 +252,19 @@ def test_c5_with_momentum(lib):
         want_x, want_v = O.momentum_update(x0, v0, votes, datagen.lr32(cfg), 0.9)
         assert np.array_equal(v.cpu().numpy().view(np.uint32), want_v.view(np.uint32)), "momentum differs"
         assert np.array_equal(x.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), "parameters differ"
-        _say(f"C5 momentum iteration {it}: x and v checked on all coordinates ({time.time() - t0:.1f} s)")
+        _say(f"{cfg.name} momentum iteration {it}: x and v checked on all coordinates ({time.time() - t0:.1f} s)")
         del g
     ctx.close()
 
 
-def test_c5_messages_through_the_wire_format(lib):
-    """Full-size C5: encode -> pack -> unpack -> vote+update.  Every packed row equals the coding
+def test_c5_with_momentum(lib):
+    _momentum_case(lib, datagen.C5, iterations=2)
+
+
+def _wire_case(lib, cfg):
+    """Full size: encode -> pack -> unpack -> vote+update.  Every packed row equals the coding
     oracle's bits, the unpacked words equal the encoded ones, x equals the fused step's x, and the
     server's answer (vote -> message -> packed) equals the oracle's."""
-    cfg = datagen.C5
     g, x = datagen.to_device(cfg)
     x_fused = x.clone()
     ctx = lib.Context(cfg.M, cfg.N, cfg.M * cfg.K, device=0)
@@ -281,7 +283,7 @@ def test_c5_messages_through_the_wire_format(lib):
     for m in range(cfg.M):
         ref = C.pack_row_fast(w[m], int(c[m]), cfg.N)
         assert np.array_equal(p[m, : ref.shape[0]], ref), f"packed row {m}"
-    _say(f"C5 uplink: {C.information_bits(cfg.N, cfg.K) / cfg.K:.2f} bits per entry packed, "
+    _say(f"{cfg.name} uplink: {C.information_bits(cfg.N, cfg.K) / cfg.K:.2f} bits per entry packed, "
          f"{1 + np.log2(cfg.N / cfg.K):.2f} by the paper's expression, 32 as words")
     # downlink
     del g
@@ -298,14 +300,17 @@ def test_c5_messages_through_the_wire_format(lib):
     assert np.array_equal(vw.cpu().numpy().view(np.uint32)[:on], ow)
     ref = C.pack_row_fast(ow, on, cfg.N)
     assert np.array_equal(vp.cpu().numpy().view(np.uint32)[0, : ref.shape[0]], ref)
-    _say(f"C5 downlink: {on} voted coordinates, {C.information_bits(cfg.N, on)} bits packed (N = {cfg.N})")
+    _say(f"{cfg.name} downlink: {on} voted coordinates, {C.information_bits(cfg.N, on)} bits packed (N = {cfg.N})")
     ctx.close()
 
 
-def test_c5_randk(lib):
-    """Algorithm 2 at the full C5 size: words and counts of every row against the oracle's keyed
+def test_c5_messages_through_the_wire_format(lib):
+    _wire_case(lib, datagen.C5)
+
+
+def _randk_case(lib, cfg):
+    """Algorithm 2 at full size: words and counts of every row against the oracle's keyed
     permutation (O(K) on the host too), the vote and update recomputed on every coordinate."""
-    cfg = datagen.C5
     g, x = datagen.to_device(cfg)
     x0 = x.cpu().numpy()
     seed, t = 0xC0FFEE1234567, 11
@@ -325,3 +330,17 @@ def test_c5_randk(lib):
         assert (w[m, c[m]:] == 0xFFFFFFFF).all()
     _check_vote_and_update(cfg, w, c, x0, x)
     ctx.close()
+
+
+def test_c5_randk(lib):
+    _randk_case(lib, datagen.C5)
+
+
+def test_longest_row_through_the_other_entry_points(lib):
+    """N = 2^31 - 2 with one worker through the step with memory, the momentum step, the wire format
+    and Algorithm 2: the same checks as at the C5 size."""
+    cfg = dataclasses.replace(datagen.C5, M=1, N=(1 << 31) - 2, K=1 << 21, name="C5 recipe at the longest row")
+    _memory_case(lib, cfg, iterations=1)
+    _momentum_case(lib, cfg, iterations=1)
+    _wire_case(lib, cfg)
+    _randk_case(lib, cfg)
