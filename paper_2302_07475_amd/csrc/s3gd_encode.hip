@@ -46,7 +46,7 @@ __device__ __forceinline__ void store_stream16(u32* p, u32 a, u32 b, u32 c, u32 
 }
 
 // e <- g~ + eta * e over the flat [M * N] array (rows are contiguous).  Used when no row of the call
-// goes through the filter pass (tiny rows, dense K, K = 0).  `head` = elements before the first
+// goes through the filter pass (tiny rows, a pool too small for the plan, K = 0).  `head` = elements before the first
 // 16-byte boundary, the same for both arrays.
 __global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__ g_tilde, float* __restrict__ err, float eta, u64 total,
                                                        u32 head) {
