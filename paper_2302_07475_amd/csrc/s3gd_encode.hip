@@ -157,7 +157,22 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
         bool take = (r.valid >> i) & 1u;
         if (LEVEL == 0) nan |= take && key > 0x7F800000u;
         if (LEVEL > 0) take = take && (key >> (SH + digit_bits(LEVEL))) == st.prefix;
-        if (take) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+        const u32 bin = (key >> SH) & (NB - 1);
+        // Rows that come here are often degenerate (mostly zeros, all equal, heavy ties): most lanes of
+        // a wave then add to one bin, and LDS serialises them.  The lanes that share lane 0's bin add
+        // once, through lane 0, when there are enough of them.
+        const u32 b0 = __builtin_amdgcn_readfirstlane(take ? bin : 0xFFFFFFFFu);
+        const bool same = take && bin == b0;
+        const u32 n_same = (u32)__popcll(ballot(same));
+        if (n_same >= 8u) {  // wave-uniform
+          if (same) {
+            if (lane_id() == 0) atomicAdd(&h[b0], n_same);
+          } else if (take) {
+            atomicAdd(&h[bin], 1u);
+          }
+        } else if (take) {
+          atomicAdd(&h[bin], 1u);
+        }
       }
     }
   } else {  // `parts` waves per segment list, each with a share of its candidates (their order does not matter here)
