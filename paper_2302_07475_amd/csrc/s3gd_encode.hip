@@ -212,10 +212,13 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
 //   kResolveFilter     2048 bins of (key - L) >> 10 filled by the filter pass: checks the candidate
 //                      route and fixes the 21-bit prefix, or starts a radix select over the
 //                      candidates (K-th key in the open top bin), or hands the row to the general route
+// `have_bins` is 0 when the filter pass is the chunked one (with a memory): that pass fills no bins
+// (kResolveFilter), and it must run over every row to form g, so no row leaves the candidate route
+// before it (kResolveSample).
 enum { kResolveRadix = 0, kResolveSample = 1, kResolveFilter = 2 };
 
 template <int LEVEL, int WHAT>
-__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins) {
+__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins, u32 sample_cap) {
   constexpr int NB = WHAT == kResolveFilter ? kHistBins : (1 << digit_bits(LEVEL));
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
@@ -273,6 +276,14 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
           st.L = st.prefix << 10;
           st.prefix = 0;
           st.k_rem = K;
+          // L = 0: the sample holds fewer than its share of non-zero entries (a mostly-zero row with K
+          // above its non-zeros), every entry would be a candidate.  The row goes to the general route
+          // before the filter pass instead of after it, unless that pass must still form g in the memory.
+          if (st.L == 0 && have_bins) st.mode = kModeGeneral;
+          // Likewise a row with so many entries at or above L that they cannot fit its share of the
+          // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
+          // sampled entries that stands for a full pool (0: no such check).
+          if (sample_cap && have_bins && acc + c[i] > sample_cap) st.mode = kModeGeneral;
         }
         if (LEVEL == 2) {
           st.T = st.prefix;
@@ -1285,10 +1296,13 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles;
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
+    // sampled entries at or above L that stand for a row's whole share of the pool (a bracket keeps only part of them)
+    const double cap = (double)p.cand_stride * ((double)p.n_units * kSampleUnit / (double)N);
+    const u32 sample_cap = p.bracket ? 0u : (cap < 1.0 ? 1u : (cap > 4.0e9 ? 0u : (u32)cap));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, sample_cap)));
     if (p.chunks && p.bracket)
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
@@ -1304,7 +1318,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
       S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
                                                                       ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status,
                                                                       ws.wave_sure)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, 0u)));
   }
   // Radix select: over the row for general rows, over the candidates for the others (the last level
   // only, unless the filter's bins could not place the K-th key).
@@ -1320,11 +1334,11 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
 #define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves, parts
   if (!all) {
     S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
     S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
     S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
   }
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
