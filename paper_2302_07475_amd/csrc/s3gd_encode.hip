@@ -124,6 +124,27 @@ struct ListWalk {
 };
 constexpr int kWalk = 4;  // candidates a lane has in flight where their order does not matter
 
+// Adds one to h[bin] for every lane with `take`.  Where most lanes of a wave add to ONE bin (the
+// rows of the general route are mostly degenerate ones: mostly zeros, all equal, heavy ties) LDS
+// serialises them: the lanes that share the first lane's bin add once, through that lane, when
+// there are at least eight of them.  (Over the candidates of a row, which share their leading
+// digits, the same was measured to gain nothing.)
+__device__ __forceinline__ void hist_add(u32* h, u32 bin, bool take) {
+  const u32 b0 = __builtin_amdgcn_readfirstlane(take ? bin : 0xFFFFFFFFu);
+  const bool same = take && bin == b0;
+  const u64 sm = ballot(same);
+  const u32 n_same = (u32)__popcll(sm);
+  if (n_same >= 8u) {  // wave-uniform
+    if (same) {
+      if (ballot_rank(sm) == 0) atomicAdd(&h[b0], n_same);
+    } else if (take) {
+      atomicAdd(&h[bin], 1u);
+    }
+  } else if (take) {
+    atomicAdd(&h[bin], 1u);
+  }
+}
+
 // Histogram pass of one radix level (11 + 10 + 10 key bits, most significant first).
 //   general rows            over the whole row
 //   wide candidate rows     over the row's candidates, every level
@@ -157,22 +178,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
         bool take = (r.valid >> i) & 1u;
         if (LEVEL == 0) nan |= take && key > 0x7F800000u;
         if (LEVEL > 0) take = take && (key >> (SH + digit_bits(LEVEL))) == st.prefix;
-        const u32 bin = (key >> SH) & (NB - 1);
-        // Rows that come here are often degenerate (mostly zeros, all equal, heavy ties): most lanes of
-        // a wave then add to one bin, and LDS serialises them.  The lanes that share lane 0's bin add
-        // once, through lane 0, when there are enough of them.
-        const u32 b0 = __builtin_amdgcn_readfirstlane(take ? bin : 0xFFFFFFFFu);
-        const bool same = take && bin == b0;
-        const u32 n_same = (u32)__popcll(ballot(same));
-        if (n_same >= 8u) {  // wave-uniform
-          if (same) {
-            if (lane_id() == 0) atomicAdd(&h[b0], n_same);
-          } else if (take) {
-            atomicAdd(&h[bin], 1u);
-          }
-        } else if (take) {
-          atomicAdd(&h[bin], 1u);
-        }
+        hist_add(h, (key >> SH) & (NB - 1), take);
       }
     }
   } else {  // `parts` waves per segment list, each with a share of its candidates (their order does not matter here)
