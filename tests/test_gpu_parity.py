@@ -391,3 +391,34 @@ def test_fresh_context_has_clear_status(lib):
             torch.cuda.synchronize()
             assert c.last_async_status() == 0
 
+
+
+def test_two_contexts_on_two_streams(lib):
+    """One context per stream is the contract: two contexts, each with its own scratch memory, take
+    steps on different inputs from two streams at once; each ends with the oracle's result."""
+    cfgs = [datagen.C2.scaled(M=6, N=400_000, K=4_000), datagen.C5.scaled(M=4, N=700_001, K=700)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs = [lib.Context(c.M, c.N, c.K, device=0) for c in cfgs]
+    try:
+        G = [datagen.gradients(c) for c in cfgs]
+        x0 = [datagen.params(c) for c in cfgs]
+        g = [torch.from_numpy(a).cuda() for a in G]
+        x = [torch.from_numpy(a.copy()).cuda() for a in x0]
+        words = [torch.empty((c.M, c.K), dtype=torch.int32, device="cuda") for c in cfgs]
+        counts = [torch.empty((c.M,), dtype=torch.int32, device="cuda") for c in cfgs]
+        torch.cuda.synchronize()
+        steps = 3
+        for _ in range(steps):
+            for i in (0, 1):
+                ctxs[i].step(g[i], cfgs[i].K, x[i], float(datagen.lr32(cfgs[i])), words[i], counts[i], None, None,
+                             stream=streams[i])
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            assert ctxs[i].last_async_status() == 0
+            want = x0[i]
+            for _ in range(steps):
+                want = oracle_step(G[i], cfgs[i].K, want, datagen.lr32(cfgs[i]))["x"]
+            assert np.array_equal(x[i].cpu().numpy().view(np.uint32), want.view(np.uint32))
+    finally:
+        for c in ctxs:
+            c.close()
