@@ -58,8 +58,9 @@ extern "C" {
 
 #define S3GD_OK 0
 #define S3GD_E_INVAL (-1) /* NULL pointer, M == 0, N == 0, K > N, size above the context's maxima,  */
-                          /* misaligned buffer, lr or eta negative or not finite, both vote outputs */
-                          /* NULL, memory buffer at another 16-byte phase than the gradients       */
+                          /* M_max > S3GD_M_LIMIT, misaligned buffer, lr or eta negative or not     */
+                          /* finite, both vote outputs NULL, memory buffer at another 16-byte phase */
+                          /* than the gradients                                                     */
 #define S3GD_E_RANGE (-2) /* N > S3GD_N_LIMIT: index, sign bit and pad word must fit 32 bits         */
 #define S3GD_E_HIP (-3)   /* a HIP runtime call failed; s3gd_last_hip_error() has its code           */
 #define S3GD_E_NOMEM (-4) /* scratch allocation failed                                               */
@@ -70,6 +71,7 @@ extern "C" {
 
 #define S3GD_PAD 0xFFFFFFFFu
 #define S3GD_N_LIMIT 2147483646ull /* 2^31 - 2 */
+#define S3GD_M_LIMIT 65535u        /* workers per context: rows are the second grid dimension of a launch */
 
 typedef struct s3gd_ctx s3gd_ctx; /* opaque */
 typedef void* s3gd_stream_t;      /* hipStream_t */
@@ -78,7 +80,9 @@ typedef void* s3gd_stream_t;      /* hipStream_t */
 S3GD_API size_t s3gd_workspace_bytes(uint32_t M_max, uint64_t N_max, uint64_t K_max);
 
 /* Creates a context on `device` and allocates its scratch once (hipMalloc).  Calls with
- * M <= M_max, N <= N_max, K <= K_max never allocate.  `out` is host memory. */
+ * M <= M_max, N <= N_max, K <= K_max never allocate.  `out` is host memory.
+ * M_max above S3GD_M_LIMIT or N_max == 0 is S3GD_E_INVAL; N_max above S3GD_N_LIMIT is S3GD_E_RANGE;
+ * K_max above N_max is taken as N_max. */
 S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_max, uint64_t K_max);
 
 /* Frees the scratch.  The caller must have synchronised every stream that used the context. */
@@ -135,8 +139,8 @@ S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N
 
 /*
  * Worker side of Algorithm 1 WITH the error-compensation memory (Section 2.2 "Gradient update with
- * sparsification error compensation", eqs. "gradupdate" and "errupdate"; Algorithm 1, the two
- * lines before "send"):
+ * sparsification error compensation", eq. "gradupdate" and the unlabelled memory equation that
+ * follows it; Algorithm 1, the two lines before "send"):
  *
  *     g_m   = g~_m + eta * e_m          evaluated in fp32 as written: a rounded product, then a
  *                                       rounded sum (eta = 1, the paper's setting, makes it one sum)
@@ -208,7 +212,7 @@ S3GD_API int s3gd_step_momentum(s3gd_ctx* ctx, const float* grads, float* err, f
                        s3gd_stream_t stream);
 
 /*
- * Worker side of Algorithm 2 (Section 3.3 "Effect of the random-K sparsification"):
+ * Worker side of Algorithm 2 (Section 3.4 "Effect of the random-K sparsification"):
  * words[m, :] = RandKSign(g_m) = sgn(RandK(g_m)) in the message format above: K coordinates drawn at
  * random instead of the K largest; there is no error memory in this variant.
  *

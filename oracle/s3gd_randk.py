@@ -1,7 +1,7 @@
 """CPU oracle for RandKSign (Algorithm 2 of the paper).  TEST INFRASTRUCTURE ONLY.
 
 RandKSign(g) = sgn(RandK(g)): K coordinates chosen at random instead of the K largest, their
-signs sent, no error memory (Section 3.3 "Effect of the random-K sparsification", Algorithm 2).
+signs sent, no error memory (Section 3.4 "Effect of the random-K sparsification", Algorithm 2).
 The paper does not say how the K coordinates are drawn; its analysis (Assumption 4, Lemma 3)
 needs every coordinate to be selected with probability K/N, independently across workers.
 

@@ -22,7 +22,7 @@ struct s3gd_ctx {
 
 namespace {
 
-constexpr u32 kMaxRows = 65535;  // rows map to gridDim.y
+constexpr u32 kMaxRows = S3GD_M_LIMIT;  // rows map to gridDim.y
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -445,7 +445,13 @@ S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on) {
     if (!ctx->prof.ev) return S3GD_E_NOMEM;
     for (int i = 0; i < 2 * Profiler::kPairs; ++i) {
       const hipError_t e = hipEventCreate(&ctx->prof.ev[i]);
-      if (e != hipSuccess) return hip_fail(ctx, e);
+      if (e != hipSuccess) {  // leave no half-made event array behind
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof.ev[j]);
+        delete[] ctx->prof.ev;
+        ctx->prof.ev = nullptr;
+        ctx->prof.mode = 0;
+        return hip_fail(ctx, e);
+      }
     }
   }
   ctx->prof.mode = on == 2 ? 2 : (on != 0 ? 1 : 0);

@@ -72,9 +72,10 @@ __global__ __launch_bounds__(kBlock) void k_ef_clear_high(const u32* __restrict_
   if ((u64)n > K) n = (u32)K;
   const EfLayout e = ef_layout(N, n);
   u32* row = packed + (size_t)m * row_words;
+  // the flags of the previous coding call go first, whatever row 0 turns out to be
+  if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) status[3] = 0;
   if (e.total_words > row_words) return;  // reported by the pack kernel
   for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < e.high_words; i += (u64)gridDim.x * blockDim.x) row[e.high_off + i] = 0;
-  if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) status[3] = 0;
 }
 
 __global__ __launch_bounds__(kBlock) void k_ef_pack(const u32* __restrict__ words, const u32* __restrict__ counts, u64 N, u64 K,

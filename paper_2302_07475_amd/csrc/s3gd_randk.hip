@@ -1,4 +1,4 @@
-// RandKSign, the worker side of Algorithm 2 (Section 3.3 "Effect of the random-K sparsification"):
+// RandKSign, the worker side of Algorithm 2 (Section 3.4 "Effect of the random-K sparsification"):
 // K coordinates drawn at random instead of the K largest, their signs sent, no error memory.
 //
 // The paper leaves the sampling law open.  Here worker m at iteration t selects

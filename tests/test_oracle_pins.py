@@ -359,6 +359,34 @@ def test_memory_hand_worked_three_iterations():
     assert x.tolist() == [-3.0, -2.0, -1.0]  # every vote was +1: x moved by -lr each time it was selected
 
 
+def test_compensate_rounds_the_product_then_the_sum():
+    """tests/golden/compensate_rounding_example.txt: hand-worked (g~, e, eta) where a rounded product
+    followed by a rounded sum and a fused multiply-add differ in the last bit (eq. "gradupdate",
+    evaluated in fp32 as written).  The fused value is reproduced here in exact rational arithmetic
+    and must differ, so that an oracle that fuses the two operations fails."""
+    import os
+    from fractions import Fraction
+    cases = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "compensate_rounding_example.txt")) as f:
+        for line in f:
+            tok = line.split()
+            if tok and tok[0] == "case":
+                cases.append([int(v, 16) for v in tok[1:]])
+    assert len(cases) == 3
+    for eta_b, g_b, e_b, want, fused in cases:
+        eta = np.array([eta_b], dtype=np.uint32).view(np.float32)[0]
+        g = np.array([[g_b]], dtype=np.uint32).view(np.float32)
+        e = np.array([[e_b]], dtype=np.uint32).view(np.float32)
+        got = O.compensate(g, e, eta).view(np.uint32)[0, 0]
+        assert got == want, (hex(got), hex(want))
+        assert want != fused
+        # one rounding of the exact value lands on the other bits: the two readings really differ here
+        exact = Fraction(float(g[0, 0])) + Fraction(float(eta)) * Fraction(float(e[0, 0]))
+        f_fused = Fraction(float(np.array([fused], np.uint32).view(np.float32)[0]))
+        f_want = Fraction(float(np.array([want], np.uint32).view(np.float32)[0]))
+        assert abs(exact - f_fused) <= abs(exact - f_want)
+
+
 @pytest.mark.parametrize("eta", [0.0, 1.0, 0.5])
 def test_memory_identities(eta):
     """(a) eta = 0 is the memoryless step; (b) g = e' + TopK(g) exactly (nothing is lost or counted

@@ -119,3 +119,101 @@ def test_planted_mistake_breaks_the_bijection(monkeypatch):
     h = R.half_bits(1000)
     img = {broken(v, h, R.round_keys(SEED, 0, 0)) for v in range(4 ** h)}
     assert len(img) < 4 ** h
+
+
+# ---- the exact bits of the generator: a worked instance ------------------------------------------
+def _worked_example():
+    """tests/golden/randk_permutation_example.txt: every round key, every value of the round function
+    and the network on its whole domain for one tiny instance, worked outside the oracle."""
+    import os
+    ex = {"fmix": [], "round": {}}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "randk_permutation_example.txt")) as f:
+        for line in f:
+            tok = line.split()
+            if not tok or tok[0].startswith("#"):
+                continue
+            if tok[0] == "fmix":
+                ex["fmix"].append((int(tok[1], 16), int(tok[2], 16)))
+            elif tok[0] == "round":
+                ex["round"][int(tok[1])] = [int(v, 16) for v in tok[2:]]
+            elif tok[0] in ("k", "keys"):
+                ex[tok[0]] = [int(v, 16) for v in tok[1:]]
+            elif tok[0] in ("net", "pi", "index_set"):
+                ex[tok[0]] = [int(v) for v in tok[1:]]
+            else:
+                ex[tok[0]] = int(tok[1], 0)
+    return ex
+
+
+def test_finaliser_matches_published_vectors_and_worked_values():
+    ex = _worked_example()
+    for z, want in ex["fmix"]:
+        assert R.fmix32(z) == want
+    for r, key in enumerate(ex["keys"]):
+        for right in range(4):
+            assert R.fmix32(right ^ key) == ex["round"][r][right]
+    z = np.array([a for a, _ in ex["fmix"]] + ex["keys"], dtype=np.uint64)
+    assert R._fmix32_np(z).tolist() == [R.fmix32(int(v)) for v in z]
+
+
+def test_round_keys_match_the_worked_instance():
+    ex = _worked_example()
+    assert R.round_keys(ex["seed"], ex["t"], ex["m"]) == ex["keys"]
+    # each of seed's halves, t and m enters: changing one changes the keys
+    for other in (R.round_keys(ex["seed"] ^ 1, ex["t"], ex["m"]), R.round_keys(ex["seed"] ^ (1 << 32), ex["t"], ex["m"]),
+                  R.round_keys(ex["seed"], ex["t"] + 1, ex["m"]), R.round_keys(ex["seed"], ex["t"], ex["m"] + 1)):
+        assert other != ex["keys"]
+
+
+def test_network_and_cycle_walk_match_the_worked_instance():
+    ex = _worked_example()
+    N, keys = ex["N"], ex["keys"]
+    assert R.half_bits(N) == ex["h"]
+    assert [R.feistel(v, ex["h"], keys) for v in range(4 ** ex["h"])] == ex["net"]
+    assert [R.permute(i, N, keys) for i in range(N)] == ex["pi"]
+    assert R.permute_many(np.arange(N), N, keys).tolist() == ex["pi"]
+    assert R.randk_index_set(N, ex["K"], ex["seed"], ex["t"], ex["m"]).tolist() == ex["index_set"]
+    g = np.array([[0.5, -1.0, 2.0, 3.0, -4.0, -0.25]] * 3, dtype=np.float32)  # worker m = 2 is the third row
+    words, counts = R.randk_sign_encode(g, ex["K"], ex["seed"], ex["t"])
+    assert counts[2] == 3 and words[2].tolist() == [(1 << 1) | 1, (2 << 1) | 0, (5 << 1) | 1]
+
+
+@pytest.mark.parametrize("mistake", ["constant", "shift", "key_order", "round_count", "halves", "no_walk"])
+def test_planted_mistakes_fail_the_worked_instance(mistake, monkeypatch):
+    """A wrong constant, shift, key derivation, round count, half order or a missing cycle walk keeps
+    every property pin green (the result is still a keyed bijection); only the worked instance fails."""
+    ex = _worked_example()
+    N, keys, h = ex["N"], ex["keys"], ex["h"]
+    if mistake == "constant":
+        def f(z):
+            z &= 0xFFFFFFFF; z ^= z >> 16; z = (z * 0x85EBCA77) & 0xFFFFFFFF; z ^= z >> 13
+            z = (z * 0xC2B2AE35) & 0xFFFFFFFF; z ^= z >> 16
+            return z
+        monkeypatch.setattr(R, "fmix32", f)
+    elif mistake == "shift":
+        def f(z):
+            z &= 0xFFFFFFFF; z ^= z >> 16; z = (z * 0x85EBCA6B) & 0xFFFFFFFF; z ^= z >> 15
+            z = (z * 0xC2B2AE35) & 0xFFFFFFFF; z ^= z >> 16
+            return z
+        monkeypatch.setattr(R, "fmix32", f)
+    elif mistake == "key_order":  # the halves of the seed enter the key derivation the other way round
+        swapped = ((ex["seed"] & 0xFFFFFFFF) << 32) | (ex["seed"] >> 32)
+        keys = R.round_keys(swapped, ex["t"], ex["m"])
+        assert keys != ex["keys"]
+    elif mistake == "round_count":
+        keys = keys[:5]
+    elif mistake == "halves":
+        def net(v, hh, ks):
+            mask = (1 << hh) - 1
+            right, left = v >> hh, v & mask  # halves taken the other way round
+            for k in ks:
+                left, right = right, left ^ (R.fmix32(right ^ k) & mask)
+            return (left << hh) | right
+        monkeypatch.setattr(R, "feistel", net)
+    if mistake == "no_walk":
+        got = [R.feistel(i, h, keys) % N for i in range(N)]
+    else:
+        if mistake in ("constant", "shift"):
+            keys = R.round_keys(ex["seed"], ex["t"], ex["m"])
+        got = [R.permute(i, N, keys) for i in range(N)]
+    assert got != ex["pi"]
