@@ -307,6 +307,24 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
 /*
+ * How an encode call of this shape would be laid over the device by this context (host only, nothing
+ * is enqueued): for tests and benchmarks that have to know which internal route a shape takes.
+ *   out  host, 12 entries:
+ *     [0] 1 if the single-pass candidate route is planned (0: the multi-pass route for every row)
+ *     [1] 1 if that pass runs as one block per 8192 entries (calls with a memory), 0: persistent waves
+ *     [2] 1 if only a bracket of magnitudes around the K-th is kept (dense K; the words then come from
+ *         a second pass over the row)
+ *     [3] blocks per row of the pass, four waves each   [4] 1024-entry tiles each wave covers, in a row
+ *     [5] candidate slots a wave reserves at a time     [6] candidate slots per row
+ *     [7] sample units per row                          [8] row entries per sample unit window
+ *     [9] rank, in the sample, of the key that becomes the lower bound of a candidate
+ *     [10] segments a wave's candidate list may have    [11] consecutive entries per sample unit
+ * s3gd_encode_sample_unit_start(u, out[8]) is the index of the first entry of sample unit u of a row.
+ */
+S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, uint64_t K, int with_memory, uint64_t* out);
+S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride);
+
+/*
  * Optional per-kernel timing for benchmarks.  When enabled (on = 1), every kernel launch made
  * through the context is bracketed by a HIP event pair recorded on the call's own stream (no host
  * synchronisation is added); on = 2 brackets only the passes over the gradients (the dominant

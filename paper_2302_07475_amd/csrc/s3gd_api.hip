@@ -437,6 +437,31 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
   return S3GD_OK;
 }
 
+S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, uint64_t K, int with_memory, uint64_t* out) {
+  if (!out) return S3GD_E_INVAL;
+  const int rc = check_shape(ctx, M, N, K);
+  if (rc) return rc;
+  const EncodePlan p = plan_encode(M, N, K, ctx->ws.cand_pool, with_memory ? ctx->ws.stream_blocks_mem : ctx->ws.stream_blocks,
+                                   with_memory != 0);
+  out[0] = p.candidates;
+  out[1] = p.chunks;
+  out[2] = p.bracket;
+  out[3] = p.gx;
+  out[4] = p.tiles_per_wave;
+  out[5] = p.slab;
+  out[6] = p.cand_stride;
+  out[7] = p.n_units;
+  out[8] = p.unit_stride;
+  out[9] = p.sample_rank;
+  out[10] = kChain;
+  out[11] = kSampleUnit;
+  return S3GD_OK;
+}
+
+S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride) {
+  return unit_stride >= (uint64_t)kSampleUnit ? sample_unit_position(u, unit_stride) : 0;
+}
+
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on) {
   if (!ctx) return S3GD_E_INVAL;
   DeviceGuard g(ctx->device);

@@ -481,11 +481,13 @@ __global__ __launch_bounds__(kBlock) void k_emit_rows(const float* grads, u64 N,
 
 // Position of sample unit u of a row: one unit per stride window, at a hashed offset inside it,
 // so that a periodic pattern in the row cannot line up with the sample.
-__device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
+__host__ __device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
   u32 h = u * 0x9E3779B1u;
   h ^= h >> 15; h *= 0x85EBCA77u; h ^= h >> 13;
   return (u64)u * stride + (u64)h % (stride - (kSampleUnit - 1));
 }
+
+u64 sample_unit_position(u32 u, u64 stride) { return sample_unit_start(u, stride); }
 
 // Histogram of one radix level over the sample of each row (gathered straight from the row).
 // With a memory (`err` non-NULL) the sampled value is g~ + eta * e.

@@ -92,6 +92,7 @@ struct EncodePlan {
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
 EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bool chunks);
+u64 sample_unit_position(u32 u, u64 unit_stride);  // first entry of sample unit u of a row (host copy of the kernels' rule)
 u32 resident_stream_blocks(int device, bool with_memory);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 

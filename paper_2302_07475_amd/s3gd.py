@@ -23,7 +23,7 @@ EXPORTS = (
     "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
-    "s3gd_strerror", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
+    "s3gd_strerror", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
 PROFILE_KERNELS = 25
 
@@ -82,6 +82,10 @@ _lib.s3gd_last_hip_error.argtypes = [_vp]
 _lib.s3gd_strerror.restype = ctypes.c_char_p
 _lib.s3gd_strerror.argtypes = [_int]
 
+_lib.s3gd_encode_plan_info.restype = _int
+_lib.s3gd_encode_plan_info.argtypes = [_vp, _u32, _u64, _u64, _int, ctypes.POINTER(_u64)]
+_lib.s3gd_encode_sample_unit_start.restype = _u64
+_lib.s3gd_encode_sample_unit_start.argtypes = [_u32, _u64]
 _lib.s3gd_profile_enable.restype = _int
 _lib.s3gd_profile_enable.argtypes = [_vp, _int]
 _lib.s3gd_profile_read.restype = _int
@@ -105,6 +109,10 @@ def strerror(code: int) -> str:
 
 def workspace_bytes(M_max: int, N_max: int, K_max: int) -> int:
     return int(_lib.s3gd_workspace_bytes(M_max, N_max, K_max))
+
+
+def encode_sample_unit_start(u: int, unit_stride: int) -> int:
+    return int(_lib.s3gd_encode_sample_unit_start(u, unit_stride))
 
 
 def packed_row_words(N: int, K: int) -> int:
@@ -303,6 +311,14 @@ class Context:
         out = (_u32 * 3)()
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
         return int(out[0]), int(out[1]), int(out[2])
+
+    def encode_plan_info(self, M: int, N: int, K: int, with_memory: bool = False) -> dict[str, int]:
+        """How an encode of this shape is laid over the device (see s3gd_encode_plan_info)."""
+        out = (_u64 * 12)()
+        self._check(_lib.s3gd_encode_plan_info(self._h, M, N, K, int(with_memory), out), "s3gd_encode_plan_info")
+        names = ("candidates", "chunks", "bracket", "blocks_per_row", "tiles_per_wave", "slab", "cand_stride", "n_units",
+                 "unit_stride", "sample_rank", "chain", "sample_unit")
+        return {k: int(v) for k, v in zip(names, out)}
 
     def profile_enable(self, on: bool | int = True):
         """True / 1: time every kernel; 2: only the passes over the gradients; False / 0: off."""

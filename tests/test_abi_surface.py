@@ -53,6 +53,7 @@ def test_create_rejects_bad_arguments_without_touching_a_device(lib):
     h = ctypes.c_void_p()
     assert lib.raw.s3gd_create(None, 0, 1, 10, 1) == lib.E_INVAL
     assert lib.raw.s3gd_create(ctypes.byref(h), 0, 0, 10, 1) == lib.E_INVAL
+    assert lib.raw.s3gd_create(ctypes.byref(h), 0, 65536, 10, 1) == lib.E_INVAL  # above S3GD_M_LIMIT, as the header says
     assert lib.raw.s3gd_create(ctypes.byref(h), 0, 1, 0, 1) == lib.E_INVAL
     assert lib.raw.s3gd_create(ctypes.byref(h), 0, 1, (1 << 31) - 1, 1) == lib.E_RANGE
     assert lib.raw.s3gd_create(ctypes.byref(h), -1, 1, 10, 1) == lib.E_INVAL

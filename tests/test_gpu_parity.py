@@ -361,18 +361,81 @@ def test_skewed_rows_grow_their_segment_lists(ctx):
     assert idx.min() >= N // 2 - band // 2 and idx.max() < N // 2 + band // 2, "the recipe is meant to put every selected entry in the band"
 
 
-def test_few_waves_long_segment_chains(lib, monkeypatch):
-    """With a grid of four blocks a wave covers 131072 entries, so a banded row makes one wave hold
-    thousands of candidates against a first slab of 256: the chain 256, 256, 512, 1024, ... is walked."""
+def _row_with_dense_head(N, head, rng):
+    """Small noise everywhere; the first `head` entries are far larger than anything else (distinct
+    magnitudes, random signs): one wave of the single pass finds a candidate in every entry it reads."""
+    g = (rng.standard_normal(N, dtype=np.float32) * np.float32(0.01))
+    big = (100.0 + rng.random(head) * 50.0) * np.sign(rng.standard_normal(head))
+    g[:head] = big.astype(np.float32)
+    return g
+
+
+def _check_rows_exactly(G, K, words, counts):
     from oracle import s3gd_oracle as O
-    monkeypatch.setenv("S3GD_STREAM_BLOCKS", "4")
+    for m in range(G.shape[0]):
+        O.check_message_row(G[m], K, words[m], int(counts[m]))  # admits one answer: the sorted one
+
+
+def test_one_wave_holds_a_long_chain_of_segments(lib):
+    """A wave of the single pass covers dozens of consecutive 1024-entry tiles.  When every entry of 24
+    of them is a candidate the wave fills its first slab at once and reserves more, each reservation
+    at least twice the slab and doubling: a list of seven or eight segments, the longest a list may
+    be.  The row stays on the candidate route (no row on the general one)."""
     rng = np.random.default_rng(12)
-    N, K, band = 1 << 21, 2_097, 8_192
-    G = _banded_rows(N, K, band, rng)[:1]
+    N, K = 1 << 27, (1 << 27) // 1000
     with lib.Context(1, N, K, device=0) as c:
+        plan = c.encode_plan_info(1, N, K)
+        assert plan["candidates"] and not plan["bracket"] and not plan["chunks"], plan
+        assert plan["chain"] == 8 and plan["slab"] <= 1024 and plan["tiles_per_wave"] >= 24, \
+            f"shape no longer puts 24 all-candidate tiles into one wave with a small first slab: {plan}"
+        G = _row_with_dense_head(N, 24 * 1024, rng)[None, :]
         words, counts, rows, general = _encode_only(c, G, K)
-        assert c.last_encode_details()[1] == 0
-    w, cc = O.topk_sign_encode(G, K)
+        assert c.last_encode_details()[:2] == (1, 0), "the chain of eight segments suffices: the row stays on the candidate route"
+    _check_rows_exactly(G, K, words, counts)
+    assert counts[0] == K and (words[0, :24 * 1024] >> 1 == np.arange(24 * 1024)).all()
+
+
+def test_full_chain_hands_the_row_to_the_general_route(lib):
+    """The same with every tile of the first wave's range a candidate tile and a range long enough to
+    exhaust eight doubling segments: the wave marks the row, nothing more is kept for it, and the
+    general multi-pass route serves it, with the same words."""
+    rng = np.random.default_rng(13)
+    M, N, K = 2, 1 << 27, (1 << 27) // 1000
+    with lib.Context(M, N, K, device=0) as c:
+        plan = c.encode_plan_info(M, N, K)
+        assert plan["candidates"] and not plan["bracket"] and not plan["chunks"], plan
+        tiles = plan["tiles_per_wave"]
+        # a list has eight segments of slab, slab, 2 slab, ... 64 slab slots, none smaller than the tile that opens it
+        longest = sum(max(plan["slab"] << max(i - 1, 0), 1024) for i in range(plan["chain"])) // 1024
+        assert tiles > longest, f"a wave's range ({tiles} tiles) no longer exceeds the longest chain ({longest} tiles): {plan}"
+        G = np.stack([_row_with_dense_head(N, tiles * 1024, rng),
+                      (rng.standard_normal(N, dtype=np.float32))])  # an ordinary row next to it keeps its route
+        words, counts, rows, general = _encode_only(c, G, K)
+        assert c.last_encode_details()[:2] == (2, 1), "row 0 ends on the general route, row 1 stays on the candidate route"
+    _check_rows_exactly(G, K, words, counts)
+
+
+def test_candidates_the_sample_missed_exhaust_the_pool(lib):
+    """A row whose sample looks ordinary while nearly every entry outside the sampled units is large:
+    the sampled bound lies among the small entries, the pass finds a candidate almost everywhere, the
+    row's share of the pool runs out (waves find no room for another slab) and the row is handed to
+    the general route.  The sample's positions come from the library."""
+    rng = np.random.default_rng(14)
+    N, K = 1 << 22, (1 << 22) // 1000
+    with lib.Context(2, N, K, device=0) as c:
+        plan = c.encode_plan_info(2, N, K)
+        assert plan["candidates"] and not plan["bracket"], plan
+        small = (rng.standard_normal(N, dtype=np.float32) * np.float32(0.01))
+        g = ((50.0 + rng.random(N) * 50.0) * np.sign(rng.standard_normal(N))).astype(np.float32)
+        for u in range(plan["n_units"]):
+            p = lib.encode_sample_unit_start(u, plan["unit_stride"])
+            g[p:p + plan["sample_unit"]] = small[p:p + plan["sample_unit"]]
+        assert N - plan["n_units"] * plan["sample_unit"] > plan["cand_stride"]
+        G = np.stack([g, rng.standard_normal(N, dtype=np.float32)])
+        words, counts, rows, general = _encode_only(c, G, K)
+        assert c.last_encode_details()[:2] == (2, 1)
+    _check_rows_exactly(G, K, words, counts)
+    w, cc = __import__("oracle.s3gd_oracle", fromlist=["x"]).topk_sign_encode(G, K)
     assert np.array_equal(counts, cc) and np.array_equal(words, w)
 
 
