@@ -69,6 +69,8 @@ extern "C" {
 #define S3GD_E_CAPACITY (-7) /* reported by s3gd_last_async_status(): an output buffer of the coding */
                              /* calls was too small for the vector it had to hold                    */
 
+#define S3GD_E_TOOBIG (-8)   /* s3gd_step_static: the shape needs more scratch than the static array holds */
+
 #define S3GD_PAD 0xFFFFFFFFu
 #define S3GD_N_LIMIT 2147483646ull /* 2^31 - 2 */
 #define S3GD_M_LIMIT 65535u        /* workers per context: rows are the second grid dimension of a launch */
@@ -136,6 +138,30 @@ S3GD_API int s3gd_apply_update(s3gd_ctx* ctx, float* x, const int8_t* votes, flo
 S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N, uint64_t K, float* x,
               float lr, uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes,
               s3gd_stream_t stream);
+
+/*
+ * s3gd_step for callers that cannot allocate device memory or hold a context: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit for bit the same outputs as s3gd_step, but the scratch (row states, histograms, candidate
+ * pool, segment tables) lives in a static device array of S3GD_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends.  The call allocates and frees nothing.
+ *
+ *   device    the GPU that holds every buffer of the call; made current for the call.
+ *   nan_flag  dev, out, nullable  [1] uint32: 1 if a NaN was seen in grads (outputs then unspecified
+ *             but in bounds), else 0; valid once the stream has reached this point.  It stands in
+ *             for s3gd_last_async_status, which needs a context.
+ *   Shapes with s3gd_workspace_bytes(M, N, K) > S3GD_STATIC_SCRATCH_BYTES are refused with
+ *   S3GD_E_TOOBIG before anything is enqueued; M above S3GD_M_LIMIT is S3GD_E_INVAL.
+ *
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (each
+ * call resets what it needs): calls that overlap in time on one GPU, from any stream or thread, race
+ * and must be ordered by the caller.  The first call on a device looks up the array's address; make
+ * one call outside a capture before capturing others.
+ */
+#define S3GD_STATIC_SCRATCH_BYTES (128ull << 20)
+S3GD_API int s3gd_step_static(int device, const float* grads, uint32_t M, uint64_t N, uint64_t K, float* x, float lr,
+                     uint32_t* words, uint32_t* counts, int32_t* tally, int8_t* votes, uint32_t* nan_flag,
+                     s3gd_stream_t stream);
 
 /*
  * Worker side of Algorithm 1 WITH the error-compensation memory (Section 2.2 "Gradient update with

@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks, scratch ownership, stage sequencing.
 #include <math.h>
+#include <mutex>
 #include <new>
 
 #include "s3gd_common.h"
@@ -48,6 +49,22 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);
   l.total = off;
   return l;
+}
+
+// Points the views of a workspace at a block of device memory laid out by `l`.
+void bind_workspace(Workspace& ws, char* b, const Layout& l) {
+  ws.rs = reinterpret_cast<RowState*>(b + l.rs);
+  ws.status = reinterpret_cast<u32*>(b + l.status);
+  ws.hist = reinterpret_cast<u32*>(b + l.hist);
+  ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
+  ws.seg = reinterpret_cast<u32*>(b + l.seg);
+  ws.wave_seg = reinterpret_cast<u64*>(b + l.wave_seg);
+  ws.wave_nseg = reinterpret_cast<u32*>(b + l.wave_nseg);
+  ws.wave_sum = reinterpret_cast<u64*>(b + l.wave_sum);
+  ws.wave_sure = reinterpret_cast<u32*>(b + l.wave_sure);
+  ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
+  ws.cand = reinterpret_cast<uint2*>(b + l.cand);
+  ws.cand_pool = l.cand_pool;
 }
 
 // Makes the context's device current for the duration of a call.
@@ -122,18 +139,7 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
     delete c;
     return S3GD_E_HIP;
   }
-  c->ws.rs = reinterpret_cast<RowState*>(b + l.rs);
-  c->ws.status = reinterpret_cast<u32*>(b + l.status);
-  c->ws.hist = reinterpret_cast<u32*>(b + l.hist);
-  c->ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
-  c->ws.seg = reinterpret_cast<u32*>(b + l.seg);
-  c->ws.wave_seg = reinterpret_cast<u64*>(b + l.wave_seg);
-  c->ws.wave_nseg = reinterpret_cast<u32*>(b + l.wave_nseg);
-  c->ws.wave_sum = reinterpret_cast<u64*>(b + l.wave_sum);
-  c->ws.wave_sure = reinterpret_cast<u32*>(b + l.wave_sure);
-  c->ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
-  c->ws.cand = reinterpret_cast<uint2*>(b + l.cand);
-  c->ws.cand_pool = l.cand_pool;
+  bind_workspace(c->ws, b, l);
   c->ws.stream_blocks = resident_stream_blocks(device, false);
   c->ws.stream_blocks_mem = resident_stream_blocks(device, true);
   c->ws.prof = &c->prof;
@@ -211,6 +217,73 @@ S3GD_API int s3gd_step(s3gd_ctx* ctx, const float* grads, uint32_t M, uint64_t N
   if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
   e = launch_vote(ctx->ws, words, counts, M, N, K, tally, votes, x, lr, s);
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+// ---- the step on a static scratch array ----------------------------------------------------------
+// For callers that cannot allocate.  `scratch` is a host-side stand-in for the array, not a device
+// address: its address on each device comes from hipGetSymbolAddress, once per device, and only that
+// pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[S3GD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  bool ready = false;
+  char* ptr = nullptr;  // this device's copy of `scratch`
+  u32 stream_blocks = 0, stream_blocks_mem = 0;
+  Profiler prof;        // never enabled: the launch functions expect one
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Looks up the array's address on `device` (which is current) the first time the device is used.
+hipError_t static_scratch(int device, StaticScratch** out) {
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticScratch& st = g_static[device];
+  if (!st.ready) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    st.ptr = static_cast<char*>(p);
+    st.stream_blocks = resident_stream_blocks(device, false);
+    st.stream_blocks_mem = resident_stream_blocks(device, true);
+    st.ready = true;
+  }
+  *out = &st;
+  return hipSuccess;
+}
+}  // namespace
+
+S3GD_API int s3gd_step_static(int device, const float* grads, uint32_t M, uint64_t N, uint64_t K, float* x, float lr, uint32_t* words,
+                     uint32_t* counts, int32_t* tally, int8_t* votes, uint32_t* nan_flag, s3gd_stream_t stream) {
+  if (device < 0 || device >= kMaxDevices) return S3GD_E_INVAL;
+  if (M == 0 || M > kMaxRows || N == 0) return S3GD_E_INVAL;
+  if (N > S3GD_N_LIMIT) return S3GD_E_RANGE;
+  if (K > N) return S3GD_E_INVAL;
+  if (!grads || !x || !counts || (K > 0 && !words)) return S3GD_E_INVAL;
+  if (!step_size_ok(lr)) return S3GD_E_INVAL;
+  if (!aligned(grads, 4) || !aligned(words, 4) || !aligned(counts, 4) || !aligned(x, 16) || !aligned(tally, 16) ||
+      !aligned(votes, 16) || !aligned(nan_flag, 4))
+    return S3GD_E_INVAL;
+  const Layout l = layout(M, N, K);
+  if (l.total > S3GD_STATIC_SCRATCH_BYTES) return S3GD_E_TOOBIG;
+  DeviceGuard g(device);
+  if (g.err != hipSuccess) return S3GD_E_HIP;
+  StaticScratch* st = nullptr;
+  if (static_scratch(device, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return S3GD_E_HIP;
+  }
+  Workspace ws{};
+  bind_workspace(ws, st->ptr, l);
+  ws.stream_blocks = st->stream_blocks;
+  ws.stream_blocks_mem = st->stream_blocks_mem;
+  ws.prof = &st->prof;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (launch_encode(ws, grads, nullptr, 0.0f, M, N, K, words, counts, s, nan_flag) != hipSuccess) return S3GD_E_HIP;
+  if (K == 0 && !tally && !votes) return S3GD_OK;  // nobody votes, nothing moves
+  return launch_vote(ws, words, counts, M, N, K, tally, votes, x, lr, s) == hipSuccess ? S3GD_OK : S3GD_E_HIP;
 }
 
 namespace {
@@ -522,6 +595,7 @@ S3GD_API const char* s3gd_strerror(int code) {
     case S3GD_E_NAN: return "NaN in gradients";
     case S3GD_E_FORMAT: return "packed vector does not decode";
     case S3GD_E_CAPACITY: return "output buffer too small";
+    case S3GD_E_TOOBIG: return "shape needs more scratch than the static array holds";
     default: return "unknown error";
   }
 }

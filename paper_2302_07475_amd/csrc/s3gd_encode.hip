@@ -1153,10 +1153,11 @@ __global__ __launch_bounds__(kBlock) void k_range_emit(const float* grads, u64 N
 
 // counts[m] and the pad words of rows that selected zeros.
 __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __restrict__ words, u32* __restrict__ counts,
-                              u32* __restrict__ status) {
+                              u32* __restrict__ status, u32* __restrict__ nan_flag) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (nan_flag && m == 0) *nan_flag = status[0] ? 1u : 0u;  // every kernel that raises it has run
     counts[m] = st.count;
     if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
     if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
@@ -1166,9 +1167,10 @@ __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __res
     out[i] = S3GD_PAD;
 }
 
-__global__ void k_zero_counts(u32* counts, u32 M) {
+__global__ void k_zero_counts(u32* counts, u32 M, u32* nan_flag) {
   const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < M) counts[i] = 0;
+  if (i == 0 && nan_flag) *nan_flag = 0;  // K = 0 looks at no entry
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1267,7 +1269,7 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
 // g = grads + eta * err, and on return err holds the new memory g - TopK(g).
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
-                         u32* counts, hipStream_t s) {
+                         u32* counts, hipStream_t s, u32* nan_flag) {
   Profiler& P = *ws.prof;
 #define S3GD_LAUNCH(KID, ...) do { P.begin(KID, s); __VA_ARGS__; P.end(s); } while (0)
   // With a memory the filter pass reads two rows and writes one: that mix runs fastest as blocks in index order.
@@ -1286,7 +1288,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_COMPENSATE, (k_compensate<<<(u32)blocks, kBlock, 0, s>>>(grads, err, eta, total, head)));
   }
   if (K == 0) {
-    k_zero_counts<<<(M + 255) / 256, 256, 0, s>>>(counts, M);
+    k_zero_counts<<<(M + 255) / 256, 256, 0, s>>>(counts, M, nan_flag);
     return hipGetLastError();
   }
   const float* src = err ? err : grads;  // what the general route reads: with a memory, g sits in err by then
@@ -1365,7 +1367,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words, err)));
   u32 fx = (u32)((K + 4095) / 4096);
   if (fx > 64) fx = 64;
-  S3GD_LAUNCH(KID_FINISH, (k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status)));
+  S3GD_LAUNCH(KID_FINISH, (k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status, nan_flag)));
 #undef S3GD_LAUNCH
   return hipGetLastError();
 }

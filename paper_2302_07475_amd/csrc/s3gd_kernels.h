@@ -96,8 +96,9 @@ u64 sample_unit_position(u32 u, u64 unit_stride);  // first entry of sample unit
 u32 resident_stream_blocks(int device, bool with_memory);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
 u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 
+// `nan_flag` (device, nullable): receives 1 if the call saw a NaN, else 0, when its last kernel runs.
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
-                         u32* counts, hipStream_t s);
+                         u32* counts, hipStream_t s, u32* nan_flag = nullptr);
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);

@@ -14,13 +14,14 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libs3gd.so")
 
-OK, E_INVAL, E_RANGE, E_HIP, E_NOMEM, E_NAN, E_FORMAT, E_CAPACITY = 0, -1, -2, -3, -4, -5, -6, -7
+OK, E_INVAL, E_RANGE, E_HIP, E_NOMEM, E_NAN, E_FORMAT, E_CAPACITY, E_TOOBIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
+STATIC_SCRATCH_BYTES = 128 << 20
 PAD = 0xFFFFFFFF
 N_LIMIT = (1 << 31) - 2
 
 EXPORTS = (
     "s3gd_workspace_bytes", "s3gd_create", "s3gd_destroy", "s3gd_topk_sign_encode", "s3gd_majority_vote",
-    "s3gd_apply_update", "s3gd_step", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
+    "s3gd_apply_update", "s3gd_step", "s3gd_step_static", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
@@ -47,6 +48,8 @@ _lib.s3gd_apply_update.restype = _int
 _lib.s3gd_apply_update.argtypes = [_vp, _vp, _vp, _f32, _u64, _vp]
 _lib.s3gd_step.restype = _int
 _lib.s3gd_step.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.s3gd_step_static.restype = _int
+_lib.s3gd_step_static.argtypes = [_int, _vp, _u32, _u64, _u64, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.s3gd_topk_sign_encode_acc.restype = _int
 _lib.s3gd_topk_sign_encode_acc.argtypes = [_vp, _vp, _u32, _u64, _u64, _vp, _vp, _vp]
 _lib.s3gd_step_acc.restype = _int
@@ -128,6 +131,15 @@ def _stream(stream) -> int | None:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream or None
+
+
+def step_static(grads: torch.Tensor, K: int, x: torch.Tensor, lr: float, words: torch.Tensor, counts: torch.Tensor,
+                tally: torch.Tensor | None = None, votes: torch.Tensor | None = None, nan_flag: torch.Tensor | None = None,
+                stream=None) -> int:
+    """s3gd_step on the library's static scratch array: no context, nothing allocated.  Returns the C return code."""
+    M, N = grads.shape
+    return int(_lib.s3gd_step_static(grads.device.index or 0, _ptr(grads), M, N, K, _ptr(x), float(lr), _ptr(words), _ptr(counts),
+                                     _ptr(tally), _ptr(votes), _ptr(nan_flag), _stream(stream)))
 
 
 class Context:
