@@ -3,20 +3,24 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5]
 
-A "step" is one pass of the whole hot path over one batch of synthetic gradients: the fused
-C-ABI call s3gd_step on a resident [M, N] fp32 tensor.  Inputs are generated on the host from
-the seeded recipes in paper_2302_07475_amd/datagen.py and are resident in HBM before the timed
-region starts.  Prints ONE JSON line:
+A "step" is one pass of the whole hot path over one batch of synthetic gradients on a resident
+[M, N] fp32 tensor.  Inputs are generated on the host from the seeded recipes in
+paper_2302_07475_amd/datagen.py and are resident in HBM before the timed region starts.
+Prints ONE JSON line:
 
-  value        M*N / t   gradient elements per second through one step
+  value        M*N / t   gradient elements per second through one step of the fused call s3gd_step
+  three_calls  the same step as the three public calls (s3gd_topk_sign_encode, s3gd_majority_vote
+               with int8 votes, s3gd_apply_update) enqueued back to back, timed in the same run
   roofline     the dominant kernel's algorithmic bytes per launch over its mean duration, measured
                with HIP events on the launch stream inside the timed region, against 8 TB/s
-  cpu_baseline the CPU oracle timed on this machine's host cores on a bounded sample of the workload
+  cpu_baseline the CPU oracle timed on this machine's host cores on a bounded sample of the workload,
+               single-threaded and with the rows spread over threads
 """
 import argparse
 import dataclasses
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -28,13 +32,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
 
-# HBM bytes per launch (read + written) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the factors a
-# plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE); figures and commands are in
-# profiles/s3gd_step_C5_hbm_traffic.md.  Reported only for the workload and kernel they were taken on.
-MEASURED_TRAFFIC_BYTES = {("C5", "filter"): 19.2000e9 + 0.0620e9}
-
-# algorithmic bytes one launch of a kernel moves, per gradient element (4 = one fp32 read of G)
-FULL_READ_KERNELS = {"hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "filter"}
+# HBM bytes per launch (read + written) of a workload's dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs of this same command, scaled by the factors a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for
+# WRITE_SIZE).  Counter figures cannot be taken inside this run; they are quoted with the file they come from.
+PROFILED_TRAFFIC = {
+    ("C5", "filter"): (19.2000e9 + 0.0620e9, "profiles/s3gd_step_C5_hbm_traffic.md"),
+}
 
 
 def log(*a):
@@ -42,28 +45,73 @@ def log(*a):
 
 
 def cpu_baseline(cfg, datagen):
-    """The oracle, as it stands, on a bounded sample: all M workers, the first N_s coordinates,
-    K scaled to keep K/N.  Sorting is O(N log N), so the per-element rate at the full N is lower."""
+    """The oracle, as it stands, on a bounded sample: all M workers, the first N_s coordinates, K scaled to
+    keep K/N.  Timed twice: on one thread (t_cpu1) and with the rows' selections spread over min(M, cores)
+    threads (t_cpuP; the vote and the update stay serial).  Sorting is O(N log N), so the per-element rate
+    at the full N is lower; the full configuration would take minutes to hours and is not run."""
+    from concurrent.futures import ThreadPoolExecutor
+
     from oracle import s3gd_oracle as O
     n_s = min(cfg.N, max(1 << 16, (120_000_000 // cfg.M)))
     k_s = max(1, round(cfg.K * n_s / cfg.N))
     small = cfg.scaled(N=n_s, K=k_s)
     G = datagen.gradients(small)
     x = datagen.params(small)
+    lr = datagen.lr32(small)
     t0 = time.perf_counter()
-    O.step(G, small.K, x, datagen.lr32(small))
-    dt = time.perf_counter() - t0
-    return {"value": cfg.M * n_s / dt, "unit": "gradient elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"all {cfg.M} workers, first {n_s} coordinates of {cfg.name}, K={k_s}, one step, {dt:.1f} s"}
+    one = O.step(G, small.K, x, lr)
+    t_cpu1 = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    threads = max(1, min(cfg.M, cores, 16))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as pool:
+        rows = list(pool.map(lambda m: O.encode_row(G[m], small.K), range(cfg.M)))
+    words = np.full((cfg.M, small.K), O.PAD, dtype=np.uint32)
+    counts = np.zeros(cfg.M, dtype=np.uint32)
+    for m, (w, c) in enumerate(rows):
+        words[m], counts[m] = w, c
+    tally, votes = O.majority_vote(words, counts, n_s)
+    xp = O.apply_update(x, votes, lr)
+    t_cpup = time.perf_counter() - t0
+    assert np.array_equal(xp.view(np.uint32), one["x"].view(np.uint32))
+    return {"value": cfg.M * n_s / t_cpup, "unit": "gradient elements/s", "cores": threads, "kind": "oracle",
+            "single_thread_value": cfg.M * n_s / t_cpu1, "t_cpu1_s": round(t_cpu1, 2), "t_cpuP_s": round(t_cpup, 2),
+            "host_cores_available": cores, "sample_fraction": n_s / cfg.N,
+            "sample": f"all {cfg.M} workers, first {n_s} of {cfg.N} coordinates of {cfg.name} ({100.0 * n_s / cfg.N:.1f} %), "
+                      f"K={k_s}, one step; 1 thread {t_cpu1:.1f} s, {threads} threads over the rows {t_cpup:.1f} s"}
+
+
+def kernel_bytes(name, M, N, K, rows, n_voted, dense_state, tally_out, votes_out):
+    """Algorithmic bytes one launch of a kernel moves: what the step needs from that pass, not what the
+    hardware counters saw.  `rows` = rows of G the pass actually reads."""
+    if name in ("filter", "hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "range_emit"):
+        return 4.0 * N * rows
+    if name == "filter_mem":  # reads g~ and e, writes the new memory
+        return 12.0 * N * rows
+    if name == "plain_read":
+        return 4.0 * M * N
+    if name == "randk":  # K gathered gradient entries and K words per row
+        return 8.0 * M * K
+    if name == "vote_sparse":  # the words, and a read and a write of every voted parameter
+        return 4.0 * M * K + 8.0 * n_voted
+    if name == "vote_dense":
+        out = (4.0 * N if tally_out else 0.0) + (1.0 * N if votes_out else 0.0)
+        return 4.0 * M * K + (out if out else 8.0 * n_voted)
+    if name == "apply_update":  # the votes, and a read and a write of every voted parameter
+        return 1.0 * N + 8.0 * n_voted
+    if name == "vote_momentum":
+        return 4.0 * M * K + (16.0 * N if dense_state else 4.0 * N + 16.0 * n_voted)
+    return None
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--three-calls", action="store_true", help="time encode, vote, update as separate calls")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="make the three separate calls the timed entry (they are always timed as a second record)")
     ap.add_argument("--memory", action="store_true",
                     help="time s3gd_step_ec: the step with the error-compensation memory (eta = 1), a second "
                          "[M, N] fp32 tensor read and rewritten every step (not the headline workload)")
@@ -71,6 +119,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run three plain device copies of this size; run it under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE to get the factor between counter units and bytes")
+    ap.add_argument("--calibrate-read", type=float, default=0.0, metavar="GiB",
+                    help="instead of the benchmark, time a plain non-temporal read of this size with the launch shape "
+                         "of the selection pass (s3gd_calibrate_read): the practical read ceiling of the memory system")
     ap.add_argument("--wire", action="store_true",
                     help="time encode -> pack -> unpack -> vote+update: the step with the messages passed through the "
                          "compact wire format, as they would be around an exchange (not the headline workload)")
@@ -102,17 +153,32 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(3)
+    dev = torch.device("cuda:0")
     if args.calibrate_copy > 0:
         n = int(args.calibrate_copy * (1 << 30)) // 4
-        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        src = torch.ones(n, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "plain copy", "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n}))
         return
+    if args.calibrate_read > 0:
+        n = (int(args.calibrate_read * (1 << 30)) // 4) // 1024 * 1024
+        buf = torch.ones(n, dtype=torch.float32, device=dev)
+        ctx = s3gd.Context(4, min(n, s3gd.N_LIMIT), 1, device=0)
+        for _ in range(2):
+            ctx.calibrate_read(buf)
+        ctx.profile_enable(2)
+        reps = 10
+        for _ in range(reps):
+            ctx.calibrate_read(buf)
+        ms, cnt = ctx.profile_read()["plain_read"]
+        print(json.dumps({"calibration": "plain non-temporal read, launch shape of the selection pass", "bytes_per_launch": 4 * n,
+                          "launches": cnt, "ms_avg": ms / cnt, "GB_per_s": 4.0 * n / (ms / cnt * 1e-3) / 1e9,
+                          "fraction_of_8TB_per_s": 4.0 * n / (ms / cnt * 1e-3) / HBM_PEAK}))
+        return
     cfg = datagen.CONFIGS[args.workload]
-    dev = torch.device("cuda:0")
     t0 = time.perf_counter()
     g, x = datagen.to_device(cfg, device="cuda:0")
     log(f"[bench] {cfg.name}: M={cfg.M} N={cfg.N} K={cfg.K} generated and uploaded in {time.perf_counter() - t0:.1f} s")
@@ -124,9 +190,7 @@ def main():
     ctx = s3gd.Context(M, N, K, device=0)
     words = torch.empty((M, K), dtype=torch.int32, device=dev)
     counts = torch.empty((M,), dtype=torch.int32, device=dev)
-    tally = votes = None
-    if args.three_calls:
-        votes = torch.empty((N,), dtype=torch.int8, device=dev)
+    votes = torch.empty((N,), dtype=torch.int8, device=dev)
     err = torch.zeros((M, N), dtype=torch.float32, device=dev) if args.memory else None
 
     mom = torch.zeros((N,), dtype=torch.float32, device=dev) if args.momentum else None
@@ -143,7 +207,15 @@ def main():
 
     step_no = [0]
 
-    def one_step():
+    def three_calls_step():
+        ctx.topk_sign_encode(g, K, words, counts)
+        ctx.majority_vote(words, counts, N, None, votes)
+        ctx.apply_update(x, votes, lr)
+
+    def fused_step():
+        ctx.step(g, K, x, lr, words, counts, None, None)
+
+    def variant_step():
         if args.randk:
             ctx.step_randk(g, K, 0x5EED, step_no[0], x, lr, words, counts, None, None)
             step_no[0] += 1
@@ -158,102 +230,152 @@ def main():
             ctx.step_acc(g, K, x, lr, words, counts, None, None)  # g plays the memory: each step's zeros stay in it
         elif args.memory:
             ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
-        elif args.three_calls:
-            ctx.topk_sign_encode(g, K, words, counts)
-            ctx.majority_vote(words, counts, N, None, votes)
-            ctx.apply_update(x, votes, lr)
         else:
-            ctx.step(g, K, x, lr, words, counts, None, None)
+            raise AssertionError
 
-    eager_step = one_step
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            eager_step()
-        torch.cuda.current_stream().wait_stream(side)
+    is_variant = args.randk or args.wire or args.momentum or args.memory_acc or args.memory
+    headline = variant_step if is_variant else (three_calls_step if args.three_calls else fused_step)
+
+    def measure(eager_step, steps, warmup, use_graph=False):
+        """W untimed steps, then exactly `steps` steps between two synchronisations.  Returns the mean wall
+        time per step, the median of the per-step times between HIP events recorded on the launch stream,
+        and the per-kernel figures (a breakdown pass with an event pair around every launch, run before the
+        timed region; the dominant passes carry their own event pair inside it)."""
+        one_step = eager_step
+        if use_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                eager_step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                eager_step()
+            one_step = graph.replay
+        for _ in range(warmup):
+            one_step()
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        assert ctx.last_async_status() == 0
+        routes = ctx.last_encode_routes()
+        ctx.profile_enable(1)
+        for _ in range(3):
             eager_step()
-        one_step = graph.replay
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    assert ctx.last_async_status() == 0
-    general_rows = ctx.last_encode_info()[1]
-    # per-kernel breakdown from a short eager pass with an event pair around every launch (not timed: the
-    # hundred events per step it records cost a few per cent)
-    ctx.profile_enable(1)
-    for _ in range(3):
-        eager_step()
-    prof = ctx.profile_read()
-    kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / 3} for k, v in prof.items()}
-    # timed region: only the selection pass (the dominant kernel) carries an event pair
-    ctx.profile_enable(0 if args.graph else 2)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    live = {} if args.graph else ctx.profile_read()
-    ctx.profile_enable(0)
-    log(f"[bench] timed {args.steps} steps in {dt * 1e3:.2f} ms")
-    for k, v in live.items():  # measured inside the timed region: these replace the figures of the breakdown pass
-        kern[k] = {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / args.steps}
+        prof = ctx.profile_read()
+        kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / 3} for k, v in prof.items()}
+        ctx.profile_enable(0 if use_graph else 2)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        marks[0].record()
+        for i in range(steps):
+            one_step()
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        live = {} if use_graph else ctx.profile_read()
+        ctx.profile_enable(0)
+        per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+        for k, v in live.items():  # measured inside the timed region: these replace the figures of the breakdown pass
+            kern[k] = {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / steps}
+        return dt * 1e3 / steps, statistics.median(per_step), kern, set(live), routes
 
-    ms_step = dt * 1e3 / args.steps
+    ms_step, ms_median, kern, live, routes = measure(headline, args.steps, args.warmup, args.graph)
+    log(f"[bench] timed {args.steps} steps: mean {ms_step:.4f} ms, median of per-step event times {ms_median:.4f} ms")
     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
         log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}" + ("  (timed region)" if k in live else ""))
-    dom = max(kern, key=lambda k: kern[k]["ms_avg"])
-    if dom == "randk":  # K gathered gradient entries and K words per row; nothing else of G is touched
-        alg_bytes = 8.0 * M * K
-    elif dom == "filter_mem":  # reads g~ and e, writes the new memory
-        alg_bytes = 12.0 * M * N
-    elif dom in FULL_READ_KERNELS:
-        alg_bytes = 4.0 * M * N
-    elif dom == "vote_momentum":
-        # the momentum is read in full; where it is non-zero (everywhere, in the dense state) it is written back and
-        # the parameter is read and written too
-        alg_bytes = 4.0 * M * K + (16.0 * N if args.dense_state else 4.0 * N)
-    else:  # the vote kernel dominates only when the gradient passes are cheaper than it
-        alg_bytes = 8.0 * M * K + 8.0 * N
-    achieved = alg_bytes / (kern[dom]["ms_avg"] * 1e-3)
-    per_pass = 12.0 if args.memory else 4.0  # with the memory a pass reads g~ and e and writes e
-    floor_bytes = per_pass * M * N + 8.0 * M * K + 8.0 * N
-    # the general route's kernels are always enqueued and return at once unless a row needs them
-    full_reads = sum(v["launches_per_step"] for k, v in kern.items()
-                     if k in ("filter", "filter_mem") or (k in FULL_READ_KERNELS and general_rows > 0))
+
+    # the support of the vote: coordinates that received a message (what the update has to touch at most)
+    seen = torch.zeros((N,), dtype=torch.bool, device=dev)
+    for m in range(M if K > 0 else 0):
+        w = words[m, : int(counts[m].item())].to(torch.int64) & 0xFFFFFFFF
+        seen[w >> 1] = True
+    n_voted = int(seen.sum().item())
+    del seen
+    n_rows, general, _wide, row_pass, range_rows, skipped = routes
+    plan = ctx.encode_plan_info(M, N, K, with_memory=args.memory)
+    # rows of G each pass reads (the kernels of routes no row takes are enqueued and return at once)
+    rows_read = {"filter": (M - skipped) if plan["candidates"] and not plan["chunks"] else 0,
+                 "filter_mem": M if plan["candidates"] and plan["chunks"] else 0,
+                 "hist_rows_0": general, "hist_rows_1": general, "hist_rows_2": general,
+                 "tile_count": general + row_pass, "emit_rows": general + row_pass, "range_emit": range_rows}
+    if args.randk:
+        rows_read = {}
+
+    def alg_bytes(name, tally_out=False, votes_out=False):
+        return kernel_bytes(name, M, N, K, rows_read.get(name, M), n_voted, args.dense_state, tally_out, votes_out)
+
+    def fractions(kern_, votes_out):
+        out = {}
+        for k, v in kern_.items():
+            b = alg_bytes(k, votes_out=votes_out)
+            if b and v["ms_avg"] > 0:
+                out[k] = {"ms": round(v["ms_avg"] * v["launches_per_step"], 5), "alg_GB": round(b / 1e9, 4),
+                          "frac_of_peak": round(b * v["launches_per_step"] / (v["ms_avg"] * v["launches_per_step"] * 1e-3) / HBM_PEAK, 4)}
+        return out
+
+    votes_in_headline = args.three_calls and not is_variant
+    dom = max(kern, key=lambda k: kern[k]["ms_avg"] * kern[k]["launches_per_step"])
+    dom_bytes = alg_bytes(dom, votes_out=votes_in_headline) or 0.0
+    achieved = dom_bytes / (kern[dom]["ms_avg"] * 1e-3)
+    # bytes of G the step reads as built, plus the words written and read; the floor is one read of G, the words,
+    # and a read and a write of every voted parameter (the fused step never moves an unvoted one)
+    per_pass = {"filter_mem": 12.0}
+    g_bytes = sum(per_pass.get(k, 4.0) * N * r for k, r in rows_read.items() if k in kern)
+    as_built = g_bytes + 8.0 * M * K + 8.0 * n_voted
+    floor_bytes = (12.0 if args.memory else 4.0) * M * N + 8.0 * M * K + 8.0 * n_voted
+    if args.randk:
+        as_built = floor_bytes = 16.0 * M * K + 8.0 * n_voted
+    traffic = PROFILED_TRAFFIC.get((cfg.name, dom)) if not (is_variant or args.three_calls or args.sparsity > 0 or args.graph) else None
+    entry = ("s3gd_step_randk (Algorithm 2)" if args.randk else
+             "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
+             ("s3gd_step_momentum (mu=0.9" + (", with memory" if args.memory else "") +
+              (", dense momentum state)" if args.dense_state else ", momentum starts at zero)")) if args.momentum else
+             "s3gd_step_acc (fused, the memory already holds the compensated gradients)" if args.memory_acc else
+             "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
+             ("s3gd_topk_sign_encode + s3gd_majority_vote (int8 votes) + s3gd_apply_update" if args.three_calls
+              else "s3gd_step (fused, vote not materialised)"))
     out = {
         "metric": "gradient elements/sec per S3GD-MV step (M*N/t)",
         "value": M * N / (ms_step * 1e-3),
         "unit": "gradient elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "ms_per_step_median_of_event_times": ms_median,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe,
-                   "entry": "s3gd_step_randk (Algorithm 2)" if args.randk else
-                            "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
-                            ("s3gd_step_momentum (mu=0.9" + (", with memory" if args.memory else "") +
-                             (", dense momentum state)" if args.dense_state else ", momentum starts at zero)")) if args.momentum else
-                            "s3gd_step_acc (fused, the memory already holds the compensated gradients)" if args.memory_acc else
-                            "s3gd_step_ec (fused, with error-compensation memory, eta=1)" if args.memory else
-                            ("three calls" if args.three_calls else "s3gd_step (fused, vote not materialised)"),
-                   "rows_on_general_path": general_rows, "launch": "HIP graph replay" if args.graph else "eager"},
+        "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe, "entry": entry,
+                   "rows": {"general_route": general, "wide_radix_select": _wide, "row_passes_known_threshold": row_pass,
+                            "second_pass_over_ranges": range_rows, "skipped_single_pass": skipped},
+                   "launch": "HIP graph replay" if args.graph else "eager"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK,
+                     "frac": achieved / HBM_PEAK, "algorithmic_bytes_per_launch": dom_bytes,
                      "duration_from": "HIP events inside the timed region" if dom in live else "HIP events, eager pass before the timed region",
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)) if not (args.three_calls or args.memory or args.memory_acc or args.momentum or args.wire or args.randk) else None},
-        "step_roofline": {"full_reads_of_G_per_step": full_reads,
-                          "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
-                          "floor_bytes": floor_bytes,
-                          "step_bytes_as_built": per_pass * M * N * full_reads + 8.0 * M * K,
-                          "f_step": (per_pass * M * N * full_reads + 8.0 * M * K) / (ms_step * 1e-3) / HBM_PEAK},
+                     "traffic": traffic[0] if traffic else None, "traffic_from": traffic[1] if traffic else None},
+        "step_roofline": {"reads_of_G_per_step": g_bytes / (4.0 * M * N),
+                          "voted_coordinates": n_voted,
+                          "floor_bytes": floor_bytes, "f_alg": floor_bytes / (ms_step * 1e-3) / HBM_PEAK,
+                          "step_bytes_as_built": as_built, "f_step": as_built / (ms_step * 1e-3) / HBM_PEAK},
         "kernels_ms": {k: round(v["ms_avg"] * v["launches_per_step"], 5) for k, v in kern.items()},
+        "kernel_fractions": fractions(kern, votes_in_headline),
         "paper_bits_per_step": {"s3gd_uplink": costs.s3gd_uplink(M, N, K), "s3gd_total": costs.s3gd_mv(M, N, K),
                                 "signsgd": costs.signsgd_mv(M, N), "packed_words": costs.packed_words_bits(M, K)},
     }
+    if not is_variant and not args.graph:
+        # the same step as the other entry: the three public calls beside the fused one (or the reverse)
+        other = fused_step if args.three_calls else three_calls_step
+        ms2, med2, kern2, live2, _ = measure(other, args.steps, args.warmup)
+        log(f"[bench] {'fused' if args.three_calls else 'three calls'}: mean {ms2:.4f} ms, median {med2:.4f} ms")
+        rec = {"entry": "s3gd_step (fused, vote not materialised)" if args.three_calls
+               else "s3gd_topk_sign_encode + s3gd_majority_vote (int8 votes) + s3gd_apply_update",
+               "ms_per_step": ms2, "ms_per_step_median_of_event_times": med2, "value": M * N / (ms2 * 1e-3),
+               "unit": "gradient elements/s", "steps": args.steps, "warmup": args.warmup,
+               "kernels_ms": {k: round(v["ms_avg"] * v["launches_per_step"], 5) for k, v in kern2.items()},
+               "kernel_fractions": fractions(kern2, not args.three_calls)}
+        b3 = g_bytes + 8.0 * M * K + 2.0 * N + 8.0 * n_voted  # + the int8 votes written and read
+        if not args.three_calls:
+            rec["step_bytes_as_built"] = b3
+            rec["f_step"] = b3 / (ms2 * 1e-3) / HBM_PEAK
+        out["fused" if args.three_calls else "three_calls"] = rec
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, datagen)
     print(json.dumps(out), flush=True)

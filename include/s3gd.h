@@ -329,7 +329,11 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
  * out[0] = number of rows, out[1] = rows that took the general multi-pass path because the
  * single-pass candidate filter did not apply to them, out[2] = rows served by the single pass whose
  * K-th magnitude lay far above the sampled bound (their radix select ran over all three levels of
- * the candidates instead of the last).  `out` is host memory, 3 entries. */
+ * the candidates instead of the last), out[3] = rows whose words came from a count and an emit pass
+ * over the row with a threshold known beforehand (dense K with a memory; K == N), out[4] = rows whose
+ * words came from a second pass over the row after the single pass (dense K), out[5] = rows of
+ * out[1] that were recognised from the sample and skipped the single pass.  `out` is host memory,
+ * 6 entries. */
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
 /*
@@ -359,10 +363,18 @@ S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 25
+#define S3GD_PROFILE_KERNELS 27
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);
+
+/*
+ * Calibration for benchmarks: a plain read of n fp32 entries of `buf` (dev, 16-byte aligned; whole
+ * 1024-entry tiles only) with the launch shape and the load instructions of the selection pass and
+ * none of its work.  Its duration (kernel id "plain_read" of the profile) is what this memory system
+ * gives a read stream of that shape: the practical ceiling the selection pass is compared with.
+ */
+S3GD_API int s3gd_calibrate_read(s3gd_ctx* ctx, const float* buf, uint64_t n, s3gd_stream_t stream);
 
 /* hipError_t value of the last failed HIP call made through this context (0 if none). */
 S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx);

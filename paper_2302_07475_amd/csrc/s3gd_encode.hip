@@ -80,7 +80,7 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
     s.bracket = bracket;
     s.row_emit = all_selected ? 2u : 0u;  // K = N: threshold 0, no tie slots (the zero-filled T and q), count from the scan
     rs[m] = s;
-    if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; }
+    if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; status[5] = 0; status[6] = 0; status[7] = 0; }
   }
 }
 
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
 enum { kResolveRadix = 0, kResolveSample = 1, kResolveFilter = 2 };
 
 template <int LEVEL, int WHAT>
-__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins, u32 sample_cap) {
+__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins, u32 sample_cap, u32* status) {
   constexpr int NB = WHAT == kResolveFilter ? kHistBins : (1 << digit_bits(LEVEL));
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
@@ -290,6 +290,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
           // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
           // sampled entries that stands for a full pool (0: no such check).
           if (sample_cap && have_bins && acc + c[i] > sample_cap) st.mode = kModeGeneral;
+          if (st.mode == kModeGeneral) atomicAdd(&status[7], 1u);
         }
         if (LEVEL == 2) {
           st.T = st.prefix;
@@ -796,6 +797,27 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
 }
 
+// A plain read of a flat array with the launch shape and the loads of k_filter (persistent waves,
+// a contiguous run of 1024-entry tiles each, the next tile requested before the current one is
+// used) and none of its work: what the memory system gives a read stream of this shape.  The one
+// compare per entry keeps the loads alive; `sink` receives a count nobody reads.
+__global__ __launch_bounds__(kBlock) void k_plain_read(const float* __restrict__ buf, u32 n_wtiles, u32 tiles_per_wave, u32* __restrict__ sink) {
+  const u32* rowv = reinterpret_cast<const u32*>(buf);
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
+  const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
+  u32 seen = 0;
+  TileRegs nxt;
+  if (t0 < t1) load_filter_tile<true>(rowv, 0, 0, t0, lane, nxt);
+  for (u32 tile = t0; tile < t1; ++tile) {
+    const TileRegs r = nxt;
+    if (tile + 1 < t1) load_filter_tile<true>(rowv, 0, 0, tile + 1, lane, nxt);
+#pragma unroll
+    for (int i = 0; i < kLoads * 4; ++i) seen += (r.b[i] & 0x7FFFFFFFu) >= 0x7F800001u;
+  }
+  if (seen == 0x7FFFFFFFu) *sink = seen;  // never: a wave sees at most 2^22 entries per launch shape used here
+}
+
 // ---- the filter pass with a memory, in chunks --------------------------------------------------
 // The row is g = grads + eta * err, and g is written over err as it is filtered (grads and err rows
 // start at the same 16-byte phase, checked by the caller).  One block per chunk of 8192 consecutive
@@ -1161,6 +1183,8 @@ __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __res
     counts[m] = st.count;
     if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
     if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
+    if (st.mode == kModeGeneral && st.row_emit) atomicAdd(&status[5], 1u);
+    if (st.mode == kModeRangeEmit) atomicAdd(&status[6], 1u);
   }
   u32* out = words + (size_t)m * K;
   for (u64 i = (u64)st.count + blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x)
@@ -1189,6 +1213,18 @@ u32 resident_stream_blocks(int device, bool with_memory) {
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   const u32 n = (u32)cus * (u32)per_cu;
   return n > kMaxStreamBlocks ? kMaxStreamBlocks : n;
+}
+
+hipError_t launch_plain_read(const Workspace& ws, const float* buf, u64 n, hipStream_t s) {
+  const u32 n_wtiles = (u32)(n / kWaveTile);  // whole tiles only: a calibration, not a reduction
+  if (n_wtiles == 0) return hipSuccess;
+  u32 gx = ws.stream_blocks;
+  if (gx > (n_wtiles + kWaves - 1) / kWaves) gx = (n_wtiles + kWaves - 1) / kWaves;
+  const u32 tiles_per_wave = (n_wtiles + gx * kWaves - 1) / (gx * kWaves);
+  ws.prof->begin(KID_PLAIN_READ, s);
+  k_plain_read<<<gx, kBlock, 0, s>>>(buf, n_wtiles, tiles_per_wave, ws.status + 7);
+  ws.prof->end(s);
+  return hipGetLastError();
 }
 
 // Upper estimate of the candidates per row when the sample rank is r and the sample fraction f:
@@ -1310,9 +1346,9 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     const double cap = (double)p.cand_stride * ((double)p.n_units * kSampleUnit / (double)N);
     const u32 sample_cap = p.bracket ? 0u : (cap < 1.0 ? 1u : (cap > 4.0e9 ? 0u : (u32)cap));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, sample_cap)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, sample_cap, ws.status)));
     if (p.chunks && p.bracket)
       S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
@@ -1328,7 +1364,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
       S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
                                                                       ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status,
                                                                       ws.wave_sure)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, 0u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, 0u, ws.status)));
   }
   // Radix select: over the row for general rows, over the candidates for the others (the last level
   // only, unless the filter's bins could not place the K-th key).
@@ -1344,11 +1380,11 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
 #define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves, parts
   if (!all) {
     S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
     S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
     S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
   }
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
@@ -1358,7 +1394,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
                                                                    n_waves, ws.wave_sum, K, words, err, N)));
     if (p.bracket && !p.chunks)
-      S3GD_LAUNCH(KID_EMIT, (k_range_emit<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.wave_sum, wstride, p.n_wtiles, p.tiles_per_wave,
+      S3GD_LAUNCH(KID_RANGE_EMIT, (k_range_emit<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.wave_sum, wstride, p.n_wtiles, p.tiles_per_wave,
                                                                  words, err)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).

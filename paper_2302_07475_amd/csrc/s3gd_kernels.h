@@ -33,6 +33,7 @@ enum KernelId : int {
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
   KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,
   KID_PACK, KID_UNPACK, KID_VOTES_TO_MESSAGE, KID_RANDK,
+  KID_RANGE_EMIT, KID_PLAIN_READ,
   KID_COUNT
 };
 
@@ -45,7 +46,7 @@ struct Profiler {
   hipEvent_t* ev = nullptr;  // 2 * kPairs events, created when profiling is first enabled
   int kid[kPairs];
   void begin(int k, hipStream_t s) {
-    open = mode != 0 && used < kPairs && (mode == 1 || k == KID_FILTER || k == KID_FILTER_MEM || k == KID_RANDK);
+    open = mode != 0 && used < kPairs && (mode == 1 || k == KID_FILTER || k == KID_FILTER_MEM || k == KID_RANDK || k == KID_PLAIN_READ);
     if (open) { kid[used] = k; (void)hipEventRecord(ev[2 * used], s); }
   }
   void end(hipStream_t s) {
@@ -61,7 +62,10 @@ struct Workspace {
   Profiler* prof;
   RowState* rs;   // [M]
   u32* status;    // [8]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags,
-                  //      4 = candidate rows whose radix select ran over all levels
+                  //      4 = candidate rows whose radix select ran over all levels, 5 = rows whose words came from the
+                  //      row passes with a threshold known beforehand (bracket with a memory, K = N), 6 = rows whose
+                  //      words came from the second pass over the waves' ranges (dense K), 7 = rows that left the
+                  //      candidate route before the filter pass (decided from the sample)
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][tiles of the launch's tiling + 1], at most seg_row_entries(N) per row
@@ -99,6 +103,8 @@ u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
 // `nan_flag` (device, nullable): receives 1 if the call saw a NaN, else 0, when its last kernel runs.
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
                          u32* counts, hipStream_t s, u32* nan_flag = nullptr);
+// Plain non-temporal read of `n` fp32 entries with the filter pass's launch shape: what this memory system gives a read stream.
+hipError_t launch_plain_read(const Workspace& ws, const float* buf, u64 n, hipStream_t s);
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);
