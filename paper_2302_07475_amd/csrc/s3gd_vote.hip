@@ -75,17 +75,27 @@ __device__ __forceinline__ void tally_wave_tile(const u32* __restrict__ words, u
   constexpr u32 kSlice = kMomTile / F::kPer;
   const u32 lane = lane_id();
   const u64 base = (u64)tile * kMomTile;
+  // the bounds of the first 64 rows are requested before the slice is filled: the fill hides their latency
+  u32 lo0 = 0, hi0 = 0;
+  if (lane < M) {
+    const u32* sg = seg + (size_t)lane * seg_stride + tile;
+    lo0 = sg[0];
+    hi0 = sg[1];
+  }
   for (u32 i = lane * 4; i < kSlice; i += 256) *reinterpret_cast<uint4*>(&t[i]) = make_uint4(F::kFill, F::kFill, F::kFill, F::kFill);
   wave_sync();
 
   for (u32 m0 = 0; m0 < M; m0 += 64) {
     const u32 rows = M - m0 < 64u ? M - m0 : 64u;
-    u32 lo = 0, cnt = 0;
-    if (lane < rows) {
-      const u32* sg = seg + (size_t)(m0 + lane) * seg_stride + tile;
-      lo = sg[0];
-      const u32 hi = sg[1];
-      cnt = hi > lo ? hi - lo : 0u;
+    u32 lo = lo0, cnt = hi0 > lo0 ? hi0 - lo0 : 0u;
+    if (m0 > 0) {
+      lo = 0; cnt = 0;
+      if (lane < rows) {
+        const u32* sg = seg + (size_t)(m0 + lane) * seg_stride + tile;
+        lo = sg[0];
+        const u32 hi = sg[1];
+        cnt = hi > lo ? hi - lo : 0u;
+      }
     }
     const u32 incl = wave_incl_scan(cnt);
     const u32 first = incl - cnt;  // number of this row's first message in the tile's flat numbering
@@ -170,10 +180,25 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
       const u64 n = base + c0;
       if (n >= N) break;
       u32 w[4] = {0, 0, 0, 0};
+      if (FB == 8) {
+        // four fields per word, each 0x40 + tally: the four vote bytes of a word at once.  A field above
+        // 0x40 carries into its top bit when 0x3F is added, a field below 0x40 does not when 0x40 is
+        // (fields stay below 0x80, so no carry crosses into the neighbour).
+        const uint4 f4 = *reinterpret_cast<const uint4*>(&t[c0 / 4]);
+        const u32 f[4] = {f4.x, f4.y, f4.z, f4.w};
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int d = tally_of(c0 + (u32)i);
-        w[i / 4] |= (u32)(((d > 0) - (d < 0)) & 0xFF) << (8 * (i % 4));
+        for (int k = 0; k < 4; ++k) {
+          const u32 v = f[k] & 0x7F7F7F7Fu;
+          const u32 pos = ((v + 0x3F3F3F3Fu) >> 7) & 0x01010101u;
+          const u32 neg = (~(v + 0x40404040u) >> 7) & 0x01010101u;
+          w[k] = pos | (neg * 0xFFu);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int d = tally_of(c0 + (u32)i);
+          w[i / 4] |= (u32)(((d > 0) - (d < 0)) & 0xFF) << (8 * (i % 4));
+        }
       }
       if (n + 16 <= N) {
         u32x4 q;  // streamed out: 1 byte per coordinate is never read back by this kernel
@@ -188,6 +213,8 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
     for (u32 c0 = lane * 4u; c0 < kMomTile; c0 += 256u) {
       const u64 n = base + c0;
       if (n >= N) break;
+      // nobody voted on these four coordinates (one word of 8-bit fields still holds the fill): nothing moves
+      if (FB == 8 && !tally && (t[c0 / 4] & 0x7F7F7F7Fu) == F::kFill) continue;
       const int d[4] = {tally_of(c0), tally_of(c0 + 1), tally_of(c0 + 2), tally_of(c0 + 3)};
       const int v[4] = {(d[0] > 0) - (d[0] < 0), (d[1] > 0) - (d[1] < 0), (d[2] > 0) - (d[2] < 0), (d[3] > 0) - (d[3] < 0)};
       if (n + 4 <= N) {
@@ -327,52 +354,67 @@ __global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ 
 // 16-byte load) at a time, kUpd such groups per round with all their loads in flight together; where
 // a group holds a vote, the lane rewrites the whole 64 bytes of x that belong to it (memory merges a
 // smaller write by reading first).
-constexpr int kUpd = 2;
+constexpr int kUpd = 4;
 
 typedef u32 u32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void load_votes(const int8_t* __restrict__ votes, u64 i0, u64 stride, u64 n16, u32x4v (&v)[kUpd]) {
+#pragma unroll
+  for (int u = 0; u < kUpd; ++u) {
+    const u64 i = i0 + (u64)u * stride;
+    v[u] = 0;
+    if (i < n16) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(votes + i * 16));
+  }
+}
+
+// One block per 256 * kUpd consecutive groups of 16 coordinates, launched in coordinate order, so that
+// the blocks running at any time touch a compact window of x (scattered accesses spread over the
+// whole vector cost address translation and DRAM page misses on top of the transfer).  Few groups
+// hold a vote (one in sixteen on a 1.2e9-coordinate model with four workers), so a lane that updated
+// its own groups would issue four loads and four stores for a handful of active lanes each time.
+// Instead the lanes of a wave queue their voted groups in LDS (the 16 votes and the group's number)
+// and the wave works the queue off sixteen groups at a time, four lanes per group: one 16-byte load
+// and one 16-byte store per lane, every lane busy, the four lanes of a group rewriting its 64 bytes
+// together.
 __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, const int8_t* __restrict__ votes, float lr, u64 N) {
+  __shared__ u32 queue_votes[kWaves][4][64 * kUpd], queue_group[kWaves][64 * kUpd];
+  const u32 lane = lane_id();
+  u32 (*qv)[64 * kUpd] = queue_votes[threadIdx.x >> 6];
+  u32* qg = queue_group[threadIdx.x >> 6];
   const u64 n16 = N / 16;
-  const u64 stride = (u64)gridDim.x * blockDim.x;
-  for (u64 i0 = (u64)blockIdx.x * blockDim.x + threadIdx.x; i0 < n16; i0 += stride * kUpd) {
-    u32x4v v[kUpd];
-    bool live[kUpd];
-    float4 q[kUpd][4];
+  const u64 i0 = (u64)blockIdx.x * (kBlock * kUpd) + threadIdx.x;  // slot u of this thread: group i0 + u * kBlock
+  u32x4v v[kUpd];
+  load_votes(votes, i0, kBlock, n16, v);
+  u32 total = 0;
 #pragma unroll
-    for (int u = 0; u < kUpd; ++u) {
-      const u64 i = i0 + (u64)u * stride;
-      v[u] = 0;
-      if (i < n16) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(votes + i * 16));
+  for (int u = 0; u < kUpd; ++u) {
+    const bool live = (v[u].x | v[u].y | v[u].z | v[u].w) != 0;  // groups past the end were loaded as zeros
+    const u64 m = ballot(live);
+    if (live) {
+      const u32 at = total + ballot_rank(m);
+      qv[0][at] = v[u].x; qv[1][at] = v[u].y; qv[2][at] = v[u].z; qv[3][at] = v[u].w;
+      qg[at] = (u32)(i0 + (u64)u * kBlock);
     }
-#pragma unroll
-    for (int u = 0; u < kUpd; ++u) {
-      live[u] = (v[u].x | v[u].y | v[u].z | v[u].w) != 0;
-      if (live[u]) {
-        const float4* p = reinterpret_cast<const float4*>(x + (i0 + (u64)u * stride) * 16);
-        q[u][0] = p[0]; q[u][1] = p[1]; q[u][2] = p[2]; q[u][3] = p[3];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kUpd; ++u) {
-      if (!live[u]) continue;
-      const u32 vw[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-      float4* p = reinterpret_cast<float4*>(x + (i0 + (u64)u * stride) * 16);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int a = (int8_t)(vw[k] & 0xFF), b = (int8_t)((vw[k] >> 8) & 0xFF), c = (int8_t)((vw[k] >> 16) & 0xFF),
-                  d = (int8_t)(vw[k] >> 24);
-        float4 xv = q[u][k];
-        if (a) xv.x = xv.x - lr * (float)a;
-        if (b) xv.y = xv.y - lr * (float)b;
-        if (c) xv.z = xv.z - lr * (float)c;
-        if (d) xv.w = xv.w - lr * (float)d;
-        p[k] = xv;
-      }
+    total += (u32)__popcll(m);
+  }
+  wave_sync();
+  for (u32 r0 = 0; r0 < total; r0 += 16) {  // wave-uniform
+    const u32 k = r0 + (lane >> 2), part = lane & 3u;
+    if (k < total) {
+      const u32 vw = qv[part][k];
+      float4* p = reinterpret_cast<float4*>(x + (u64)qg[k] * 16 + part * 4);
+      float4 xv = *p;
+      const int a = (int8_t)(vw & 0xFF), b = (int8_t)((vw >> 8) & 0xFF), c = (int8_t)((vw >> 16) & 0xFF), d = (int8_t)(vw >> 24);
+      if (a) xv.x = xv.x - lr * (float)a;
+      if (b) xv.y = xv.y - lr * (float)b;
+      if (c) xv.z = xv.z - lr * (float)c;
+      if (d) xv.w = xv.w - lr * (float)d;
+      *p = xv;
     }
   }
   if (blockIdx.x == 0) {
     for (u64 n = n16 * 16 + threadIdx.x; n < N; n += blockDim.x) {
-      const int v = votes[n];
-      if (v) x[n] = x[n] - lr * (float)v;
+      const int vt = votes[n];
+      if (vt) x[n] = x[n] - lr * (float)vt;
     }
   }
 }
@@ -600,8 +642,7 @@ hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts,
 }
 
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s) {
-  u64 blocks = (N / 16 + kBlock - 1) / kBlock;
-  if (blocks > 256u * 32u) blocks = 256u * 32u;
+  u64 blocks = (N / 16 + kBlock * kUpd - 1) / (kBlock * kUpd);  // at most 2^27 / 1024 blocks
   if (blocks < 1) blocks = 1;
   ws.prof->begin(KID_UPDATE, s);
   k_apply_update<<<(u32)blocks, kBlock, 0, s>>>(x, votes, lr, N);
