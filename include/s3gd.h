@@ -342,8 +342,8 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  *   out  host, 12 entries:
  *     [0] 1 if the single-pass candidate route is planned (0: the multi-pass route for every row)
  *     [1] 1 if that pass runs as one block per 8192 entries (calls with a memory), 0: persistent waves
- *     [2] 1 if only a bracket of magnitudes around the K-th is kept (dense K; the words then come from
- *         a second pass over the row)
+ *     [2] s: a run of n candidate slots comes with room for n >> s records of candidates whose
+ *         selection is still open after the pass (the others are selected whatever the threshold)
  *     [3] blocks per row of the pass, four waves each   [4] 1024-entry tiles each wave covers, in a row
  *     [5] candidate slots a wave reserves at a time     [6] candidate slots per row
  *     [7] sample units per row                          [8] row entries per sample unit window
@@ -351,6 +351,12 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  *     [10] segments a wave's candidate list may have    [11] consecutive entries per sample unit
  * s3gd_encode_sample_unit_start(u, out[8]) is the index of the first entry of sample unit u of a row.
  */
+/* The selection state row m was left in by the last encode on this context (16 words, host memory;
+ * synchronises `stream`): in order the key prefix and rank of the radix select, the threshold T, the
+ * tie quota, the entries above T, the words sent, the route (0 multi-pass, 1-3 single pass), the two
+ * sampled bounds, an out-of-room flag, candidates kept, candidates whose selection the pass left
+ * open, slots reserved (two counters), the K = N flag, one unused word.  For tests. */
+S3GD_API int s3gd_last_row_state(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t m, uint32_t* out);
 S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, uint64_t K, int with_memory, uint64_t* out);
 S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride);
 

@@ -28,8 +28,8 @@ constexpr u32 kMaxRows = S3GD_M_LIMIT;  // rows map to gridDim.y
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_nseg, wave_sum, wave_sure, cand, total;
-  u64 cand_pool;
+  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_segb, wave_nseg, wave_sum, pool, total;
+  u64 pool_bytes;
 };
 
 Layout layout(u32 M, u64 N, u64 K) {
@@ -43,10 +43,10 @@ Layout layout(u32 M, u64 N, u64 K) {
   l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N) * kChain, 256);
   l.wave_nseg = off; off = align_up(off + sizeof(u32) * wave_table_entries(M, N), 256);
   l.wave_sum = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N), 256);
-  l.wave_sure = off; off = align_up(off + sizeof(u32) * wave_table_entries(M, N), 256);
+  l.wave_segb = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N) * kChain, 256);
   l.blk_sum = off;  off = align_up(off + sizeof(u64) * (size_t)M * blk_stride(N), 256);
-  l.cand_pool = candidate_pool_entries(M, N, K);
-  l.cand = off;     off = align_up(off + sizeof(uint2) * (size_t)l.cand_pool, 256);
+  l.pool_bytes = candidate_pool_bytes(M, N, K);
+  l.pool = off;     off = align_up(off + (size_t)l.pool_bytes, 256);
   l.total = off;
   return l;
 }
@@ -61,10 +61,10 @@ void bind_workspace(Workspace& ws, char* b, const Layout& l) {
   ws.wave_seg = reinterpret_cast<u64*>(b + l.wave_seg);
   ws.wave_nseg = reinterpret_cast<u32*>(b + l.wave_nseg);
   ws.wave_sum = reinterpret_cast<u64*>(b + l.wave_sum);
-  ws.wave_sure = reinterpret_cast<u32*>(b + l.wave_sure);
+  ws.wave_segb = reinterpret_cast<u64*>(b + l.wave_segb);
   ws.blk_sum = reinterpret_cast<u64*>(b + l.blk_sum);
-  ws.cand = reinterpret_cast<uint2*>(b + l.cand);
-  ws.cand_pool = l.cand_pool;
+  ws.pool = b + l.pool;
+  ws.pool_bytes = l.pool_bytes;
 }
 
 // Makes the context's device current for the duration of a call.
@@ -513,15 +513,23 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
   return S3GD_OK;
 }
 
+S3GD_API int s3gd_last_row_state(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t m, uint32_t* out) {
+  if (!ctx || !out || m >= ctx->M_max) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) e = hipMemcpy(out, ctx->ws.rs + m, sizeof(RowState), hipMemcpyDeviceToHost);
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
 S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, uint64_t K, int with_memory, uint64_t* out) {
   if (!out) return S3GD_E_INVAL;
   const int rc = check_shape(ctx, M, N, K);
   if (rc) return rc;
-  const EncodePlan p = plan_encode(M, N, K, ctx->ws.cand_pool, with_memory ? ctx->ws.stream_blocks_mem : ctx->ws.stream_blocks,
+  const EncodePlan p = plan_encode(M, N, K, ctx->ws.pool_bytes, with_memory ? ctx->ws.stream_blocks_mem : ctx->ws.stream_blocks,
                                    with_memory != 0);
   out[0] = p.candidates;
   out[1] = p.chunks;
-  out[2] = p.bracket;
+  out[2] = p.brk_shift;
   out[3] = p.gx;
   out[4] = p.tiles_per_wave;
   out[5] = p.slab;

@@ -1,6 +1,7 @@
 // Shared declarations of the S3GD-MV HIP library (gfx950, wave64).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "s3gd.h"
@@ -28,31 +29,38 @@ struct RowState {
   u32 prefix;     // key bits fixed so far (right aligned)
   u32 k_rem;      // rank still sought inside the current prefix, 1-based from the largest
   u32 T;          // K-th largest key: the threshold rho taken at the K-th value (eq. "topk")
+                  // (while the sample is resolved: the prefix of the sample key that becomes U)
   u32 q;          // entries with key == T that are selected (lowest indices first); 0 when T == 0
+                  // (while the sample is resolved: the rank still sought for U; 0 = there is no U)
   u32 c_gt;       // entries with key > T
   u32 count;      // words the row emits = c_gt + q
   u32 mode;       // kModeGeneral, kModeCandidates or kModeCandWide
-  u32 L;          // candidate path: lower bound on the key of a candidate, a multiple of 1024
-  u32 n_cand;     // candidate path: candidates collected by the filter pass
-  u32 n_alloc;    // candidate path: candidate slots handed out to blocks (slab allocator)
-  u32 overflow;   // candidate path: a block found no room for its candidates
-  u32 bracket;    // candidate path with a bracket: entries at or above L + (kHistBins - 1) * 1024 are counted, not kept
-  u32 n_sure;     // bracket: entries at or above the bracket's upper end (all of them are selected)
+  u32 L;          // candidate route: every entry with key >= L is a candidate; a multiple of 1024
+  u32 U;          // candidate route: a candidate with key >= U is selected whatever the threshold turns out to
+                  // be; the others (L <= key < U, the bracket) take part in the radix select.  A multiple of
+                  // 1024, or 0x80000000 when no entry is sure
+  u32 overflow;   // candidate route: a wave or block found no room for its candidates
+  u32 n_cand;     // candidate route: candidates the filter pass kept ...
+  u32 n_brk;      // ... and those of them inside the bracket (the two are added to as one 64-bit word)
+  u32 n_alloc;    // candidate route: candidate slots handed out (slab allocator / exact reservations)
+  u32 n_alloc_b;  // filter pass in chunks: bracket slots handed out
   u32 row_emit;   // the row passes (count, emit) serve the row with a threshold that is already known:
-                  // 1 = from a bracket (chunked filter pass), 2 = K = N (threshold 0, count from the scan)
-  u32 pad[2];
+                  // 2 = K = N (threshold 0, count from the scan)
+  u32 pad;
 };
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
+static_assert(offsetof(RowState, n_cand) % 8 == 0 && offsetof(RowState, n_brk) == offsetof(RowState, n_cand) + 4, "n_cand and n_brk form one aligned 64-bit word");
 
 constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
-constexpr u32 kModeCandidates = 1;  // sampled lower bound, one filter pass, last ten key bits resolved among the candidates
-constexpr u32 kModeCandWide = 2;    // as above, but the K-th key lies far above the bound: full radix select among the candidates
-constexpr u32 kModeRangeEmit = 3;   // dense K: threshold known from the bracket; a second pass over the waves' ranges emits the words
+constexpr u32 kModeCandidates = 1;  // sampled bounds, one filter pass, last ten key bits resolved among the bracket's candidates
+constexpr u32 kModeCandWide = 2;    // as above, but the bracket is wider than the filter's bins: full radix select among its candidates
+constexpr u32 kModeCandDone = 3;    // candidate row whose threshold the filter pass already fixed (every selected entry lies above the bracket)
+constexpr u32 kNoUpper = 0x80000000u;  // U when no entry is sure: above every key
 
 constexpr int kWaveTile = 64 * 4 * kLoads;  // 1024 entries: the unit of the candidate route (one wave, no barriers)
 constexpr int kChunkTiles = 2;      // wave tiles a wave of the chunked filter pass holds: a block covers 8192 entries
-constexpr u32 kSlabMin = 256;       // candidate slots a wave reserves at a time: a power of two chosen per call ...
-constexpr u32 kSlabMax = 1u << 16;  // ... between these, from the candidates expected per wave
+constexpr u32 kSlabMin = 256;       // candidate slots a wave reserves at a time: a multiple of this chosen per call ...
+constexpr u32 kSlabMax = 1u << 20;  // ... up to this, from the candidates expected per wave
 constexpr int kChain = 8;           // segments (slabs) a wave of the filter pass may leave behind
 constexpr int kSampleUnit = 16;     // consecutive entries per sample unit (one 64-byte line)
 constexpr int kSamplePerBlock = 4096;

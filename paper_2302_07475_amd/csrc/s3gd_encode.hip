@@ -7,19 +7,21 @@
 // threshold lies between the K-th and (K+1)-th magnitude; ties go to the lowest index).
 //
 // Two routes reach the same T, q and words:
-//   candidate route  a strided sample of the row gives a lower bound L with, very likely,
-//                    K <= #{key >= L} <= capacity.  ONE pass over the row copies those candidates
-//                    (index, bits) into per-wave segments of a pool and histograms them; T is then
-//                    resolved and the words are emitted from the candidates alone.
-//                    If the K-th key lies far above L (a row whose magnitudes are spread widely
-//                    around the threshold) the radix select simply runs over the candidates.
-//                    At dense sparsity levels (K > N/16) the pass keeps only a bracket of keys above L
-//                    and counts the entries above it; the words then come from a second pass over the
-//                    row (two reads).  K = N selects nothing: count and emit (two reads).
+//   candidate route  a strided sample of the row gives two bounds L < U with, very likely,
+//                    #{key >= U} <= K <= #{key >= L}.  ONE pass over the row writes the message word
+//                    of every candidate (key >= L), in ascending index, into per-wave segments of a
+//                    pool; the candidates inside the bracket [L, U) also leave a record (position,
+//                    bits) and are histogrammed.  T is then resolved among the bracket's records,
+//                    and the emit pass copies the candidate words minus the bracket's losers.  The
+//                    entries at or above U are selected whatever T turns out to be, so nothing but
+//                    their words is ever kept: at K = N/10 the row is read once and a tenth of it is
+//                    written, read and written again, instead of the row being read twice.
+//                    If the bracket is wider than the pass's 2048 bins the radix select simply runs
+//                    over its records.  K = N selects nothing: count and emit (two reads).
 //   general route    three histogram passes over the row (11 + 10 + 10 key bits), a per-tile count
 //                    pass and an emit pass.  Any row for which the candidate route's checks fail
-//                    (too few or too many candidates, tiny rows) takes it; the choice is made on
-//                    the device, per row, with no host synchronisation.
+//                    (too few or too many candidates, tiny rows, K above N/2) takes it; the choice is
+//                    made on the device, per row, with no host synchronisation.
 #include <math.h>
 
 #include "s3gd_common.h"
@@ -44,6 +46,8 @@ __device__ __forceinline__ void store_stream16(u32* p, u32 a, u32 b, u32 c, u32 
   u32x4 q; q.x = a; q.y = b; q.z = c; q.w = d;
   __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(p));
 }
+__device__ __forceinline__ void store_stream8(u64* p, u64 v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_stream4(u32* p, u32 v) { __builtin_nontemporal_store(v, p); }
 
 // e <- g~ + eta * e over the flat [M * N] array (rows are contiguous).  Used when no row of the call
 // goes through the filter pass (tiny rows, a pool too small for the plan, K = 0).  `head` = elements before the first
@@ -68,16 +72,18 @@ __global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // state reset (a kernel rather than a memset so that callers may capture the call into a graph)
-__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 mode, u32 first_alloc, u32 bracket, u32 all_selected) {
+__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 upper_rank, u32 mode, u32 first_alloc,
+                              u32 all_selected) {
   const u32 m = blockIdx.y;
   for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x)
     hist[(size_t)m * kHistBins + i] = 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     RowState s{};
-    s.k_rem = first_rank;  // K on the general route, the sample rank on the candidate route
+    s.k_rem = first_rank;  // K on the general route, the sample rank of L on the candidate route
+    s.q = upper_rank;      // candidate route: the sample rank of U (0: no entry is sure); cleared once U is there
     s.mode = mode;
+    s.U = kNoUpper;
     s.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
-    s.bracket = bracket;
     s.row_emit = all_selected ? 2u : 0u;  // K = N: threshold 0, no tie slots (the zero-filled T and q), count from the scan
     rs[m] = s;
     if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; status[5] = 0; status[6] = 0; status[7] = 0; }
@@ -86,23 +92,69 @@ __global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 f
 
 // ------------------------------------------------------------------------------------------------
 // The candidates of a row, as the filter pass left them: a table of segment lists, each of at most
-// kChain segments (first slot, count) of the row's pool.  Lists in order and segments in order
-// enumerate the candidates in ascending index.  A ListWalk numbers the candidates of one list
-// 0 .. total-1 across its segments, so that a wave takes them 64 (or more) at a time whatever the
-// segment lengths are: a list may be two long slabs or eight short runs.
-struct ListWalk {
-  u32 first[kChain], count[kChain], slot[kChain];  // flat number of a segment's first candidate, its length, its first slot
-  u32 total;
-  bool single;  // the whole list is one run of the pool (the usual case: the wave's first slab sufficed); wave-uniform
+// kChain segments.  A segment is a run of candidate words (the message words of entries with key >= L,
+// in ascending index) in the row's word pool, and a run of bracket records in the row's record pool:
+// one record (position of the candidate inside its segment, fp32 bits) for every candidate of the
+// segment with key < U, in the same order.  Lists in order and segments in order enumerate the
+// candidates in ascending index.  A walk numbers the entries of one list 0 .. total-1 across its
+// segments, so that a wave takes them 64 (or more) at a time whatever the segment lengths are.
+struct RecordWalk {  // the bracket records of a list
+  u32 first[kChain], count[kChain], slot[kChain];  // flat number of a segment's first record, its length, its first slot
+  u32 total;        // records in the list
+  u32 words_total;  // candidate words in the list
+  bool single;      // at most one segment (the usual case: the wave's first slab sufficed); wave-uniform
   const uint2* pool;
-  __device__ ListWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const uint2* cand,
+  __device__ RecordWalk(const u64* __restrict__ wave_seg, const u64* __restrict__ wave_segb, const u32* __restrict__ wave_nseg,
+                        u32 wave_stride, const uint2* recs, u32 brk_stride, u32 m, u32 g)
+      : total(0), words_total(0), pool(recs + (size_t)m * brk_stride) {
+    const u64* segs = wave_segb + ((size_t)m * wave_stride + g) * kChain;
+    const u64* wsegs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
+    const u32 n_seg = wave_nseg[(size_t)m * wave_stride + g];
+#pragma unroll
+    for (int c = 0; c < kChain; ++c) {
+      const u64 sg = segs[c], wg = wsegs[c];  // the whole lines are loaded; entries past n_seg are stale
+      slot[c] = (u32)(sg >> 32);
+      count[c] = (u32)c < n_seg ? (u32)sg : 0u;
+      first[c] = total;
+      total += count[c];
+      words_total += (u32)c < n_seg ? (u32)wg : 0u;
+    }
+    single = __builtin_amdgcn_readfirstlane(n_seg <= 1u ? 1 : 0) != 0;
+  }
+  // pool slot of record j < total
+  __device__ __forceinline__ u32 locate(u32 j) const {
+    if (single) return slot[0] + j;
+    u32 at = 0;
+#pragma unroll
+    for (int c = 0; c < kChain; ++c) {
+      const u32 d = j - first[c];  // wraps to a huge value for records of earlier segments
+      if (d < count[c]) at = slot[c] + d;
+    }
+    return at;
+  }
+  // the segment record j < total belongs to
+  __device__ __forceinline__ u32 segment_of(u32 j) const {
+    u32 sg = 0;
+#pragma unroll
+    for (int c = 1; c < kChain; ++c)
+      if (j >= first[c] && count[c]) sg = (u32)c;
+    return sg;
+  }
+};
+
+struct WordWalk {  // the candidate words of a list
+  u32 first[kChain], count[kChain], slot[kChain];
+  u32 total;
+  bool single;
+  const u32* pool;
+  __device__ WordWalk(const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg, u32 wave_stride, const u32* words,
                       u32 cand_stride, u32 m, u32 g)
-      : total(0), pool(cand + (size_t)m * cand_stride) {
+      : total(0), pool(words + (size_t)m * cand_stride) {
     const u64* segs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
     const u32 n_seg = wave_nseg[(size_t)m * wave_stride + g];
 #pragma unroll
     for (int c = 0; c < kChain; ++c) {
-      const u64 sg = segs[c];  // the whole line is loaded; entries past n_seg are stale
+      const u64 sg = segs[c];
       slot[c] = (u32)(sg >> 32);
       count[c] = (u32)c < n_seg ? (u32)sg : 0u;
       first[c] = total;
@@ -110,19 +162,18 @@ struct ListWalk {
     }
     single = __builtin_amdgcn_readfirstlane(n_seg <= 1u ? 1 : 0) != 0;
   }
-  // pool slot of candidate j < total
   __device__ __forceinline__ u32 locate(u32 j) const {
     if (single) return slot[0] + j;
     u32 at = 0;
 #pragma unroll
     for (int c = 0; c < kChain; ++c) {
-      const u32 d = j - first[c];  // wraps to a huge value for candidates of earlier segments
+      const u32 d = j - first[c];
       if (d < count[c]) at = slot[c] + d;
     }
     return at;
   }
 };
-constexpr int kWalk = 4;  // candidates a lane has in flight where their order does not matter
+constexpr int kWalk = 4;  // entries a lane has in flight where their order does not matter
 
 // Adds one to h[bin] for every lane with `take`.  Where most lanes of a wave add to ONE bin (the
 // rows of the general route are mostly degenerate ones: mostly zeros, all equal, heavy ties) LDS
@@ -147,19 +198,20 @@ __device__ __forceinline__ void hist_add(u32* h, u32 bin, bool take) {
 
 // Histogram pass of one radix level (11 + 10 + 10 key bits, most significant first).
 //   general rows            over the whole row
-//   wide candidate rows     over the row's candidates, every level
-//   other candidate rows    over the candidates at the last level only: the filter pass has already
-//                           fixed the upper 21 bits
+//   wide candidate rows     over the row's bracket records, every level
+//   other candidate rows    over the bracket records at the last level only: the filter pass has
+//                           already fixed the upper 21 bits
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
                                                       u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status,
-                                                      const uint2* __restrict__ cand, u32 cand_stride, const u64* __restrict__ wave_seg,
-                                                      const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves, u32 parts) {
+                                                      const uint2* __restrict__ recs, u32 brk_stride, const u64* __restrict__ wave_seg,
+                                                      const u64* __restrict__ wave_segb, const u32* __restrict__ wave_nseg,
+                                                      u32 wave_stride, u32 n_waves, u32 parts) {
   constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int SH = digit_shift(LEVEL);
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode == kModeCandidates && LEVEL != 2) return;
+  if (st.mode == kModeCandDone || (st.mode == kModeCandidates && LEVEL != 2)) return;
   __shared__ u32 h[NB];
   for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
   __syncthreads();
@@ -181,11 +233,11 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
         hist_add(h, (key >> SH) & (NB - 1), take);
       }
     }
-  } else {  // `parts` waves per segment list, each with a share of its candidates (their order does not matter here)
+  } else {  // `parts` waves per segment list, each with a share of its records (their order does not matter here)
     const u32 lane = lane_id();
     for (u32 w = blockIdx.x * kWaves + (threadIdx.x >> 6); w < n_waves * parts; w += gridDim.x * kWaves) {
       const u32 g = w / parts, part = w - g * parts;
-      const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+      const RecordWalk lw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
       const u32 share = ((lw.total + parts - 1) / parts + 63u) & ~63u;
       const u32 lo = part * share;
       const u32 hi = lo + share < lw.total ? lo + share : lw.total;
@@ -211,28 +263,40 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
   if (LEVEL == 0 && nan) status[0] = 1;
 }
 
-// Picks the digit that holds the sought rank, narrows the prefix and clears the histogram.
-//   kResolveRadix      a level of the radix select filled by k_hist_rows: every level for general
-//                      and wide candidate rows, the last level for the other candidate rows
-//   kResolveSample     levels 0..1 over the sample: ends with L = 21-bit prefix << 10
-//   kResolveFilter     2048 bins of (key - L) >> 10 filled by the filter pass: checks the candidate
-//                      route and fixes the 21-bit prefix, or starts a radix select over the
-//                      candidates (K-th key in the open top bin), or hands the row to the general route
-// `have_bins` is 0 when the filter pass is the chunked one (with a memory): that pass fills no bins
-// (kResolveFilter), and it must run over every row to form g, so no row leaves the candidate route
-// before it (kResolveSample).
-enum { kResolveRadix = 0, kResolveSample = 1, kResolveFilter = 2 };
+// ------------------------------------------------------------------------------------------------
+// The resolve kernels: one block per row picks the bin that holds a sought rank from the row's
+// histogram (thread 0 owns the highest bins) and clears the histogram for its next use.
 
-template <int LEVEL, int WHAT>
-__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K, u32 have_bins, u32 sample_cap, u32* status) {
-  constexpr int NB = WHAT == kResolveFilter ? kHistBins : (1 << digit_bits(LEVEL));
+// Among `PER` consecutive bins of this thread (c[0] the highest), with `above` entries in the bins
+// above them: the bin that holds rank k (1-based from the largest), if it is one of them.
+template <int PER>
+__device__ __forceinline__ bool find_rank(const u32 (&c)[PER], u32 above, u32 k, int top, u32* digit, u32* rank_inside, u32* upto) {
+  u32 acc = above;
+  bool found = false;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if (k >= 1 && acc < k && k <= acc + c[i]) {
+      *digit = (u32)(top - i);
+      *rank_inside = k - acc;
+      *upto = acc + c[i];
+      found = true;
+    }
+    acc += c[i];
+  }
+  return found;
+}
+
+// A level of the radix select filled by k_hist_rows: every level for general and wide candidate
+// rows, the last level for the other candidate rows.
+template <int LEVEL>
+__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K) {
+  constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int PER = NB / kBlock;
   const u32 m = blockIdx.x;
   RowState st = rs[m];
-  if (WHAT == kResolveRadix ? (st.mode == kModeCandidates && LEVEL != 2) : (st.mode != kModeCandidates)) return;
+  if (st.mode == kModeCandDone || (st.mode == kModeCandidates && LEVEL != 2)) return;
   __shared__ u32 lds[kWaves];
   u32* h = hist + (size_t)m * kHistBins;
-  // thread 0 owns the highest bins
   const int top = NB - 1 - (int)threadIdx.x * PER;
   u32 c[PER];
   u32 s = 0;
@@ -242,72 +306,148 @@ __global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32
   const u32 above = block_excl_scan<u32>(s, &total, lds);
 #pragma unroll
   for (int i = 0; i < PER; ++i) h[top - i] = 0;
-  // With a bracket the n_sure entries above it come first in the order: the K-th overall is the
-  // (K - n_sure)-th of the candidates (n_sure is 0 without a bracket).
-  const u32 k = WHAT == kResolveFilter ? (K > st.n_sure ? K - st.n_sure : 0u) : st.k_rem;
-  if (WHAT == kResolveFilter) {
-    // The candidate route stands only if no wave ran out of room and the K-th largest key is among
-    // the candidates.  If it sits in the open-ended top bin (thread 0's c[0]) the bins say nothing
-    // about it: the radix select then starts over, among the candidates.
-    __shared__ u32 verdict;
-    // (A filter pass in chunks fills no bins: its candidates are the slots it handed out.)
-    if (!have_bins) st.n_cand = st.n_alloc;
-    if (threadIdx.x == 0) {
-      const bool usable = !st.overflow && k >= 1 && st.n_cand >= k && (!have_bins || total == st.n_cand);
-      // a bracket has no way on if the K-th key lies above it (k == 0): those entries were not kept
-      // (with bins; without them the radix select over the candidates finds the (K - n_sure)-th)
-      verdict = usable ? ((have_bins && c[0] < k) ? 2u : ((st.bracket && have_bins) ? 0u : 1u)) : 0u;
+  u32 digit, inside, upto;
+  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) {
+    st.prefix = (st.prefix << digit_bits(LEVEL)) | digit;
+    st.k_rem = inside;
+    if (LEVEL == 2) {
+      st.T = st.prefix;
+      st.q = st.T == 0 ? 0u : st.k_rem;
+      st.c_gt = K - st.k_rem;
+      st.count = st.c_gt + st.q;
     }
-    __syncthreads();
-    if (verdict != 2u) {
-      if (threadIdx.x == 0) {
-        st.mode = verdict ? kModeCandWide : kModeGeneral;
-        st.prefix = 0;
-        st.k_rem = verdict ? k : K;
-        rs[m] = st;
-      }
-      return;
-    }
+    rs[m] = st;
   }
-  if (above < k && k <= above + s) {
-    u32 acc = above;
+}
+
+// The sample, first level (key bits [30:20]): the bins that hold the sample ranks of L and of U.
+// Until U is there its prefix and its rank travel in the fields T and q.
+__global__ __launch_bounds__(kBlock) void k_resolve_sample0(RowState* rs, u32* hist) {
+  constexpr int PER = kHistBins / kBlock;
+  const u32 m = blockIdx.x;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 lds[kWaves];
+  u32* h = hist + (size_t)m * kHistBins;
+  const int top = kHistBins - 1 - (int)threadIdx.x * PER;
+  u32 c[PER];
+  u32 s = 0;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      if (acc < k && k <= acc + c[i]) {
-        const u32 digit = (u32)(top - i);
-        if (WHAT == kResolveFilter) st.prefix = (st.L >> 10) + digit;
-        else st.prefix = (st.prefix << digit_bits(LEVEL)) | digit;
-        st.k_rem = k - acc;
-        if (WHAT == kResolveSample && LEVEL == 1) {
-          st.L = st.prefix << 10;
-          st.prefix = 0;
-          st.k_rem = K;
-          // L = 0: the sample holds fewer than its share of non-zero entries (a mostly-zero row with K
-          // above its non-zeros), every entry would be a candidate.  The row goes to the general route
-          // before the filter pass instead of after it, unless that pass must still form g in the memory.
-          if (st.L == 0 && have_bins) st.mode = kModeGeneral;
-          // Likewise a row with so many entries at or above L that they cannot fit its share of the
-          // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
-          // sampled entries that stands for a full pool (0: no such check).
-          if (sample_cap && have_bins && acc + c[i] > sample_cap) st.mode = kModeGeneral;
-          if (st.mode == kModeGeneral) atomicAdd(&status[7], 1u);
-        }
-        if (LEVEL == 2) {
-          st.T = st.prefix;
-          st.q = st.T == 0 ? 0u : st.k_rem;
-          st.c_gt = K - st.k_rem;
-          st.count = st.c_gt + st.q;
-          if (st.mode == kModeCandidates && st.bracket) {
-            st.mode = kModeRangeEmit;  // the candidates do not hold every selected entry: a second pass over the waves' ranges emits
-          } else if (st.mode == kModeCandWide && st.bracket) {
-            st.mode = kModeGeneral;    // chunked pass: the row passes count and emit with this T
-            st.row_emit = 1;
-          }
-        }
-        rs[m] = st;
+  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
+  u32 total;
+  const u32 above = block_excl_scan<u32>(s, &total, lds);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) h[top - i] = 0;
+  u32 digit, inside, upto;
+  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) { rs[m].prefix = digit; rs[m].k_rem = inside; }
+  if (find_rank<PER>(c, above, st.q, top, &digit, &inside, &upto)) { rs[m].T = digit; rs[m].q = inside; }
+}
+
+// The sample, second level (key bits [19:10]): bins 0..1023 hold the keys under L's prefix, bins
+// 1024..2047 those under U's.  Ends with L = the 21-bit prefix of the sample key of rank `rank_lo`,
+// U = one past the 21-bit prefix of the sample key of the upper rank (both shifted back to key
+// units), so that at least rank_lo sampled keys are >= L and fewer than the upper rank are >= U.
+// `have_bins` is 0 when the filter pass is the chunked one (with a memory): that pass must run over
+// every row to form g, so no row leaves the candidate route before it.
+__global__ __launch_bounds__(kBlock) void k_resolve_sample1(RowState* rs, u32* hist, u32 K, u32 rank_lo, u32 have_bins, u32 sample_cap,
+                                                            u32* status) {
+  constexpr int PER = 1024 / kBlock;
+  const u32 m = blockIdx.x;
+  const RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 lds[kWaves];
+  u32* h = hist + (size_t)m * kHistBins;
+  const int top = 1023 - (int)threadIdx.x * PER;
+  u32 c[PER], d[PER];
+  u32 s = 0, sd = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; d[i] = h[1024 + top - i]; sd += d[i]; }
+  u32 total;
+  const u32 above = block_excl_scan<u32>(s, &total, lds);
+  const u32 above_d = block_excl_scan<u32>(sd, &total, lds);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { h[top - i] = 0; h[1024 + top - i] = 0; }
+  u32 digit, inside, upto;
+  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) {
+    const u32 L = ((st.prefix << 10) | digit) << 10;
+    u32 mode = kModeCandidates;
+    // L = 0: the sample holds fewer than its share of non-zero entries (a mostly-zero row with K
+    // above its non-zeros), every entry would be a candidate.  The row goes to the general route
+    // before the filter pass instead of after it, unless that pass must still form g in the memory.
+    if (L == 0 && have_bins) mode = kModeGeneral;
+    // Likewise a row with so many entries at or above L that they cannot fit its share of the
+    // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
+    // sampled entries that stands for a full pool (0: no such check).
+    if (sample_cap && have_bins && (rank_lo - st.k_rem) + upto > sample_cap) mode = kModeGeneral;
+    if (mode == kModeGeneral) atomicAdd(&status[7], 1u);
+    rs[m].L = L;
+    rs[m].mode = mode;
+    rs[m].prefix = 0;
+    rs[m].k_rem = K;
+  }
+  if (find_rank<PER>(d, above_d, st.q, top, &digit, &inside, &upto)) {
+    const u32 p = (st.T << 10) | digit;  // below 2^21
+    rs[m].U = (p + 1u) << 10;            // at most 2^31 = kNoUpper
+    rs[m].T = 0;
+    rs[m].q = 0;
+  }
+}
+
+// After the filter pass: does the candidate route stand, and where does the radix select start.
+// The filter pass histogrammed the bracket's records into 2048 bins of (key - L) >> 10, the last one
+// open-ended (a pass in chunks fills no bins: `have_bins` 0).  With n_sure = candidates outside the
+// bracket (all of them selected), the K-th key overall is the (K - n_sure)-th of the bracket.
+__global__ __launch_bounds__(kBlock) void k_resolve_filter(RowState* rs, u32* hist, u32 K, u32 have_bins) {
+  constexpr int PER = kHistBins / kBlock;
+  const u32 m = blockIdx.x;
+  RowState st = rs[m];
+  if (st.mode != kModeCandidates) return;
+  __shared__ u32 lds[kWaves];
+  __shared__ u32 verdict;
+  u32* h = hist + (size_t)m * kHistBins;
+  const int top = kHistBins - 1 - (int)threadIdx.x * PER;
+  u32 c[PER];
+  u32 s = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
+  u32 total;
+  const u32 above = block_excl_scan<u32>(s, &total, lds);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) h[top - i] = 0;
+  if (!have_bins) { st.n_cand = st.n_alloc; st.n_brk = st.n_alloc_b; }  // a pass in chunks: what its blocks reserved
+  const u32 n_sure = st.n_cand - st.n_brk;
+  const u32 k = K >= n_sure ? K - n_sure : 0u;
+  // The route stands only if no wave ran out of room, no more than K entries were taken for sure and
+  // the K-th largest key is among the bracket's records (or is the smallest sure one: k = 0).
+  if (threadIdx.x == 0) {
+    const bool usable = !st.overflow && n_sure <= K && st.n_brk >= k && (!have_bins || total == st.n_brk);
+    // 3: every selected entry is a sure one; 2: the bins place the K-th key; 1: it sits in the open top bin
+    // (or there are no bins): the radix select starts over, among the records; 0: general route
+    verdict = !usable ? 0u : (k == 0 ? 3u : ((have_bins && c[0] < k) ? 2u : 1u));
+  }
+  __syncthreads();
+  const u32 v = verdict;
+  if (v != 2u) {
+    if (threadIdx.x == 0) {
+      st.prefix = 0;
+      if (v == 0u) { st.mode = kModeGeneral; st.k_rem = K; }
+      if (v == 1u) { st.mode = kModeCandWide; st.k_rem = k; }
+      if (v == 3u) {  // the threshold is the bracket's upper end: nothing inside the bracket is selected
+        st.mode = kModeCandDone;
+        st.T = st.U - 1u;
+        st.q = 0;
+        st.c_gt = K;
+        st.count = K;
       }
-      acc += c[i];
+      rs[m] = st;
     }
+    return;
+  }
+  u32 digit, inside, upto;
+  if (find_rank<PER>(c, above, k, top, &digit, &inside, &upto)) {
+    st.prefix = (st.L >> 10) + digit;
+    st.k_rem = inside;
+    rs[m] = st;
   }
 }
 
@@ -491,22 +631,23 @@ __host__ __device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
 u64 sample_unit_position(u32 u, u64 stride) { return sample_unit_start(u, stride); }
 
 // Histogram of one radix level over the sample of each row (gathered straight from the row).
+// Level 0: key bits [30:20] into 2048 bins.  Level 1: key bits [19:10] of the keys under L's prefix
+// into bins 0..1023 and of the keys under U's prefix into bins 1024..2047.
 // With a memory (`err` non-NULL) the sampled value is g~ + eta * e.
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict__ grads, const float* __restrict__ err, float eta, u64 N,
                                                         const RowState* __restrict__ rs, u32* __restrict__ hist, u32 n_units,
                                                         u64 unit_stride) {
-  constexpr int NB = 1 << digit_bits(LEVEL);
-  constexpr int SH = digit_shift(LEVEL);
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
-  __shared__ u32 h[NB];
-  for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
+  __shared__ u32 h[kHistBins];
+  for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
   const u32* erow = err ? reinterpret_cast<const u32*>(err + (size_t)m * N) : nullptr;
   const u32 n_samples = n_units * kSampleUnit;
+  const bool upper = st.q != 0;  // a rank is sought for U as well
 #pragma unroll 4
   for (u32 i = blockIdx.x * kSamplePerBlock + threadIdx.x; i < (blockIdx.x + 1) * kSamplePerBlock && i < n_samples; i += kBlock) {
     const u32 u = i / kSampleUnit, e = i % kSampleUnit;
@@ -514,29 +655,38 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
     u32 bits = row[pos];
     if (erow) bits = compensate_bits(bits, erow[pos], eta);
     const u32 key = bits & 0x7FFFFFFFu;
-    if (LEVEL == 0 || (key >> (SH + digit_bits(LEVEL))) == st.prefix) atomicAdd(&h[(key >> SH) & (NB - 1)], 1u);
+    if (LEVEL == 0) {
+      atomicAdd(&h[key >> 20], 1u);
+    } else {
+      const u32 d = (key >> 10) & 1023u;
+      if ((key >> 20) == st.prefix) atomicAdd(&h[d], 1u);
+      if (upper && (key >> 20) == st.T) atomicAdd(&h[1024u + d], 1u);
+    }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < NB; i += kBlock) {
+  for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
     if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
   }
 }
 
-// The one pass over the gradients: every entry with key >= L becomes a candidate (index, bits).
+// The one pass over the gradients.  Every entry with key >= L is a candidate: its message word
+// (n << 1) | (g < 0) is kept; if its key is below U it also leaves a bracket record (its position
+// among the words of its segment, its fp32 bits).
 // Waves work independently (no block barrier inside the loop): a wave owns a contiguous run of
 // wave tiles (1024 entries each) and appends its candidates, in ascending index, to slabs of the
-// row's candidate pool.  What a wave leaves behind is its SEGMENT LIST: up to kChain pairs
-// (first slot, count), written once when the wave ends.  Waves in order, and each wave's segments
-// in order, list the row's candidates in ascending index; the kernels after the pass walk them
-// that way, one wave per list.  The block also histograms (key - L) >> 10 into 2048 bins, the
-// last of which is open-ended.
+// row's pools.  What a wave leaves behind is its SEGMENT LIST: up to kChain segments (first word
+// slot, words; first record slot, records), written once when the wave ends.  Waves in order, and
+// each wave's segments in order, list the row's candidates in ascending index; the kernels after
+// the pass walk them that way, one wave per list.  The block also histograms (key - L) >> 10 of the
+// bracket's records into 2048 bins, the last of which is open-ended.
 //
-// Slabs.  Every wave starts with a slab of its own, assigned by position (no atomic), sized to
-// about twice the candidates a wave expects; only a wave that fills it (skewed rows) reserves
-// another, twice as large each time, with a returning atomic on the row's counter.  A wave that
-// would need more than kChain segments (more than a hundred times its share) marks the row for
-// the general route.  Those atomics are what must stay rare:
+// Slabs.  A slab of n word slots comes with n >> brk_shift record slots (record slot = word slot >>
+// brk_shift, so one reservation serves both).  Every wave starts with a slab of its own, assigned by
+// position (no atomic), sized to about twice the candidates a wave expects; only a wave that fills
+// it (skewed rows) reserves another, twice as large each time, with a returning atomic on the row's
+// counter.  A wave that would need more than kChain segments (more than a hundred times its share)
+// marks the row for the general route.  Those atomics are what must stay rare:
 // all waves of a row hit ONE address, a few thousand of them per millisecond queue up behind each
 // other, and a wave waiting for its atomic also waits for its prefetched tile (measured with
 // 256-entry slabs reserved on demand: 26 000 atomics cost 0.4 ms of a 3.2 ms pass).
@@ -544,64 +694,79 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
 // Stores are rare and non-temporal: on this memory system ANY store traffic mixed into the read
 // stream costs several per cent of read bandwidth, whatever its volume (measured: one 8-byte store
 // per 4 KB read, or one 512-byte store per 256 KB read, both cost 9 %; non-temporal stores issued
-// every 2 MB read cost 2.5 %).  So candidates are staged in LDS and written about nine hundred at a
-// time, and nothing else is stored per tile.
-constexpr int kStage = 1024;       // staged candidates per wave
+// every 2 MB read cost 2.5 %).  So candidates are staged in LDS, as (index, bits), and leave it about
+// nine hundred at a time; only then is a candidate turned into its word and, inside the bracket,
+// its record, binned and tested for NaN: a candidate per lane instead of a lane or two at a time
+// under the per-tile code's branches.
+constexpr int kStage = 1024;       // staged candidates per wave (a tile never holds more)
 constexpr int kStageFlush = 896;   // flush once this many are staged
 
 struct FilterWave {
-  u32 cur, end, total;  // slab cursor, slab end, candidates so far (wave-uniform)
-  u32 fill;             // candidates staged in LDS; they belong to out[cur - fill, cur)
-  u32 seg_base, n_seg;  // first slot of the segment being filled; segments already closed
-  u64* segs;            // the wave's segment list in global memory, kChain entries
-  u32 sure;  // bracket: entries at or above the bracket's upper end seen by this wave
+  u32 cur, end, total;  // word slab cursor, slab end, candidates so far (wave-uniform)
+  u32 fill;             // candidates staged in LDS; they belong to word slots [cur - fill, cur)
+  u32 seg_base, n_seg;  // first word slot of the segment being filled; segments already closed
+  u32 nb, nb_total;     // bracket records written for the segment being filled / by the wave so far
+  u32 pend;             // upper bound on the records the staged candidates will leave
+  u32 brk_cap;          // bracket records the segment being filled has room for
+  u64* segs;            // the wave's segment list in global memory, kChain entries: words ...
+  u64* segsb;           // ... and records
   bool overflow, nan;
 };
 
-// Ends the segment being filled: its (first slot, count) goes to the wave's list.
-__device__ __forceinline__ void close_segment(FilterWave& w, u32 lane) {
+// Ends the segment being filled: its runs go to the wave's list.
+__device__ __forceinline__ void close_segment(FilterWave& w, u32 lane, u32 brk_shift) {
   const u32 count = w.cur - w.seg_base;
   if (count == 0) return;  // wave-uniform
   if (w.n_seg < (u32)kChain) {
-    if (lane == 0) w.segs[w.n_seg] = ((u64)w.seg_base << 32) | count;
+    if (lane == 0) {
+      w.segs[w.n_seg] = ((u64)w.seg_base << 32) | count;
+      w.segsb[w.n_seg] = ((u64)(w.seg_base >> brk_shift) << 32) | w.nb;
+    }
     ++w.n_seg;
   } else {
     w.overflow = true;
   }
+  w.nb_total += w.nb;
+  w.nb = 0;
 }
 
-__device__ __forceinline__ void store_stream8(u64* p, u64 v) { __builtin_nontemporal_store(v, p); }
-
-// Writes the staged candidates to the wave's slab and enters them into the block's bins.  Binning
-// here, a candidate per lane, rather than where a candidate is found (a lane or two at a time under
-// its own branch) takes the bin arithmetic and the NaN test out of the per-tile code: a quarter of
-// the pass's instructions once a tile holds ten candidates (K = N / 100).
-__device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, uint2* __restrict__ out, u32 lane, u32 L, u32* h) {
+// Turns the staged candidates into words and records, written to the wave's slab, and enters the
+// records into the block's bins.
+__device__ __forceinline__ void flush_stage(FilterWave& w, const u64* stage, u32* __restrict__ out, uint2* __restrict__ outb, u32 lane,
+                                            u32 L, u32 U, u32 brk_shift, u32* h) {
   __builtin_amdgcn_wave_barrier();
-  u64* dst = reinterpret_cast<u64*>(out) + (w.cur - w.fill);
+  const u32 first = w.cur - w.fill;
+  u32* dst = out + first;
+  u64* dstb = reinterpret_cast<u64*>(outb) + (w.seg_base >> brk_shift);
   const u32 Lq = L >> 10;
-  for (u32 i = lane; i < w.fill; i += 64) {
-    const u64 cd = stage[i];
-    store_stream8(dst + i, cd);
-    const u32 key = (u32)(cd >> 32) & 0x7FFFFFFFu;
-    w.nan |= key > 0x7F800000u;
-    const u32 bin = (key >> 10) - Lq;
-    // the open top bin takes most candidates of a heavy-tailed row: one add per wave for those
-    const bool top = bin >= (u32)kHistBins - 1;
-    const u64 tm = ballot(top);
-    if (!top) atomicAdd(&h[bin], 1u);
-    else if (ballot_rank(tm) == 0) atomicAdd(&h[kHistBins - 1], (u32)__popcll(tm));
+  for (u32 i0 = 0; i0 < w.fill; i0 += 64) {  // wave-uniform
+    const u32 i = i0 + lane;
+    const bool ok = i < w.fill;
+    const u64 cd = ok ? stage[i] : 0ull;
+    const u32 bits = (u32)(cd >> 32), key = bits & 0x7FFFFFFFu;
+    if (ok) store_stream4(dst + i, ((u32)cd << 1) | (bits >> 31));
+    w.nan |= ok && key > 0x7F800000u;
+    const bool brk = ok && key < U;
+    const u64 bm = ballot(brk);
+    if (brk) {
+      store_stream8(dstb + w.nb + ballot_rank(bm), ((u64)bits << 32) | (first + i - w.seg_base));
+      const u32 bin = (key >> 10) - Lq;
+      // the open top bin takes most records of a row whose bracket is far wider than the bins: one add per wave for those
+      const bool top = bin >= (u32)kHistBins - 1;
+      const u64 tm = ballot(top);
+      if (!top) atomicAdd(&h[bin], 1u);
+      else if (ballot_rank(tm) == 0) atomicAdd(&h[kHistBins - 1], (u32)__popcll(tm));
+    }
+    w.nb += (u32)__popcll(bm);
   }
   __builtin_amdgcn_wave_barrier();
   w.fill = 0;
+  w.pend = 0;
 }
 
-// Writes the candidates of one tile, in ascending index, to the LDS stage or (DIRECT) to memory.
-template <bool DIRECT, bool BINS, bool NANS>
+// Writes the candidates of one tile, in ascending index, to the LDS stage.
 __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (&pr)[kLoads * 4], const u64 (&mk)[kLoads * 4],
-                                                 const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u32 L, u32* h,
-                                                 uint2* __restrict__ dst_global, u64* dst_stage, bool& nan) {
-  const u32 Lq = L >> 10;
+                                                 const u32 (&tot)[kLoads], u32 first_slot, u64 v0, u64* dst_stage) {
   u32 run = first_slot;
 #pragma unroll
   for (int j = 0; j < kLoads; ++j) {
@@ -612,15 +777,8 @@ __device__ __forceinline__ void place_candidates(const TileRegs& r, const bool (
     for (int e = 0; e < 4; ++e) {
       const int i = 4 * j + e;
       if (pr[i]) {
-        const u32 key = r.b[i] & 0x7FFFFFFFu;
-        const uint2 cd = make_uint2((u32)(v0 + (u64)j * 256 + e), r.b[i]);
-        if (DIRECT) dst_global[o] = cd; else dst_stage[o] = ((u64)cd.y << 32) | cd.x;
+        dst_stage[o] = ((u64)r.b[i] << 32) | (u32)(v0 + (u64)j * 256 + e);
         ++o;
-        if (NANS) nan |= key > 0x7F800000u;
-        if (BINS) {
-          const u32 bin = (key >> 10) - Lq;
-          atomicAdd(&h[bin < (u32)kHistBins - 1 ? bin : (u32)kHistBins - 1], 1u);
-        }
       }
     }
     run += tot[j];
@@ -664,13 +822,12 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
   }
 }
 
-template <bool INTERIOR, bool BRACKET>
-__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32* h, u64* stage, u32* n_alloc,
-                                            uint2* __restrict__ out, u32 cand_stride, u32 slab, FilterWave& w) {
+template <bool INTERIOR>
+__device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32* h, u64* stage, u32* n_alloc,
+                                            u32* __restrict__ out, uint2* __restrict__ outb, u32 cand_stride, u32 slab, u32 brk_shift,
+                                            FilterWave& w) {
   // One compare per entry; its lane mask doubles as the wave ballot, so counting and ranking the
-  // candidates below is scalar work plus a few mbcnt.  With a bracket an entry at or above its upper
-  // end U (the start of the open top bin) is only counted: it is selected whatever the threshold.
-  const u32 U = L + ((u32)(kHistBins - 1) << 10);
+  // candidates below is scalar work plus a few mbcnt.
   bool pr[kLoads * 4];
   u64 mk[kLoads * 4];
   u64 any = 0;
@@ -679,12 +836,6 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     const u32 key = r.b[i] & 0x7FFFFFFFu;
     pr[i] = key >= L;
     if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
-    if (BRACKET) {
-      const bool top = pr[i] && key >= U;
-      w.sure += (u32)__popcll(ballot(top));
-      w.nan |= top && key > 0x7F800000u;
-      pr[i] = pr[i] && !top;
-    }
     mk[i] = ballot(pr[i]);
     any |= mk[i];
   }
@@ -696,18 +847,33 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     total += tot[j];
   }
   if (w.overflow) return;
-  if (w.cur + total > w.end) {
-    flush_stage(w, stage, out, lane, L, h);  // staged candidates belong to the old slab
-    close_segment(w, lane);
+  // Room for the tile's words and for its records.  Which candidates lie inside the bracket is only
+  // looked at when they leave the stage; until the records could run out every candidate counts as one.
+  bool full = w.cur + total > w.end;
+  u32 recs_here = total;
+  if (!full && w.nb + w.pend + total > w.brk_cap) {
+    recs_here = 0;  // the tile's records, counted
+#pragma unroll
+    for (int i = 0; i < kLoads * 4; ++i) recs_here += (u32)__popcll(ballot(pr[i] && (r.b[i] & 0x7FFFFFFFu) < U));
+    if (w.nb + w.pend + recs_here > w.brk_cap) {
+      flush_stage(w, stage, out, outb, lane, L, U, brk_shift, h);  // now the segment's record count is exact
+      full = w.nb + recs_here > w.brk_cap;
+    }
+  }
+  if (full) {
+    flush_stage(w, stage, out, outb, lane, L, U, brk_shift, h);  // staged candidates belong to the old slab
+    close_segment(w, lane, brk_shift);
     // the next slab: twice the previous one (slab, slab, 2 slab, 4 slab, ...), and at least what the tile needs
     const u32 grown = slab << (w.n_seg > 1 ? w.n_seg - 1 : 0);
-    const u32 fit = (total + slab - 1) & ~(slab - 1);  // slab is a power of two
+    const u32 room = total > (recs_here << brk_shift) ? total : (recs_here << brk_shift);
+    const u32 fit = (room + slab - 1) / slab * slab;
     const u32 need = grown > fit ? grown : fit;
     u32 b = 0;
     if (lane == 0) b = atomicAdd(n_alloc, need);
     w.cur = __builtin_amdgcn_readfirstlane(b);
     w.end = w.cur + need;
     w.seg_base = w.cur;
+    w.brk_cap = need >> brk_shift;
     if (w.end > cand_stride || w.end < w.cur) {  // pool exhausted (or the counter wrapped): nothing more is written
       w.overflow = true;
       w.end = w.cur;
@@ -715,47 +881,47 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
     }
   }
   if (w.overflow) return;
-  if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, lane, L, h);
+  if (w.fill + total > (u32)kStage) flush_stage(w, stage, out, outb, lane, L, U, brk_shift, h);
   const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-  if (total > (u32)kStage) {  // a tile too dense to stage writes straight to memory (stage is empty here)
-    place_candidates<true, true, true>(r, pr, mk, tot, w.cur, v0, L, h, out, stage, w.nan);
-  } else {
-    place_candidates<false, false, false>(r, pr, mk, tot, w.fill, v0, L, h, out, stage, w.nan);
-    w.fill += total;
-  }
+  place_candidates(r, pr, mk, tot, w.fill, v0, stage);
+  w.fill += total;
+  w.pend += recs_here;
   w.cur += total;
   w.total += total;
-  if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, lane, L, h);
+  if (w.fill >= (u32)kStageFlush) flush_stage(w, stage, out, outb, lane, L, U, brk_shift, h);
 }
 
 // The filter pass over rows that are read only: persistent waves, each with a range of its own.
-// BRACKET (dense K, where keeping every entry at or above L would need a pool as large as the row):
-// only the entries inside the 2047 closed bins above L are kept, the ones above are counted.
-template <bool BRACKET>
-__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist, uint2* __restrict__ cand,
-                                                   u32 cand_stride, u64* __restrict__ wave_seg, u32* __restrict__ wave_nseg,
-                                                   u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
-                                                   u32* __restrict__ status, u32* __restrict__ wave_sure) {
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist,
+                                                   u32* __restrict__ cand, uint2* __restrict__ recs, u32 cand_stride, u32 brk_stride,
+                                                   u32 brk_shift, u64* __restrict__ wave_seg, u64* __restrict__ wave_segb,
+                                                   u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
+                                                   u32* __restrict__ status) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;
   __shared__ u32 h[kHistBins];
   __shared__ u64 stage_all[kWaves][kStage];
+  __shared__ u32 block_cand, block_brk;
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
+  if (threadIdx.x == 0) { block_cand = 0; block_brk = 0; }
   __syncthreads();
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
   const u64 vend = N + a;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
-  uint2* out = cand + (size_t)m * cand_stride;
+  u32* out = cand + (size_t)m * cand_stride;
+  uint2* outb = recs + (size_t)m * brk_stride;
   u64* stage = stage_all[wave];
   const u32 g = blockIdx.x * kWaves + wave;  // the wave's position among the waves of its row
   FilterWave w{};
   w.cur = g * slab;  // the wave's first slab; rs[m].n_alloc starts past all of them
   w.end = w.cur + slab;
   w.seg_base = w.cur;
+  w.brk_cap = slab >> brk_shift;
   w.segs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
+  w.segsb = wave_segb + ((size_t)m * wave_stride + g) * kChain;
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
   // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
@@ -773,24 +939,27 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
       else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
-    if (tile >= first && tile < last) filter_tile<true, BRACKET>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
-    else filter_tile<false, BRACKET>(r, a, tile, lane, st.L, h, stage, &rs[m].n_alloc, out, cand_stride, slab, w);
+    if (tile >= first && tile < last)
+      filter_tile<true>(r, a, tile, lane, st.L, st.U, h, stage, &rs[m].n_alloc, out, outb, cand_stride, slab, brk_shift, w);
+    else
+      filter_tile<false>(r, a, tile, lane, st.L, st.U, h, stage, &rs[m].n_alloc, out, outb, cand_stride, slab, brk_shift, w);
   }
   if (!w.overflow) {
-    flush_stage(w, stage, out, lane, st.L, h);
-    close_segment(w, lane);
+    flush_stage(w, stage, out, outb, lane, st.L, st.U, brk_shift, h);
+    close_segment(w, lane, brk_shift);
   }
   if (lane == 0) {
     wave_nseg[(size_t)m * wave_stride + g] = w.overflow ? 0u : w.n_seg;
-    if (w.total) atomicAdd(&rs[m].n_cand, w.total);
-    if (BRACKET) {
-      wave_sure[(size_t)m * wave_stride + g] = w.sure;
-      if (w.sure) atomicAdd(&rs[m].n_sure, w.sure);
-    }
+    if (w.total) atomicAdd(&block_cand, w.total);
+    if (w.nb_total) atomicAdd(&block_brk, w.nb_total);
     if (w.overflow) rs[m].overflow = 1;
   }
   if (w.nan) status[0] = 1;
   __syncthreads();
+  // one addition per block for both counts: every wave of the row ends at about the same time, and
+  // additions to one address complete one after the other
+  if (threadIdx.x == 0 && block_cand)
+    atomicAdd(reinterpret_cast<unsigned long long*>(&rs[m].n_cand), ((unsigned long long)block_brk << 32) | block_cand);
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
     if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
@@ -818,75 +987,85 @@ __global__ __launch_bounds__(kBlock) void k_plain_read(const float* __restrict__
   if (seen == 0x7FFFFFFFu) *sink = seen;  // never: a wave sees at most 2^22 entries per launch shape used here
 }
 
+constexpr int kChunkWavesPerSimd = 6;  // see the measurements in the design notes: six waves per SIMD beat the five the kernel takes by itself
+
 // ---- the filter pass with a memory, in chunks --------------------------------------------------
 // The row is g = grads + eta * err, and g is written over err as it is filtered (grads and err rows
 // start at the same 16-byte phase, checked by the caller).  One block per chunk of 8192 consecutive
 // entries, launched in index order; a wave holds its kChunkTiles consecutive wave tiles in
-// registers.  The block counts its candidates, reserves exactly that many slots of the row's pool
-// with one atomic, and its waves write them there in ascending index.  Chunk c leaves the segment
-// (first slot, count) as entry c of the row's segment table, so that list g of the table (kChain
-// entries) is chunks g*kChain .. g*kChain + kChain - 1 in order.  No bins are filled: the radix
-// select then runs over the candidates at every level.
+// registers.  The block counts its candidates and its bracket records, reserves exactly that many
+// slots of the row's two pools with one atomic each, and its waves write them there in ascending
+// index.  Chunk c leaves its two runs as entry c of the row's segment tables, so that list g of the
+// tables (kChain entries) is chunks g*kChain .. g*kChain + kChain - 1 in order.  No bins are filled:
+// the radix select then runs over the records at every level.
 //
 // Why not persistent waves as in k_filter: this pass reads two rows and writes one, and blocks
 // dispatched in index order keep the running blocks inside a compact window of the three streams,
 // which the memory system rewards (a bare read-modify-write stream: 5.9 TB/s against 5.2 TB/s for
-// waves that each stream a far-apart range).  A read-only pass gains nothing from it, and the one
-// returning atomic per block, harmless next to 96 KB of traffic, would bound it: atomics on one
+// waves that each stream a far-apart range).  A read-only pass gains nothing from it, and the
+// returning atomics per block, harmless next to 96 KB of traffic, would bound it: atomics on one
 // counter (or on the neighbouring counters of a few rows) complete at about 86 per microsecond.
-// BRACKET: entries at or above U are counted in `sure` and not kept.
-template <bool INTERIOR, bool BRACKET>
-__device__ __forceinline__ u32 count_candidates(const TileRegs& r, u32 L, u32 U, u32& sure, bool& nan) {
-  u32 total = 0;
+template <bool INTERIOR>
+__device__ __forceinline__ void count_chunk_tile(const TileRegs& r, u32 L, u32 U, u32& cand, u32& brk, bool& nan) {
 #pragma unroll
   for (int i = 0; i < kLoads * 4; ++i) {
     const u32 key = r.b[i] & 0x7FFFFFFFu;
     bool p = key >= L;
     if (!INTERIOR) p = p && ((r.valid >> i) & 1u);
-    if (BRACKET) {
-      const bool top = p && key >= U;
-      sure += (u32)__popcll(ballot(top));
-      nan |= top && key > 0x7F800000u;
-      p = p && !top;
-    }
-    total += (u32)__popcll(ballot(p));
+    nan |= p && key > 0x7F800000u;
+    cand += (u32)__popcll(ballot(p));
+    brk += (u32)__popcll(ballot(p && key < U));
   }
-  return total;
 }
 
-template <bool INTERIOR, bool BRACKET>
-__device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32 first_slot,
-                                                 uint2* __restrict__ out, bool& nan) {
-  bool pr[kLoads * 4];
-  u64 mk[kLoads * 4];
-#pragma unroll
-  for (int i = 0; i < kLoads * 4; ++i) {
-    const u32 key = r.b[i] & 0x7FFFFFFFu;
-    pr[i] = key >= L && (!BRACKET || key < U);
-    if (!INTERIOR) pr[i] = pr[i] && ((r.valid >> i) & 1u);
-    mk[i] = ballot(pr[i]);
-  }
-  u32 tot[kLoads];
-#pragma unroll
-  for (int j = 0; j < kLoads; ++j)
-    tot[j] = (u32)__popcll(mk[4 * j]) + (u32)__popcll(mk[4 * j + 1]) + (u32)__popcll(mk[4 * j + 2]) + (u32)__popcll(mk[4 * j + 3]);
+// Writes the words and the records of one tile at their exact slots.  `first_word`, `first_rec`: the
+// tile's first slots; `seg_word`: the first word slot of the chunk (records hold positions relative to it).
+template <bool INTERIOR>
+__device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32 first_word, u32 first_rec,
+                                                 u32 seg_word, u32* __restrict__ out, uint2* __restrict__ outb) {
   const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-  place_candidates<true, false, true>(r, pr, mk, tot, first_slot, v0, L, nullptr, out, nullptr, nan);
+  u32 run = first_word, runb = first_rec;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    bool pr[4], br[4];
+    u64 mk[4], bk[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const u32 key = r.b[4 * j + e] & 0x7FFFFFFFu;
+      pr[e] = key >= L;
+      if (!INTERIOR) pr[e] = pr[e] && ((r.valid >> (4 * j + e)) & 1u);
+      br[e] = pr[e] && key < U;
+      mk[e] = ballot(pr[e]);
+      bk[e] = ballot(br[e]);
+    }
+    if ((mk[0] | mk[1] | mk[2] | mk[3]) == 0) continue;  // wave-uniform
+    u32 o = run + ballot_rank(mk[0]) + ballot_rank(mk[1]) + ballot_rank(mk[2]) + ballot_rank(mk[3]);
+    u32 ob = runb + ballot_rank(bk[0]) + ballot_rank(bk[1]) + ballot_rank(bk[2]) + ballot_rank(bk[3]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (pr[e]) {
+        const u32 bits = r.b[4 * j + e];
+        out[o] = ((u32)(v0 + (u64)j * 256 + e) << 1) | (bits >> 31);
+        if (br[e]) { outb[ob] = make_uint2(o - seg_word, bits); ++ob; }
+        ++o;
+      }
+    }
+    run += (u32)__popcll(mk[0]) + (u32)__popcll(mk[1]) + (u32)__popcll(mk[2]) + (u32)__popcll(mk[3]);
+    runb += (u32)__popcll(bk[0]) + (u32)__popcll(bk[1]) + (u32)__popcll(bk[2]) + (u32)__popcll(bk[3]);
+  }
 }
 
-// Six waves per SIMD (80 registers, four of them spilled) measured 2 % to 6 % faster than the five the
-// kernel would take by itself; seven lose again, and so do eight waves of one tile each.
-template <bool BRACKET>
-__global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
-                                                          RowState* __restrict__ rs, uint2* __restrict__ cand, u32 cand_stride,
-                                                          u64* __restrict__ list_seg, u32* __restrict__ list_nseg, u32 list_stride,
+__global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
+                                                          RowState* __restrict__ rs, u32* __restrict__ cand, uint2* __restrict__ recs,
+                                                          u32 cand_stride, u32 brk_stride, u64* __restrict__ list_seg,
+                                                          u64* __restrict__ list_segb, u32* __restrict__ list_nseg, u32 list_stride,
                                                           u32 n_chunks, u32* __restrict__ status) {
   static_assert(kChunkTiles == 2, "the two wave tiles of a chunk are held in named registers");
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode != kModeCandidates) return;  // block-uniform
-  __shared__ u32 wsum[kWaves], wsure[kWaves];
-  __shared__ u32 sbase;
+  __shared__ u32 wsum[kWaves], wsumb[kWaves];
+  __shared__ u32 sbase, sbaseb;
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
@@ -898,88 +1077,88 @@ __global__ __launch_bounds__(kBlock, 6) void k_filter_chunks(const float* __rest
   const u32 first = a ? 1u : 0u;              // tiles from here on do not start before the row
   const u32 last = (u32)(vend / kWaveTile);   // tiles below this index end inside the row
   const bool in0 = t0 >= first && t0 < last, in1 = t1 >= first && t1 < last;  // wave-uniform
-  TileRegs r0, r1, e0, e1;
-  if (in0) { load_filter_tile<true>(rowv, a, vend, t0, lane, r0); load_filter_tile<true>(errv, a, vend, t0, lane, e0); }
-  else { load_filter_tile<false>(rowv, a, vend, t0, lane, r0); load_filter_tile<false>(errv, a, vend, t0, lane, e0); }
-  if (in1) { load_filter_tile<true>(rowv, a, vend, t1, lane, r1); load_filter_tile<true>(errv, a, vend, t1, lane, e1); }
-  else { load_filter_tile<false>(rowv, a, vend, t1, lane, r1); load_filter_tile<false>(errv, a, vend, t1, lane, e1); }
-  // g = grads + eta * err goes over err right away: the stores are under way while the candidates are counted
+  TileRegs r0, r1;
+  {
+    TileRegs e0, e1;
+    if (in0) { load_filter_tile<true>(rowv, a, vend, t0, lane, r0); load_filter_tile<true>(errv, a, vend, t0, lane, e0); }
+    else { load_filter_tile<false>(rowv, a, vend, t0, lane, r0); load_filter_tile<false>(errv, a, vend, t0, lane, e0); }
+    if (in1) { load_filter_tile<true>(rowv, a, vend, t1, lane, r1); load_filter_tile<true>(errv, a, vend, t1, lane, e1); }
+    else { load_filter_tile<false>(rowv, a, vend, t1, lane, r1); load_filter_tile<false>(errv, a, vend, t1, lane, e1); }
+    // g = grads + eta * err goes over err right away: the stores are under way while the candidates are counted
 #pragma unroll
-  for (int i = 0; i < kLoads * 4; ++i) r0.b[i] = compensate_bits(r0.b[i], e0.b[i], eta);
-  if (in0) store_filter_tile<true>(errv, t0, lane, r0); else store_filter_tile<false>(errv, t0, lane, r0);
+    for (int i = 0; i < kLoads * 4; ++i) r0.b[i] = compensate_bits(r0.b[i], e0.b[i], eta);
+    if (in0) store_filter_tile<true>(errv, t0, lane, r0); else store_filter_tile<false>(errv, t0, lane, r0);
 #pragma unroll
-  for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
-  if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
-  // dense K: the same bracket as the persistent pass keeps (its 2047 closed bins), though no bins are filled here
-  const u32 U = st.L + ((u32)(kHistBins - 1) << 10);
-  u32 sure = 0;
-  bool nan = false;
-  const u32 c0 = in0 ? count_candidates<true, BRACKET>(r0, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r0, st.L, U, sure, nan);
-  const u32 c1 = in1 ? count_candidates<true, BRACKET>(r1, st.L, U, sure, nan) : count_candidates<false, BRACKET>(r1, st.L, U, sure, nan);
-  if (lane == 0) {
-    wsum[wave] = c0 + c1;
-    if (BRACKET) wsure[wave] = sure;
+    for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
+    if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
   }
+  u32 c0 = 0, b0 = 0, c1 = 0, b1 = 0;
+  bool nan = false;
+  if (in0) count_chunk_tile<true>(r0, st.L, st.U, c0, b0, nan); else count_chunk_tile<false>(r0, st.L, st.U, c0, b0, nan);
+  if (in1) count_chunk_tile<true>(r1, st.L, st.U, c1, b1, nan); else count_chunk_tile<false>(r1, st.L, st.U, c1, b1, nan);
+  if (lane == 0) { wsum[wave] = c0 + c1; wsumb[wave] = b0 + b1; }
   if (nan) status[0] = 1;
   __syncthreads();
-  u32 before = 0, total = 0;
+  u32 before = 0, total = 0, beforeb = 0, totalb = 0;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
-    const u32 c = wsum[w];
-    if ((u32)w < wave) before += c;
+    const u32 c = wsum[w], b = wsumb[w];
+    if ((u32)w < wave) { before += c; beforeb += b; }
     total += c;
+    totalb += b;
   }
   if (threadIdx.x == 0) {
-    if (BRACKET) {
-      u32 block_sure = 0;
-      for (int w = 0; w < kWaves; ++w) block_sure += wsure[w];
-      if (block_sure) atomicAdd(&rs[m].n_sure, block_sure);
-    }
-    u32 base = 0;
+    u32 base = 0, baseb = 0;
     bool fits = true;
     if (total) {
       base = atomicAdd(&rs[m].n_alloc, total);
       fits = base + total <= cand_stride && base + total >= base;
+      if (totalb) {
+        baseb = atomicAdd(&rs[m].n_alloc_b, totalb);
+        fits = fits && baseb + totalb <= brk_stride && baseb + totalb >= baseb;
+      }
       if (!fits) rs[m].overflow = 1;
     }
     sbase = fits ? base : 0xFFFFFFFFu;
+    sbaseb = baseb;
     list_seg[(size_t)m * list_stride * kChain + chunk] = fits ? (((u64)base << 32) | total) : 0ull;
+    list_segb[(size_t)m * list_stride * kChain + chunk] = fits ? (((u64)baseb << 32) | totalb) : 0ull;
     if (chunk % kChain == 0) {
       const u32 left = n_chunks - chunk;
       list_nseg[(size_t)m * list_stride + chunk / kChain] = left < (u32)kChain ? left : (u32)kChain;
     }
   }
   __syncthreads();
-  const u32 base = sbase;
+  const u32 base = sbase, baseb = sbaseb;
   if (total == 0 || base == 0xFFFFFFFFu) return;
-  uint2* out = cand + (size_t)m * cand_stride;
+  u32* out = cand + (size_t)m * cand_stride;
+  uint2* outb = recs + (size_t)m * brk_stride;
   if (c0) {
-    if (in0) place_chunk_tile<true, BRACKET>(r0, a, t0, lane, st.L, U, base + before, out, nan);
-    else place_chunk_tile<false, BRACKET>(r0, a, t0, lane, st.L, U, base + before, out, nan);
+    if (in0) place_chunk_tile<true>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb);
+    else place_chunk_tile<false>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb);
   }
   if (c1) {
-    if (in1) place_chunk_tile<true, BRACKET>(r1, a, t1, lane, st.L, U, base + before + c0, out, nan);
-    else place_chunk_tile<false, BRACKET>(r1, a, t1, lane, st.L, U, base + before + c0, out, nan);
+    if (in1) place_chunk_tile<true>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb);
+    else place_chunk_tile<false>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb);
   }
-  if (nan) status[0] = 1;
 }
 
-// The kernels below walk the candidates of a row in ascending index (ListWalk): a wave per segment
-// list.
-// (eq << 32) | gt of each segment list against the final threshold; scanned afterwards.
-__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                       const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
-                                                       u32 wave_stride, u32 n_waves, u64* __restrict__ wave_sum,
-                                                       const u32* __restrict__ wave_sure) {
+// The kernels below walk the candidates of a row in ascending index: a wave per segment list.
+// Per list, against the final threshold: (records equal to T << 32) | (candidates that are selected
+// without being ties: the records above T and every candidate outside the bracket); scanned afterwards.
+__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ recs, u32 brk_stride,
+                                                       const u64* __restrict__ wave_seg, const u64* __restrict__ wave_segb,
+                                                       const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves,
+                                                       u64* __restrict__ wave_sum) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
   if (st.mode == kModeGeneral) return;
   const u32 lane = lane_id();
   for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
-    const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+    const RecordWalk lw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
     u32 gt = 0, eq = 0;
     u32 done = 0;
-    if (lw.single && (lw.slot[0] & 1u) == 0) {  // wave-uniform: two candidates per lane and load, 16 bytes
+    if (lw.single && (lw.slot[0] & 1u) == 0) {  // wave-uniform: two records per lane and load, 16 bytes
       const uint4* p4 = reinterpret_cast<const uint4*>(lw.pool + lw.slot[0]);
       const u32 pairs = lw.total >> 1;
       for (u32 i0 = lane; i0 < pairs; i0 += 64 * kWalk) {
@@ -1014,162 +1193,90 @@ __global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restric
     }
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
-    if (st.mode == kModeRangeEmit) gt += wave_sure[(size_t)m * wave_stride + g];  // above the bracket: all greater than T
+    gt += lw.words_total - lw.total;  // outside the bracket: all greater than T
     if (lane == 0) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
   }
 }
 
-// Emits the words of each segment list at its scanned offset, in ascending index, the tie quota
-// applied in index order.  With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
-__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const uint2* __restrict__ cand, u32 cand_stride,
-                                                      const u64* __restrict__ wave_seg, const u32* __restrict__ wave_nseg,
-                                                      u32 wave_stride, u32 n_waves, const u64* __restrict__ wave_sum, u64 K,
-                                                      u32* __restrict__ words, float* __restrict__ err, u64 N) {
+// Emits the words of each segment list at its scanned offset, in ascending index: the list's
+// candidate words minus the bracket's losers (records below T, and the ties beyond the quota, which
+// is applied in index order).  The losers of kDropRound candidates at a time are marked in an LDS bit
+// map by a walk over the records, then the words of the round are copied past the marks.
+// With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
+constexpr u32 kDropRound = 8192;
+__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const u32* __restrict__ cand, const uint2* __restrict__ recs,
+                                                      u32 cand_stride, u32 brk_stride, const u64* __restrict__ wave_seg,
+                                                      const u64* __restrict__ wave_segb, const u32* __restrict__ wave_nseg, u32 wave_stride,
+                                                      u32 n_waves, const u64* __restrict__ wave_sum, u64 K, u32* __restrict__ words,
+                                                      float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   const RowState st = rs[m];
-  if (st.mode == kModeGeneral || st.mode == kModeRangeEmit) return;
+  if (st.mode == kModeGeneral) return;
+  __shared__ u32 drop_all[kWaves][kDropRound / 32];
+  u32* drop = drop_all[threadIdx.x >> 6];
   const u32 lane = lane_id();
   float* erow = err ? err + (size_t)m * N : nullptr;
   u32* out = words + (size_t)m * K;
   for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
-    const ListWalk lw(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
-    if (lw.total == 0) continue;
+    const WordWalk ww(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
+    if (ww.total == 0) continue;
+    const RecordWalk rw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
     const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
     u32 eq_seen = (u32)(before >> 32);
     u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-    for (u32 i0 = 0; i0 < lw.total; i0 += 64 * kWalk) {  // wave-uniform trip count
-      // kWalk groups of 64 candidates are loaded together, then placed one group after the other
-      uint2 cds[kWalk];
+    u32 rec_next = 0;  // records before this one are dealt with
+    for (u32 a0 = 0; a0 < ww.total; a0 += kDropRound) {  // wave-uniform
+      const u32 a1 = a0 + kDropRound < ww.total ? a0 + kDropRound : ww.total;
+      for (u32 i = lane; i < kDropRound / 32; i += 64) drop[i] = 0;
+      wave_sync();
+      // the records of candidates a0 .. a1-1: they ascend, so these are the next ones, up to the first beyond a1
+      while (rec_next < rw.total) {  // wave-uniform
+        const u32 j = rec_next + lane;
+        const bool ok = j < rw.total;
+        const uint2 rec = ok ? rw.pool[rw.locate(j)] : make_uint2(0, 0);
+        u32 seg_first = ww.first[0];  // number, in the list, of the first candidate of the record's segment
 #pragma unroll
-      for (int u = 0; u < kWalk; ++u) {
-        const u32 j = i0 + (u32)u * 64u + lane;
-        cds[u] = j < lw.total ? lw.pool[lw.locate(j)] : make_uint2(0, 0);
+        for (int c = 1; c < kChain; ++c)
+          if (j >= rw.first[c] && rw.count[c]) seg_first = ww.first[c];
+        const u32 at = seg_first + rec.x;
+        const bool inside = ok && at < a1;
+        const u64 im = ballot(inside);
+        const u32 key = rec.y & 0x7FFFFFFFu;
+        const bool is_eq = inside && key == st.T;
+        const u64 eqm = ballot(is_eq);
+        const bool sel = inside && (key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q));
+        if (inside && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
+        eq_seen += (u32)__popcll(eqm);
+        const u32 n_in = (u32)__popcll(im);
+        rec_next += n_in;
+        if (n_in < 64u) break;  // the others belong to later rounds
       }
+      wave_sync();
+      for (u32 i0 = a0; i0 < a1; i0 += 64 * kWalk) {  // wave-uniform trip count
+        u32 wd[kWalk];
 #pragma unroll
-      for (int u = 0; u < kWalk; ++u) {
-        if (i0 + (u32)u * 64u >= lw.total) break;  // wave-uniform
-        const bool ok = i0 + (u32)u * 64u + lane < lw.total;
-        const uint2 cd = cds[u];
-        const u32 key = cd.y & 0x7FFFFFFFu;
-        const bool is_eq = ok && key == st.T;
-        const u64 eq_mask = ballot(is_eq);
-        const bool sel = ok && (key > st.T || (is_eq && eq_seen + ballot_rank(eq_mask) < st.q));
-        const u64 sel_mask = ballot(sel);
-        if (sel) {
-          const u32 pos = o + ballot_rank(sel_mask);
-          if (pos < K) {  // pos < K by construction
-            out[pos] = (cd.x << 1) | (cd.y >> 31);
-            if (erow) erow[cd.x] = 0.0f;
+        for (int u = 0; u < kWalk; ++u) {
+          const u32 j = i0 + (u32)u * 64u + lane;
+          wd[u] = j < a1 ? ww.pool[ww.locate(j)] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+          if (i0 + (u32)u * 64u >= a1) break;  // wave-uniform
+          const u32 j = i0 + (u32)u * 64u + lane;
+          const bool sel = j < a1 && !((drop[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u);
+          const u64 sel_mask = ballot(sel);
+          if (sel) {
+            const u32 pos = o + ballot_rank(sel_mask);
+            if (pos < K) {  // pos < K by construction
+              out[pos] = wd[u];
+              if (erow) erow[wd[u] >> 1] = 0.0f;
+            }
           }
+          o += (u32)__popcll(sel_mask);
         }
-        o += (u32)__popcll(sel_mask);
-        eq_seen += (u32)__popcll(eq_mask);
       }
+      wave_sync();  // the marks are cleared for the next round
     }
-  }
-}
-
-// ---- dense K: the words from a second pass over the waves' ranges -------------------------------
-// The filter pass with a bracket kept only the candidates inside it, so the words cannot come from
-// the pool.  Every wave walks the same run of wave tiles as in the filter pass; its first output slot
-// is the scanned count of its predecessors (candidates above T plus the entries above the bracket,
-// and the ties before it), so no count pass over the row is needed.
-template <bool INTERIOR>
-__device__ __forceinline__ void emit_range_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 T, u32 q, u32& o, u32& eq_seen,
-                                                u32* __restrict__ out, u64 K, u32* zero_row) {
-  bool sel[kLoads * 4], eqb[kLoads * 4];
-  u64 eqm[kLoads * 4];
-  u64 eq_any = 0;
-#pragma unroll
-  for (int i = 0; i < kLoads * 4; ++i) {
-    const u32 key = r.b[i] & 0x7FFFFFFFu;
-    const bool ok = INTERIOR || ((r.valid >> i) & 1u);
-    sel[i] = ok && key > T;
-    eqb[i] = ok && key == T;
-    eqm[i] = ballot(eqb[i]);
-    eq_any |= eqm[i];
-  }
-  if (eq_any) {  // wave-uniform
-    if (eq_seen < q) {  // tie slots are left: they go to the equal entries in ascending index
-      u32 run = eq_seen;
-#pragma unroll
-      for (int j = 0; j < kLoads; ++j) {
-        u32 rk = run + ballot_rank(eqm[4 * j]) + ballot_rank(eqm[4 * j + 1]) + ballot_rank(eqm[4 * j + 2]) + ballot_rank(eqm[4 * j + 3]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (eqb[4 * j + e]) { sel[4 * j + e] = rk < q; ++rk; }
-        }
-        run += (u32)__popcll(eqm[4 * j]) + (u32)__popcll(eqm[4 * j + 1]) + (u32)__popcll(eqm[4 * j + 2]) + (u32)__popcll(eqm[4 * j + 3]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kLoads * 4; ++i) eq_seen += (u32)__popcll(eqm[i]);
-  }
-  const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
-#pragma unroll
-  for (int j = 0; j < kLoads; ++j) {
-    const u64 m0 = ballot(sel[4 * j]), m1 = ballot(sel[4 * j + 1]), m2 = ballot(sel[4 * j + 2]), m3 = ballot(sel[4 * j + 3]);
-    if ((m0 | m1 | m2 | m3) == 0) continue;  // wave-uniform
-    u32 p = o + ballot_rank(m0) + ballot_rank(m1) + ballot_rank(m2) + ballot_rank(m3);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int i = 4 * j + e;
-      if (sel[i]) {
-        if (p < K) out[p] = ((u32)(v0 + (u64)j * 256 + e) << 1) | (r.b[i] >> 31);  // p < K by construction
-        ++p;
-      }
-    }
-    o += (u32)__popcll(m0) + (u32)__popcll(m1) + (u32)__popcll(m2) + (u32)__popcll(m3);
-    if (zero_row) {  // the row is a memory: +0.0 over the sent entries, as whole 64-byte runs (see k_emit_rows)
-      const u32 s4 = (u32)sel[4 * j] | ((u32)sel[4 * j + 1] << 1) | ((u32)sel[4 * j + 2] << 2) | ((u32)sel[4 * j + 3] << 3);
-      if (((ballot(s4 != 0) >> (lane & 60u)) & 0xFull) == 0) continue;
-      u32* p = zero_row + (u64)tile * kWaveTile + (u64)j * 256 + (u64)lane * 4;
-      if (INTERIOR) {
-        *reinterpret_cast<uint4*>(p) = make_uint4((s4 & 1u) ? 0u : r.b[4 * j], (s4 & 2u) ? 0u : r.b[4 * j + 1],
-                                                  (s4 & 4u) ? 0u : r.b[4 * j + 2], (s4 & 8u) ? 0u : r.b[4 * j + 3]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if ((s4 >> e) & 1u) p[e] = 0u;
-      }
-    }
-  }
-}
-
-// `zero` non-NULL: `grads` is a memory holding g (the same buffer): every sent entry becomes +0.0.
-__global__ __launch_bounds__(kBlock) void k_range_emit(const float* grads, u64 N, u64 K, const RowState* __restrict__ rs,
-                                                       const u64* __restrict__ wave_sum, u32 wave_stride, u32 n_wtiles,
-                                                       u32 tiles_per_wave, u32* __restrict__ words, float* zero) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeRangeEmit) return;
-  const float* row = grads + (size_t)m * N;
-  const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
-  const u32* rowv = reinterpret_cast<const u32*>(row) - a;
-  const u64 vend = N + a;
-  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
-  const u32 g = blockIdx.x * kWaves + wave;  // the same wave, the same run of tiles as in the filter pass
-  const u32 t0 = g * tiles_per_wave;
-  const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
-  if (t0 >= t1) return;  // wave-uniform; nothing below synchronises across waves
-  const u64 before = wave_sum[(size_t)m * wave_stride + g];
-  u32 eq_seen = (u32)(before >> 32);
-  u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-  u32* out = words + (size_t)m * K;
-  u32* zero_row = zero ? reinterpret_cast<u32*>(zero + (size_t)m * N) - a : nullptr;
-  const u32 first = a ? 1u : 0u;
-  const u32 last = (u32)(vend / kWaveTile);
-  TileRegs nxt;
-  if (t0 >= first && t0 < last) load_filter_tile<true>(rowv, a, vend, t0, lane, nxt);
-  else load_filter_tile<false>(rowv, a, vend, t0, lane, nxt);
-  for (u32 tile = t0; tile < t1; ++tile) {
-    const TileRegs r = nxt;
-    if (tile + 1 < t1) {
-      if (tile + 1 >= first && tile + 1 < last) load_filter_tile<true>(rowv, a, vend, tile + 1, lane, nxt);
-      else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
-    }
-    if (tile >= first && tile < last) emit_range_tile<true>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K, zero_row);
-    else emit_range_tile<false>(r, a, tile, lane, st.T, st.q, o, eq_seen, out, K, zero_row);
   }
 }
 
@@ -1184,7 +1291,6 @@ __global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __res
     if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
     if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
     if (st.mode == kModeGeneral && st.row_emit) atomicAdd(&status[5], 1u);
-    if (st.mode == kModeRangeEmit) atomicAdd(&status[6], 1u);
   }
   u32* out = words + (size_t)m * K;
   for (u64 i = (u64)st.count + blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x)
@@ -1208,8 +1314,8 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
 u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks<false>, kBlock, 0)
-                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter<false>, kBlock, 0);
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks, kBlock, 0)
+                                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   const u32 n = (u32)cus * (u32)per_cu;
   return n > kMaxStreamBlocks ? kMaxStreamBlocks : n;
@@ -1231,75 +1337,101 @@ hipError_t launch_plain_read(const Workspace& ws, const float* buf, u64 n, hipSt
 // the count of keys above the r-th largest sample key is about r / f with deviation sqrt(r) / f.
 static double candidate_bound(double r, double f) { return 1.25 * (r + 6.0 * sqrt(r) + 8.0) / f; }
 
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bool chunks) {
+// Word slots a row needs beyond the first slabs of its waves: what waves of skewed rows reserve on
+// top (the bound is a quarter above the candidates expected, so this is nearly twice the row's
+// candidates: all of them in later slabs, and most of that again lost to the doubling); at dense K,
+// where the bound itself is a large part of the row and the candidates cannot crowd into a few
+// waves' ranges, a sixteenth of the row and a quarter of the bound.
+static double extra_slots(double bound, u64 N) {
+  const double a = 1.5 * bound, b = 0.25 * bound + (double)N / 16.0;
+  return a < b ? a : b;
+}
+static double first_slab_factor(double bound, u64 N) { return bound > (double)N / 16.0 ? 1.1 : 1.25; }
+
+// The sample: how many entries, the ranks of the two bounds, the candidates to expect.
+struct SamplePlan {
+  u64 s;          // sampled entries per row (a power of two)
+  double r, r_hi; // sample ranks of L and of U (r_hi 0: no entry is sure)
+  double bound;   // upper estimate of the candidates per row
+  u32 brk_shift;  // a segment of n word slots gets n >> brk_shift record slots
+  bool ok;
+};
+static SamplePlan plan_sample(u64 N, u64 K) {
+  SamplePlan sp{};
+  // about 1024 sampled entries above the K-th magnitude, between 2^15 and 2^18 and never more than an
+  // eighth of the row; at dense K (where every candidate kept costs a word written, read and written
+  // again) the largest sample, for the tightest bounds
+  const bool dense = K * 64 > N;
+  u64 s = 1ull << 15;
+  while (s < (1ull << 18) && s * 8 <= N && (dense || (double)s * (double)K < 1024.0 * (double)N)) s <<= 1;
+  const double f = (double)s / (double)N, kf = (double)K * f;
+  sp.s = s;
+  sp.r = ceil(kf + 6.0 * sqrt(kf) + 8.0);
+  sp.r_hi = floor(kf - 6.0 * sqrt(kf) - 8.0);
+  if (sp.r_hi < 1.0) sp.r_hi = 0.0;
+  sp.bound = candidate_bound(sp.r, f);
+  // the share of the candidates that lies inside the bracket, with the same slack as the bound
+  const double phi = (sp.r - sp.r_hi + 12.0 * sqrt(sp.r)) / sp.r;
+  sp.brk_shift = phi > 0.2 ? 0u : (phi > 0.1 ? 1u : (phi > 0.05 ? 2u : 3u));
+  sp.ok = sp.r < (double)s && sp.bound <= 0.75 * (double)N;
+  return sp;
+}
+
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 pool_bytes, u32 stream_blocks, bool chunks) {
   EncodePlan p{};
   p.n_tiles = encode_tiles(N);
   p.gx = blocks_per_row(M, p.n_tiles, stream_blocks);
   p.candidates = false;
-  if (K == 0 || N < (1ull << 17)) return p;
-  // Dense K: keeping every entry at or above L would take a pool as large as the row.  The filter
-  // pass then keeps only the entries inside the bins above L (a bracket around the K-th key), counts
-  // the ones above, and the words come from a second pass over the row once the threshold is known:
-  // two reads instead of the general route's five.  With a memory (the chunked pass fills no bins) the
-  // radix select runs over the bracket's candidates and the row passes count and emit: three reads.
-  p.bracket = K * 16 > N;
-  // sample size: about 256 sampled entries above the K-th magnitude, between 2^15 and 2^18,
-  // and never more than a quarter of the row
-  // (with a bracket the largest sample: the K-th key has to fall inside the bins above L)
-  u64 s = 1ull << 15;
-  while (s < (1ull << 18) && s * 8 <= N && (p.bracket || (double)s * (double)K < 256.0 * (double)N)) s <<= 1;
-  const double f = (double)s / (double)N, kf = (double)K * f;
-  const double r = ceil(kf + 6.0 * sqrt(kf) + 8.0);
-  if (r >= (double)s) return p;
+  if (K == 0 || K == N || N < (1ull << 17)) return p;  // K = N selects nothing: count and emit
+  const SamplePlan sp = plan_sample(N, K);
+  if (!sp.ok) return p;  // K above about N/2: the candidates would be most of the row
   p.n_wtiles = (u32)((N + 3 + kWaveTile - 1) / kWaveTile);
   p.tiles_per_wave = (p.n_wtiles + p.gx * kWaves - 1) / (p.gx * kWaves);
-  p.bound = candidate_bound(r, f);
-  // slab: the power of two at or above the candidates expected per wave of the filter pass
-  const double per_wave = p.bound / ((double)p.gx * kWaves);
-  p.slab = kSlabMin;
-  while (p.slab < kSlabMax && (double)p.slab < per_wave) p.slab <<= 1;
-  // a row needs room for its candidates, for the first slab of every wave, for the unused part of the
-  // later (doubling) slabs of waves that overflowed (at most what they hold), and a tile of slack
-  double need = 2.0 * p.bound + (double)p.gx * kWaves * p.slab + kWaveTile;
-  if (p.bracket) {
-    // how many entries fall inside the bracket depends on the distribution: the row takes its share of
-    // the pool, half of it as first slabs; a row that needs more falls back to the general route
-    need = floor((double)cand_pool / M);
-    if (need > (double)N + 2.0 * kWaveTile) need = (double)N + 2.0 * kWaveTile;
-    p.slab = kSlabMin;
-    while (p.slab < kSlabMax && (double)p.slab * 2.0 * p.gx * kWaves < need / 2.0) p.slab <<= 1;
-    if ((double)p.gx * kWaves * p.slab + kWaveTile > need) return p;
-  }
+  p.bound = sp.bound;
+  p.brk_shift = sp.brk_shift;
+  // slab: somewhat above the candidates expected per wave of the filter pass, a multiple of 256
+  const double per_wave = first_slab_factor(sp.bound, N) * sp.bound / ((double)p.gx * kWaves);
+  double slab = ceil(per_wave / kSlabMin) * kSlabMin;
+  if (slab < kSlabMin) slab = kSlabMin;
+  if (slab > kSlabMax) slab = kSlabMax;
+  p.slab = (u32)slab;
+  // a row needs room for the first slab of every wave and for what waves of skewed rows reserve on top
+  double need = extra_slots(sp.bound, N) + (double)p.gx * kWaves * p.slab + kWaveTile;
   if (chunks) {  // blocks reserve exactly what they found: no slabs
-    if (!p.bracket) need = 2.0 * p.bound + kWaveTile;
+    need = sp.bound + kWaveTile;
     p.n_chunks = chunk_count(N);
     p.n_lists = chunk_lists(N);
   }
-  if (need * M > (double)cand_pool || need > 4.0e9) return p;
+  if (need > 4.0e9) return p;
+  p.cand_stride = ((u32)need + 3u) & ~3u;
+  p.brk_stride = (((p.cand_stride >> p.brk_shift) + 64u) + 1u) & ~1u;
+  if ((double)M * (4.0 * p.cand_stride + 8.0 * p.brk_stride) > (double)pool_bytes) return p;
   p.candidates = true;
   p.chunks = chunks;
-  p.n_units = (u32)(s / kSampleUnit);
+  p.n_units = (u32)(sp.s / kSampleUnit);
   p.unit_stride = N / p.n_units;
-  p.sample_rank = (u32)r;
-  p.cand_stride = (u32)need;
+  p.sample_rank = (u32)sp.r;
+  p.sample_rank_hi = (u32)sp.r_hi;
   return p;
 }
 
-u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max) {
+u64 candidate_pool_bytes(u32 M_max, u64 N_max, u64 K_max) {
+  // the need is not monotone in K (the sample size changes in powers of two, the record share in
+  // steps): take the largest over K_max and the sparsities below it down to 1e-5
   double best = 0;
-  // the bound is not monotone in K (the sample size changes in powers of two): take the largest
-  // over K_max and the sparsities below it down to 1e-5
-  for (double k = (double)(K_max < N_max / 16 ? K_max : N_max / 16); k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
-    const EncodePlan p = plan_encode(1, N_max, (u64)k, ~0ull, 1, false);
-    if (p.candidates && p.bound > best) best = p.bound;
+  for (double k = (double)K_max; k >= 1.0 && k >= 1e-5 * (double)N_max; k /= 2.0) {
+    if ((u64)k >= N_max || N_max < (1ull << 17)) continue;
+    const SamplePlan sp = plan_sample(N_max, (u64)k);
+    if (!sp.ok) continue;
+    // per row: what skewed waves reserve on top, the first slabs (rounded up to whole slabs below), two tiles of slack
+    const double slots = extra_slots(sp.bound, N_max) + first_slab_factor(sp.bound, N_max) * sp.bound + 2.0 * kWaveTile;
+    const double bytes = 4.0 * (slots + 4.0) + 8.0 * (slots / (double)(1u << sp.brk_shift) + 66.0);
+    if (bytes > best) best = bytes;
   }
   if (best == 0) return 0;
-  // per row: twice the bound, as much again (at most twice the bound) in first slabs, one tile of
-  // slack; once: a smallest slab per wave of a streaming launch
-  u64 pool = (u64)M_max * (4 * (u64)best + kWaveTile) + (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin;
-  // dense K (bracket): an eighth of the row, 25 % of the gradients' bytes
-  if (K_max * 16 > N_max && pool < (u64)M_max * (N_max / 8)) pool = (u64)M_max * (N_max / 8);
-  return pool;
+  // once: the rounding of every wave's first slab to a whole smallest slab, words and records
+  const u64 rounding = (u64)(kMaxStreamBlocks + M_max) * kWaves * kSlabMin * 12ull;
+  return (u64)M_max * (u64)best + rounding;
 }
 
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
@@ -1314,7 +1446,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const bool formed = err && !grads;
   if (formed) grads = err;
   float* mem = formed ? nullptr : err;  // the memory to add in, if any
-  const EncodePlan p = plan_encode(M, N, K, ws.cand_pool, mem ? ws.stream_blocks_mem : ws.stream_blocks, mem != nullptr);
+  const EncodePlan p = plan_encode(M, N, K, ws.pool_bytes, mem ? ws.stream_blocks_mem : ws.stream_blocks, mem != nullptr);
   if (mem && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
     const u64 total = (u64)M * N;
     const u32 head = (u32)((4 - ((reinterpret_cast<uintptr_t>(err) >> 2) & 3u)) & 3u);
@@ -1334,68 +1466,63 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const u32 k32 = (u32)K;
   const bool all = K == N;  // signSGD with majority vote: every non-zero entry is sent, nothing to select
   S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
+                                                                         p.candidates ? p.sample_rank_hi : 0u,
                                                                          p.candidates ? kModeCandidates : kModeGeneral,
                                                                          p.candidates && !p.chunks ? p.gx * (u32)kWaves * p.slab : 0u,
-                                                                         p.candidates && p.bracket ? 1u : 0u, all ? 1u : 0u)));
+                                                                         all ? 1u : 0u)));
   const u32 n_waves = !p.candidates ? 0u : (p.chunks ? p.n_lists : p.gx * (u32)kWaves);  // segment lists per row
   const u32 wstride = p.chunks ? p.n_lists + 4 : wave_stride(p.gx);
+  // the pool: the candidate words of every row, then their bracket records
+  u32* cand = reinterpret_cast<u32*>(ws.pool);
+  uint2* recs = reinterpret_cast<uint2*>(ws.pool + (((size_t)M * p.cand_stride * 4 + 15) & ~(size_t)15));
   if (p.candidates) {
     const u32 n_wt = p.n_wtiles;
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
-    // sampled entries at or above L that stand for a row's whole share of the pool (a bracket keeps only part of them)
+    // sampled entries at or above L that stand for a row's whole share of the pool
     const double cap = (double)p.cand_stride * ((double)p.n_units * kSampleUnit / (double)N);
-    const u32 sample_cap = p.bracket ? 0u : (cap < 1.0 ? 1u : (cap > 4.0e9 ? 0u : (u32)cap));
+    const u32 sample_cap = cap < 1.0 ? 1u : (cap > 4.0e9 ? 0u : (u32)cap);
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_sample0<<<M, kBlock, 0, s>>>(ws.rs, ws.hist)));
     S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveSample><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, sample_cap, ws.status)));
-    if (p.chunks && p.bracket)
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
-                                                                                               ws.wave_seg, ws.wave_nseg, wstride,
-                                                                                               p.n_chunks, ws.status)));
-    else if (p.chunks)
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, ws.cand, p.cand_stride,
-                                                                                                ws.wave_seg, ws.wave_nseg, wstride,
-                                                                                                p.n_chunks, ws.status)));
-    else if (p.bracket)
-      S3GD_LAUNCH(KID_FILTER, (k_filter<true><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
-                                                                     ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status, ws.wave_sure)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_sample1<<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.sample_rank, p.chunks ? 0u : 1u, sample_cap,
+                                                                     ws.status)));
+    if (p.chunks)
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, cand, recs, p.cand_stride,
+                                                                                         p.brk_stride, ws.wave_seg, ws.wave_segb,
+                                                                                         ws.wave_nseg, wstride, p.n_chunks, ws.status)));
     else
-      S3GD_LAUNCH(KID_FILTER, (k_filter<false><<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, ws.cand, p.cand_stride, ws.wave_seg,
-                                                                      ws.wave_nseg, wstride, n_wt, p.tiles_per_wave, p.slab, ws.status,
-                                                                      ws.wave_sure)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveFilter><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u, 0u, ws.status)));
+      S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, cand, recs, p.cand_stride, p.brk_stride, p.brk_shift,
+                                                               ws.wave_seg, ws.wave_segb, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
+                                                               p.slab, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_filter<<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
   }
-  // Radix select: over the row for general rows, over the candidates for the others (the last level
-  // only, unless the filter's bins could not place the K-th key).
+  // Radix select: over the row for general rows, over the bracket's records for the others (the last
+  // level only, unless the filter's bins could not place the K-th key).
   // launches that walk segment lists: a wave per list, up to four rounds of resident blocks
   u32 lx = (n_waves + kWaves - 1) / kWaves;
   if (lx > 4 * p.gx) lx = 4 * p.gx;
   if (lx < p.gx) lx = p.gx;
   const dim3 lgrid(lx, M);
   const dim3 hgrid(p.candidates ? 4 * p.gx : p.gx, M);  // histogram launches
-  // where the candidates' order does not matter a list is shared by as many waves as that grid has for it
+  // where the records' order does not matter a list is shared by as many waves as that grid has for it
   u32 parts = n_waves ? hgrid.x * (u32)kWaves / n_waves : 1u;
   parts = parts < 1 ? 1u : (parts > 4 ? 4u : parts);
-#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride, n_waves, parts
+#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, recs, p.brk_stride, ws.wave_seg, ws.wave_segb, ws.wave_nseg, wstride, n_waves, parts
   if (!all) {
     S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
     S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2, kResolveRadix><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, 1u, 0u, ws.status)));
+    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
   }
 #undef S3GD_HIST_ARGS
   if (p.candidates) {  // one wave per segment list
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
-                                                                      n_waves, ws.wave_sum, ws.wave_sure)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, recs, p.brk_stride, ws.wave_seg, ws.wave_segb, ws.wave_nseg,
+                                                                      wstride, n_waves, ws.wave_sum)));
     S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, 1u)));
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, ws.cand, p.cand_stride, ws.wave_seg, ws.wave_nseg, wstride,
-                                                                   n_waves, ws.wave_sum, K, words, err, N)));
-    if (p.bracket && !p.chunks)
-      S3GD_LAUNCH(KID_RANGE_EMIT, (k_range_emit<<<grid, kBlock, 0, s>>>(grads, N, K, ws.rs, ws.wave_sum, wstride, p.n_wtiles, p.tiles_per_wave,
-                                                                 words, err)));
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, cand, recs, p.cand_stride, p.brk_stride, ws.wave_seg, ws.wave_segb,
+                                                                   ws.wave_nseg, wstride, n_waves, ws.wave_sum, K, words, err, N)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows).
   S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride, ws.status)));

@@ -63,19 +63,19 @@ struct Workspace {
   RowState* rs;   // [M]
   u32* status;    // [8]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags,
                   //      4 = candidate rows whose radix select ran over all levels, 5 = rows whose words came from the
-                  //      row passes with a threshold known beforehand (bracket with a memory, K = N), 6 = rows whose
-                  //      words came from the second pass over the waves' ranges (dense K), 7 = rows that left the
+                  //      row passes with a threshold known beforehand (K = N), 6 = unused, 7 = rows that left the
                   //      candidate route before the filter pass (decided from the sample)
   u32* hist;      // [M][kHistBins]
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][tiles of the launch's tiling + 1], at most seg_row_entries(N) per row
   u64* blk_sum;   // [M][blk_stride]   scratch of the random-K scan
-  u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment a filter wave left
-  u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each wave's list
-  u64* wave_sum;  // [M][wave_stride]  candidate route: (eq << 32 | gt) of each list, scanned in place
-  u32* wave_sure; // [M][wave_stride]  bracket: entries at or above the bracket's upper end in each wave's range
-  uint2* cand;    // [cand_pool]       candidate route: (index, fp32 bits), rows cand_stride apart
-  u64 cand_pool;  // entries of `cand`
+  u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment of candidate words
+  u64* wave_segb; // [M][wave_stride][kChain]  the same for the segment's bracket records
+  u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each list
+  u64* wave_sum;  // [M][wave_stride]  candidate route: (eq << 32 | selected without the ties) of each list, scanned in place
+  char* pool;     // candidate route: the candidate words of all rows, then their bracket records (carved per call);
+                  // random-K: (word, arrival number) records
+  u64 pool_bytes;
   u32 stream_blocks;  // blocks of a streaming launch = blocks resident on the device at once (one round, no tail)
   u32 stream_blocks_mem;  // the same for the filter pass that also carries the error-compensation memory
 };
@@ -84,21 +84,23 @@ struct Workspace {
 struct EncodePlan {
   bool candidates;   // try the candidate route first
   bool chunks;       // the filter pass runs in chunks (one block each, in index order) instead of persistent waves
-  bool bracket;      // dense K: the filter pass keeps the entries inside a bracket around the K-th key and counts those above
   u32 n_chunks, n_lists;  // chunked filter pass: blocks per row, segment lists per row
   u32 n_tiles, gx;   // 4096-entry tiles per row, streaming blocks per row
   u32 n_wtiles, tiles_per_wave;  // candidate route: 1024-entry wave tiles per row, and per wave of the filter
   u32 n_units;       // sample units (16 entries each) per row
   u64 unit_stride;   // row entries per sample unit window
   u32 sample_rank;   // rank, among the sample, of the key that becomes the lower bound L
-  u32 cand_stride;   // candidate slots per row
+  u32 sample_rank_hi;  // rank of the key that becomes the bracket's upper end U (0: no entry is sure)
+  u32 cand_stride;   // candidate word slots per row
+  u32 brk_shift;     // a segment of n word slots has room for n >> brk_shift bracket records
+  u32 brk_stride;    // bracket record slots per row
   u32 slab;          // candidate slots a wave of the filter pass owns at a time (a power of two)
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
-EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 cand_pool, u32 stream_blocks, bool chunks);
+EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 pool_bytes, u32 stream_blocks, bool chunks);
 u64 sample_unit_position(u32 u, u64 unit_stride);  // first entry of sample unit u of a row (host copy of the kernels' rule)
 u32 resident_stream_blocks(int device, bool with_memory);  // from the occupancy of the filter kernel; at most kMaxStreamBlocks
-u64 candidate_pool_entries(u32 M_max, u64 N_max, u64 K_max);
+u64 candidate_pool_bytes(u32 M_max, u64 N_max, u64 K_max);
 
 // `nan_flag` (device, nullable): receives 1 if the call saw a NaN, else 0, when its last kernel runs.
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,

@@ -277,8 +277,8 @@ hipError_t launch_randk_encode(const Workspace& ws, const float* grads, u32 M, u
   u32 gb = (nb + kWaves * 64 - 1) / (kWaves * 64);
   if (gb > cap) gb = cap;
   // room for (word, arrival number) of every selected entry in the candidate pool, which this call does not use otherwise?
-  const bool ranked = (u64)M * K <= ws.cand_pool;
-  uint2* tmp = ws.cand;
+  const bool ranked = (u64)M * K * sizeof(uint2) <= ws.pool_bytes;
+  uint2* tmp = reinterpret_cast<uint2*>(ws.pool);
   P.begin(KID_RANDK, s);
   k_randk_clear<<<dim3((nb + 255) / 256 < 64 ? (nb + 255) / 256 : 64, M), 256, 0, s>>>(bucket, nb, bstride, ws.status, M);
   if (K > 0) {

@@ -24,7 +24,7 @@ EXPORTS = (
     "s3gd_apply_update", "s3gd_step", "s3gd_step_static", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
-    "s3gd_strerror", "s3gd_calibrate_read", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
+    "s3gd_strerror", "s3gd_last_row_state", "s3gd_calibrate_read", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
 PROFILE_KERNELS = 27
 
@@ -85,6 +85,8 @@ _lib.s3gd_last_hip_error.argtypes = [_vp]
 _lib.s3gd_strerror.restype = ctypes.c_char_p
 _lib.s3gd_strerror.argtypes = [_int]
 
+_lib.s3gd_last_row_state.restype = _int
+_lib.s3gd_last_row_state.argtypes = [_vp, _vp, _u32, ctypes.POINTER(_u32)]
 _lib.s3gd_calibrate_read.restype = _int
 _lib.s3gd_calibrate_read.argtypes = [_vp, _vp, _u64, _vp]
 _lib.s3gd_encode_plan_info.restype = _int
@@ -331,6 +333,13 @@ class Context:
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
         return tuple(int(v) for v in out)
 
+    def last_row_state(self, m: int, stream=None) -> dict[str, int]:
+        out = (_u32 * 16)()
+        self._check(_lib.s3gd_last_row_state(self._h, _stream(stream), m, out), "s3gd_last_row_state")
+        names = ("prefix", "k_rem", "T", "q", "c_gt", "count", "mode", "L", "U", "overflow", "n_cand", "n_brk", "n_alloc",
+                 "n_alloc_b", "row_emit", "pad")
+        return {k: int(v) for k, v in zip(names, out)}
+
     def calibrate_read(self, buf: torch.Tensor, stream=None):
         """A plain read of `buf` (fp32) with the selection pass's launch shape; timed through the profile."""
         self._check(_lib.s3gd_calibrate_read(self._h, _ptr(buf), buf.numel(), _stream(stream)), "s3gd_calibrate_read")
@@ -339,7 +348,7 @@ class Context:
         """How an encode of this shape is laid over the device (see s3gd_encode_plan_info)."""
         out = (_u64 * 12)()
         self._check(_lib.s3gd_encode_plan_info(self._h, M, N, K, int(with_memory), out), "s3gd_encode_plan_info")
-        names = ("candidates", "chunks", "bracket", "blocks_per_row", "tiles_per_wave", "slab", "cand_stride", "n_units",
+        names = ("candidates", "chunks", "record_shift", "blocks_per_row", "tiles_per_wave", "slab", "cand_stride", "n_units",
                  "unit_stride", "sample_rank", "chain", "sample_unit")
         return {k: int(v) for k, v in zip(names, out)}
 
