@@ -354,8 +354,8 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
 /* The selection state row m was left in by the last encode on this context (16 words, host memory;
  * synchronises `stream`): in order the key prefix and rank of the radix select, the threshold T, the
  * tie quota, the entries above T, the words sent, the route (0 multi-pass, 1-3 single pass), the two
- * sampled bounds, an out-of-room flag, candidates kept, candidates whose selection the pass left
- * open, slots reserved (two counters), the K = N flag, one unused word.  For tests. */
+ * sampled bounds, the K = N flag, candidates kept, candidates whose selection the pass left open,
+ * four unused words.  For tests. */
 S3GD_API int s3gd_last_row_state(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t m, uint32_t* out);
 S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, uint64_t K, int with_memory, uint64_t* out);
 S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride);

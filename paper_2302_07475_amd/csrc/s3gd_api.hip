@@ -28,16 +28,17 @@ constexpr u32 kMaxRows = S3GD_M_LIMIT;  // rows map to gridDim.y
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t rs, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_segb, wave_nseg, wave_sum, pool, total;
+  size_t rs, rc, status, hist, tile_cnt, seg, blk_sum, wave_seg, wave_segb, wave_nseg, wave_sum, pool, total;
   u64 pool_bytes;
 };
 
 Layout layout(u32 M, u64 N, u64 K) {
   Layout l{};
   size_t off = 0;
-  l.rs = off;       off = align_up(off + sizeof(RowState) * (size_t)M, 256);
+  l.rs = off;       off = align_up(off + 2 * sizeof(RowState) * (size_t)M, 256);
+  l.rc = off;       off = align_up(off + sizeof(RowCounters) * (size_t)M, 256);
   l.status = off;   off = align_up(off + sizeof(u32) * 8, 256);
-  l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)M * kHistBins, 256);
+  l.hist = off;     off = align_up(off + sizeof(u32) * (size_t)kHistStages * M * kHistBins, 256);
   l.tile_cnt = off; off = align_up(off + sizeof(u64) * (size_t)M * tile_stride(N), 256);
   l.seg = off;      off = align_up(off + sizeof(u32) * (size_t)M * seg_row_entries(N), 256);
   l.wave_seg = off; off = align_up(off + sizeof(u64) * wave_table_entries(M, N) * kChain, 256);
@@ -54,6 +55,7 @@ Layout layout(u32 M, u64 N, u64 K) {
 // Points the views of a workspace at a block of device memory laid out by `l`.
 void bind_workspace(Workspace& ws, char* b, const Layout& l) {
   ws.rs = reinterpret_cast<RowState*>(b + l.rs);
+  ws.rc = reinterpret_cast<RowCounters*>(b + l.rc);
   ws.status = reinterpret_cast<u32*>(b + l.status);
   ws.hist = reinterpret_cast<u32*>(b + l.hist);
   ws.tile_cnt = reinterpret_cast<u64*>(b + l.tile_cnt);
@@ -133,13 +135,18 @@ S3GD_API int s3gd_create(s3gd_ctx** out, int device, uint32_t M_max, uint64_t N_
   c->bytes = l.total;
   char* b = static_cast<char*>(c->base);
   // the status words start clear: each call resets only the flags it can raise itself
-  if (hipMemset(b + l.status, 0, sizeof(u32) * 8) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+  // ... and the histograms start all zero: every call leaves them that way
+  if (hipMemset(b + l.status, 0, sizeof(u32) * 8) != hipSuccess ||
+      hipMemset(b + l.hist, 0, sizeof(u32) * (size_t)kHistStages * M_max * kHistBins) != hipSuccess ||
+      hipDeviceSynchronize() != hipSuccess) {
     (void)hipGetLastError();
     (void)hipFree(c->base);
     delete c;
     return S3GD_E_HIP;
   }
   bind_workspace(c->ws, b, l);
+  c->ws.M_max = M_max;
+  c->ws.hist_dirty = false;
   c->ws.stream_blocks = resident_stream_blocks(device, false);
   c->ws.stream_blocks_mem = resident_stream_blocks(device, true);
   c->ws.prof = &c->prof;
@@ -277,6 +284,8 @@ S3GD_API int s3gd_step_static(int device, const float* grads, uint32_t M, uint64
   }
   Workspace ws{};
   bind_workspace(ws, st->ptr, l);
+  ws.M_max = M;
+  ws.hist_dirty = true;  // the array is laid out anew for every shape: what lies under the histograms is anybody's
   ws.stream_blocks = st->stream_blocks;
   ws.stream_blocks_mem = st->stream_blocks_mem;
   ws.prof = &st->prof;

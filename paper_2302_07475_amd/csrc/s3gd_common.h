@@ -17,6 +17,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kLoads = 4;                   // 16-byte loads per thread and tile
 constexpr int kTile = kBlock * 4 * kLoads;  // 4096 gradient entries per tile
 constexpr int kHistBins = 2048;             // first radix digit: key bits [30:20]
+constexpr int kHistStages = 6;              // histograms of one encode call: sample (two levels), filter bins, radix select (three levels)
 constexpr unsigned kMomTile = 4096;         // coordinates one wave of the momentum sweep owns (the finest vote tiling)
 constexpr int kScanBlock = 1024;
 
@@ -24,7 +25,10 @@ constexpr int kScanBlock = 1024;
 __host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 20 : (level == 1 ? 10 : 0); }
 __host__ __device__ constexpr int digit_bits(int level) { return level == 0 ? 11 : 10; }
 
-// Per-row selection state, device resident.
+// Per-row selection state, device resident.  Every kernel of an encode call reads the state its
+// predecessor left (one buffer), advances it by one resolve step where a histogram has been filled
+// since (every block on its own, all to the same result) and its first block writes it to the other
+// buffer for the successor: no kernel reads a state that is being written.
 struct RowState {
   u32 prefix;     // key bits fixed so far (right aligned)
   u32 k_rem;      // rank still sought inside the current prefix, 1-based from the largest
@@ -34,22 +38,30 @@ struct RowState {
                   // (while the sample is resolved: the rank still sought for U; 0 = there is no U)
   u32 c_gt;       // entries with key > T
   u32 count;      // words the row emits = c_gt + q
-  u32 mode;       // kModeGeneral, kModeCandidates or kModeCandWide
+  u32 mode;       // kModeGeneral, kModeCandidates, kModeCandWide or kModeCandDone
   u32 L;          // candidate route: every entry with key >= L is a candidate; a multiple of 1024
   u32 U;          // candidate route: a candidate with key >= U is selected whatever the threshold turns out to
                   // be; the others (L <= key < U, the bracket) take part in the radix select.  A multiple of
                   // 1024, or 0x80000000 when no entry is sure
-  u32 overflow;   // candidate route: a wave or block found no room for its candidates
-  u32 n_cand;     // candidate route: candidates the filter pass kept ...
-  u32 n_brk;      // ... and those of them inside the bracket (the two are added to as one 64-bit word)
-  u32 n_alloc;    // candidate route: candidate slots handed out (slab allocator / exact reservations)
-  u32 n_alloc_b;  // filter pass in chunks: bracket slots handed out
   u32 row_emit;   // the row passes (count, emit) serve the row with a threshold that is already known:
                   // 2 = K = N (threshold 0, count from the scan)
-  u32 pad;
+  u32 n_cand;     // candidate route, for diagnostics: candidates the filter pass kept ...
+  u32 n_brk;      // ... and those of them inside the bracket
+  u32 pad[4];
 };
 static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
-static_assert(offsetof(RowState, n_cand) % 8 == 0 && offsetof(RowState, n_brk) == offsetof(RowState, n_cand) + 4, "n_cand and n_brk form one aligned 64-bit word");
+
+// Per-row counters that the blocks of one kernel add to (never rewritten as a whole).
+struct RowCounters {
+  u32 n_cand;     // candidates the filter pass kept ...
+  u32 n_brk;      // ... and those of them inside the bracket (the two are added to as one 64-bit word)
+  u32 n_alloc;    // candidate slots handed out (slab allocator / exact reservations)
+  u32 n_alloc_b;  // filter pass in chunks: bracket slots handed out
+  u32 overflow;   // a wave or block found no room for its candidates
+  u32 ticket;     // emit pass: blocks take their segment lists in the order they start
+  u32 pad[2];
+};
+static_assert(sizeof(RowCounters) == 32, "RowCounters is half a 64-byte line");
 
 constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
 constexpr u32 kModeCandidates = 1;  // sampled bounds, one filter pass, last ten key bits resolved among the bracket's candidates

@@ -71,26 +71,6 @@ __global__ __launch_bounds__(kBlock) void k_compensate(const float* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
-// state reset (a kernel rather than a memset so that callers may capture the call into a graph)
-__global__ void k_encode_init(RowState* rs, u32* hist, u32* status, u32 M, u32 first_rank, u32 upper_rank, u32 mode, u32 first_alloc,
-                              u32 all_selected) {
-  const u32 m = blockIdx.y;
-  for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x)
-    hist[(size_t)m * kHistBins + i] = 0;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    RowState s{};
-    s.k_rem = first_rank;  // K on the general route, the sample rank of L on the candidate route
-    s.q = upper_rank;      // candidate route: the sample rank of U (0: no entry is sure); cleared once U is there
-    s.mode = mode;
-    s.U = kNoUpper;
-    s.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
-    s.row_emit = all_selected ? 2u : 0u;  // K = N: threshold 0, no tie slots (the zero-filled T and q), count from the scan
-    rs[m] = s;
-    if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; status[5] = 0; status[6] = 0; status[7] = 0; }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // The candidates of a row, as the filter pass left them: a table of segment lists, each of at most
 // kChain segments.  A segment is a run of candidate words (the message words of entries with key >= L,
 // in ascending index) in the row's word pool, and a run of bracket records in the row's record pool:
@@ -196,23 +176,248 @@ __device__ __forceinline__ void hist_add(u32* h, u32 bin, bool take) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Resolve steps.  A histogram filled by one kernel is read by the NEXT kernel: every block of that
+// kernel picks the bin that holds the sought rank (a block-wide scan over the row's bins, thread 0
+// owning the highest), all blocks arriving at the same state, and the first block of the row writes
+// the state to the buffer the kernel after reads.  This takes the place of a one-block-per-row
+// kernel between every two passes: a launch costs about as much as such a kernel runs (4 to 5 us),
+// and a step over a few hundred MB is a dozen of them.
+
+// Among `PER` consecutive bins of this thread (c[0] the highest), with `above` entries in the bins
+// above them: the bin that holds rank k (1-based from the largest), if it is one of them.
+template <int PER>
+__device__ __forceinline__ bool find_rank(const u32 (&c)[PER], u32 above, u32 k, int top, u32* digit, u32* rank_inside, u32* upto) {
+  u32 acc = above;
+  bool found = false;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if (k >= 1 && acc < k && k <= acc + c[i]) {
+      *digit = (u32)(top - i);
+      *rank_inside = k - acc;
+      *upto = acc + c[i];
+      found = true;
+    }
+    acc += c[i];
+  }
+  return found;
+}
+
+struct Found {
+  u32 hit;        // the rank lies inside the histogram
+  u32 digit;      // the bin that holds it
+  u32 inside;     // its rank among the entries of that bin
+  u32 upto;       // entries in that bin and the bins above it
+};
+
+// Looks up two ranks (k2 may be 0: none) in the NB bins at h.  Called by every thread of the block;
+// every thread receives the same answers.  *total = entries in all bins, *top_count = entries in the
+// highest bin.  `lds`: kWaves + 10 words.
+template <int NB>
+__device__ __forceinline__ void find_in_bins(const u32* __restrict__ h, u32 k1, u32 k2, u32* lds, Found* f1, Found* f2, u32* total,
+                                             u32* top_count) {
+  constexpr int PER = NB / kBlock;
+  const int top = NB - 1 - (int)threadIdx.x * PER;
+  u32 c[PER];
+  u32 s = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
+  const u32 above = block_excl_scan<u32>(s, total, lds);
+  u32* r = lds + kWaves;
+  if (threadIdx.x == 0) { r[0] = 0; r[4] = 0; r[8] = c[0]; }
+  __syncthreads();
+  u32 digit, inside, upto;
+  if (find_rank<PER>(c, above, k1, top, &digit, &inside, &upto)) { r[0] = 1; r[1] = digit; r[2] = inside; r[3] = upto; }
+  if (find_rank<PER>(c, above, k2, top, &digit, &inside, &upto)) { r[4] = 1; r[5] = digit; r[6] = inside; r[7] = upto; }
+  __syncthreads();
+  *f1 = Found{r[0], r[1], r[2], r[3]};
+  *f2 = Found{r[4], r[5], r[6], r[7]};
+  *top_count = r[8];
+  __syncthreads();  // r is free again
+}
+
+constexpr int kResolveLds = kWaves + 10;
+
+// The sample, first level (key bits [30:20]): the bins that hold the sample ranks of L and of U.
+// Until U is there its prefix and its rank travel in the fields T and q.
+__device__ __forceinline__ RowState advance_sample0(RowState st, const u32* __restrict__ h, u32* lds) {
+  if (st.mode != kModeCandidates) return st;  // block-uniform
+  Found lo, hi;
+  u32 total, top_count;
+  find_in_bins<kHistBins>(h, st.k_rem, st.q, lds, &lo, &hi, &total, &top_count);
+  if (lo.hit) { st.prefix = lo.digit; st.k_rem = lo.inside; }
+  if (hi.hit) { st.T = hi.digit; st.q = hi.inside; }
+  return st;
+}
+
+// The sample, second level (key bits [19:10]): bins 0..1023 hold the keys under L's prefix, bins
+// 1024..2047 those under U's.  Ends with L = the 21-bit prefix of the sample key of rank `rank_lo`,
+// U = one past the 21-bit prefix of the sample key of the upper rank (both shifted back to key
+// units), so that at least rank_lo sampled keys are >= L and fewer than the upper rank are >= U.
+// `have_bins` is 0 when the filter pass is the chunked one (with a memory): that pass must run over
+// every row to form g, so no row leaves the candidate route before it.
+__device__ __forceinline__ RowState advance_sample1(RowState st, const u32* __restrict__ h, u32 K, u32 rank_lo, u32 have_bins,
+                                                    u32 sample_cap, u32* lds, bool* diverted) {
+  *diverted = false;
+  if (st.mode != kModeCandidates) return st;  // block-uniform
+  Found lo, hi, none;
+  u32 total, top_count;
+  find_in_bins<1024>(h, st.k_rem, 0u, lds, &lo, &none, &total, &top_count);
+  find_in_bins<1024>(h + 1024, st.q, 0u, lds, &hi, &none, &total, &top_count);
+  if (lo.hit) {
+    st.L = ((st.prefix << 10) | lo.digit) << 10;
+    // L = 0: the sample holds fewer than its share of non-zero entries (a mostly-zero row with K
+    // above its non-zeros), every entry would be a candidate.  The row goes to the general route
+    // before the filter pass instead of after it, unless that pass must still form g in the memory.
+    if (st.L == 0 && have_bins) st.mode = kModeGeneral;
+    // Likewise a row with so many entries at or above L that they cannot fit its share of the
+    // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
+    // sampled entries that stands for a full pool (0: no such check).
+    if (sample_cap && have_bins && (rank_lo - st.k_rem) + lo.upto > sample_cap) st.mode = kModeGeneral;
+    *diverted = st.mode == kModeGeneral;
+  }
+  st.U = kNoUpper;
+  if (hi.hit) st.U = (((st.T << 10) | hi.digit) + 1u) << 10;  // the prefix is below 2^21: at most 2^31 = kNoUpper
+  st.prefix = 0;
+  st.k_rem = K;
+  st.T = 0;
+  st.q = 0;
+  return st;
+}
+
+// After the filter pass: does the candidate route stand, and where does the radix select start.
+// The filter pass histogrammed the bracket's records into 2048 bins of (key - L) >> 10, the last one
+// open-ended (a pass in chunks fills no bins: `have_bins` 0).  With n_sure = candidates outside the
+// bracket (all of them selected), the K-th key overall is the (K - n_sure)-th of the bracket.
+__device__ __forceinline__ RowState advance_filter(RowState st, const u32* __restrict__ h, const RowCounters& rc, u32 K, u32 have_bins,
+                                                   u32* lds) {
+  if (st.mode != kModeCandidates) return st;  // block-uniform
+  st.n_cand = have_bins ? rc.n_cand : rc.n_alloc;  // a pass in chunks: what its blocks reserved
+  st.n_brk = have_bins ? rc.n_brk : rc.n_alloc_b;
+  const u32 n_sure = st.n_cand - st.n_brk;
+  const u32 k = K >= n_sure ? K - n_sure : 0u;
+  Found f, none;
+  u32 total, top_count;
+  find_in_bins<kHistBins>(h, k, 0u, lds, &f, &none, &total, &top_count);
+  // The route stands only if no wave ran out of room, no more than K entries were taken for sure and
+  // the K-th largest key is among the bracket's records (or is the smallest sure one: k = 0).
+  const bool usable = !rc.overflow && n_sure <= K && st.n_brk >= k && (!have_bins || total == st.n_brk);
+  st.prefix = 0;
+  if (!usable) {
+    st.mode = kModeGeneral;
+    st.k_rem = K;
+  } else if (k == 0) {  // every selected entry is a sure one: the threshold is the bracket's upper end
+    st.mode = kModeCandDone;
+    st.T = st.U - 1u;
+    st.q = 0;
+    st.c_gt = K;
+    st.count = K;
+  } else if (have_bins && top_count < k && f.hit) {  // the bins place the K-th key: its upper 21 bits are fixed
+    st.prefix = (st.L >> 10) + f.digit;
+    st.k_rem = f.inside;
+  } else {  // it sits in the open top bin (or there are no bins): the radix select starts over, among the records
+    st.mode = kModeCandWide;
+    st.k_rem = k;
+  }
+  return st;
+}
+
+// One level of the radix select (11 + 10 + 10 key bits).
+template <int LEVEL>
+__device__ __forceinline__ RowState advance_radix(RowState st, const u32* __restrict__ h, u32 K, u32* lds) {
+  constexpr int NB = 1 << digit_bits(LEVEL);
+  Found f, none;
+  u32 total, top_count;
+  find_in_bins<NB>(h, st.k_rem, 0u, lds, &f, &none, &total, &top_count);
+  if (f.hit) {
+    st.prefix = (st.prefix << digit_bits(LEVEL)) | f.digit;
+    st.k_rem = f.inside;
+    if (LEVEL == 2) {
+      st.T = st.prefix;
+      st.q = st.T == 0 ? 0u : st.k_rem;
+      st.c_gt = K - st.k_rem;
+      st.count = st.c_gt + st.q;
+    }
+  }
+  return st;
+}
+
+// Which rows a level of the radix select is still open for when its histogram has been filled.
+__device__ __forceinline__ bool radix_open(const RowState& st, int level) {
+  if (st.mode == kModeGeneral) return st.row_emit == 0;
+  if (st.mode == kModeCandWide) return true;
+  return st.mode == kModeCandidates && level == 2;  // the filter's bins fixed the upper 21 bits
+}
+
+__device__ __forceinline__ u32* stage_hist(u32* hist, int stage, u32 M, u32 m) { return hist + ((size_t)stage * M + m) * kHistBins; }
+enum { kStageSample0 = 0, kStageSample1 = 1, kStageFilter = 2, kStageRadix0 = 3 };  // radix level l: kStageRadix0 + l
+
+// The tables the filter pass leaves for the kernels after it.
+struct CandTables {
+  u32* cand;       // [M][cand_stride] candidate words
+  uint2* recs;     // [M][brk_stride]  bracket records
+  u32 cand_stride, brk_stride, brk_shift;
+  u64* wave_seg;   // [M][wave_stride][kChain]
+  u64* wave_segb;  // [M][wave_stride][kChain]
+  u32* wave_nseg;  // [M][wave_stride]
+  u64* look;       // [M][wave_stride]  what each list publishes for the lists after it
+  u32 wave_stride, n_lists;
+};
+
+// ------------------------------------------------------------------------------------------------
+// state reset for calls that take no sample (tiny rows, K = N): a kernel rather than a memset so that
+// callers may capture the call into a graph.  Calls that do take one reset the state in its first kernel.
+__device__ __forceinline__ void init_row(RowState* rs, RowCounters* rc, u32* status, u32 m, u32 M, u32 first_rank, u32 upper_rank, u32 mode,
+                                         u32 first_alloc, u32 all_selected) {
+  RowState s{};
+  s.k_rem = first_rank;  // K on the general route, the sample rank of L on the candidate route
+  s.q = upper_rank;      // candidate route: the sample rank of U (0: no entry is sure); cleared once U is there
+  s.mode = mode;
+  s.U = kNoUpper;
+  s.row_emit = all_selected ? 2u : 0u;  // K = N: threshold 0, no tie slots (the zero-filled T and q), count from the scan
+  rs[m] = s;
+  RowCounters c{};
+  c.n_alloc = first_alloc;  // candidate slots already handed out: the first slab of every wave of the filter pass
+  rc[m] = c;
+  if (m == 0) { status[0] = 0; status[1] = 0; status[2] = M; status[4] = 0; status[5] = 0; status[6] = 0; status[7] = 0; }
+}
+
+__global__ void k_encode_init(RowState* rs, RowCounters* rc, u32* status, u32 M, u32 K, u32 all_selected) {
+  const u32 m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m < M) init_row(rs, rc, status, m, M, K, 0u, kModeGeneral, 0u, all_selected);
+}
+
+// Zeroes the histograms of a call whose scratch may hold anything (scratch shared between shapes).
+__global__ void k_clear_hist(u32* hist, u64 n) {
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (u64)gridDim.x * blockDim.x) hist[i] = 0;
+}
+
 // Histogram pass of one radix level (11 + 10 + 10 key bits, most significant first).
 //   general rows            over the whole row
 //   wide candidate rows     over the row's bracket records, every level
 //   other candidate rows    over the bracket records at the last level only: the filter pass has
 //                           already fixed the upper 21 bits
+// Before that, every block takes the resolve step that has become possible: level 0 the verdict on
+// the filter pass, the other levels the level before.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
-                                                      u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status,
-                                                      const uint2* __restrict__ recs, u32 brk_stride, const u64* __restrict__ wave_seg,
-                                                      const u64* __restrict__ wave_segb, const u32* __restrict__ wave_nseg,
-                                                      u32 wave_stride, u32 n_waves, u32 parts) {
+__global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ grads, u64 N, u32 K, const RowState* __restrict__ rs_in,
+                                                      RowState* __restrict__ rs_out, const RowCounters* __restrict__ rc,
+                                                      u32* __restrict__ hist, u32 n_tiles, u32* __restrict__ status, CandTables t,
+                                                      u32 parts, u32 have_bins) {
   constexpr int NB = 1 << digit_bits(LEVEL);
   constexpr int SH = digit_shift(LEVEL);
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode == kModeCandDone || (st.mode == kModeCandidates && LEVEL != 2)) return;
+  const u32 m = blockIdx.y, M = gridDim.y;
   __shared__ u32 h[NB];
+  __shared__ u32 lds[kResolveLds];
+  RowState st = rs_in[m];
+  if (LEVEL == 0) {
+    if (st.mode == kModeCandidates) st = advance_filter(st, stage_hist(hist, kStageFilter, M, m), rc[m], K, have_bins, lds);
+  } else if (radix_open(st, LEVEL - 1)) {
+    if (LEVEL == 1) st = advance_radix<0>(st, stage_hist(hist, kStageRadix0, M, m), K, lds);
+    else st = advance_radix<1>(st, stage_hist(hist, kStageRadix0 + 1, M, m), K, lds);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+  if (!radix_open(st, LEVEL)) return;  // block-uniform
   for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
   __syncthreads();
   bool nan = false;
@@ -235,9 +440,9 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
     }
   } else {  // `parts` waves per segment list, each with a share of its records (their order does not matter here)
     const u32 lane = lane_id();
-    for (u32 w = blockIdx.x * kWaves + (threadIdx.x >> 6); w < n_waves * parts; w += gridDim.x * kWaves) {
+    for (u32 w = blockIdx.x * kWaves + (threadIdx.x >> 6); w < t.n_lists * parts; w += gridDim.x * kWaves) {
       const u32 g = w / parts, part = w - g * parts;
-      const RecordWalk lw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
+      const RecordWalk lw(t.wave_seg, t.wave_segb, t.wave_nseg, t.wave_stride, t.recs, t.brk_stride, m, g);
       const u32 share = ((lw.total + parts - 1) / parts + 63u) & ~63u;
       const u32 lo = part * share;
       const u32 hi = lo + share < lw.total ? lo + share : lw.total;
@@ -256,209 +461,26 @@ __global__ __launch_bounds__(kBlock) void k_hist_rows(const float* __restrict__ 
     }
   }
   __syncthreads();
+  u32* out = stage_hist(hist, kStageRadix0 + LEVEL, M, m);
   for (int i = threadIdx.x; i < NB; i += kBlock) {
     const u32 c = h[i];
-    if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
+    if (c) atomicAdd(&out[i], c);
   }
   if (LEVEL == 0 && nan) status[0] = 1;
 }
 
-// ------------------------------------------------------------------------------------------------
-// The resolve kernels: one block per row picks the bin that holds a sought rank from the row's
-// histogram (thread 0 owns the highest bins) and clears the histogram for its next use.
-
-// Among `PER` consecutive bins of this thread (c[0] the highest), with `above` entries in the bins
-// above them: the bin that holds rank k (1-based from the largest), if it is one of them.
-template <int PER>
-__device__ __forceinline__ bool find_rank(const u32 (&c)[PER], u32 above, u32 k, int top, u32* digit, u32* rank_inside, u32* upto) {
-  u32 acc = above;
-  bool found = false;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    if (k >= 1 && acc < k && k <= acc + c[i]) {
-      *digit = (u32)(top - i);
-      *rank_inside = k - acc;
-      *upto = acc + c[i];
-      found = true;
-    }
-    acc += c[i];
-  }
-  return found;
-}
-
-// A level of the radix select filled by k_hist_rows: every level for general and wide candidate
-// rows, the last level for the other candidate rows.
-template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_resolve(RowState* rs, u32* hist, u32 K) {
-  constexpr int NB = 1 << digit_bits(LEVEL);
-  constexpr int PER = NB / kBlock;
-  const u32 m = blockIdx.x;
-  RowState st = rs[m];
-  if (st.mode == kModeCandDone || (st.mode == kModeCandidates && LEVEL != 2)) return;
-  __shared__ u32 lds[kWaves];
-  u32* h = hist + (size_t)m * kHistBins;
-  const int top = NB - 1 - (int)threadIdx.x * PER;
-  u32 c[PER];
-  u32 s = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
-  u32 total;
-  const u32 above = block_excl_scan<u32>(s, &total, lds);
-#pragma unroll
-  for (int i = 0; i < PER; ++i) h[top - i] = 0;
-  u32 digit, inside, upto;
-  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) {
-    st.prefix = (st.prefix << digit_bits(LEVEL)) | digit;
-    st.k_rem = inside;
-    if (LEVEL == 2) {
-      st.T = st.prefix;
-      st.q = st.T == 0 ? 0u : st.k_rem;
-      st.c_gt = K - st.k_rem;
-      st.count = st.c_gt + st.q;
-    }
-    rs[m] = st;
-  }
-}
-
-// The sample, first level (key bits [30:20]): the bins that hold the sample ranks of L and of U.
-// Until U is there its prefix and its rank travel in the fields T and q.
-__global__ __launch_bounds__(kBlock) void k_resolve_sample0(RowState* rs, u32* hist) {
-  constexpr int PER = kHistBins / kBlock;
-  const u32 m = blockIdx.x;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
-  __shared__ u32 lds[kWaves];
-  u32* h = hist + (size_t)m * kHistBins;
-  const int top = kHistBins - 1 - (int)threadIdx.x * PER;
-  u32 c[PER];
-  u32 s = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
-  u32 total;
-  const u32 above = block_excl_scan<u32>(s, &total, lds);
-#pragma unroll
-  for (int i = 0; i < PER; ++i) h[top - i] = 0;
-  u32 digit, inside, upto;
-  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) { rs[m].prefix = digit; rs[m].k_rem = inside; }
-  if (find_rank<PER>(c, above, st.q, top, &digit, &inside, &upto)) { rs[m].T = digit; rs[m].q = inside; }
-}
-
-// The sample, second level (key bits [19:10]): bins 0..1023 hold the keys under L's prefix, bins
-// 1024..2047 those under U's.  Ends with L = the 21-bit prefix of the sample key of rank `rank_lo`,
-// U = one past the 21-bit prefix of the sample key of the upper rank (both shifted back to key
-// units), so that at least rank_lo sampled keys are >= L and fewer than the upper rank are >= U.
-// `have_bins` is 0 when the filter pass is the chunked one (with a memory): that pass must run over
-// every row to form g, so no row leaves the candidate route before it.
-__global__ __launch_bounds__(kBlock) void k_resolve_sample1(RowState* rs, u32* hist, u32 K, u32 rank_lo, u32 have_bins, u32 sample_cap,
-                                                            u32* status) {
-  constexpr int PER = 1024 / kBlock;
-  const u32 m = blockIdx.x;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
-  __shared__ u32 lds[kWaves];
-  u32* h = hist + (size_t)m * kHistBins;
-  const int top = 1023 - (int)threadIdx.x * PER;
-  u32 c[PER], d[PER];
-  u32 s = 0, sd = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; d[i] = h[1024 + top - i]; sd += d[i]; }
-  u32 total;
-  const u32 above = block_excl_scan<u32>(s, &total, lds);
-  const u32 above_d = block_excl_scan<u32>(sd, &total, lds);
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { h[top - i] = 0; h[1024 + top - i] = 0; }
-  u32 digit, inside, upto;
-  if (find_rank<PER>(c, above, st.k_rem, top, &digit, &inside, &upto)) {
-    const u32 L = ((st.prefix << 10) | digit) << 10;
-    u32 mode = kModeCandidates;
-    // L = 0: the sample holds fewer than its share of non-zero entries (a mostly-zero row with K
-    // above its non-zeros), every entry would be a candidate.  The row goes to the general route
-    // before the filter pass instead of after it, unless that pass must still form g in the memory.
-    if (L == 0 && have_bins) mode = kModeGeneral;
-    // Likewise a row with so many entries at or above L that they cannot fit its share of the
-    // pool (all entries equal, heavy ties at the threshold): `sample_cap` is the number of
-    // sampled entries that stands for a full pool (0: no such check).
-    if (sample_cap && have_bins && (rank_lo - st.k_rem) + upto > sample_cap) mode = kModeGeneral;
-    if (mode == kModeGeneral) atomicAdd(&status[7], 1u);
-    rs[m].L = L;
-    rs[m].mode = mode;
-    rs[m].prefix = 0;
-    rs[m].k_rem = K;
-  }
-  if (find_rank<PER>(d, above_d, st.q, top, &digit, &inside, &upto)) {
-    const u32 p = (st.T << 10) | digit;  // below 2^21
-    rs[m].U = (p + 1u) << 10;            // at most 2^31 = kNoUpper
-    rs[m].T = 0;
-    rs[m].q = 0;
-  }
-}
-
-// After the filter pass: does the candidate route stand, and where does the radix select start.
-// The filter pass histogrammed the bracket's records into 2048 bins of (key - L) >> 10, the last one
-// open-ended (a pass in chunks fills no bins: `have_bins` 0).  With n_sure = candidates outside the
-// bracket (all of them selected), the K-th key overall is the (K - n_sure)-th of the bracket.
-__global__ __launch_bounds__(kBlock) void k_resolve_filter(RowState* rs, u32* hist, u32 K, u32 have_bins) {
-  constexpr int PER = kHistBins / kBlock;
-  const u32 m = blockIdx.x;
-  RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
-  __shared__ u32 lds[kWaves];
-  __shared__ u32 verdict;
-  u32* h = hist + (size_t)m * kHistBins;
-  const int top = kHistBins - 1 - (int)threadIdx.x * PER;
-  u32 c[PER];
-  u32 s = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { c[i] = h[top - i]; s += c[i]; }
-  u32 total;
-  const u32 above = block_excl_scan<u32>(s, &total, lds);
-#pragma unroll
-  for (int i = 0; i < PER; ++i) h[top - i] = 0;
-  if (!have_bins) { st.n_cand = st.n_alloc; st.n_brk = st.n_alloc_b; }  // a pass in chunks: what its blocks reserved
-  const u32 n_sure = st.n_cand - st.n_brk;
-  const u32 k = K >= n_sure ? K - n_sure : 0u;
-  // The route stands only if no wave ran out of room, no more than K entries were taken for sure and
-  // the K-th largest key is among the bracket's records (or is the smallest sure one: k = 0).
-  if (threadIdx.x == 0) {
-    const bool usable = !st.overflow && n_sure <= K && st.n_brk >= k && (!have_bins || total == st.n_brk);
-    // 3: every selected entry is a sure one; 2: the bins place the K-th key; 1: it sits in the open top bin
-    // (or there are no bins): the radix select starts over, among the records; 0: general route
-    verdict = !usable ? 0u : (k == 0 ? 3u : ((have_bins && c[0] < k) ? 2u : 1u));
-  }
-  __syncthreads();
-  const u32 v = verdict;
-  if (v != 2u) {
-    if (threadIdx.x == 0) {
-      st.prefix = 0;
-      if (v == 0u) { st.mode = kModeGeneral; st.k_rem = K; }
-      if (v == 1u) { st.mode = kModeCandWide; st.k_rem = k; }
-      if (v == 3u) {  // the threshold is the bracket's upper end: nothing inside the bracket is selected
-        st.mode = kModeCandDone;
-        st.T = st.U - 1u;
-        st.q = 0;
-        st.c_gt = K;
-        st.count = K;
-      }
-      rs[m] = st;
-    }
-    return;
-  }
-  u32 digit, inside, upto;
-  if (find_rank<PER>(c, above, k, top, &digit, &inside, &upto)) {
-    st.prefix = (st.L >> 10) + digit;
-    st.k_rem = inside;
-    rs[m] = st;
-  }
-}
-
 // Per tile: entries above the threshold and entries equal to it, packed as (eq << 32) | gt.
-__global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__ grads, u64 N, const RowState* __restrict__ rs,
+// Every block first takes the last resolve step of the rows the radix select ran over the whole row for.
+__global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__ grads, u64 N, u32 K, const RowState* __restrict__ rs_in,
+                                                       RowState* __restrict__ rs_out, u32* __restrict__ hist,
                                                        u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
                                                        u32* __restrict__ status) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
+  const u32 m = blockIdx.y, M = gridDim.y;
+  __shared__ u32 lds[2 * kWaves > kResolveLds ? 2 * kWaves : kResolveLds];
+  RowState st = rs_in[m];
+  if (st.mode == kModeGeneral && st.row_emit == 0) st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), K, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
   if (st.mode != kModeGeneral) return;
-  __shared__ u32 lds[2 * kWaves];
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
@@ -494,8 +516,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_count(const float* __restrict__
 
 // In-place exclusive scan of a row's packed tile counts; entry n_tiles receives the row total.
 __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
-                                                           RowState* __restrict__ rs, u32 candidate_rows) {
-  if ((rs[blockIdx.x].mode != kModeGeneral) != (candidate_rows != 0)) return;
+                                                           RowState* __restrict__ rs) {
+  if (rs[blockIdx.x].mode != kModeGeneral) return;
   __shared__ u64 lds[kScanBlock / 64];
   u64* t = tile_cnt + (size_t)blockIdx.x * tile_stride;
   u64 carry = 0;
@@ -516,7 +538,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ til
   }
   if (threadIdx.x == 0) {
     t[n_tiles] = carry;
-    if (!candidate_rows && rs[blockIdx.x].row_emit == 2u) {  // K = N: every non-zero entry is sent
+    if (rs[blockIdx.x].row_emit == 2u) {  // K = N: every non-zero entry is sent
       rs[blockIdx.x].c_gt = (u32)carry;
       rs[blockIdx.x].count = (u32)carry;
     }
@@ -526,11 +548,29 @@ __global__ __launch_bounds__(kScanBlock) void k_scan_tiles(u64* __restrict__ til
 // Emits the words of every tile at its scanned offset, in ascending index.
 // With a memory (`err` non-NULL) `grads` IS the memory buffer holding g, and every entry whose sign
 // is sent is overwritten with +0.0; a tile is read and rewritten by the same block only.
+// As the last kernel of a call it also ends the call for every row, whatever its route: counts[m],
+// the pad words of rows that selected zeros, the route counters, the NaN flag, the histograms back to
+// zero for the next call, and the rows' final state in the first state buffer.
 __global__ __launch_bounds__(kBlock) void k_emit_rows(const float* grads, u64 N, u64 K, const RowState* __restrict__ rs,
-                                                      const u64* __restrict__ tile_cnt, u32 n_tiles, u32 tile_stride,
-                                                      u32* __restrict__ words, float* err) {
-  const u32 m = blockIdx.y;
+                                                      RowState* __restrict__ rs_copy, const u64* __restrict__ tile_cnt, u32 n_tiles,
+                                                      u32 tile_stride, u32* __restrict__ words, float* err, u32* __restrict__ counts,
+                                                      u32* __restrict__ status, u32* __restrict__ nan_flag, u32* __restrict__ hist) {
+  const u32 m = blockIdx.y, M = gridDim.y;
   const RowState st = rs[m];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (nan_flag && m == 0) *nan_flag = status[0] ? 1u : 0u;  // every kernel that raises it has run
+    counts[m] = st.count;
+    if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
+    if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
+    if (st.mode == kModeGeneral && st.row_emit) atomicAdd(&status[5], 1u);
+    if (rs_copy) rs_copy[m] = st;
+  }
+  for (u64 i = (u64)st.count + blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x)
+    words[(size_t)m * K + i] = S3GD_PAD;
+  for (int stage = 0; stage < kHistStages; ++stage) {
+    u32* h = stage_hist(hist, stage, M, m);
+    for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < (u32)kHistBins; i += gridDim.x * blockDim.x) h[i] = 0;
+  }
   if (st.mode != kModeGeneral) return;
   __shared__ u32 lds[kLoads * kWaves];
   const float* row = grads + (size_t)m * N;
@@ -631,17 +671,25 @@ __host__ __device__ __forceinline__ u64 sample_unit_start(u32 u, u64 stride) {
 u64 sample_unit_position(u32 u, u64 stride) { return sample_unit_start(u, stride); }
 
 // Histogram of one radix level over the sample of each row (gathered straight from the row).
-// Level 0: key bits [30:20] into 2048 bins.  Level 1: key bits [19:10] of the keys under L's prefix
-// into bins 0..1023 and of the keys under U's prefix into bins 1024..2047.
+// Level 0: key bits [30:20] into 2048 bins; its first block per row also resets the row's state and
+// counters for the call.  Level 1: every block first resolves level 0, then key bits [19:10] of the
+// keys under L's prefix go into bins 0..1023 and of the keys under U's prefix into bins 1024..2047.
 // With a memory (`err` non-NULL) the sampled value is g~ + eta * e.
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict__ grads, const float* __restrict__ err, float eta, u64 N,
-                                                        const RowState* __restrict__ rs, u32* __restrict__ hist, u32 n_units,
-                                                        u64 unit_stride) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
+                                                        const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
+                                                        RowCounters* __restrict__ rc, u32* __restrict__ status, u32* __restrict__ hist,
+                                                        u32 n_units, u64 unit_stride, u32 rank_lo, u32 rank_hi, u32 first_alloc) {
+  const u32 m = blockIdx.y, M = gridDim.y;
   __shared__ u32 h[kHistBins];
+  __shared__ u32 lds[kResolveLds];
+  RowState st{};
+  if (LEVEL == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) init_row(rs_out, rc, status, m, M, rank_lo, rank_hi, kModeCandidates, first_alloc, 0u);
+  } else {
+    st = advance_sample0(rs_in[m], stage_hist(hist, kStageSample0, M, m), lds);
+    if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+  }
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   __syncthreads();
   const u32* row = reinterpret_cast<const u32*>(grads + (size_t)m * N);
@@ -664,9 +712,10 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
     }
   }
   __syncthreads();
+  u32* out = stage_hist(hist, LEVEL == 0 ? kStageSample0 : kStageSample1, M, m);
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
-    if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
+    if (c) atomicAdd(&out[i], c);
   }
 }
 
@@ -892,17 +941,23 @@ __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, 
 }
 
 // The filter pass over rows that are read only: persistent waves, each with a range of its own.
-__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, RowState* __restrict__ rs, u32* __restrict__ hist,
-                                                   u32* __restrict__ cand, uint2* __restrict__ recs, u32 cand_stride, u32 brk_stride,
-                                                   u32 brk_shift, u64* __restrict__ wave_seg, u64* __restrict__ wave_segb,
-                                                   u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_wtiles, u32 tiles_per_wave, u32 slab,
+// Every block first resolves the second level of the sample: the bounds L and U of its row.
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ grads, u64 N, u32 K, const RowState* __restrict__ rs_in,
+                                                   RowState* __restrict__ rs_out, RowCounters* __restrict__ rc, u32* __restrict__ hist,
+                                                   CandTables t, u32 n_wtiles, u32 tiles_per_wave, u32 slab, u32 rank_lo, u32 sample_cap,
                                                    u32* __restrict__ status) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;
+  const u32 m = blockIdx.y, M = gridDim.y;
   __shared__ u32 h[kHistBins];
   __shared__ u64 stage_all[kWaves][kStage];
+  __shared__ u32 lds[kResolveLds];
   __shared__ u32 block_cand, block_brk;
+  bool diverted;
+  const RowState st = advance_sample1(rs_in[m], stage_hist(hist, kStageSample1, M, m), K, rank_lo, 1u, sample_cap, lds, &diverted);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    rs_out[m] = st;
+    if (diverted) atomicAdd(&status[7], 1u);
+  }
+  if (st.mode != kModeCandidates) return;  // block-uniform
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
   if (threadIdx.x == 0) { block_cand = 0; block_brk = 0; }
   __syncthreads();
@@ -911,17 +966,17 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
   const u64 vend = N + a;
   const u32 lane = lane_id(), wave = threadIdx.x >> 6;
-  u32* out = cand + (size_t)m * cand_stride;
-  uint2* outb = recs + (size_t)m * brk_stride;
+  u32* out = t.cand + (size_t)m * t.cand_stride;
+  uint2* outb = t.recs + (size_t)m * t.brk_stride;
   u64* stage = stage_all[wave];
   const u32 g = blockIdx.x * kWaves + wave;  // the wave's position among the waves of its row
   FilterWave w{};
-  w.cur = g * slab;  // the wave's first slab; rs[m].n_alloc starts past all of them
+  w.cur = g * slab;  // the wave's first slab; the row's slot counter starts past all of them
   w.end = w.cur + slab;
   w.seg_base = w.cur;
-  w.brk_cap = slab >> brk_shift;
-  w.segs = wave_seg + ((size_t)m * wave_stride + g) * kChain;
-  w.segsb = wave_segb + ((size_t)m * wave_stride + g) * kChain;
+  w.brk_cap = slab >> t.brk_shift;
+  w.segs = t.wave_seg + ((size_t)m * t.wave_stride + g) * kChain;
+  w.segsb = t.wave_segb + ((size_t)m * t.wave_stride + g) * kChain;
   const u32 t0 = (blockIdx.x * kWaves + wave) * tiles_per_wave;
   const u32 t1 = t0 + tiles_per_wave < n_wtiles ? t0 + tiles_per_wave : n_wtiles;
   // interior tiles: [first, last) where the tile neither starts before the row nor ends after it
@@ -940,29 +995,31 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
       else load_filter_tile<false>(rowv, a, vend, tile + 1, lane, nxt);
     }
     if (tile >= first && tile < last)
-      filter_tile<true>(r, a, tile, lane, st.L, st.U, h, stage, &rs[m].n_alloc, out, outb, cand_stride, slab, brk_shift, w);
+      filter_tile<true>(r, a, tile, lane, st.L, st.U, h, stage, &rc[m].n_alloc, out, outb, t.cand_stride, slab, t.brk_shift, w);
     else
-      filter_tile<false>(r, a, tile, lane, st.L, st.U, h, stage, &rs[m].n_alloc, out, outb, cand_stride, slab, brk_shift, w);
+      filter_tile<false>(r, a, tile, lane, st.L, st.U, h, stage, &rc[m].n_alloc, out, outb, t.cand_stride, slab, t.brk_shift, w);
   }
   if (!w.overflow) {
-    flush_stage(w, stage, out, outb, lane, st.L, st.U, brk_shift, h);
-    close_segment(w, lane, brk_shift);
+    flush_stage(w, stage, out, outb, lane, st.L, st.U, t.brk_shift, h);
+    close_segment(w, lane, t.brk_shift);
   }
   if (lane == 0) {
-    wave_nseg[(size_t)m * wave_stride + g] = w.overflow ? 0u : w.n_seg;
+    t.wave_nseg[(size_t)m * t.wave_stride + g] = w.overflow ? 0u : w.n_seg;
+    t.look[(size_t)m * t.wave_stride + g] = 0;  // nothing published yet: the emit pass starts from here
     if (w.total) atomicAdd(&block_cand, w.total);
     if (w.nb_total) atomicAdd(&block_brk, w.nb_total);
-    if (w.overflow) rs[m].overflow = 1;
+    if (w.overflow) rc[m].overflow = 1;
   }
   if (w.nan) status[0] = 1;
   __syncthreads();
   // one addition per block for both counts: every wave of the row ends at about the same time, and
   // additions to one address complete one after the other
   if (threadIdx.x == 0 && block_cand)
-    atomicAdd(reinterpret_cast<unsigned long long*>(&rs[m].n_cand), ((unsigned long long)block_brk << 32) | block_cand);
+    atomicAdd(reinterpret_cast<unsigned long long*>(&rc[m].n_cand), ((unsigned long long)block_brk << 32) | block_cand);
+  u32* bins = stage_hist(hist, kStageFilter, M, m);
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
-    if (c) atomicAdd(&hist[(size_t)m * kHistBins + i], c);
+    if (c) atomicAdd(&bins[i], c);
   }
 }
 
@@ -1056,16 +1113,23 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
 }
 
 __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
-                                                          RowState* __restrict__ rs, u32* __restrict__ cand, uint2* __restrict__ recs,
-                                                          u32 cand_stride, u32 brk_stride, u64* __restrict__ list_seg,
-                                                          u64* __restrict__ list_segb, u32* __restrict__ list_nseg, u32 list_stride,
-                                                          u32 n_chunks, u32* __restrict__ status) {
+                                                          const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
+                                                          RowCounters* __restrict__ rc, CandTables t, u32 n_chunks,
+                                                          u32* __restrict__ status) {
   static_assert(kChunkTiles == 2, "the two wave tiles of a chunk are held in named registers");
   const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode != kModeCandidates) return;  // block-uniform
   __shared__ u32 wsum[kWaves], wsumb[kWaves];
   __shared__ u32 sbase, sbaseb;
+  // (the bounds L and U were resolved by a kernel of their own: this one has a block per 32 KB of the row)
+  const RowState st = rs_in[m];
+  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+  if (st.mode != kModeCandidates) return;  // block-uniform
+  u32* const cand = t.cand;
+  uint2* const recs = t.recs;
+  const u32 cand_stride = t.cand_stride, brk_stride = t.brk_stride, list_stride = t.wave_stride;
+  u64* const list_seg = t.wave_seg;
+  u64* const list_segb = t.wave_segb;
+  u32* const list_nseg = t.wave_nseg;
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
@@ -1111,13 +1175,13 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
     u32 base = 0, baseb = 0;
     bool fits = true;
     if (total) {
-      base = atomicAdd(&rs[m].n_alloc, total);
+      base = atomicAdd(&rc[m].n_alloc, total);
       fits = base + total <= cand_stride && base + total >= base;
       if (totalb) {
-        baseb = atomicAdd(&rs[m].n_alloc_b, totalb);
+        baseb = atomicAdd(&rc[m].n_alloc_b, totalb);
         fits = fits && baseb + totalb <= brk_stride && baseb + totalb >= baseb;
       }
-      if (!fits) rs[m].overflow = 1;
+      if (!fits) rc[m].overflow = 1;
     }
     sbase = fits ? base : 0xFFFFFFFFu;
     sbaseb = baseb;
@@ -1126,6 +1190,7 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
     if (chunk % kChain == 0) {
       const u32 left = n_chunks - chunk;
       list_nseg[(size_t)m * list_stride + chunk / kChain] = left < (u32)kChain ? left : (u32)kChain;
+      t.look[(size_t)m * list_stride + chunk / kChain] = 0;  // nothing published yet: the emit pass starts from here
     }
   }
   __syncthreads();
@@ -1143,158 +1208,190 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
   }
 }
 
-// The kernels below walk the candidates of a row in ascending index: a wave per segment list.
-// Per list, against the final threshold: (records equal to T << 32) | (candidates that are selected
-// without being ties: the records above T and every candidate outside the bracket); scanned afterwards.
-__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs, const uint2* __restrict__ recs, u32 brk_stride,
-                                                       const u64* __restrict__ wave_seg, const u64* __restrict__ wave_segb,
-                                                       const u32* __restrict__ wave_nseg, u32 wave_stride, u32 n_waves,
-                                                       u64* __restrict__ wave_sum) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode == kModeGeneral) return;
-  const u32 lane = lane_id();
-  for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
-    const RecordWalk lw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
-    u32 gt = 0, eq = 0;
-    u32 done = 0;
-    if (lw.single && (lw.slot[0] & 1u) == 0) {  // wave-uniform: two records per lane and load, 16 bytes
-      const uint4* p4 = reinterpret_cast<const uint4*>(lw.pool + lw.slot[0]);
-      const u32 pairs = lw.total >> 1;
-      for (u32 i0 = lane; i0 < pairs; i0 += 64 * kWalk) {
-        uint4 c[kWalk];
-#pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-          const u32 j = i0 + (u32)u * 64u;
-          c[u] = j < pairs ? p4[j] : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-          const bool ok = i0 + (u32)u * 64u < pairs;
-          const u32 k0 = c[u].y & 0x7FFFFFFFu, k1 = c[u].w & 0x7FFFFFFFu;
-          gt += (ok && k0 > st.T) + (ok && k1 > st.T);
-          eq += (ok && k0 == st.T) + (ok && k1 == st.T);
-        }
-      }
-      done = pairs << 1;
+// ---- the emit pass of the candidate route --------------------------------------------------------
+// One wave per segment list, the lists of a row taken in order.  A wave
+//   1. (with its block) takes the last resolve step: the threshold T and the tie quota q;
+//   2. counts its list against them: the records above T, the records equal to T, and the
+//      candidates outside the bracket, which are selected whatever T is;
+//   3. publishes the counts and collects those of the lists before it (below), which gives the slot
+//      of its first word and the ties already served;
+//   4. copies its candidate words minus the bracket's losers (records below T, and the ties beyond
+//      the quota, which is applied in index order) to the row's message, in ascending index.  The
+//      losers of kDropRound candidates at a time are marked in an LDS bit map by a walk over the
+//      records, then the words of the round are copied past the marks.
+//      With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
+//
+// Step 3 is a scan along the lists without a pass of its own.  Every list has one 64-bit word:
+// (state << 62) | (ties << 31) | (selected without ties), state 0 = nothing yet, 1 = the list's own
+// counts, 2 = the counts of the list and of all lists before it.  A wave publishes its own counts,
+// then reads the words of the 64 lists before it at once: it waits (re-reads) until every list
+// between itself and the nearest list in state 2 has published, adds those counts up, and if there is
+// no list in state 2 among the 64 goes on with the 64 before them.  Then it publishes its own word in
+// state 2.  Waiting is safe: a wave only ever waits for lists with lower numbers, and blocks take
+// their lists from a counter in the order in which they start, so those lists belong to waves that
+// are running already and that wait, in turn, only for lower ones.  The words are cleared by the
+// filter pass, the counter by the call's first kernel.
+constexpr u32 kDropRound = 8192;
+constexpr u64 kLookMask = (1ull << 31) - 1;
+
+__device__ __forceinline__ u64 look_load(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void look_store(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Sum of the words published by lists 0 .. g-1 (fields added separately; each stays below 2^31).
+__device__ __forceinline__ u64 look_back(const u64* look, u32 g, u32 lane) {
+  u64 sum = 0;
+  int base = (int)g - 1;
+  while (base >= 0) {  // wave-uniform
+    const int idx = base - (int)lane;
+    u64 v = idx >= 0 ? look_load(look + idx) : (2ull << 62);  // before the first list: nothing, and final
+    const u64 incl = ballot((v >> 62) == 2ull);
+    const u32 stop = incl ? (u32)__builtin_ctzll(incl) : 64u;          // nearest list whose word covers all before it
+    const u64 need = stop >= 63u ? ~0ull : ((2ull << stop) - 1ull);     // the lanes up to and including it
+    if (ballot((v >> 62) == 0ull) & need) {  // somebody in between has not published yet: look again
+      __builtin_amdgcn_s_sleep(2);
+      continue;
     }
-    for (u32 i0 = done + lane; i0 < lw.total; i0 += 64 * kWalk) {
-      u32 key[kWalk];
+    u64 part = lane <= stop ? (v & ((1ull << 62) - 1)) : 0ull;
 #pragma unroll
-      for (int u = 0; u < kWalk; ++u) {
-        const u32 j = i0 + (u32)u * 64u;
-        key[u] = j < lw.total ? (lw.pool[lw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
-      }
-#pragma unroll
-      for (int u = 0; u < kWalk; ++u) {
-        gt += key[u] != 0xFFFFFFFFu && key[u] > st.T;
-        eq += key[u] == st.T;  // T is a key, never the filler
-      }
-    }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
-    gt += lw.words_total - lw.total;  // outside the bracket: all greater than T
-    if (lane == 0) wave_sum[(size_t)m * wave_stride + g] = ((u64)eq << 32) | gt;
+    for (int d = 32; d > 0; d >>= 1) part += __shfl_xor(part, d, 64);
+    sum += part;
+    if (stop < 64u) break;
+    base -= 64;
   }
+  return sum;
 }
 
-// Emits the words of each segment list at its scanned offset, in ascending index: the list's
-// candidate words minus the bracket's losers (records below T, and the ties beyond the quota, which
-// is applied in index order).  The losers of kDropRound candidates at a time are marked in an LDS bit
-// map by a walk over the records, then the words of the round are copied past the marks.
-// With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
-constexpr u32 kDropRound = 8192;
-__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, const u32* __restrict__ cand, const uint2* __restrict__ recs,
-                                                      u32 cand_stride, u32 brk_stride, const u64* __restrict__ wave_seg,
-                                                      const u64* __restrict__ wave_segb, const u32* __restrict__ wave_nseg, u32 wave_stride,
-                                                      u32 n_waves, const u64* __restrict__ wave_sum, u64 K, u32* __restrict__ words,
-                                                      float* __restrict__ err, u64 N) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (st.mode == kModeGeneral) return;
+__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
+                                                      RowCounters* __restrict__ rc, u32* __restrict__ hist, CandTables t, u64 K,
+                                                      u32* __restrict__ words, float* __restrict__ err, u64 N, u32 resolved) {
+  const u32 m = blockIdx.y, M = gridDim.y;
+  __shared__ u32 lds[kResolveLds];
   __shared__ u32 drop_all[kWaves][kDropRound / 32];
-  u32* drop = drop_all[threadIdx.x >> 6];
+  __shared__ u32 first_list;
+  RowState st = rs_in[m];
+  if (!resolved && (st.mode == kModeCandidates || st.mode == kModeCandWide)) st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), (u32)K, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+  if (st.mode == kModeGeneral) return;  // block-uniform
+  if (threadIdx.x == 0) first_list = atomicAdd(&rc[m].ticket, 1u) * kWaves;
+  __syncthreads();
   const u32 lane = lane_id();
+  const u32 g = first_list + (threadIdx.x >> 6);
+  if (g >= t.n_lists) return;  // whole waves leave; nothing below synchronises across waves
+  u32* drop = drop_all[threadIdx.x >> 6];
+  u64* look = t.look + (size_t)m * t.wave_stride;
   float* erow = err ? err + (size_t)m * N : nullptr;
   u32* out = words + (size_t)m * K;
-  for (u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6); g < n_waves; g += gridDim.x * kWaves) {  // wave-uniform
-    const WordWalk ww(wave_seg, wave_nseg, wave_stride, cand, cand_stride, m, g);
-    if (ww.total == 0) continue;
-    const RecordWalk rw(wave_seg, wave_segb, wave_nseg, wave_stride, recs, brk_stride, m, g);
-    const u64 before = wave_sum[(size_t)m * wave_stride + g];  // exclusive prefix over the lists before this one
-    u32 eq_seen = (u32)(before >> 32);
-    u32 o = (u32)before + (eq_seen < st.q ? eq_seen : st.q);
-    u32 rec_next = 0;  // records before this one are dealt with
-    for (u32 a0 = 0; a0 < ww.total; a0 += kDropRound) {  // wave-uniform
-      const u32 a1 = a0 + kDropRound < ww.total ? a0 + kDropRound : ww.total;
-      for (u32 i = lane; i < kDropRound / 32; i += 64) drop[i] = 0;
-      wave_sync();
-      // the records of candidates a0 .. a1-1: they ascend, so these are the next ones, up to the first beyond a1
-      while (rec_next < rw.total) {  // wave-uniform
-        const u32 j = rec_next + lane;
-        const bool ok = j < rw.total;
-        const uint2 rec = ok ? rw.pool[rw.locate(j)] : make_uint2(0, 0);
-        u32 seg_first = ww.first[0];  // number, in the list, of the first candidate of the record's segment
+  const WordWalk ww(t.wave_seg, t.wave_nseg, t.wave_stride, t.cand, t.cand_stride, m, g);
+  const RecordWalk rw(t.wave_seg, t.wave_segb, t.wave_nseg, t.wave_stride, t.recs, t.brk_stride, m, g);
+
+  // 2. the list's counts
+  u32 gt = 0, eq = 0;
+  for (u32 i0 = lane; i0 < rw.total; i0 += 64 * kWalk) {
+    u32 key[kWalk];
 #pragma unroll
-        for (int c = 1; c < kChain; ++c)
-          if (j >= rw.first[c] && rw.count[c]) seg_first = ww.first[c];
-        const u32 at = seg_first + rec.x;
-        const bool inside = ok && at < a1;
-        const u64 im = ballot(inside);
-        const u32 key = rec.y & 0x7FFFFFFFu;
-        const bool is_eq = inside && key == st.T;
-        const u64 eqm = ballot(is_eq);
-        const bool sel = inside && (key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q));
-        if (inside && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
-        eq_seen += (u32)__popcll(eqm);
-        const u32 n_in = (u32)__popcll(im);
-        rec_next += n_in;
-        if (n_in < 64u) break;  // the others belong to later rounds
-      }
-      wave_sync();
-      for (u32 i0 = a0; i0 < a1; i0 += 64 * kWalk) {  // wave-uniform trip count
-        u32 wd[kWalk];
+    for (int u = 0; u < kWalk; ++u) {
+      const u32 j = i0 + (u32)u * 64u;
+      key[u] = j < rw.total ? (rw.pool[rw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int u = 0; u < kWalk; ++u) {
+      gt += key[u] != 0xFFFFFFFFu && key[u] > st.T;
+      eq += key[u] == st.T;  // T is a key, never the filler
+    }
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+  gt += ww.total - rw.total;  // outside the bracket: all greater than T
+  const u64 own = ((u64)eq << 31) | gt;
+
+  // 3. the lists before this one
+  if (lane == 0 && g > 0) look_store(look + g, (1ull << 62) | own);
+  const u64 before = look_back(look, g, lane);
+  if (lane == 0) look_store(look + g, (2ull << 62) | (before + own));
+  u32 eq_seen = (u32)(before >> 31);
+  u32 o = (u32)(before & kLookMask) + (eq_seen < st.q ? eq_seen : st.q);
+
+  // 4. the words
+  u32 rec_next = 0;  // records before this one are dealt with
+  for (u32 a0 = 0; a0 < ww.total; a0 += kDropRound) {  // wave-uniform
+    const u32 a1 = a0 + kDropRound < ww.total ? a0 + kDropRound : ww.total;
+    // the first words of the round are requested before the records are walked
+    u32 wd[kWalk];
+#pragma unroll
+    for (int u = 0; u < kWalk; ++u) {
+      const u32 j = a0 + (u32)u * 64u + lane;
+      wd[u] = j < a1 ? ww.pool[ww.locate(j)] : 0u;
+    }
+    for (u32 i = lane; i < kDropRound / 32; i += 64) drop[i] = 0;
+    wave_sync();
+    // the records of candidates a0 .. a1-1: they ascend, so these are the next ones, up to the first beyond a1
+    while (rec_next < rw.total) {  // wave-uniform
+      const u32 j = rec_next + lane;
+      const bool ok = j < rw.total;
+      const uint2 rec = ok ? rw.pool[rw.locate(j)] : make_uint2(0, 0);
+      u32 seg_first = ww.first[0];  // number, in the list, of the first candidate of the record's segment
+#pragma unroll
+      for (int c = 1; c < kChain; ++c)
+        if (j >= rw.first[c] && rw.count[c]) seg_first = ww.first[c];
+      const u32 at = seg_first + rec.x;
+      const bool inside = ok && at < a1;
+      const u64 im = ballot(inside);
+      const u32 key = rec.y & 0x7FFFFFFFu;
+      const bool is_eq = inside && key == st.T;
+      const u64 eqm = ballot(is_eq);
+      const bool sel = inside && (key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q));
+      if (inside && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
+      eq_seen += (u32)__popcll(eqm);
+      const u32 n_in = (u32)__popcll(im);
+      rec_next += n_in;
+      if (n_in < 64u) break;  // the others belong to later rounds
+    }
+    wave_sync();
+    for (u32 i0 = a0; i0 < a1; i0 += 64 * kWalk) {  // wave-uniform trip count
+      if (i0 != a0) {
 #pragma unroll
         for (int u = 0; u < kWalk; ++u) {
           const u32 j = i0 + (u32)u * 64u + lane;
           wd[u] = j < a1 ? ww.pool[ww.locate(j)] : 0u;
         }
-#pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-          if (i0 + (u32)u * 64u >= a1) break;  // wave-uniform
-          const u32 j = i0 + (u32)u * 64u + lane;
-          const bool sel = j < a1 && !((drop[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u);
-          const u64 sel_mask = ballot(sel);
-          if (sel) {
-            const u32 pos = o + ballot_rank(sel_mask);
-            if (pos < K) {  // pos < K by construction
-              out[pos] = wd[u];
-              if (erow) erow[wd[u] >> 1] = 0.0f;
-            }
-          }
-          o += (u32)__popcll(sel_mask);
-        }
       }
-      wave_sync();  // the marks are cleared for the next round
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) {
+        if (i0 + (u32)u * 64u >= a1) break;  // wave-uniform
+        const u32 j = i0 + (u32)u * 64u + lane;
+        const bool sel = j < a1 && !((drop[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u);
+        const u64 sel_mask = ballot(sel);
+        if (sel) {
+          const u32 pos = o + ballot_rank(sel_mask);
+          if (pos < K) {  // pos < K by construction
+            out[pos] = wd[u];
+            if (erow) erow[wd[u] >> 1] = 0.0f;
+          }
+        }
+        o += (u32)__popcll(sel_mask);
+      }
     }
+    wave_sync();  // the marks are cleared for the next round
   }
 }
 
-// counts[m] and the pad words of rows that selected zeros.
-__global__ void k_finish_rows(const RowState* __restrict__ rs, u64 K, u32* __restrict__ words, u32* __restrict__ counts,
-                              u32* __restrict__ status, u32* __restrict__ nan_flag) {
-  const u32 m = blockIdx.y;
-  const RowState st = rs[m];
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (nan_flag && m == 0) *nan_flag = status[0] ? 1u : 0u;  // every kernel that raises it has run
-    counts[m] = st.count;
-    if (st.mode == kModeGeneral && !st.row_emit) atomicAdd(&status[1], 1u);
-    if (st.mode == kModeCandWide) atomicAdd(&status[4], 1u);
-    if (st.mode == kModeGeneral && st.row_emit) atomicAdd(&status[5], 1u);
+// A resolve step as a kernel of its own (one block per row), for the consumers whose grids are too
+// large to repeat it in every block.
+enum { kStepSample1 = 0, kStepRadix2Cand = 1 };
+template <int STEP>
+__global__ __launch_bounds__(kBlock) void k_advance(const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out, u32* __restrict__ hist,
+                                                    u32 K, u32 rank_lo, u32 have_bins, u32 sample_cap, u32* __restrict__ status) {
+  const u32 m = blockIdx.x, M = gridDim.x;
+  __shared__ u32 lds[kResolveLds];
+  RowState st = rs_in[m];
+  if (STEP == kStepSample1) {
+    bool diverted;
+    st = advance_sample1(st, stage_hist(hist, kStageSample1, M, m), K, rank_lo, have_bins, sample_cap, lds, &diverted);
+    if (threadIdx.x == 0 && diverted) atomicAdd(&status[7], 1u);
+  } else if (st.mode == kModeCandidates || st.mode == kModeCandWide) {
+    st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), K, lds);
   }
-  u32* out = words + (size_t)m * K;
-  for (u64 i = (u64)st.count + blockIdx.x * blockDim.x + threadIdx.x; i < K; i += (u64)gridDim.x * blockDim.x)
-    out[i] = S3GD_PAD;
+  if (threadIdx.x == 0) rs_out[m] = st;
 }
 
 __global__ void k_zero_counts(u32* counts, u32 M, u32* nan_flag) {
@@ -1436,6 +1533,10 @@ u64 candidate_pool_bytes(u32 M_max, u64 N_max, u64 K_max) {
 
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
 // g = grads + eta * err, and on return err holds the new memory g - TopK(g).
+//
+// A call on the candidate route is ten launches (sample x 2, filter, radix histograms x 3, emit,
+// and the three kernels of the general route, which return at once unless a row needs them): every
+// resolve step between two passes is taken by the blocks of the later pass.
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
                          u32* counts, hipStream_t s, u32* nan_flag) {
   Profiler& P = *ws.prof;
@@ -1465,72 +1566,84 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const dim3 grid(p.gx, M);
   const u32 k32 = (u32)K;
   const bool all = K == N;  // signSGD with majority vote: every non-zero entry is sent, nothing to select
-  S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<dim3(2, M), 256, 0, s>>>(ws.rs, ws.hist, ws.status, M, p.candidates ? p.sample_rank : k32,
-                                                                         p.candidates ? p.sample_rank_hi : 0u,
-                                                                         p.candidates ? kModeCandidates : kModeGeneral,
-                                                                         p.candidates && !p.chunks ? p.gx * (u32)kWaves * p.slab : 0u,
-                                                                         all ? 1u : 0u)));
-  const u32 n_waves = !p.candidates ? 0u : (p.chunks ? p.n_lists : p.gx * (u32)kWaves);  // segment lists per row
-  const u32 wstride = p.chunks ? p.n_lists + 4 : wave_stride(p.gx);
-  // the pool: the candidate words of every row, then their bracket records
-  u32* cand = reinterpret_cast<u32*>(ws.pool);
-  uint2* recs = reinterpret_cast<uint2*>(ws.pool + (((size_t)M * p.cand_stride * 4 + 15) & ~(size_t)15));
+  if (ws.hist_dirty) {
+    const u64 n = (u64)kHistStages * M * kHistBins;
+    S3GD_LAUNCH(KID_ENCODE_INIT, (k_clear_hist<<<(u32)((n + 1023) / 1024 < 256 ? (n + 1023) / 1024 : 256), 256, 0, s>>>(ws.hist, n)));
+  }
+  // the two state buffers: every kernel reads `cur` and writes `nxt`
+  RowState* cur = ws.rs;
+  RowState* nxt = ws.rs + ws.M_max;
+#define S3GD_SWAP do { RowState* t_ = cur; cur = nxt; nxt = t_; } while (0)
+  CandTables t{};
+  t.wave_seg = ws.wave_seg;
+  t.wave_segb = ws.wave_segb;
+  t.wave_nseg = ws.wave_nseg;
+  t.look = ws.wave_sum;
+  u32 have_bins = 1;
   if (p.candidates) {
-    const u32 n_wt = p.n_wtiles;
+    t.n_lists = p.chunks ? p.n_lists : p.gx * (u32)kWaves;  // segment lists per row
+    t.wave_stride = p.chunks ? p.n_lists + 4 : wave_stride(p.gx);
+    // the pool: the candidate words of every row, then their bracket records
+    t.cand = reinterpret_cast<u32*>(ws.pool);
+    t.recs = reinterpret_cast<uint2*>(ws.pool + (((size_t)M * p.cand_stride * 4 + 15) & ~(size_t)15));
+    t.cand_stride = p.cand_stride;
+    t.brk_stride = p.brk_stride;
+    t.brk_shift = p.brk_shift;
+    have_bins = p.chunks ? 0u : 1u;
     const dim3 sgrid((p.n_units * kSampleUnit + kSamplePerBlock - 1) / kSamplePerBlock, M);
     // sampled entries at or above L that stand for a row's whole share of the pool
     const double cap = (double)p.cand_stride * ((double)p.n_units * kSampleUnit / (double)N);
     const u32 sample_cap = cap < 1.0 ? 1u : (cap > 4.0e9 ? 0u : (u32)cap);
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_sample0<<<M, kBlock, 0, s>>>(ws.rs, ws.hist)));
-    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, ws.rs, ws.hist, p.n_units, p.unit_stride)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_sample1<<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.sample_rank, p.chunks ? 0u : 1u, sample_cap,
-                                                                     ws.status)));
-    if (p.chunks)
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, ws.rs, cand, recs, p.cand_stride,
-                                                                                         p.brk_stride, ws.wave_seg, ws.wave_segb,
-                                                                                         ws.wave_nseg, wstride, p.n_chunks, ws.status)));
-    else
-      S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, ws.rs, ws.hist, cand, recs, p.cand_stride, p.brk_stride, p.brk_shift,
-                                                               ws.wave_seg, ws.wave_segb, ws.wave_nseg, wstride, n_wt, p.tiles_per_wave,
-                                                               p.slab, ws.status)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve_filter<<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32, p.chunks ? 0u : 1u)));
+    const u32 first_alloc = p.chunks ? 0u : p.gx * (u32)kWaves * p.slab;
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<0><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, cur, cur, ws.rc, ws.status, ws.hist, p.n_units,
+                                                                       p.unit_stride, p.sample_rank, p.sample_rank_hi, first_alloc)));
+    S3GD_LAUNCH(KID_SAMPLE, (k_sample_hist<1><<<sgrid, kBlock, 0, s>>>(grads, mem, eta, N, cur, nxt, ws.rc, ws.status, ws.hist, p.n_units,
+                                                                       p.unit_stride, p.sample_rank, p.sample_rank_hi, first_alloc)));
+    S3GD_SWAP;
+    if (p.chunks) {
+      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepSample1><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, p.sample_rank, 0u, 0u, ws.status)));
+      S3GD_SWAP;
+      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t, p.n_chunks,
+                                                                                         ws.status)));
+    } else {
+      S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, k32, cur, nxt, ws.rc, ws.hist, t, p.n_wtiles, p.tiles_per_wave, p.slab,
+                                                               p.sample_rank, sample_cap, ws.status)));
+    }
+    S3GD_SWAP;
+  } else {
+    S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<(M + 255) / 256, 256, 0, s>>>(cur, ws.rc, ws.status, M, k32, all ? 1u : 0u)));
   }
   // Radix select: over the row for general rows, over the bracket's records for the others (the last
   // level only, unless the filter's bins could not place the K-th key).
-  // launches that walk segment lists: a wave per list, up to four rounds of resident blocks
-  u32 lx = (n_waves + kWaves - 1) / kWaves;
-  if (lx > 4 * p.gx) lx = 4 * p.gx;
-  if (lx < p.gx) lx = p.gx;
-  const dim3 lgrid(lx, M);
   const dim3 hgrid(p.candidates ? 4 * p.gx : p.gx, M);  // histogram launches
   // where the records' order does not matter a list is shared by as many waves as that grid has for it
-  u32 parts = n_waves ? hgrid.x * (u32)kWaves / n_waves : 1u;
+  u32 parts = t.n_lists ? hgrid.x * (u32)kWaves / t.n_lists : 1u;
   parts = parts < 1 ? 1u : (parts > 4 ? 4u : parts);
-#define S3GD_HIST_ARGS src, N, ws.rs, ws.hist, n_tiles, ws.status, recs, p.brk_stride, ws.wave_seg, ws.wave_segb, ws.wave_nseg, wstride, n_waves, parts
   if (!all) {
-    S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<0><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<1><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
-    S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(S3GD_HIST_ARGS)));
-    S3GD_LAUNCH(KID_RESOLVE, (k_resolve<2><<<M, kBlock, 0, s>>>(ws.rs, ws.hist, k32)));
+    S3GD_LAUNCH(KID_HIST0, (k_hist_rows<0><<<hgrid, kBlock, 0, s>>>(src, N, k32, cur, nxt, ws.rc, ws.hist, n_tiles, ws.status, t, parts, have_bins)));
+    S3GD_SWAP;
+    S3GD_LAUNCH(KID_HIST1, (k_hist_rows<1><<<hgrid, kBlock, 0, s>>>(src, N, k32, cur, nxt, ws.rc, ws.hist, n_tiles, ws.status, t, parts, have_bins)));
+    S3GD_SWAP;
+    S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(src, N, k32, cur, nxt, ws.rc, ws.hist, n_tiles, ws.status, t, parts, have_bins)));
+    S3GD_SWAP;
   }
-#undef S3GD_HIST_ARGS
-  if (p.candidates) {  // one wave per segment list
-    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<lgrid, kBlock, 0, s>>>(ws.rs, recs, p.brk_stride, ws.wave_seg, ws.wave_segb, ws.wave_nseg,
-                                                                      wstride, n_waves, ws.wave_sum)));
-    S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.wave_sum, n_waves, wstride, ws.rs, 1u)));
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<lgrid, kBlock, 0, s>>>(ws.rs, cand, recs, p.cand_stride, p.brk_stride, ws.wave_seg, ws.wave_segb,
-                                                                   ws.wave_nseg, wstride, n_waves, ws.wave_sum, K, words, err, N)));
+  if (p.candidates) {  // one wave per segment list, the blocks of a row taking their lists in the order they start
+    const u32 ex = (t.n_lists + kWaves - 1) / kWaves;
+    if (ex > 2048) {  // too many blocks to repeat the last resolve step in each
+      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepRadix2Cand><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status)));
+      S3GD_SWAP;
+    }
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(ex, M), kBlock, 0, s>>>(cur, nxt, ws.rc, ws.hist, t, K, words, err, N, ex > 2048 ? 1u : 0u)));
+    S3GD_SWAP;
   }
-  // General rows: per-tile counts and the emit pass (both return at once for the other rows).
-  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, ws.rs, ws.tile_cnt, n_tiles, stride, ws.status)));
-  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, ws.rs, 0u)));
-  S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, ws.rs, ws.tile_cnt, n_tiles, stride, words, err)));
-  u32 fx = (u32)((K + 4095) / 4096);
-  if (fx > 64) fx = 64;
-  S3GD_LAUNCH(KID_FINISH, (k_finish_rows<<<dim3(fx, M), 256, 0, s>>>(ws.rs, K, words, counts, ws.status, nan_flag)));
+  // General rows: per-tile counts and the emit pass (both return at once for the other rows); the emit
+  // kernel also ends the call for every row.
+  S3GD_LAUNCH(KID_TILE_COUNT, (k_tile_count<<<grid, kBlock, 0, s>>>(src, N, k32, cur, nxt, ws.hist, ws.tile_cnt, n_tiles, stride, ws.status)));
+  S3GD_SWAP;
+  S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_tiles<<<M, kScanBlock, 0, s>>>(ws.tile_cnt, n_tiles, stride, cur)));
+  S3GD_LAUNCH(KID_EMIT, (k_emit_rows<<<grid, kBlock, 0, s>>>(src, N, K, cur, cur == ws.rs ? nullptr : ws.rs, ws.tile_cnt, n_tiles, stride, words, err,
+                                                            counts, ws.status, nan_flag, ws.hist)));
+#undef S3GD_SWAP
 #undef S3GD_LAUNCH
   return hipGetLastError();
 }

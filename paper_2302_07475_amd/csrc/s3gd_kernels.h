@@ -60,19 +60,22 @@ constexpr u32 kCodingCapacity = 2;  // an output buffer was too small for the ve
 
 struct Workspace {
   Profiler* prof;
-  RowState* rs;   // [M]
+  RowState* rs;   // [2][M_max]  the two state buffers the kernels of a call alternate between; the final state ends in the first
+  RowCounters* rc;  // [M]
   u32* status;    // [8]: 0 = NaN seen, 1 = rows on the general path, 2 = rows of the last encode, 3 = coding flags,
                   //      4 = candidate rows whose radix select ran over all levels, 5 = rows whose words came from the
                   //      row passes with a threshold known beforehand (K = N), 6 = unused, 7 = rows that left the
                   //      candidate route before the filter pass (decided from the sample)
-  u32* hist;      // [M][kHistBins]
+  u32* hist;      // [kHistStages][M][kHistBins]: all zero between calls (the last kernel of a call clears what it used)
+  bool hist_dirty;  // the histograms may hold data (scratch shared with other shapes): clear them before the call
+  u32 M_max;
   u64* tile_cnt;  // [M][tile_stride]  (the coding kernels use it as u32 block sums)
   u32* seg;       // [M][tiles of the launch's tiling + 1], at most seg_row_entries(N) per row
   u64* blk_sum;   // [M][blk_stride]   scratch of the random-K scan
   u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment of candidate words
   u64* wave_segb; // [M][wave_stride][kChain]  the same for the segment's bracket records
   u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each list
-  u64* wave_sum;  // [M][wave_stride]  candidate route: (eq << 32 | selected without the ties) of each list, scanned in place
+  u64* wave_sum;  // [M][wave_stride]  candidate route: what each list publishes for the lists after it (emit pass)
   char* pool;     // candidate route: the candidate words of all rows, then their bracket records (carved per call);
                   // random-K: (word, arrival number) records
   u64 pool_bytes;

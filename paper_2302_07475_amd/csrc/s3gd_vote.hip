@@ -209,6 +209,42 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
       }
     }
   }
+  if (x && !tally && base + kMomTile <= N) {
+    // The fused sweep over a tile that lies inside the vector: four groups of four coordinates per lane
+    // at a time, the parameters of all four requested before any is written back.
+    constexpr int kGroups = 4;
+    for (u32 cb = lane * 4u; cb < kMomTile; cb += 256u * kGroups) {
+      int v[kGroups][4];
+      bool live[kGroups];
+      float4 xv[kGroups];
+#pragma unroll
+      for (int u = 0; u < kGroups; ++u) {
+        const u32 c0 = cb + (u32)u * 256u;
+        live[u] = !(FB == 8 && (t[c0 / 4] & 0x7F7F7F7Fu) == F::kFill);  // one word of 8-bit fields still holds the fill: nobody voted
+        if (live[u]) {
+          u32 any = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int d = tally_of(c0 + (u32)e);
+            v[u][e] = (d > 0) - (d < 0);
+            any |= (u32)v[u][e];
+          }
+          live[u] = any != 0;
+        }
+        if (live[u]) xv[u] = *reinterpret_cast<const float4*>(x + base + c0);
+      }
+#pragma unroll
+      for (int u = 0; u < kGroups; ++u) {
+        if (!live[u]) continue;
+        if (v[u][0]) xv[u].x = xv[u].x - lr * (float)v[u][0];
+        if (v[u][1]) xv[u].y = xv[u].y - lr * (float)v[u][1];
+        if (v[u][2]) xv[u].z = xv[u].z - lr * (float)v[u][2];
+        if (v[u][3]) xv[u].w = xv[u].w - lr * (float)v[u][3];
+        *reinterpret_cast<float4*>(x + base + cb + (u32)u * 256u) = xv[u];
+      }
+    }
+    return;
+  }
   if (tally || x) {
     for (u32 c0 = lane * 4u; c0 < kMomTile; c0 += 256u) {
       const u64 n = base + c0;

@@ -336,8 +336,7 @@ class Context:
     def last_row_state(self, m: int, stream=None) -> dict[str, int]:
         out = (_u32 * 16)()
         self._check(_lib.s3gd_last_row_state(self._h, _stream(stream), m, out), "s3gd_last_row_state")
-        names = ("prefix", "k_rem", "T", "q", "c_gt", "count", "mode", "L", "U", "overflow", "n_cand", "n_brk", "n_alloc",
-                 "n_alloc_b", "row_emit", "pad")
+        names = ("prefix", "k_rem", "T", "q", "c_gt", "count", "mode", "L", "U", "row_emit", "n_cand", "n_brk")
         return {k: int(v) for k, v in zip(names, out)}
 
     def calibrate_read(self, buf: torch.Tensor, stream=None):
