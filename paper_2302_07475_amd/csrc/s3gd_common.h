@@ -58,8 +58,7 @@ struct RowCounters {
   u32 n_alloc;    // candidate slots handed out (slab allocator / exact reservations)
   u32 n_alloc_b;  // filter pass in chunks: bracket slots handed out
   u32 overflow;   // a wave or block found no room for its candidates
-  u32 ticket;     // emit pass: blocks take their segment lists in the order they start
-  u32 pad[2];
+  u32 pad[3];
 };
 static_assert(sizeof(RowCounters) == 32, "RowCounters is half a 64-byte line");
 

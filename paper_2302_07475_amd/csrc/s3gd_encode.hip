@@ -93,11 +93,12 @@ struct RecordWalk {  // the bracket records of a list
 #pragma unroll
     for (int c = 0; c < kChain; ++c) {
       const u64 sg = segs[c], wg = wsegs[c];  // the whole lines are loaded; entries past n_seg are stale
-      slot[c] = (u32)(sg >> 32);
-      count[c] = (u32)c < n_seg ? (u32)sg : 0u;
+      // (the same in every lane: said so, they live in scalar registers)
+      slot[c] = __builtin_amdgcn_readfirstlane((u32)(sg >> 32));
+      count[c] = __builtin_amdgcn_readfirstlane((u32)c < n_seg ? (u32)sg : 0u);
       first[c] = total;
       total += count[c];
-      words_total += (u32)c < n_seg ? (u32)wg : 0u;
+      words_total += __builtin_amdgcn_readfirstlane((u32)c < n_seg ? (u32)wg : 0u);
     }
     single = __builtin_amdgcn_readfirstlane(n_seg <= 1u ? 1 : 0) != 0;
   }
@@ -135,8 +136,8 @@ struct WordWalk {  // the candidate words of a list
 #pragma unroll
     for (int c = 0; c < kChain; ++c) {
       const u64 sg = segs[c];
-      slot[c] = (u32)(sg >> 32);
-      count[c] = (u32)c < n_seg ? (u32)sg : 0u;
+      slot[c] = __builtin_amdgcn_readfirstlane((u32)(sg >> 32));
+      count[c] = __builtin_amdgcn_readfirstlane((u32)c < n_seg ? (u32)sg : 0u);
       first[c] = total;
       total += count[c];
     }
@@ -360,7 +361,6 @@ struct CandTables {
   u64* wave_seg;   // [M][wave_stride][kChain]
   u64* wave_segb;  // [M][wave_stride][kChain]
   u32* wave_nseg;  // [M][wave_stride]
-  u64* look;       // [M][wave_stride]  what each list publishes for the lists after it
   u32 wave_stride, n_lists;
 };
 
@@ -947,10 +947,12 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
                                                    CandTables t, u32 n_wtiles, u32 tiles_per_wave, u32 slab, u32 rank_lo, u32 sample_cap,
                                                    u32* __restrict__ status) {
   const u32 m = blockIdx.y, M = gridDim.y;
+  // A little over 40 KB of LDS: three blocks share a compute unit.  (With the resolve scratch taken from
+  // the stage area four fit, and the pass is 1 % to 6 % slower: more waves in flight help a stream of
+  // reads no further, and the stores of four blocks disturb it more than those of three.)
   __shared__ u32 h[kHistBins];
   __shared__ u64 stage_all[kWaves][kStage];
   __shared__ u32 lds[kResolveLds];
-  __shared__ u32 block_cand, block_brk;
   bool diverted;
   const RowState st = advance_sample1(rs_in[m], stage_hist(hist, kStageSample1, M, m), K, rank_lo, 1u, sample_cap, lds, &diverted);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -959,7 +961,6 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
   if (st.mode != kModeCandidates) return;  // block-uniform
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) h[i] = 0;
-  if (threadIdx.x == 0) { block_cand = 0; block_brk = 0; }
   __syncthreads();
   const float* row = grads + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
@@ -1005,17 +1006,19 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ gra
   }
   if (lane == 0) {
     t.wave_nseg[(size_t)m * t.wave_stride + g] = w.overflow ? 0u : w.n_seg;
-    t.look[(size_t)m * t.wave_stride + g] = 0;  // nothing published yet: the emit pass starts from here
-    if (w.total) atomicAdd(&block_cand, w.total);
-    if (w.nb_total) atomicAdd(&block_brk, w.nb_total);
     if (w.overflow) rc[m].overflow = 1;
   }
   if (w.nan) status[0] = 1;
+  __syncthreads();  // every wave is done with its stage
+  if (lane == 0) { lds[2 * wave] = w.total; lds[2 * wave + 1] = w.nb_total; }
   __syncthreads();
   // one addition per block for both counts: every wave of the row ends at about the same time, and
   // additions to one address complete one after the other
-  if (threadIdx.x == 0 && block_cand)
-    atomicAdd(reinterpret_cast<unsigned long long*>(&rc[m].n_cand), ((unsigned long long)block_brk << 32) | block_cand);
+  if (threadIdx.x == 0) {
+    u32 block_cand = 0, block_brk = 0;
+    for (int i = 0; i < kWaves; ++i) { block_cand += lds[2 * i]; block_brk += lds[2 * i + 1]; }
+    if (block_cand) atomicAdd(reinterpret_cast<unsigned long long*>(&rc[m].n_cand), ((unsigned long long)block_brk << 32) | block_cand);
+  }
   u32* bins = stage_hist(hist, kStageFilter, M, m);
   for (int i = threadIdx.x; i < kHistBins; i += kBlock) {
     const u32 c = h[i];
@@ -1190,7 +1193,6 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
     if (chunk % kChain == 0) {
       const u32 left = n_chunks - chunk;
       list_nseg[(size_t)m * list_stride + chunk / kChain] = left < (u32)kChain ? left : (u32)kChain;
-      t.look[(size_t)m * list_stride + chunk / kChain] = 0;  // nothing published yet: the emit pass starts from here
     }
   }
   __syncthreads();
@@ -1208,158 +1210,306 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
   }
 }
 
-// ---- the emit pass of the candidate route --------------------------------------------------------
-// One wave per segment list, the lists of a row taken in order.  A wave
-//   1. (with its block) takes the last resolve step: the threshold T and the tie quota q;
-//   2. counts its list against them: the records above T, the records equal to T, and the
-//      candidates outside the bracket, which are selected whatever T is;
-//   3. publishes the counts and collects those of the lists before it (below), which gives the slot
-//      of its first word and the ties already served;
-//   4. copies its candidate words minus the bracket's losers (records below T, and the ties beyond
-//      the quota, which is applied in index order) to the row's message, in ascending index.  The
-//      losers of kDropRound candidates at a time are marked in an LDS bit map by a walk over the
-//      records, then the words of the round are copied past the marks.
-//      With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
-//
-// Step 3 is a scan along the lists without a pass of its own.  Every list has one 64-bit word:
-// (state << 62) | (ties << 31) | (selected without ties), state 0 = nothing yet, 1 = the list's own
-// counts, 2 = the counts of the list and of all lists before it.  A wave publishes its own counts,
-// then reads the words of the 64 lists before it at once: it waits (re-reads) until every list
-// between itself and the nearest list in state 2 has published, adds those counts up, and if there is
-// no list in state 2 among the 64 goes on with the 64 before them.  Then it publishes its own word in
-// state 2.  Waiting is safe: a wave only ever waits for lists with lower numbers, and blocks take
-// their lists from a counter in the order in which they start, so those lists belong to waves that
-// are running already and that wait, in turn, only for lower ones.  The words are cleared by the
-// filter pass, the counter by the call's first kernel.
-constexpr u32 kDropRound = 8192;
-constexpr u64 kLookMask = (1ull << 31) - 1;
+// ---- the count and emit passes of the candidate route ---------------------------------------------
+// k_cand_count, a wave per segment list: takes the last resolve step (the threshold T and the tie
+// quota q) and leaves (records equal to T << 32) | (candidates that are selected without being ties:
+// the records above T and every candidate outside the bracket) of each list.
+// k_cand_emit, a block per segment list: adds up the counts of the lists before its own (every block
+// for itself, with all loads in flight at once: a row has at most a few thousand lists; beyond that a
+// scan kernel runs in between and the block reads its sum), which gives the slot of its first word
+// and the ties already served, then copies its candidate words minus the bracket's losers (records
+// below T, and the ties beyond the quota, which is applied in index order) to the row's message, in
+// ascending index.  The losers of kDropRound candidates at a time are marked in an LDS bit map by the
+// waves' walks over their records (a quarter of the list's records per wave); a wave then copies its
+// quarter of the round's words past the marks, its first slot following from the marks before its
+// quarter.  With a memory (`err` non-NULL), +0.0 goes over every entry whose sign is sent.
+// A list is the candidates of one wave of the filter pass (a few hundred to tens of thousands), and
+// every step of a walk over it is a round trip to memory: four waves per list, each with four groups
+// of 64 entries in flight, keep those chains short.
+constexpr u32 kDropRound = 65536;
+constexpr u32 kSumDirect = 2048;  // lists per row up to which an emit block adds up its predecessors' counts itself
 
-__device__ __forceinline__ u64 look_load(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void look_store(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-// Sum of the words published by lists 0 .. g-1 (fields added separately; each stays below 2^31).
-__device__ __forceinline__ u64 look_back(const u64* look, u32 g, u32 lane) {
-  u64 sum = 0;
-  int base = (int)g - 1;
-  while (base >= 0) {  // wave-uniform
-    const int idx = base - (int)lane;
-    u64 v = idx >= 0 ? look_load(look + idx) : (2ull << 62);  // before the first list: nothing, and final
-    const u64 incl = ballot((v >> 62) == 2ull);
-    const u32 stop = incl ? (u32)__builtin_ctzll(incl) : 64u;          // nearest list whose word covers all before it
-    const u64 need = stop >= 63u ? ~0ull : ((2ull << stop) - 1ull);     // the lanes up to and including it
-    if (ballot((v >> 62) == 0ull) & need) {  // somebody in between has not published yet: look again
-      __builtin_amdgcn_s_sleep(2);
-      continue;
-    }
-    u64 part = lane <= stop ? (v & ((1ull << 62) - 1)) : 0ull;
+// One group of kWalk * 64 entries of a walk, all loads issued together.
+template <typename Walk, typename T>
+__device__ __forceinline__ void load_group(const Walk& w, u32 j0, u32 end, u32 lane, T (&buf)[kWalk]) {
 #pragma unroll
-    for (int d = 32; d > 0; d >>= 1) part += __shfl_xor(part, d, 64);
-    sum += part;
-    if (stop < 64u) break;
-    base -= 64;
+  for (int u = 0; u < kWalk; ++u) {
+    const u32 j = j0 + (u32)u * 64u + lane;
+    buf[u] = j < end ? w.pool[w.locate(j)] : T{};
   }
-  return sum;
 }
 
-__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
-                                                      RowCounters* __restrict__ rc, u32* __restrict__ hist, CandTables t, u64 K,
-                                                      u32* __restrict__ words, float* __restrict__ err, u64 N, u32 resolved) {
+// The share of wave `wave` when `n` entries starting at `first` are dealt out to the block's waves in
+// runs of whole 64s.
+__device__ __forceinline__ void wave_share(u32 first, u32 n, u32 wave, u32 n_waves, u32* lo, u32* hi) {
+  const u32 each = (((n + n_waves - 1) / n_waves) + 63u) & ~63u;
+  const u32 a = wave * each < n ? wave * each : n;
+  const u32 b = a + each < n ? a + each : n;
+  *lo = first + a;
+  *hi = first + b;
+}
+
+__global__ __launch_bounds__(kBlock) void k_cand_count(const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
+                                                       u32* __restrict__ hist, CandTables t, u32 K, u64* __restrict__ list_counts,
+                                                       u32 resolved) {
   const u32 m = blockIdx.y, M = gridDim.y;
   __shared__ u32 lds[kResolveLds];
-  __shared__ u32 drop_all[kWaves][kDropRound / 32];
-  __shared__ u32 first_list;
   RowState st = rs_in[m];
-  if (!resolved && (st.mode == kModeCandidates || st.mode == kModeCandWide)) st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), (u32)K, lds);
-  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
-  if (st.mode == kModeGeneral) return;  // block-uniform
-  if (threadIdx.x == 0) first_list = atomicAdd(&rc[m].ticket, 1u) * kWaves;
-  __syncthreads();
+  if (st.mode == kModeGeneral) {  // block-uniform
+    if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+    return;
+  }
   const u32 lane = lane_id();
-  const u32 g = first_list + (threadIdx.x >> 6);
-  if (g >= t.n_lists) return;  // whole waves leave; nothing below synchronises across waves
-  u32* drop = drop_all[threadIdx.x >> 6];
-  u64* look = t.look + (size_t)m * t.wave_stride;
-  float* erow = err ? err + (size_t)m * N : nullptr;
-  u32* out = words + (size_t)m * K;
-  const WordWalk ww(t.wave_seg, t.wave_nseg, t.wave_stride, t.cand, t.cand_stride, m, g);
-  const RecordWalk rw(t.wave_seg, t.wave_segb, t.wave_nseg, t.wave_stride, t.recs, t.brk_stride, m, g);
-
-  // 2. the list's counts
+  const u32 g = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const bool mine = g < t.n_lists;  // wave-uniform
+  // the list's table and its first records are requested before the threshold is resolved
+  const RecordWalk rw(t.wave_seg, t.wave_segb, t.wave_nseg, t.wave_stride, t.recs, t.brk_stride, m, mine ? g : 0u);
+  uint2 rbuf[kWalk];
+  load_group(rw, 0u, mine ? rw.total : 0u, lane, rbuf);
+  if (!resolved && (st.mode == kModeCandidates || st.mode == kModeCandWide))
+    st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), K, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) rs_out[m] = st;
+  if (!mine) return;  // whole waves leave; nothing below synchronises across waves
   u32 gt = 0, eq = 0;
-  for (u32 i0 = lane; i0 < rw.total; i0 += 64 * kWalk) {
-    u32 key[kWalk];
+  for (u32 i0 = 0; i0 < rw.total; i0 += 64 * kWalk) {  // wave-uniform
+    uint2 rec[kWalk];
+    if (i0 == 0) {
 #pragma unroll
-    for (int u = 0; u < kWalk; ++u) {
-      const u32 j = i0 + (u32)u * 64u;
-      key[u] = j < rw.total ? (rw.pool[rw.locate(j)].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+      for (int u = 0; u < kWalk; ++u) rec[u] = rbuf[u];
+    } else {
+      load_group(rw, i0, rw.total, lane, rec);
     }
 #pragma unroll
     for (int u = 0; u < kWalk; ++u) {
-      gt += key[u] != 0xFFFFFFFFu && key[u] > st.T;
-      eq += key[u] == st.T;  // T is a key, never the filler
+      const bool ok = i0 + (u32)u * 64u + lane < rw.total;
+      const u32 key = rec[u].y & 0x7FFFFFFFu;
+      gt += ok && key > st.T;
+      eq += ok && key == st.T;
     }
   }
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
-  gt += ww.total - rw.total;  // outside the bracket: all greater than T
-  const u64 own = ((u64)eq << 31) | gt;
+  gt += rw.words_total - rw.total;  // outside the bracket: all greater than T
+  if (lane == 0) list_counts[(size_t)m * t.wave_stride + g] = ((u64)eq << 32) | gt;
+}
 
-  // 3. the lists before this one
-  if (lane == 0 && g > 0) look_store(look + g, (1ull << 62) | own);
-  const u64 before = look_back(look, g, lane);
-  if (lane == 0) look_store(look + g, (2ull << 62) | (before + own));
-  u32 eq_seen = (u32)(before >> 31);
-  u32 o = (u32)(before & kLookMask) + (eq_seen < st.q ? eq_seen : st.q);
+// In-place exclusive scan of the lists' counts of every row (rows with more than kSumDirect lists).
+__global__ __launch_bounds__(kScanBlock) void k_scan_lists(u64* __restrict__ list_counts, u32 n_lists, u32 stride,
+                                                           const RowState* __restrict__ rs) {
+  if (rs[blockIdx.x].mode == kModeGeneral) return;
+  __shared__ u64 lds[kScanBlock / 64];
+  u64* t = list_counts + (size_t)blockIdx.x * stride;
+  u64 carry = 0;
+  for (u32 base = 0; base < n_lists; base += kScanBlock * 4) {
+    const u32 i0 = base + threadIdx.x * 4;
+    u64 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = (i0 + k < n_lists) ? t[i0 + k] : 0;
+    const u64 s = v[0] + v[1] + v[2] + v[3];
+    u64 total;
+    u64 ex = carry + block_excl_scan<u64>(s, &total, lds);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (i0 + k < n_lists) t[i0 + k] = ex;
+      ex += v[k];
+    }
+    carry += total;
+  }
+}
 
-  // 4. the words
-  u32 rec_next = 0;  // records before this one are dealt with
-  for (u32 a0 = 0; a0 < ww.total; a0 += kDropRound) {  // wave-uniform
-    const u32 a1 = a0 + kDropRound < ww.total ? a0 + kDropRound : ww.total;
-    // the first words of the round are requested before the records are walked
-    u32 wd[kWalk];
+// The tables of one list in LDS (the emit pass: a block per list).
+struct ListTable {
+  u32 wslot[kChain], wcount[kChain], wfirst[kChain];  // words: first slot, length, flat number of the first word of each segment
+  u32 rslot[kChain], rcount[kChain], rfirst[kChain];  // records: the same
+  u32 wtotal, rtotal, nseg;
+};
+__device__ __forceinline__ u32 locate_word(const ListTable& lt, u32 j) {
+  if (lt.nseg <= 1u) return lt.wslot[0] + j;  // block-uniform
+  u32 at = 0;
 #pragma unroll
-    for (int u = 0; u < kWalk; ++u) {
-      const u32 j = a0 + (u32)u * 64u + lane;
-      wd[u] = j < a1 ? ww.pool[ww.locate(j)] : 0u;
+  for (int c = 0; c < kChain; ++c) {
+    const u32 d = j - lt.wfirst[c];  // wraps to a huge value for words of earlier segments
+    if (d < lt.wcount[c]) at = lt.wslot[c] + d;
+  }
+  return at;
+}
+// slot of record j, and the flat number of the first word of its segment
+__device__ __forceinline__ u32 locate_record(const ListTable& lt, u32 j, u32* seg_word) {
+  if (lt.nseg <= 1u) { *seg_word = 0; return lt.rslot[0] + j; }  // block-uniform
+  u32 at = 0, sw = 0;
+#pragma unroll
+  for (int c = 0; c < kChain; ++c) {
+    const u32 d = j - lt.rfirst[c];
+    if (d < lt.rcount[c]) { at = lt.rslot[c] + d; sw = lt.wfirst[c]; }
+  }
+  *seg_word = sw;
+  return at;
+}
+__device__ __forceinline__ void load_words(const ListTable& lt, const u32* pool, u32 j0, u32 end, u32 lane, u32 (&buf)[kWalk]) {
+#pragma unroll
+  for (int u = 0; u < kWalk; ++u) {
+    const u32 j = j0 + (u32)u * 64u + lane;
+    buf[u] = j < end ? pool[locate_word(lt, j)] : 0u;
+  }
+}
+// records with the flat number of their candidate in .x
+__device__ __forceinline__ void load_records(const ListTable& lt, const uint2* pool, u32 j0, u32 end, u32 lane, uint2 (&buf)[kWalk]) {
+#pragma unroll
+  for (int u = 0; u < kWalk; ++u) {
+    const u32 j = j0 + (u32)u * 64u + lane;
+    u32 seg_word = 0;
+    buf[u] = j < end ? pool[locate_record(lt, j, &seg_word)] : make_uint2(0, 0);
+    buf[u].x += seg_word;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, CandTables t, u64 K, const u64* __restrict__ list_counts,
+                                                      u32 scanned, u32* __restrict__ words, float* __restrict__ err, u64 N) {
+  const u32 m = blockIdx.y;
+  __shared__ u32 drop[kDropRound / 32];
+  __shared__ u32 part_eq[kWaves];
+  __shared__ u64 lists_before;
+  __shared__ ListTable lt;
+  const RowState st = rs[m];
+  if (st.mode == kModeGeneral) return;  // block-uniform
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;  // one, two or four waves per list
+  const u32 g = blockIdx.x;
+  const u64* counts = list_counts + (size_t)m * t.wave_stride;
+  // the counts of the lists before this one: the last wave adds them up, all loads in flight at once
+  u64 mine = 0;
+  if (wave == n_waves - 1) {
+    if (scanned) {
+      mine = lane == 0 ? counts[g] : 0ull;
+    } else {
+      for (u32 i = lane; i < g; i += 64) mine += counts[i];
     }
-    for (u32 i = lane; i < kDropRound / 32; i += 64) drop[i] = 0;
-    wave_sync();
-    // the records of candidates a0 .. a1-1: they ascend, so these are the next ones, up to the first beyond a1
-    while (rec_next < rw.total) {  // wave-uniform
-      const u32 j = rec_next + lane;
-      const bool ok = j < rw.total;
-      const uint2 rec = ok ? rw.pool[rw.locate(j)] : make_uint2(0, 0);
-      u32 seg_first = ww.first[0];  // number, in the list, of the first candidate of the record's segment
+  }
+  // the list's tables, by the first lanes of the first wave
+  if (threadIdx.x < (u32)kChain) {
+    const u32 c = threadIdx.x;
+    const u32 n_seg = t.wave_nseg[(size_t)m * t.wave_stride + g];
+    const u64 wg = t.wave_seg[((size_t)m * t.wave_stride + g) * kChain + c];
+    const u64 rg = t.wave_segb[((size_t)m * t.wave_stride + g) * kChain + c];
+    const u32 wc = c < n_seg ? (u32)wg : 0u, rcnt = c < n_seg ? (u32)rg : 0u;
+    lt.wslot[c] = (u32)(wg >> 32);
+    lt.rslot[c] = (u32)(rg >> 32);
+    lt.wcount[c] = wc;
+    lt.rcount[c] = rcnt;
+    u32 wf = 0, rf = 0, wt = 0, rt = 0;  // the eight lanes scan their counts
 #pragma unroll
-      for (int c = 1; c < kChain; ++c)
-        if (j >= rw.first[c] && rw.count[c]) seg_first = ww.first[c];
-      const u32 at = seg_first + rec.x;
-      const bool inside = ok && at < a1;
-      const u64 im = ballot(inside);
-      const u32 key = rec.y & 0x7FFFFFFFu;
-      const bool is_eq = inside && key == st.T;
-      const u64 eqm = ballot(is_eq);
-      const bool sel = inside && (key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q));
-      if (inside && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
-      eq_seen += (u32)__popcll(eqm);
-      const u32 n_in = (u32)__popcll(im);
-      rec_next += n_in;
-      if (n_in < 64u) break;  // the others belong to later rounds
+    for (int d = 0; d < kChain; ++d) {
+      const u32 wo = __shfl(wc, d, 64), ro = __shfl(rcnt, d, 64);
+      if ((u32)d < c) { wf += wo; rf += ro; }
+      wt += wo;
+      rt += ro;
     }
-    wave_sync();
-    for (u32 i0 = a0; i0 < a1; i0 += 64 * kWalk) {  // wave-uniform trip count
-      if (i0 != a0) {
+    lt.wfirst[c] = wf;
+    lt.rfirst[c] = rf;
+    if (c == 0) { lt.wtotal = wt; lt.rtotal = rt; lt.nseg = n_seg; }
+  }
+  __syncthreads();
+  if (lt.wtotal == 0) return;  // block-uniform
+  const u32* wpool = t.cand + (size_t)m * t.cand_stride;
+  const uint2* rpool = t.recs + (size_t)m * t.brk_stride;
+  u32 rlo, rhi;  // this wave's records
+  wave_share(0u, lt.rtotal, wave, n_waves, &rlo, &rhi);
+  u32 wlo, whi;  // this wave's words of the first round
+  wave_share(0u, lt.wtotal < kDropRound ? lt.wtotal : kDropRound, wave, n_waves, &wlo, &whi);
+  uint2 rbuf[kWalk];
+  u32 wbuf[kWalk];
+  load_records(lt, rpool, rlo, rhi, lane, rbuf);
+  load_words(lt, wpool, wlo, whi, lane, wbuf);
+  float* erow = err ? err + (size_t)m * N : nullptr;
+  u32* out = words + (size_t)m * K;
+  // the ties among this wave's records (the waves after it must know)
+  u32 eq = 0;
+  for (u32 i0 = rlo; i0 < rhi; i0 += 64 * kWalk) {  // wave-uniform
+    uint2 rec[kWalk];
+    if (i0 == rlo) {
 #pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-          const u32 j = i0 + (u32)u * 64u + lane;
-          wd[u] = j < a1 ? ww.pool[ww.locate(j)] : 0u;
-        }
+      for (int u = 0; u < kWalk; ++u) rec[u] = rbuf[u];
+    } else {
+      load_records(lt, rpool, i0, rhi, lane, rec);
+    }
+#pragma unroll
+    for (int u = 0; u < kWalk; ++u) eq += i0 + (u32)u * 64u + lane < rhi && (rec[u].y & 0x7FFFFFFFu) == st.T;
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) eq += __shfl_xor(eq, d, 64);
+  if (wave == n_waves - 1) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    if (lane == 0) lists_before = mine;
+  }
+  if (lane == 0) part_eq[wave] = eq;
+  if (threadIdx.x + n_waves < (u32)kWaves) part_eq[threadIdx.x + n_waves] = 0;  // the waves the block does not have
+  __syncthreads();
+  const u64 before = lists_before;  // (ties << 32) | selected without ties, over the lists before this one
+  u32 eq_first = (u32)(before >> 32);  // ties before this wave's first record
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w)
+    if ((u32)w < wave) eq_first += part_eq[w];
+  u32 o_round = (u32)before + ((u32)(before >> 32) < st.q ? (u32)(before >> 32) : st.q);
+  const u32 wtotal = lt.wtotal;
+
+  for (u32 a0 = 0; a0 < wtotal; a0 += kDropRound) {  // block-uniform
+    const u32 a1 = a0 + kDropRound < wtotal ? a0 + kDropRound : wtotal;
+    for (u32 i = threadIdx.x; i < (a1 - a0 + 31) / 32; i += blockDim.x) drop[i] = 0;
+    __syncthreads();
+    // this wave's records, in order: those of candidates before the round only count as ties seen, those
+    // of the round are marked if they lose, and the walk ends at the first one beyond the round
+    u32 eq_seen = eq_first;
+    for (u32 i0 = rlo; i0 < rhi; i0 += 64 * kWalk) {  // wave-uniform
+      uint2 rec[kWalk];
+      if (i0 == rlo) {
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) rec[u] = rbuf[u];
+      } else {
+        load_records(lt, rpool, i0, rhi, lane, rec);
       }
+      bool beyond = false;
 #pragma unroll
       for (int u = 0; u < kWalk; ++u) {
-        if (i0 + (u32)u * 64u >= a1) break;  // wave-uniform
+        const bool ok = i0 + (u32)u * 64u + lane < rhi;
+        const u32 at = rec[u].x;  // number of the record's candidate in the list
+        const bool upto = ok && at < a1;  // the records ascend: these lanes are the low ones
+        const u32 key = rec[u].y & 0x7FFFFFFFu;
+        const bool is_eq = upto && key == st.T;
+        const u64 eqm = ballot(is_eq);
+        const bool sel = key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q);
+        if (upto && at >= a0 && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
+        eq_seen += (u32)__popcll(eqm);
+        beyond = beyond || ballot(ok && !upto) != 0;
+      }
+      if (beyond) break;  // wave-uniform
+    }
+    __syncthreads();
+    // this wave's quarter of the round's words: its first slot follows from the marks before it
+    if (a0 != 0) wave_share(a0, a1 - a0, wave, n_waves, &wlo, &whi);
+    u32 marked = 0, marked_all = 0;
+    for (u32 i = lane; i < (a1 - a0 + 31) / 32; i += 64) {
+      const u32 c = (u32)__popc(drop[i]);
+      marked_all += c;
+      if (i * 32 < wlo - a0) marked += c;  // wlo - a0 is a multiple of 64: whole words
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) { marked += __shfl_xor(marked, d, 64); marked_all += __shfl_xor(marked_all, d, 64); }
+    u32 o = o_round + (wlo - a0) - marked;
+    u32 wd[kWalk];
+    if (a0 == 0) {
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) wd[u] = wbuf[u];
+    } else {
+      load_words(lt, wpool, wlo, whi, lane, wd);
+    }
+    for (u32 i0 = wlo; i0 < whi; i0 += 64 * kWalk) {  // wave-uniform trip count
+      u32 nx[kWalk];  // the next group is requested before this one is placed
+      load_words(lt, wpool, i0 + 64 * kWalk, whi, lane, nx);
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) {
+        if (i0 + (u32)u * 64u >= whi) break;  // wave-uniform
         const u32 j = i0 + (u32)u * 64u + lane;
-        const bool sel = j < a1 && !((drop[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u);
+        const bool sel = j < whi && !((drop[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u);
         const u64 sel_mask = ballot(sel);
         if (sel) {
           const u32 pos = o + ballot_rank(sel_mask);
@@ -1370,8 +1520,11 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
         }
         o += (u32)__popcll(sel_mask);
       }
+#pragma unroll
+      for (int u = 0; u < kWalk; ++u) wd[u] = nx[u];
     }
-    wave_sync();  // the marks are cleared for the next round
+    o_round += (a1 - a0) - marked_all;
+    __syncthreads();  // the marks are cleared for the next round
   }
 }
 
@@ -1534,9 +1687,9 @@ u64 candidate_pool_bytes(u32 M_max, u64 N_max, u64 K_max) {
 // `err` NULL: the rows of `grads` are compressed as they are.  Otherwise the rows are
 // g = grads + eta * err, and on return err holds the new memory g - TopK(g).
 //
-// A call on the candidate route is ten launches (sample x 2, filter, radix histograms x 3, emit,
-// and the three kernels of the general route, which return at once unless a row needs them): every
-// resolve step between two passes is taken by the blocks of the later pass.
+// A call on the candidate route is eleven launches (sample x 2, filter, radix histograms x 3, count,
+// emit, and the three kernels of the general route, which return at once unless a row needs them):
+// every resolve step between two passes is taken by the blocks of the later pass.
 hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, float eta, u32 M, u64 N, u64 K, u32* words,
                          u32* counts, hipStream_t s, u32* nan_flag) {
   Profiler& P = *ws.prof;
@@ -1578,7 +1731,6 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   t.wave_seg = ws.wave_seg;
   t.wave_segb = ws.wave_segb;
   t.wave_nseg = ws.wave_nseg;
-  t.look = ws.wave_sum;
   u32 have_bins = 1;
   if (p.candidates) {
     t.n_lists = p.chunks ? p.n_lists : p.gx * (u32)kWaves;  // segment lists per row
@@ -1627,14 +1779,23 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     S3GD_LAUNCH(KID_HIST2, (k_hist_rows<2><<<hgrid, kBlock, 0, s>>>(src, N, k32, cur, nxt, ws.rc, ws.hist, n_tiles, ws.status, t, parts, have_bins)));
     S3GD_SWAP;
   }
-  if (p.candidates) {  // one wave per segment list, the blocks of a row taking their lists in the order they start
-    const u32 ex = (t.n_lists + kWaves - 1) / kWaves;
-    if (ex > 2048) {  // too many blocks to repeat the last resolve step in each
+  if (p.candidates) {
+    const u32 cx = (t.n_lists + kWaves - 1) / kWaves;  // count: a wave per segment list
+    const u32 pre = cx > 2048 ? 1u : 0u;  // too many blocks to repeat the last resolve step in each
+    if (pre) {
       S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepRadix2Cand><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status)));
       S3GD_SWAP;
     }
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(ex, M), kBlock, 0, s>>>(cur, nxt, ws.rc, ws.hist, t, K, words, err, N, ex > 2048 ? 1u : 0u)));
+    S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(cx, M), kBlock, 0, s>>>(cur, nxt, ws.hist, t, k32, ws.wave_sum, pre)));
     S3GD_SWAP;
+    const u32 scanned = t.n_lists > kSumDirect ? 1u : 0u;
+    if (scanned) S3GD_LAUNCH(KID_SCAN_TILES, (k_scan_lists<<<M, kScanBlock, 0, s>>>(ws.wave_sum, t.n_lists, t.wave_stride, cur)));
+    // a block per list, of two or four waves by the length of the lists: every block is a chain of round
+    // trips to memory, and smaller blocks leave room for more of them at a time (measured with one, two
+    // and four waves on lists of 300 to 5000 candidates: two waves best throughout)
+    const double per_list = p.bound / (double)t.n_lists;
+    const u32 ew = per_list < 6144.0 ? 128u : (u32)kBlock;
+    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(t.n_lists, M), ew, 0, s>>>(cur, t, K, ws.wave_sum, scanned, words, err, N)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows); the emit
   // kernel also ends the call for every row.

@@ -75,7 +75,7 @@ struct Workspace {
   u64* wave_seg;  // [M][wave_stride][kChain]  candidate route: (first slot << 32) | count of each segment of candidate words
   u64* wave_segb; // [M][wave_stride][kChain]  the same for the segment's bracket records
   u32* wave_nseg; // [M][wave_stride]  candidate route: segments in each list
-  u64* wave_sum;  // [M][wave_stride]  candidate route: what each list publishes for the lists after it (emit pass)
+  u64* wave_sum;  // [M][wave_stride]  candidate route: (ties << 32) | (selected without ties) of each list against the threshold
   char* pool;     // candidate route: the candidate words of all rows, then their bracket records (carved per call);
                   // random-K: (word, arrival number) records
   u64 pool_bytes;

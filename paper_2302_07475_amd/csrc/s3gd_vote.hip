@@ -211,35 +211,44 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
   }
   if (x && !tally && base + kMomTile <= N) {
     // The fused sweep over a tile that lies inside the vector: four groups of four coordinates per lane
-    // at a time, the parameters of all four requested before any is written back.
+    // at a time, the parameters of all four requested before any is written back.  Every lane runs
+    // through every group whether anybody voted there or not (a wave only skips what all its lanes
+    // skip), so the work per group is kept small: with 8-bit fields the four votes of a word come out
+    // of a few bit operations on the whole word, and the step is applied as x - d with d one of
+    // lr, -lr, 0 (x - 0 keeps the bits of x, also of -0.0).
     constexpr int kGroups = 4;
+    const u32 lr_bits = __float_as_uint(lr);
     for (u32 cb = lane * 4u; cb < kMomTile; cb += 256u * kGroups) {
-      int v[kGroups][4];
-      bool live[kGroups];
+      u32 pos[kGroups], neg[kGroups];  // bit 8e: coordinate e of the group is voted up / down
       float4 xv[kGroups];
 #pragma unroll
       for (int u = 0; u < kGroups; ++u) {
         const u32 c0 = cb + (u32)u * 256u;
-        live[u] = !(FB == 8 && (t[c0 / 4] & 0x7F7F7F7Fu) == F::kFill);  // one word of 8-bit fields still holds the fill: nobody voted
-        if (live[u]) {
-          u32 any = 0;
+        if (FB == 8) {
+          const u32 v = t[c0 / 4] & 0x7F7F7F7Fu;  // four fields of 0x40 + tally
+          pos[u] = ((v + 0x3F3F3F3Fu) >> 7) & 0x01010101u;
+          neg[u] = (~(v + 0x40404040u) >> 7) & 0x01010101u;
+        } else {
+          pos[u] = 0;
+          neg[u] = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int d = tally_of(c0 + (u32)e);
-            v[u][e] = (d > 0) - (d < 0);
-            any |= (u32)v[u][e];
+            pos[u] |= (u32)(d > 0) << (8 * e);
+            neg[u] |= (u32)(d < 0) << (8 * e);
           }
-          live[u] = any != 0;
         }
-        if (live[u]) xv[u] = *reinterpret_cast<const float4*>(x + base + c0);
+        if (pos[u] | neg[u]) xv[u] = *reinterpret_cast<const float4*>(x + base + c0);
       }
 #pragma unroll
       for (int u = 0; u < kGroups; ++u) {
-        if (!live[u]) continue;
-        if (v[u][0]) xv[u].x = xv[u].x - lr * (float)v[u][0];
-        if (v[u][1]) xv[u].y = xv[u].y - lr * (float)v[u][1];
-        if (v[u][2]) xv[u].z = xv[u].z - lr * (float)v[u][2];
-        if (v[u][3]) xv[u].w = xv[u].w - lr * (float)v[u][3];
+        if (!(pos[u] | neg[u])) continue;
+        float* xe = &xv[u].x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const u32 d = ((pos[u] >> (8 * e)) & 1u) ? lr_bits : (((neg[u] >> (8 * e)) & 1u) ? (lr_bits ^ 0x80000000u) : 0u);
+          xe[e] = xe[e] - __uint_as_float(d);
+        }
         *reinterpret_cast<float4*>(x + base + cb + (u32)u * 256u) = xv[u];
       }
     }
