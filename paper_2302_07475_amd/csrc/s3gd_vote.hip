@@ -155,6 +155,17 @@ __device__ __forceinline__ void tally_wave_tile(const u32* __restrict__ words, u
   wave_sync();
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream_f4(const float* p) {
+  const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(q.x, q.y, q.z, q.w);
+}
+__device__ __forceinline__ void store_stream_f4(float* p, float4 a) {
+  f32x4 q;
+  q.x = a.x; q.y = a.y; q.z = a.z; q.w = a.w;
+  __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
+}
+
 // Dense variant: writes every element of tally and/or votes, optionally updates x.  A wave per
 // kMomTile coordinates: tally in its own LDS slice, then 16 votes (one 16-byte store) per lane and
 // round, and four tally entries (one 16-byte store) per lane and round.
@@ -220,6 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
     const u32 lr_bits = __float_as_uint(lr);
     for (u32 cb = lane * 4u; cb < kMomTile; cb += 256u * kGroups) {
       u32 pos[kGroups], neg[kGroups];  // bit 8e: coordinate e of the group is voted up / down
+      bool line[kGroups];
       float4 xv[kGroups];
 #pragma unroll
       for (int u = 0; u < kGroups; ++u) {
@@ -238,18 +250,22 @@ __global__ __launch_bounds__(kBlock) void k_vote_dense(const u32* __restrict__ w
             neg[u] |= (u32)(d < 0) << (8 * e);
           }
         }
-        if (pos[u] | neg[u]) xv[u] = *reinterpret_cast<const float4*>(x + base + c0);
+        // four lanes share 64 bytes of x: if one of them has a vote all four rewrite their part (the same
+        // bits where nothing moves), so that memory sees whole 64-byte writes and not 16-byte pieces,
+        // which it would have to merge by reading first
+        line[u] = ((ballot((pos[u] | neg[u]) != 0) >> (lane & 60u)) & 0xFull) != 0;
+        if (line[u]) xv[u] = load_stream_f4(x + base + c0);
       }
 #pragma unroll
       for (int u = 0; u < kGroups; ++u) {
-        if (!(pos[u] | neg[u])) continue;
+        if (!line[u]) continue;
         float* xe = &xv[u].x;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const u32 d = ((pos[u] >> (8 * e)) & 1u) ? lr_bits : (((neg[u] >> (8 * e)) & 1u) ? (lr_bits ^ 0x80000000u) : 0u);
           xe[e] = xe[e] - __uint_as_float(d);
         }
-        *reinterpret_cast<float4*>(x + base + cb + (u32)u * 256u) = xv[u];
+        store_stream_f4(x + base + cb + (u32)u * 256u, xv[u]);
       }
     }
     return;
@@ -525,17 +541,6 @@ __device__ __forceinline__ void momentum_group(float* __restrict__ x, float* __r
 constexpr int kMomRounds = 4;                      // groups of four coordinates a lane has in flight
 constexpr u32 kMomBatch = 256u * kMomRounds;       // coordinates of a wave per batch of rounds
 constexpr int kMomBatches = kMomTile / kMomBatch;  // batches per tile; the momenta of the next are fetched a batch ahead
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 load_stream_f4(const float* p) {
-  const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  return make_float4(q.x, q.y, q.z, q.w);
-}
-__device__ __forceinline__ void store_stream_f4(float* p, float4 a) {
-  f32x4 q;
-  q.x = a.x; q.y = a.y; q.z = a.z; q.w = a.w;
-  __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
-}
 
 template <int FB>
 __global__ __launch_bounds__(kBlock) void k_vote_momentum(const u32* __restrict__ words, u64 K, const u32* __restrict__ seg,
