@@ -439,6 +439,54 @@ def test_candidates_the_sample_missed_exhaust_the_pool(lib):
     assert np.array_equal(counts, cc) and np.array_equal(words, w)
 
 
+def test_list_longer_than_one_emit_round(lib):
+    """The emit pass marks the bracket's losers of 65536 candidates at a time.  One wave of the single
+    pass finds 80 all-candidate tiles in a row (dense K, so its slabs are large enough to hold them):
+    its list takes two rounds.  The row stays on the candidate route."""
+    rng = np.random.default_rng(15)
+    N = 1 << 28
+    K = N // 16
+    with lib.Context(1, N, K, device=0) as c:
+        plan = c.encode_plan_info(1, N, K)
+        assert plan["candidates"] and not plan["chunks"] and plan["tiles_per_wave"] >= 80, plan
+        assert plan["slab"] * 100 > 80 * 1024 << plan["record_shift"], f"the chain of this shape no longer holds 80 tiles: {plan}"
+        G = _row_with_dense_head(N, 80 * 1024, rng)[None, :]
+        G[0, 80 * 1024:] *= np.float32(100.0)  # spread the rest so that the bracket holds an ordinary share of it
+        words, counts, rows, general = _encode_only(c, G, K)
+        assert c.last_encode_details()[:2] == (1, 0)
+    _check_rows_exactly(G, K, words, counts)
+    assert (words[0, :80 * 1024] >> 1 == np.arange(80 * 1024)).all()
+
+
+def test_every_selected_entry_above_the_bracket(lib):
+    """A row built against the sample: exactly K large entries, none of them in a sampled unit, and a
+    middle level that fills the sample's upper ranks.  Both sampled bounds land on the middle level, so
+    the pass takes exactly K entries for sure and the whole bracket loses: the threshold is the
+    bracket's upper end and no radix select runs."""
+    rng = np.random.default_rng(16)
+    N, K = 1 << 22, 1 << 12
+    with lib.Context(2, N, K, device=0) as c:
+        plan = c.encode_plan_info(2, N, K)
+        assert plan["candidates"], plan
+        sampled = np.zeros(N, dtype=bool)
+        for u in range(plan["n_units"]):
+            p = lib.encode_sample_unit_start(u, plan["unit_stride"])
+            sampled[p:p + plan["sample_unit"]] = True
+        g = np.full(N, 0.001, dtype=np.float32)
+        g[rng.random(N) < 1.5 * K / N] = 0.5                      # the middle level, sampled like everything else
+        free = np.nonzero(~sampled)[0]
+        top = rng.choice(free, size=K, replace=False)               # the K entries to select: the sample sees none
+        g[top] = (100.0 + rng.random(K)).astype(np.float32) * np.sign(rng.standard_normal(K)).astype(np.float32)
+        G = np.stack([g, rng.standard_normal(N, dtype=np.float32)])
+        words, counts, rows, general = _encode_only(c, G, K)
+        st = c.last_row_state(0)
+        assert st["mode"] == 3 and st["n_cand"] - st["n_brk"] == K and st["T"] == st["U"] - 1, st
+        assert c.last_encode_details()[:2] == (2, 0)
+    w, cc = __import__("oracle.s3gd_oracle", fromlist=["x"]).topk_sign_encode(G, K)
+    assert np.array_equal(counts, cc) and np.array_equal(words, w)
+    assert np.array_equal(np.sort(top), (words[0] >> 1).astype(np.int64))
+
+
 def test_fresh_context_has_clear_status(lib):
     """The status words belong to the workspace, which is not cleared as a whole: a context created
     over memory that held other data before must still report no stale flag after its first call."""
