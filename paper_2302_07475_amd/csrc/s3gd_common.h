@@ -55,12 +55,13 @@ static_assert(sizeof(RowState) == 64, "RowState is one 64-byte line");
 struct RowCounters {
   u32 n_cand;     // candidates the filter pass kept ...
   u32 n_brk;      // ... and those of them inside the bracket (the two are added to as one 64-bit word)
-  u32 n_alloc;    // candidate slots handed out (slab allocator / exact reservations)
-  u32 n_alloc_b;  // filter pass in chunks: bracket slots handed out
+  u32 n_alloc;    // candidate slots handed out (slab allocator / exact reservations) ...
+  u32 n_alloc_b;  // ... and, by the filter pass in chunks, bracket slots (reserved together, as one 64-bit word)
   u32 overflow;   // a wave or block found no room for its candidates
   u32 pad[3];
 };
 static_assert(sizeof(RowCounters) == 32, "RowCounters is half a 64-byte line");
+static_assert(offsetof(RowCounters, n_cand) % 8 == 0 && offsetof(RowCounters, n_alloc) % 8 == 0, "the counter pairs are aligned 64-bit words");
 
 constexpr u32 kModeGeneral = 0;     // multi-pass radix select over the whole row
 constexpr u32 kModeCandidates = 1;  // sampled bounds, one filter pass, last ten key bits resolved among the bracket's candidates

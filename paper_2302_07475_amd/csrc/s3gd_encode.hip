@@ -1047,7 +1047,10 @@ __global__ __launch_bounds__(kBlock) void k_plain_read(const float* __restrict__
   if (seen == 0x7FFFFFFFu) *sink = seen;  // never: a wave sees at most 2^22 entries per launch shape used here
 }
 
-constexpr int kChunkWavesPerSimd = 6;  // see the measurements in the design notes: six waves per SIMD beat the five the kernel takes by itself
+// Six waves per SIMD (80 registers, seven of them spilled) measured 2 % faster than the five the kernel takes
+// by itself (85 registers); so did it against a variant that reaches six without spilling (its block sums
+// and wave number kept in scalar registers: 79 registers, 3 % slower on the same machine).
+constexpr int kChunkWavesPerSimd = 6;
 
 // ---- the filter pass with a memory, in chunks --------------------------------------------------
 // The row is g = grads + eta * err, and g is written over err as it is filtered (grads and err rows
@@ -1178,12 +1181,13 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
     u32 base = 0, baseb = 0;
     bool fits = true;
     if (total) {
-      base = atomicAdd(&rc[m].n_alloc, total);
-      fits = base + total <= cand_stride && base + total >= base;
-      if (totalb) {
-        baseb = atomicAdd(&rc[m].n_alloc_b, totalb);
-        fits = fits && baseb + totalb <= brk_stride && baseb + totalb >= baseb;
-      }
+      // one returning addition serves both pools (the two counters are one aligned 64-bit word): such
+      // additions complete one after the other, about 86 per microsecond, and every block makes one
+      const unsigned long long both = atomicAdd(reinterpret_cast<unsigned long long*>(&rc[m].n_alloc),
+                                                ((unsigned long long)totalb << 32) | total);
+      base = (u32)both;
+      baseb = (u32)(both >> 32);
+      fits = base + total <= cand_stride && base + total >= base && baseb + totalb <= brk_stride && baseb + totalb >= baseb;
       if (!fits) rc[m].overflow = 1;
     }
     sbase = fits ? base : 0xFFFFFFFFu;
