@@ -462,14 +462,14 @@ __global__ __launch_bounds__(kBlock) void k_apply_update(float* __restrict__ x, 
     const u32 k = r0 + (lane >> 2), part = lane & 3u;
     if (k < total) {
       const u32 vw = qv[part][k];
-      float4* p = reinterpret_cast<float4*>(x + (u64)qg[k] * 16 + part * 4);
-      float4 xv = *p;
+      float* p = x + (u64)qg[k] * 16 + part * 4;
+      float4 xv = load_stream_f4(p);
       const int a = (int8_t)(vw & 0xFF), b = (int8_t)((vw >> 8) & 0xFF), c = (int8_t)((vw >> 16) & 0xFF), d = (int8_t)(vw >> 24);
       if (a) xv.x = xv.x - lr * (float)a;
       if (b) xv.y = xv.y - lr * (float)b;
       if (c) xv.z = xv.z - lr * (float)c;
       if (d) xv.w = xv.w - lr * (float)d;
-      *p = xv;
+      store_stream_f4(p, xv);
     }
   }
   if (blockIdx.x == 0) {
