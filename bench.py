@@ -35,8 +35,18 @@ HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
 # HBM bytes per launch (read + written) of a workload's dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs of this same command, scaled by the factors a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for
 # WRITE_SIZE).  Counter figures cannot be taken inside this run; they are quoted with the file they come from.
-PROFILED_TRAFFIC = {
-    ("C5", "filter"): (19.2000e9 + 0.0620e9, "profiles/s3gd_step_C5_hbm_traffic.md"),
+PROFILED_TRAFFIC = {  # (workload, variant, dominant kernel): bytes read + bytes written per launch
+    ("C5", "", "filter"): (19.2003e9 + 0.0644e9, "profiles/s3gd_step_C5_hbm_traffic.md"),
+    ("C5", "three-calls", "filter"): (19.2003e9 + 0.0644e9, "profiles/s3gd_three_calls_C5_hbm_traffic.md"),
+    ("C4", "", "filter"): (3.9688e9 + 0.0876e9, "profiles/s3gd_step_C4_hbm_traffic.md"),
+    ("C3", "", "filter"): (3.2792e9 + 0.0166e9, "profiles/s3gd_step_C3_hbm_traffic.md"),
+    ("C2", "", "filter"): (0.7181e9 + 0.0183e9, "profiles/s3gd_step_C2_hbm_traffic.md"),
+    ("C4", "sparsity 0.1", "filter"): (3.9688e9 + 0.5572e9, "profiles/s3gd_step_C4_gamma0.1_hbm_traffic.md"),
+    ("C5", "memory", "filter_mem"): (38.4205e9 + 21.2991e9, "profiles/s3gd_step_ec_C5_hbm_traffic.md"),
+    ("C5", "memory-acc", "filter"): (19.2004e9 + 0.0644e9, "profiles/s3gd_step_acc_C5_hbm_traffic.md"),
+    ("C5", "momentum", "filter"): (19.2004e9 + 0.0643e9, "profiles/s3gd_step_momentum_C5_hbm_traffic.md"),
+    ("C5", "momentum dense-state", "vote_momentum"): (9.6932e9 + 9.6004e9, "profiles/s3gd_step_momentum_dense_C5_hbm_traffic.md"),
+    ("C5", "wire", "filter"): (19.2004e9 + 0.0644e9, "profiles/s3gd_wire_format_C5_hbm_traffic.md"),
 }
 
 
@@ -84,7 +94,7 @@ def cpu_baseline(cfg, datagen):
 def kernel_bytes(name, M, N, K, rows, n_voted, dense_state, tally_out, votes_out):
     """Algorithmic bytes one launch of a kernel moves: what the step needs from that pass, not what the
     hardware counters saw.  `rows` = rows of G the pass actually reads."""
-    if name in ("filter", "hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows", "range_emit"):
+    if name in ("filter", "hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows"):
         return 4.0 * N * rows
     if name == "filter_mem":  # reads g~ and e, writes the new memory
         return 12.0 * N * rows
@@ -122,6 +132,9 @@ def main():
     ap.add_argument("--calibrate-read", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, time a plain non-temporal read of this size with the launch shape "
                          "of the selection pass (s3gd_calibrate_read): the practical read ceiling of the memory system")
+    ap.add_argument("--calibrate-rmw", type=float, default=0.0, metavar="GiB",
+                    help="instead of the benchmark, time b <- a + b over two buffers of this size with the launch shape of the "
+                         "selection pass with a memory (s3gd_calibrate_rmw): the practical ceiling of a two-reads-one-write stream")
     ap.add_argument("--wire", action="store_true",
                     help="time encode -> pack -> unpack -> vote+update: the step with the messages passed through the "
                          "compact wire format, as they would be around an exchange (not the headline workload)")
@@ -177,6 +190,26 @@ def main():
         print(json.dumps({"calibration": "plain non-temporal read, launch shape of the selection pass", "bytes_per_launch": 4 * n,
                           "launches": cnt, "ms_avg": ms / cnt, "GB_per_s": 4.0 * n / (ms / cnt * 1e-3) / 1e9,
                           "fraction_of_8TB_per_s": 4.0 * n / (ms / cnt * 1e-3) / HBM_PEAK}))
+        return
+    if args.calibrate_rmw > 0:
+        n = (int(args.calibrate_rmw * (1 << 30)) // 4) // 8192 * 8192
+        a = torch.ones(n, dtype=torch.float32, device=dev)
+        b = torch.zeros(n, dtype=torch.float32, device=dev)
+        ctx = s3gd.Context(4, min(n, s3gd.N_LIMIT), 1, device=0)
+        for _ in range(2):
+            ctx.calibrate_rmw(a, b)
+        ctx.profile_enable(2)
+        reps = 10
+        for _ in range(reps):
+            ctx.calibrate_rmw(a, b)
+        ms, cnt = ctx.profile_read()["plain_rmw"]
+        torch.cuda.synchronize()
+        if not bool((b == float(reps + 2)).all()):
+            log("bench.py: the calibration stream did not add up")
+            sys.exit(1)
+        print(json.dumps({"calibration": "plain b <- a + b, launch shape of the selection pass with a memory", "bytes_per_launch": 12 * n,
+                          "launches": cnt, "ms_avg": ms / cnt, "GB_per_s": 12.0 * n / (ms / cnt * 1e-3) / 1e9,
+                          "fraction_of_8TB_per_s": 12.0 * n / (ms / cnt * 1e-3) / HBM_PEAK}))
         return
     cfg = datagen.CONFIGS[args.workload]
     t0 = time.perf_counter()
@@ -292,13 +325,13 @@ def main():
         seen[w >> 1] = True
     n_voted = int(seen.sum().item())
     del seen
-    n_rows, general, _wide, row_pass, range_rows, skipped = routes
+    n_rows, general, _wide, row_pass, skipped = routes
     plan = ctx.encode_plan_info(M, N, K, with_memory=args.memory)
     # rows of G each pass reads (the kernels of routes no row takes are enqueued and return at once)
     rows_read = {"filter": (M - skipped) if plan["candidates"] and not plan["chunks"] else 0,
                  "filter_mem": M if plan["candidates"] and plan["chunks"] else 0,
                  "hist_rows_0": general, "hist_rows_1": general, "hist_rows_2": general,
-                 "tile_count": general + row_pass, "emit_rows": general + row_pass, "range_emit": range_rows}
+                 "tile_count": general + row_pass, "emit_rows": general + row_pass}
     if args.randk:
         rows_read = {}
 
@@ -326,7 +359,10 @@ def main():
     floor_bytes = (12.0 if args.memory else 4.0) * M * N + 8.0 * M * K + 8.0 * n_voted
     if args.randk:
         as_built = floor_bytes = 16.0 * M * K + 8.0 * n_voted
-    traffic = PROFILED_TRAFFIC.get((cfg.name, dom)) if not (is_variant or args.three_calls or args.sparsity > 0 or args.graph) else None
+    variant = " ".join(name for name, on in (("three-calls", args.three_calls), ("memory", args.memory), ("memory-acc", args.memory_acc),
+                                             ("momentum", args.momentum), ("dense-state", args.dense_state), ("wire", args.wire),
+                                             ("randk", args.randk), (f"sparsity {args.sparsity:g}", args.sparsity > 0)) if on)
+    traffic = PROFILED_TRAFFIC.get((cfg.name, variant, dom))
     entry = ("s3gd_step_randk (Algorithm 2)" if args.randk else
              "encode, pack, unpack, vote_update (messages through the wire format)" if args.wire else
              ("s3gd_step_momentum (mu=0.9" + (", with memory" if args.memory else "") +
@@ -345,7 +381,7 @@ def main():
         "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe, "entry": entry,
                    "rows": {"general_route": general, "wide_radix_select": _wide, "row_passes_known_threshold": row_pass,
-                            "second_pass_over_ranges": range_rows, "skipped_single_pass": skipped},
+                            "skipped_single_pass": skipped},
                    "launch": "HIP graph replay" if args.graph else "eager"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK, "algorithmic_bytes_per_launch": dom_bytes,

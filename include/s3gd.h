@@ -330,10 +330,8 @@ S3GD_API int s3gd_last_async_status(s3gd_ctx* ctx, s3gd_stream_t stream);
  * single-pass candidate filter did not apply to them, out[2] = rows served by the single pass whose
  * K-th magnitude lay far above the sampled bound (their radix select ran over all three levels of
  * the candidates instead of the last), out[3] = rows whose words came from a count and an emit pass
- * over the row with a threshold known beforehand (dense K with a memory; K == N), out[4] = rows whose
- * words came from a second pass over the row after the single pass (dense K), out[5] = rows of
- * out[1] that were recognised from the sample and skipped the single pass.  `out` is host memory,
- * 6 entries. */
+ * over the row with a threshold known beforehand (K == N), out[4] = rows of out[1] that were
+ * recognised from the sample and skipped the single pass.  `out` is host memory, 5 entries. */
 S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t* out);
 
 /*
@@ -381,6 +379,13 @@ S3GD_API const char* s3gd_profile_kernel_name(int id);
  * gives a read stream of that shape: the practical ceiling the selection pass is compared with.
  */
 S3GD_API int s3gd_calibrate_read(s3gd_ctx* ctx, const float* buf, uint64_t n, s3gd_stream_t stream);
+
+/*
+ * The same for the selection pass with a memory: reads n entries of `a` and of `b` and writes a + b
+ * over b (both dev, 16-byte aligned, not overlapping; whole chunks of 8192 entries only) with the
+ * launch shape, loads and stores of that pass and none of its selection work (kernel id "plain_rmw").
+ */
+S3GD_API int s3gd_calibrate_rmw(s3gd_ctx* ctx, const float* a, float* b, uint64_t n, s3gd_stream_t stream);
 
 /* hipError_t value of the last failed HIP call made through this context (0 if none). */
 S3GD_API int s3gd_last_hip_error(const s3gd_ctx* ctx);

@@ -517,8 +517,7 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
   out[1] = st[1];
   out[2] = st[4];
   out[3] = st[5];
-  out[4] = st[6];
-  out[5] = st[7];
+  out[4] = st[7];
   return S3GD_OK;
 }
 
@@ -599,7 +598,7 @@ S3GD_API const char* s3gd_profile_kernel_name(int id) {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
       "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
       "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum", "pack", "unpack",
-      "votes_to_message", "randk", "range_emit", "plain_read"};
+      "votes_to_message", "randk", "plain_read", "plain_rmw"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;
 }
 
@@ -608,6 +607,14 @@ S3GD_API int s3gd_calibrate_read(s3gd_ctx* ctx, const float* buf, uint64_t n, s3
   DeviceGuard g(ctx->device);
   if (g.err != hipSuccess) return hip_fail(ctx, g.err);
   const hipError_t e = launch_plain_read(ctx->ws, buf, n, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
+}
+
+S3GD_API int s3gd_calibrate_rmw(s3gd_ctx* ctx, const float* a, float* b, uint64_t n, s3gd_stream_t stream) {
+  if (!ctx || !a || !b || !aligned(a, 16) || !aligned(b, 16)) return S3GD_E_INVAL;
+  DeviceGuard g(ctx->device);
+  if (g.err != hipSuccess) return hip_fail(ctx, g.err);
+  const hipError_t e = launch_plain_rmw(ctx->ws, a, b, n, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? S3GD_OK : hip_fail(ctx, e);
 }
 

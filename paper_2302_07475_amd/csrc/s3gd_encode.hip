@@ -1047,6 +1047,28 @@ __global__ __launch_bounds__(kBlock) void k_plain_read(const float* __restrict__
   if (seen == 0x7FFFFFFFu) *sink = seen;  // never: a wave sees at most 2^22 entries per launch shape used here
 }
 
+// The chunked pass with a memory, bare: a block per 8192 consecutive entries, launched in index order,
+// reads its part of `a` and of `b` and writes a + b over b (the loads, the stores and the rounding of
+// k_filter_chunks with eta = 1, none of its counting, reserving or placing).
+__global__ __launch_bounds__(kBlock) void k_plain_rmw(const float* __restrict__ a, float* __restrict__ b) {
+  const u32* av = reinterpret_cast<const u32*>(a);
+  u32* bv = reinterpret_cast<u32*>(b);
+  const u32 lane = lane_id(), wave = threadIdx.x >> 6;
+  const u32 t0 = (blockIdx.x * kWaves + wave) * kChunkTiles;
+  TileRegs r[kChunkTiles], e[kChunkTiles];
+#pragma unroll
+  for (int k = 0; k < kChunkTiles; ++k) {
+    load_filter_tile<true>(av, 0, 0, t0 + k, lane, r[k]);
+    load_filter_tile<true>(bv, 0, 0, t0 + k, lane, e[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < kChunkTiles; ++k) {
+#pragma unroll
+    for (int i = 0; i < kLoads * 4; ++i) r[k].b[i] = compensate_bits(r[k].b[i], e[k].b[i], 1.0f);
+    store_filter_tile<true>(bv, t0 + k, lane, r[k]);
+  }
+}
+
 // Six waves per SIMD (80 registers, seven of them spilled) measured 2 % faster than the five the kernel takes
 // by itself (85 registers); so did it against a variant that reaches six without spilling (its block sums
 // and wave number kept in scalar registers: 79 registers, 3 % slower on the same machine).
@@ -1583,6 +1605,16 @@ hipError_t launch_plain_read(const Workspace& ws, const float* buf, u64 n, hipSt
   const u32 tiles_per_wave = (n_wtiles + gx * kWaves - 1) / (gx * kWaves);
   ws.prof->begin(KID_PLAIN_READ, s);
   k_plain_read<<<gx, kBlock, 0, s>>>(buf, n_wtiles, tiles_per_wave, ws.status + 7);
+  ws.prof->end(s);
+  return hipGetLastError();
+}
+
+hipError_t launch_plain_rmw(const Workspace& ws, const float* a, float* b, u64 n, hipStream_t s) {
+  const u64 n_chunks = n / ((u64)kWaveTile * kChunkTiles * kWaves);  // whole chunks only
+  if (n_chunks == 0) return hipSuccess;
+  if (n_chunks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  ws.prof->begin(KID_PLAIN_RMW, s);
+  k_plain_rmw<<<(u32)n_chunks, kBlock, 0, s>>>(a, b);
   ws.prof->end(s);
   return hipGetLastError();
 }

@@ -33,7 +33,7 @@ enum KernelId : int {
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
   KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,
   KID_PACK, KID_UNPACK, KID_VOTES_TO_MESSAGE, KID_RANDK,
-  KID_RANGE_EMIT, KID_PLAIN_READ,
+  KID_PLAIN_READ, KID_PLAIN_RMW,
   KID_COUNT
 };
 
@@ -46,7 +46,7 @@ struct Profiler {
   hipEvent_t* ev = nullptr;  // 2 * kPairs events, created when profiling is first enabled
   int kid[kPairs];
   void begin(int k, hipStream_t s) {
-    open = mode != 0 && used < kPairs && (mode == 1 || k == KID_FILTER || k == KID_FILTER_MEM || k == KID_RANDK || k == KID_PLAIN_READ);
+    open = mode != 0 && used < kPairs && (mode == 1 || k == KID_FILTER || k == KID_FILTER_MEM || k == KID_RANDK || k == KID_PLAIN_READ || k == KID_PLAIN_RMW);
     if (open) { kid[used] = k; (void)hipEventRecord(ev[2 * used], s); }
   }
   void end(hipStream_t s) {
@@ -110,6 +110,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                          u32* counts, hipStream_t s, u32* nan_flag = nullptr);
 // Plain non-temporal read of `n` fp32 entries with the filter pass's launch shape: what this memory system gives a read stream.
 hipError_t launch_plain_read(const Workspace& ws, const float* buf, u64 n, hipStream_t s);
+hipError_t launch_plain_rmw(const Workspace& ws, const float* a, float* b, u64 n, hipStream_t s);
 hipError_t launch_vote(const Workspace& ws, const u32* words, const u32* counts, u32 M, u64 N, u64 K, int32_t* tally,
                        int8_t* votes, float* x, float lr, hipStream_t s);
 hipError_t launch_update(const Workspace& ws, float* x, const int8_t* votes, float lr, u64 N, hipStream_t s);

@@ -24,7 +24,7 @@ EXPORTS = (
     "s3gd_apply_update", "s3gd_step", "s3gd_step_static", "s3gd_topk_sign_encode_ec", "s3gd_step_ec", "s3gd_topk_sign_encode_acc", "s3gd_step_acc",
     "s3gd_apply_update_momentum", "s3gd_step_momentum", "s3gd_vote_update", "s3gd_packed_row_words",
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
-    "s3gd_strerror", "s3gd_last_row_state", "s3gd_calibrate_read", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
+    "s3gd_strerror", "s3gd_last_row_state", "s3gd_calibrate_read", "s3gd_calibrate_rmw", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
 PROFILE_KERNELS = 27
 
@@ -89,6 +89,8 @@ _lib.s3gd_last_row_state.restype = _int
 _lib.s3gd_last_row_state.argtypes = [_vp, _vp, _u32, ctypes.POINTER(_u32)]
 _lib.s3gd_calibrate_read.restype = _int
 _lib.s3gd_calibrate_read.argtypes = [_vp, _vp, _u64, _vp]
+_lib.s3gd_calibrate_rmw.restype = _int
+_lib.s3gd_calibrate_rmw.argtypes = [_vp, _vp, _vp, _u64, _vp]
 _lib.s3gd_encode_plan_info.restype = _int
 _lib.s3gd_encode_plan_info.argtypes = [_vp, _u32, _u64, _u64, _int, ctypes.POINTER(_u64)]
 _lib.s3gd_encode_sample_unit_start.restype = _u64
@@ -326,10 +328,10 @@ class Context:
         """(rows, rows on the general route, single-pass rows that needed the full radix select)."""
         return self.last_encode_routes(stream)[:3]
 
-    def last_encode_routes(self, stream=None) -> tuple[int, int, int, int, int, int]:
-        """The six counters of s3gd_last_encode_info: rows, general route, wide radix select, row passes with a
-        known threshold, second pass over the waves' ranges, general rows that skipped the single pass."""
-        out = (_u32 * 6)()
+    def last_encode_routes(self, stream=None) -> tuple[int, int, int, int, int]:
+        """The five counters of s3gd_last_encode_info: rows, general route, wide radix select, row passes with a
+        known threshold, general rows that skipped the single pass."""
+        out = (_u32 * 5)()
         self._check(_lib.s3gd_last_encode_info(self._h, _stream(stream), out), "s3gd_last_encode_info")
         return tuple(int(v) for v in out)
 
@@ -342,6 +344,12 @@ class Context:
     def calibrate_read(self, buf: torch.Tensor, stream=None):
         """A plain read of `buf` (fp32) with the selection pass's launch shape; timed through the profile."""
         self._check(_lib.s3gd_calibrate_read(self._h, _ptr(buf), buf.numel(), _stream(stream)), "s3gd_calibrate_read")
+
+    def calibrate_rmw(self, a: torch.Tensor, b: torch.Tensor, stream=None):
+        """b <- a + b (fp32) with the launch shape of the selection pass with a memory; timed through the profile."""
+        if a.numel() != b.numel():
+            raise ValueError("calibrate_rmw: a and b differ in size")
+        self._check(_lib.s3gd_calibrate_rmw(self._h, _ptr(a), _ptr(b), a.numel(), _stream(stream)), "s3gd_calibrate_rmw")
 
     def encode_plan_info(self, M: int, N: int, K: int, with_memory: bool = False) -> dict[str, int]:
         """How an encode of this shape is laid over the device (see s3gd_encode_plan_info)."""
