@@ -412,9 +412,9 @@ __global__ __launch_bounds__(kBlock) void k_vote_sparse(const u32* __restrict__ 
 }
 
 // Standalone update from a materialised vote vector.  A lane takes 16 consecutive votes (one
-// 16-byte load) at a time, kUpd such groups per round with all their loads in flight together; where
-// a group holds a vote, the lane rewrites the whole 64 bytes of x that belong to it (memory merges a
-// smaller write by reading first).
+// 16-byte load) at a time, kUpd such groups with all their loads in flight together; a group that
+// holds a vote has the whole 64 bytes of x that belong to it rewritten (memory merges a smaller write
+// by reading first).
 constexpr int kUpd = 4;
 
 typedef u32 u32x4v __attribute__((ext_vector_type(4)));

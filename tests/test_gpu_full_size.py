@@ -140,8 +140,8 @@ def test_longest_row_the_word_format_allows(lib):
 
 
 def test_c4_at_a_tenth_of_the_coordinates(lib):
-    """K/N = 0.1, the sparsity the paper finds best for ten workers: the filter pass with a bracket
-    and the second pass over the wave ranges, at full size, on the recipe with ties and exact zeros."""
+    """K/N = 0.1, the sparsity the paper finds best for ten workers: the single pass that keeps a word per
+    candidate and records for the bracket only, at full size, on the recipe with ties and exact zeros."""
     cfg = dataclasses.replace(datagen.C4, K=datagen.C4.N // 10)
     _property_case(lib, cfg, sample_rows=(0, 5), samples_per_row=2)
 

@@ -135,8 +135,9 @@ def test_filter_chunk_boundaries(ctx, N):
 
 @pytest.mark.parametrize("gamma", [0.1, 0.3, 0.7, 1.0])
 def test_dense_sparsity_levels_with_memory(ctx, gamma):
-    """K/N up to 1 with the memory: the chunked filter pass keeps a bracket of one binade above the
-    sampled bound; two iterations so that the memory left by the first feeds the second."""
+    """K/N up to 1 with the memory: the chunked filter pass keeps the words of all candidates and
+    records for those between the two sampled bounds; two iterations so that the memory left by the
+    first feeds the second."""
     rng = np.random.default_rng(int(gamma * 100))
     M, N = 3, 262_147
     K = min(N, int(round(gamma * N)))
@@ -160,7 +161,7 @@ def test_dense_sparsity_levels_with_memory(ctx, gamma):
 def test_memory_already_holding_the_sum(ctx, shape, fused):
     """s3gd_topk_sign_encode_acc / s3gd_step_acc: the caller has formed g = g~ + e in the buffer.  Words,
     counts, the new memory and the parameters are those of the two-tensor call on (g~, e); every
-    route of the encode is taken (small rows, single pass, bracket, K = N, K = 0, fallback rows)."""
+    route of the encode is taken (small rows, single pass at sparse and dense K, K = N, K = 0, fallback rows)."""
     M, N, K = shape
     rng = np.random.default_rng(N + K)
     Gt = rng.standard_normal((M, N)).astype(np.float32)

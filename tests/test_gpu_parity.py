@@ -209,8 +209,8 @@ def _encode_only(ctx, G, K):
 @pytest.mark.parametrize("gamma", [0.07, 0.1, 0.25, 0.5, 0.9, 0.999, 1.0])
 def test_dense_sparsity_levels(ctx, gamma, kind):
     """K/N from 0.07 to 1 (the paper sweeps the sparsity up to 1, signSGD with majority vote): the
-    filter pass keeps a bracket around the K-th magnitude and counts what lies above; K = N selects
-    nothing.  Whatever route a row ends on, words, votes and parameters are the oracle's; on
+    filter pass keeps records for a bracket around the K-th magnitude and only the words of what lies
+    above; K = N selects nothing.  Whatever route a row ends on, words, votes and parameters are the oracle's; on
     well-spread data up to K = N/2 no row needs the general route."""
     from oracle import s3gd_oracle as O
     rng = np.random.default_rng(int(gamma * 1000))

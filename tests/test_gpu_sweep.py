@@ -2,8 +2,8 @@
 of the entry-point combinations (fused step, the three calls, with the memory, with momentum, random-K,
 through the wire format) and compared with the CPU oracle bit for bit (tolerance 0).  The
 cases are drawn so that every route of the encode is hit: rows below and above the smallest row the
-single pass serves (2^17 entries), K on both sides of N/16 (where the pass starts to keep a bracket
-instead of every candidate), K = N, K of a handful, ties, zeros, magnitudes spread over decades."""
+single pass serves (2^17 entries), K on both sides of N/16 and N/64 (where the sample and the share
+of records per candidate change), K = N, K of a handful, ties, zeros, magnitudes spread over decades."""
 import os
 
 import numpy as np
