@@ -339,7 +339,8 @@ S3GD_API int s3gd_last_encode_info(s3gd_ctx* ctx, s3gd_stream_t stream, uint32_t
  * is enqueued): for tests and benchmarks that have to know which internal route a shape takes.
  *   out  host, 12 entries:
  *     [0] 1 if the single-pass candidate route is planned (0: the multi-pass route for every row)
- *     [1] 1 if that pass runs as one block per 8192 entries (calls with a memory), 0: persistent waves
+ *     [1] 0: persistent waves; 1: that pass runs as one block per 8192 entries (calls with a memory);
+ *         3: it also stores +0.0 over the entries that are selected whatever the threshold (K >= N/512)
  *     [2] s: a run of n candidate slots comes with room for n >> s records of candidates whose
  *         selection is still open after the pass (the others are selected whatever the threshold)
  *     [3] blocks per row of the pass, four waves each   [4] 1024-entry tiles each wave covers, in a row

@@ -536,7 +536,7 @@ S3GD_API int s3gd_encode_plan_info(const s3gd_ctx* ctx, uint32_t M, uint64_t N, 
   const EncodePlan p = plan_encode(M, N, K, ctx->ws.pool_bytes, with_memory ? ctx->ws.stream_blocks_mem : ctx->ws.stream_blocks,
                                    with_memory != 0);
   out[0] = p.candidates;
-  out[1] = p.chunks;
+  out[1] = (p.chunks ? 1u : 0u) | (p.zero_sure ? 2u : 0u);
   out[2] = p.brk_shift;
   out[3] = p.gx;
   out[4] = p.tiles_per_wave;

@@ -357,6 +357,8 @@ enum { kStageSample0 = 0, kStageSample1 = 1, kStageFilter = 2, kStageRadix0 = 3 
 struct CandTables {
   u32* cand;       // [M][cand_stride] candidate words
   uint2* recs;     // [M][brk_stride]  bracket records
+  u32* kept;       // [M][cand_stride] the fp32 bits of every candidate, slot for slot with its word (only the
+                   // pass with a memory keeps them: it stores +0.0 over entries it takes for sure); else NULL
   u32 cand_stride, brk_stride, brk_shift;
   u64* wave_seg;   // [M][wave_stride][kChain]
   u64* wave_segb;  // [M][wave_stride][kChain]
@@ -873,6 +875,26 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
   }
 }
 
+// The same for the pass with a memory: entries whose key is at or above `sure_from` are stored as +0.0.
+template <bool INTERIOR>
+__device__ __forceinline__ void store_chunk_tile(u32* __restrict__ rowv, u32 tile, u32 lane, const TileRegs& r, u32 sure_from) {
+  const u64 vbase = (u64)tile * kWaveTile;
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    u32* p = rowv + vbase + (u64)j * 256 + (u64)lane * 4;
+    u32 v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (r.b[4 * j + e] & 0x7FFFFFFFu) >= sure_from ? 0u : r.b[4 * j + e];
+    if (INTERIOR || ((r.valid >> (4 * j)) & 0xFu) == 0xFu) {
+      store_stream16(p, v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if ((r.valid >> (4 * j + e)) & 1u) p[e] = v[e];
+    }
+  }
+}
+
 template <bool INTERIOR>
 __device__ __forceinline__ void filter_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32* h, u64* stage, u32* n_alloc,
                                             u32* __restrict__ out, uint2* __restrict__ outb, u32 cand_stride, u32 slab, u32 brk_shift,
@@ -1073,8 +1095,12 @@ __global__ __launch_bounds__(kBlock) void k_plain_rmw(const float* __restrict__ 
 
 // Six waves per SIMD (80 registers, seven of them spilled) measured 2 % faster than the five the kernel takes
 // by itself (85 registers); so did it against a variant that reaches six without spilling (its block sums
-// and wave number kept in scalar registers: 79 registers, 3 % slower on the same machine).
+// and wave number kept in scalar registers: 79 registers, 3 % slower on the same machine).  The form that
+// stores zeros over the sure entries needs 100 registers (the stored values are new 16-byte tuples beside
+// the tile's own): at six waves it spills 54 and is 10 % slower, at five it spills two and is 3 % slower
+// than the plain form, so it runs at five and only where the zeros it saves the emit pass outweigh that.
 constexpr int kChunkWavesPerSimd = 6;
+constexpr int kChunkWavesPerSimdZero = 5;
 
 // ---- the filter pass with a memory, in chunks --------------------------------------------------
 // The row is g = grads + eta * err, and g is written over err as it is filtered (grads and err rows
@@ -1109,7 +1135,7 @@ __device__ __forceinline__ void count_chunk_tile(const TileRegs& r, u32 L, u32 U
 // tile's first slots; `seg_word`: the first word slot of the chunk (records hold positions relative to it).
 template <bool INTERIOR>
 __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 tile, u32 lane, u32 L, u32 U, u32 first_word, u32 first_rec,
-                                                 u32 seg_word, u32* __restrict__ out, uint2* __restrict__ outb) {
+                                                 u32 seg_word, u32* __restrict__ out, uint2* __restrict__ outb, u32* __restrict__ kept) {
   const u64 v0 = (u64)tile * kWaveTile + (u64)lane * 4 - a;
   u32 run = first_word, runb = first_rec;
 #pragma unroll
@@ -1133,6 +1159,7 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
       if (pr[e]) {
         const u32 bits = r.b[4 * j + e];
         out[o] = ((u32)(v0 + (u64)j * 256 + e) << 1) | (bits >> 31);
+        if (kept) kept[o] = bits;  // (uniform)
         if (br[e]) { outb[ob] = make_uint2(o - seg_word, bits); ++ob; }
         ++o;
       }
@@ -1142,7 +1169,8 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
   }
 }
 
-__global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
+template <bool ZERO_SURE>
+__global__ __launch_bounds__(kBlock, ZERO_SURE ? kChunkWavesPerSimdZero : kChunkWavesPerSimd) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
                                                           const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
                                                           RowCounters* __restrict__ rc, CandTables t, u32 n_chunks,
                                                           u32* __restrict__ status) {
@@ -1178,13 +1206,19 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
     else { load_filter_tile<false>(rowv, a, vend, t0, lane, r0); load_filter_tile<false>(errv, a, vend, t0, lane, e0); }
     if (in1) { load_filter_tile<true>(rowv, a, vend, t1, lane, r1); load_filter_tile<true>(errv, a, vend, t1, lane, e1); }
     else { load_filter_tile<false>(rowv, a, vend, t1, lane, r1); load_filter_tile<false>(errv, a, vend, t1, lane, e1); }
-    // g = grads + eta * err goes over err right away: the stores are under way while the candidates are counted
+    // g = grads + eta * err goes over err right away: the stores are under way while the candidates are counted.
+    // ZERO_SURE: the entries at or above U go as +0.0: they are selected whatever the threshold turns out to
+    // be, and the emit pass is spared a scattered 4-byte store per sent entry.  Their magnitudes stay in
+    // `kept`, beside their words, for the rare row that is handed to the general route after all (k_restore_kept).
+    const u32 sure_from = ZERO_SURE ? st.U : kNoUpper;
 #pragma unroll
     for (int i = 0; i < kLoads * 4; ++i) r0.b[i] = compensate_bits(r0.b[i], e0.b[i], eta);
-    if (in0) store_filter_tile<true>(errv, t0, lane, r0); else store_filter_tile<false>(errv, t0, lane, r0);
+    if (ZERO_SURE) { if (in0) store_chunk_tile<true>(errv, t0, lane, r0, sure_from); else store_chunk_tile<false>(errv, t0, lane, r0, sure_from); }
+    else { if (in0) store_filter_tile<true>(errv, t0, lane, r0); else store_filter_tile<false>(errv, t0, lane, r0); }
 #pragma unroll
     for (int i = 0; i < kLoads * 4; ++i) r1.b[i] = compensate_bits(r1.b[i], e1.b[i], eta);
-    if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1);
+    if (ZERO_SURE) { if (in1) store_chunk_tile<true>(errv, t1, lane, r1, sure_from); else store_chunk_tile<false>(errv, t1, lane, r1, sure_from); }
+    else { if (in1) store_filter_tile<true>(errv, t1, lane, r1); else store_filter_tile<false>(errv, t1, lane, r1); }
   }
   u32 c0 = 0, b0 = 0, c1 = 0, b1 = 0;
   bool nan = false;
@@ -1225,16 +1259,21 @@ __global__ __launch_bounds__(kBlock, kChunkWavesPerSimd) void k_filter_chunks(co
   }
   __syncthreads();
   const u32 base = sbase, baseb = sbaseb;
+  if (ZERO_SURE && total != 0 && base == 0xFFFFFFFFu) {  // no room: nothing of this chunk is kept, so its part of g goes back whole
+    if (in0) store_chunk_tile<true>(errv, t0, lane, r0, kNoUpper); else store_chunk_tile<false>(errv, t0, lane, r0, kNoUpper);
+    if (in1) store_chunk_tile<true>(errv, t1, lane, r1, kNoUpper); else store_chunk_tile<false>(errv, t1, lane, r1, kNoUpper);
+  }
   if (total == 0 || base == 0xFFFFFFFFu) return;
   u32* out = cand + (size_t)m * cand_stride;
+  u32* kept = ZERO_SURE ? t.kept + (size_t)m * cand_stride : nullptr;
   uint2* outb = recs + (size_t)m * brk_stride;
   if (c0) {
-    if (in0) place_chunk_tile<true>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb);
-    else place_chunk_tile<false>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb);
+    if (in0) place_chunk_tile<true>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb, kept);
+    else place_chunk_tile<false>(r0, a, t0, lane, st.L, st.U, base + before, baseb + beforeb, base, out, outb, kept);
   }
   if (c1) {
-    if (in1) place_chunk_tile<true>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb);
-    else place_chunk_tile<false>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb);
+    if (in1) place_chunk_tile<true>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb, kept);
+    else place_chunk_tile<false>(r1, a, t1, lane, st.L, st.U, base + before + c0, baseb + beforeb + b0, base, out, outb, kept);
   }
 }
 
@@ -1395,6 +1434,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
                                                       u32 scanned, u32* __restrict__ words, float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   __shared__ u32 drop[kDropRound / 32];
+  __shared__ u32 won[kDropRound / 32];  // with `kept`: the bracket's winners, the only sent entries not yet zero in the memory
   __shared__ u32 part_eq[kWaves];
   __shared__ u64 lists_before;
   __shared__ ListTable lt;
@@ -1448,6 +1488,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
   load_records(lt, rpool, rlo, rhi, lane, rbuf);
   load_words(lt, wpool, wlo, whi, lane, wbuf);
   float* erow = err ? err + (size_t)m * N : nullptr;
+  const bool bracket_only = erow && t.kept;  // the filter pass has already stored +0.0 over the sure entries
   u32* out = words + (size_t)m * K;
   // the ties among this wave's records (the waves after it must know)
   u32 eq = 0;
@@ -1482,7 +1523,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
 
   for (u32 a0 = 0; a0 < wtotal; a0 += kDropRound) {  // block-uniform
     const u32 a1 = a0 + kDropRound < wtotal ? a0 + kDropRound : wtotal;
-    for (u32 i = threadIdx.x; i < (a1 - a0 + 31) / 32; i += blockDim.x) drop[i] = 0;
+    for (u32 i = threadIdx.x; i < (a1 - a0 + 31) / 32; i += blockDim.x) { drop[i] = 0; won[i] = 0; }
     __syncthreads();
     // this wave's records, in order: those of candidates before the round only count as ties seen, those
     // of the round are marked if they lose, and the walk ends at the first one beyond the round
@@ -1506,6 +1547,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
         const u64 eqm = ballot(is_eq);
         const bool sel = key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q);
         if (upto && at >= a0 && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
+        if (upto && at >= a0 && sel && bracket_only) atomicOr(&won[(at - a0) >> 5], 1u << ((at - a0) & 31u));
         eq_seen += (u32)__popcll(eqm);
         beyond = beyond || ballot(ok && !upto) != 0;
       }
@@ -1543,7 +1585,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
           const u32 pos = o + ballot_rank(sel_mask);
           if (pos < K) {  // pos < K by construction
             out[pos] = wd[u];
-            if (erow) erow[wd[u] >> 1] = 0.0f;
+            if (erow && (!bracket_only || ((won[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u))) erow[wd[u] >> 1] = 0.0f;
           }
         }
         o += (u32)__popcll(sel_mask);
@@ -1558,21 +1600,44 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
 
 // A resolve step as a kernel of its own (one block per row), for the consumers whose grids are too
 // large to repeat it in every block.
-enum { kStepSample1 = 0, kStepRadix2Cand = 1 };
+enum { kStepSample1 = 0, kStepRadix2Cand = 1, kStepFilter = 2 };
 template <int STEP>
 __global__ __launch_bounds__(kBlock) void k_advance(const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out, u32* __restrict__ hist,
-                                                    u32 K, u32 rank_lo, u32 have_bins, u32 sample_cap, u32* __restrict__ status) {
+                                                    u32 K, u32 rank_lo, u32 have_bins, u32 sample_cap, u32* __restrict__ status,
+                                                    const RowCounters* __restrict__ rcs) {
   const u32 m = blockIdx.x, M = gridDim.x;
+  const RowCounters* rc = rcs + m;
   __shared__ u32 lds[kResolveLds];
   RowState st = rs_in[m];
   if (STEP == kStepSample1) {
     bool diverted;
     st = advance_sample1(st, stage_hist(hist, kStageSample1, M, m), K, rank_lo, have_bins, sample_cap, lds, &diverted);
     if (threadIdx.x == 0 && diverted) atomicAdd(&status[7], 1u);
+  } else if (STEP == kStepFilter) {  // the row leaves kModeCandidates here when there are no bins, so the histogram pass does not repeat the step
+    if (st.mode == kModeCandidates) st = advance_filter(st, stage_hist(hist, kStageFilter, M, m), *rc, K, have_bins, lds);
   } else if (st.mode == kModeCandidates || st.mode == kModeCandWide) {
     st = advance_radix<2>(st, stage_hist(hist, kStageRadix0 + 2, M, m), K, lds);
   }
   if (threadIdx.x == 0) rs_out[m] = st;
+}
+
+// The pass with a memory stored +0.0 over the entries it took for sure.  A row that is handed to the general
+// route after that pass (its pool ran out, or more than K entries were at or above U) gets them back: every
+// candidate that found room has its bits in `kept`, slot for slot with its word (for the candidates inside
+// the bracket this rewrites what is there).  A wave per chunk of the pass; chunks without room kept nothing
+// and zeroed nothing (their table entry is empty).
+__global__ __launch_bounds__(kBlock) void k_restore_kept(const RowState* __restrict__ rs, CandTables t, u32 n_chunks, float* __restrict__ err, u64 N) {
+  const u32 m = blockIdx.y;
+  if (rs[m].mode != kModeGeneral) return;  // block-uniform
+  const u32 lane = lane_id();
+  const u32* words = t.cand + (size_t)m * t.cand_stride;
+  const u32* kept = t.kept + (size_t)m * t.cand_stride;
+  u32* row = reinterpret_cast<u32*>(err + (size_t)m * N);
+  for (u32 c = blockIdx.x * kWaves + (threadIdx.x >> 6); c < n_chunks; c += gridDim.x * kWaves) {
+    const u64 sg = t.wave_seg[(size_t)m * t.wave_stride * kChain + c];
+    const u32 base = (u32)(sg >> 32), count = (u32)sg;
+    for (u32 j = lane; j < count; j += 64) row[words[base + j] >> 1] = kept[base + j];
+  }
 }
 
 __global__ void k_zero_counts(u32* counts, u32 M, u32* nan_flag) {
@@ -1592,7 +1657,7 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
 u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks, kBlock, 0)
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks<false>, kBlock, 0)
                                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   const u32 n = (u32)cus * (u32)per_cu;
@@ -1693,7 +1758,10 @@ EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 pool_bytes, u32 stream_blocks, b
   if (need > 4.0e9) return p;
   p.cand_stride = ((u32)need + 3u) & ~3u;
   p.brk_stride = (((p.cand_stride >> p.brk_shift) + 64u) + 1u) & ~1u;
-  if ((double)M * (4.0 * p.cand_stride + 8.0 * p.brk_stride) > (double)pool_bytes) return p;
+  // with a memory, from K = N/512 on, the pass stores zeros over the entries it takes for sure and keeps their bits
+  // beside their words (below that the scattered zeros of the emit pass cost less than the slower pass)
+  p.zero_sure = chunks && K * 512 >= N;
+  if ((double)M * ((p.zero_sure ? 8.0 : 4.0) * p.cand_stride + 8.0 * p.brk_stride) + 16.0 > (double)pool_bytes) return p;
   p.candidates = true;
   p.chunks = chunks;
   p.n_units = (u32)(sp.s / kSampleUnit);
@@ -1715,6 +1783,10 @@ u64 candidate_pool_bytes(u32 M_max, u64 N_max, u64 K_max) {
     const double slots = extra_slots(sp.bound, N_max) + first_slab_factor(sp.bound, N_max) * sp.bound + 2.0 * kWaveTile;
     const double bytes = 4.0 * (slots + 4.0) + 8.0 * (slots / (double)(1u << sp.brk_shift) + 66.0);
     if (bytes > best) best = bytes;
+    // the pass with a memory: exactly the candidates found, and their bits kept beside their words
+    const double slots_c = sp.bound + 2.0 * kWaveTile;
+    const double bytes_c = 8.0 * (slots_c + 4.0) + 8.0 * (slots_c / (double)(1u << sp.brk_shift) + 66.0);
+    if (bytes_c > best) best = bytes_c;
   }
   if (best == 0) return 0;
   // once: the rounding of every wave's first slab to a whole smallest slab, words and records
@@ -1776,6 +1848,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     // the pool: the candidate words of every row, then their bracket records
     t.cand = reinterpret_cast<u32*>(ws.pool);
     t.recs = reinterpret_cast<uint2*>(ws.pool + (((size_t)M * p.cand_stride * 4 + 15) & ~(size_t)15));
+    t.kept = p.zero_sure ? reinterpret_cast<u32*>(ws.pool + ((((size_t)M * p.cand_stride * 4 + 15) & ~(size_t)15) + (size_t)M * p.brk_stride * 8))
+                      : nullptr;
     t.cand_stride = p.cand_stride;
     t.brk_stride = p.brk_stride;
     t.brk_shift = p.brk_shift;
@@ -1791,15 +1865,27 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
                                                                        p.unit_stride, p.sample_rank, p.sample_rank_hi, first_alloc)));
     S3GD_SWAP;
     if (p.chunks) {
-      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepSample1><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, p.sample_rank, 0u, 0u, ws.status)));
+      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepSample1><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, p.sample_rank, 0u, 0u, ws.status, ws.rc)));
       S3GD_SWAP;
-      S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t, p.n_chunks,
-                                                                                         ws.status)));
+      if (p.zero_sure) {
+        S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
+                                                                                                 p.n_chunks, ws.status)));
+        S3GD_SWAP;
+        // the verdict on the pass, and for a row it sends to the general route the entries back that the pass stored as zeros
+        S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepFilter><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status, ws.rc)));
+        S3GD_SWAP;
+        const u32 rx = (p.n_chunks + kWaves - 1) / kWaves;
+        S3GD_LAUNCH(KID_RESOLVE, (k_restore_kept<<<dim3(rx < 1024u ? rx : 1024u, M), kBlock, 0, s>>>(cur, t, p.n_chunks, err, N)));
+      } else {
+        S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
+                                                                                                  p.n_chunks, ws.status)));
+        S3GD_SWAP;
+      }
     } else {
       S3GD_LAUNCH(KID_FILTER, (k_filter<<<grid, kBlock, 0, s>>>(grads, N, k32, cur, nxt, ws.rc, ws.hist, t, p.n_wtiles, p.tiles_per_wave, p.slab,
                                                                p.sample_rank, sample_cap, ws.status)));
+      S3GD_SWAP;
     }
-    S3GD_SWAP;
   } else {
     S3GD_LAUNCH(KID_ENCODE_INIT, (k_encode_init<<<(M + 255) / 256, 256, 0, s>>>(cur, ws.rc, ws.status, M, k32, all ? 1u : 0u)));
   }
@@ -1821,7 +1907,7 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     const u32 cx = (t.n_lists + kWaves - 1) / kWaves;  // count: a wave per segment list
     const u32 pre = cx > 2048 ? 1u : 0u;  // too many blocks to repeat the last resolve step in each
     if (pre) {
-      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepRadix2Cand><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status)));
+      S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepRadix2Cand><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status, ws.rc)));
       S3GD_SWAP;
     }
     S3GD_LAUNCH(KID_CAND_SELECT, (k_cand_count<<<dim3(cx, M), kBlock, 0, s>>>(cur, nxt, ws.hist, t, k32, ws.wave_sum, pre)));

@@ -87,6 +87,7 @@ struct Workspace {
 struct EncodePlan {
   bool candidates;   // try the candidate route first
   bool chunks;       // the filter pass runs in chunks (one block each, in index order) instead of persistent waves
+  bool zero_sure;    // that pass stores +0.0 over the entries at or above U and keeps their bits beside their words
   u32 n_chunks, n_lists;  // chunked filter pass: blocks per row, segment lists per row
   u32 n_tiles, gx;   // 4096-entry tiles per row, streaming blocks per row
   u32 n_wtiles, tiles_per_wave;  // candidate route: 1024-entry wave tiles per row, and per wave of the filter
@@ -97,7 +98,7 @@ struct EncodePlan {
   u32 cand_stride;   // candidate word slots per row
   u32 brk_shift;     // a segment of n word slots has room for n >> brk_shift bracket records
   u32 brk_stride;    // bracket record slots per row
-  u32 slab;          // candidate slots a wave of the filter pass owns at a time (a power of two)
+  u32 slab;          // candidate slots a wave of the filter pass owns at a time (a multiple of 256)
   double bound;      // upper estimate of the candidates per row, without slab slack
 };
 EncodePlan plan_encode(u32 M, u64 N, u64 K, u64 pool_bytes, u32 stream_blocks, bool chunks);

@@ -357,7 +357,10 @@ class Context:
         self._check(_lib.s3gd_encode_plan_info(self._h, M, N, K, int(with_memory), out), "s3gd_encode_plan_info")
         names = ("candidates", "chunks", "record_shift", "blocks_per_row", "tiles_per_wave", "slab", "cand_stride", "n_units",
                  "unit_stride", "sample_rank", "chain", "sample_unit")
-        return {k: int(v) for k, v in zip(names, out)}
+        info = {k: int(v) for k, v in zip(names, out)}
+        info["zero_sure"] = info["chunks"] >> 1
+        info["chunks"] &= 1
+        return info
 
     def profile_enable(self, on: bool | int = True):
         """True / 1: time every kernel; 2: only the passes over the gradients; False / 0: off."""

@@ -235,6 +235,88 @@ def test_rows_fall_back_independently_with_memory(ctx):
     assert ctx.last_encode_info()[1] == 3
 
 
+def _unsampled_positions(lib, plan, N):
+    sampled = np.zeros(N, dtype=bool)
+    for u in range(plan["n_units"]):
+        p = lib.encode_sample_unit_start(u, plan["unit_stride"])
+        sampled[p:p + plan["sample_unit"]] = True
+    return sampled
+
+
+def _memory_case_against_the_sample(lib, make_g, N, K, expect_general, expect_mode=None):
+    """Row 0 of g = g~ + e is built by `make_g(sampled, plan, rng)` against the positions the sample looks
+    at; row 1 is ordinary.  The step with a memory must return the oracle's words, counts, parameters and
+    memory (every coordinate: whatever the pass stored as zero and was not sent has to be back)."""
+    rng = np.random.default_rng(N % 1000 + K)
+    with lib.Context(2, N, K, device=0) as c:
+        plan = c.encode_plan_info(2, N, K, with_memory=True)
+        assert plan["candidates"] and plan["chunks"] and plan["zero_sure"], plan
+        g0 = make_g(_unsampled_positions(lib, plan, N), plan, rng)
+        E = np.stack([(rng.standard_normal(N) * 0.25).astype(np.float32), (rng.standard_normal(N) * 0.3).astype(np.float32)])
+        E[0] = np.round(E[0] * 64) / 64        # dyadic, so that g~ = g - e and g~ + e = g are both exact in fp32
+        g0 = (np.round(g0.astype(np.float64) * 4096) / 4096).astype(np.float32)
+        Gt = np.stack([(g0 - E[0]).astype(np.float32), rng.standard_normal(N).astype(np.float32)])
+        assert np.array_equal((Gt[0] + E[0]).astype(np.float32), g0)
+        x = rng.standard_normal(N).astype(np.float32)
+        want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
+        got = gpu_step_ec(c, Gt, E, 1.0, K, x, 1e-3, fused=True, dense_outputs=False)
+        assert_same(got, want, keys=("words", "counts", "err", "x"), what="memory, row built against the sample")
+        assert c.last_encode_details()[:2] == (2, expect_general)
+        if expect_mode is not None:
+            assert c.last_row_state(0)["mode"] == expect_mode, c.last_row_state(0)
+    return got
+
+
+def test_zeroed_entries_come_back_when_the_pool_runs_out(lib):
+    """Nearly every entry outside the sampled units is large: both sampled bounds lie among the small
+    entries, so the pass with a memory takes the large ones for sure and stores zeros over them, chunk after
+    chunk, until the row's pool runs out.  The row is handed to the general route, which must find g
+    whole: the zeroed entries are written back from the bits kept beside their words."""
+    N, K = 1 << 22, (1 << 22) // 250
+
+    def make_g(sampled, plan, rng):
+        g = ((50.0 + rng.random(N) * 50.0) * np.sign(rng.standard_normal(N))).astype(np.float32)
+        small = (rng.standard_normal(N) * 0.01).astype(np.float32)
+        g[sampled] = small[sampled]
+        assert N - int(sampled.sum()) > plan["cand_stride"]
+        return g
+    _memory_case_against_the_sample(lib, make_g, N, K, expect_general=1)
+
+
+def _hidden_top_row(N, n_top, sampled, rng):
+    """0.001 everywhere; 1500 entries of 0.5, all at sampled positions (both sampled bounds land on them); n_top
+    large entries, none at a sampled position."""
+    g = np.full(N, 0.001, dtype=np.float32)
+    g[rng.choice(np.nonzero(sampled)[0], size=1500, replace=False)] = 0.5
+    top = rng.choice(np.nonzero(~sampled)[0], size=n_top, replace=False)
+    g[top] = ((100.0 + rng.random(n_top) * 20.0) * np.sign(rng.standard_normal(n_top))).astype(np.float32)
+    return g
+
+
+def test_zeroed_entries_come_back_when_too_many_were_taken_for_sure(lib):
+    """K + 2000 large entries that the sample does not see: the pass takes them all for sure (more than K,
+    all stored as zeros), everything fits the pool, and the verdict after the pass sends the row to the
+    general route."""
+    N, K = 1 << 22, 1 << 14
+
+    def make_g(sampled, plan, rng):
+        assert plan["sample_rank"] < 1500 and K + 2000 + 1500 + 2048 < plan["cand_stride"], plan
+        return _hidden_top_row(N, K + 2000, sampled, rng)
+    _memory_case_against_the_sample(lib, make_g, N, K, expect_general=1)
+
+
+def test_every_sent_entry_zeroed_by_the_pass_itself(lib):
+    """Exactly K large entries that the sample does not see: the pass takes exactly K for sure, the whole
+    bracket loses, and the emit pass has no zero left to write (threshold known after the pass: mode 3)."""
+    N, K = 1 << 22, 1 << 14
+
+    def make_g(sampled, plan, rng):
+        assert plan["sample_rank"] < 1500 and K + 1500 + 2048 < plan["cand_stride"], plan
+        return _hidden_top_row(N, K, sampled, rng)
+    got = _memory_case_against_the_sample(lib, make_g, N, K, expect_general=0, expect_mode=3)
+    assert int((got["err"][0] == 0).sum()) == K
+
+
 def test_special_values(ctx):
     """Denormals stay denormal in g~ + eta * e; -0.0 and +0.0; infinities are selected and replaced
     by +0.0 in the memory; selected zeros keep their bits."""
