@@ -260,21 +260,30 @@ def main():
         elif args.momentum:
             ctx.step_momentum(g, K, x, mom, lr, 0.9, words, counts, err=err, eta=1.0)
         elif args.memory_acc:
-            ctx.step_acc(g, K, x, lr, words, counts, None, None)  # g plays the memory: each step's zeros stay in it
+            ctx.step_acc(acc, K, x, lr, words, counts, None, None)
         elif args.memory:
             ctx.step_ec(g, err, 1.0, K, x, lr, words, counts, None, None)
         else:
             raise AssertionError
 
+    # s3gd_step_acc finds g~ + e in the memory: the producer of the gradients accumulates them there.  Here that is an
+    # addition before every step, outside the step's event pair (the step's time is then the mean of the event times).
+    acc = g.clone() if args.memory_acc else None
+    before_step = (lambda: acc.add_(g)) if args.memory_acc else None
+
     is_variant = args.randk or args.wire or args.momentum or args.memory_acc or args.memory
     headline = variant_step if is_variant else (three_calls_step if args.three_calls else fused_step)
 
-    def measure(eager_step, steps, warmup, use_graph=False):
+    def measure(eager_step, steps, warmup, use_graph=False, pre=None):
         """W untimed steps, then exactly `steps` steps between two synchronisations.  Returns the mean wall
         time per step, the median of the per-step times between HIP events recorded on the launch stream,
         and the per-kernel figures (a breakdown pass with an event pair around every launch, run before the
         timed region; the dominant passes carry their own event pair inside it)."""
         one_step = eager_step
+        if pre is not None:
+            def one_step():
+                pre()
+                eager_step()
         if use_graph:
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
@@ -293,27 +302,39 @@ def main():
         routes = ctx.last_encode_routes()
         ctx.profile_enable(1)
         for _ in range(3):
-            eager_step()
+            one_step() if pre is not None else eager_step()
         prof = ctx.profile_read()
         kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / 3} for k, v in prof.items()}
         ctx.profile_enable(0 if use_graph else 2)
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps if pre is not None else 1)]
+        ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        marks[0].record()
-        for i in range(steps):
-            one_step()
-            marks[i + 1].record()
+        if pre is None:
+            starts[0].record()
+            for i in range(steps):
+                one_step()
+                ends[i].record()
+        else:
+            for i in range(steps):
+                pre()
+                starts[i].record()
+                eager_step()
+                ends[i].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         live = {} if use_graph else ctx.profile_read()
         ctx.profile_enable(0)
-        per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+        if pre is None:  # a step runs from the end of the step before it to its own end: launch gaps included
+            per_step = [starts[0].elapsed_time(ends[0])] + [ends[i - 1].elapsed_time(ends[i]) for i in range(1, steps)]
+        else:  # the producer's work before each step lies outside the step's event pair
+            per_step = [starts[i].elapsed_time(ends[i]) for i in range(steps)]
+            dt = sum(per_step) * 1e-3
         for k, v in live.items():  # measured inside the timed region: these replace the figures of the breakdown pass
             kern[k] = {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / steps}
         return dt * 1e3 / steps, statistics.median(per_step), kern, set(live), routes
 
-    ms_step, ms_median, kern, live, routes = measure(headline, args.steps, args.warmup, args.graph)
+    ms_step, ms_median, kern, live, routes = measure(headline, args.steps, args.warmup, args.graph, pre=before_step)
     log(f"[bench] timed {args.steps} steps: mean {ms_step:.4f} ms, median of per-step event times {ms_median:.4f} ms")
     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["ms_avg"] * kv[1]["launches_per_step"]):
         log(f"[bench]   {k:14s} {v['ms_avg']:9.4f} ms x {v['launches_per_step']:.0f}" + ("  (timed region)" if k in live else ""))
@@ -382,7 +403,10 @@ def main():
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe, "entry": entry,
                    "rows": {"general_route": general, "wide_radix_select": _wide, "row_passes_known_threshold": row_pass,
                             "skipped_single_pass": skipped},
-                   "launch": "HIP graph replay" if args.graph else "eager"},
+                   "launch": "HIP graph replay" if args.graph else "eager",
+                   "timing": ("mean of per-step HIP event times; before each step the gradients are accumulated into the memory "
+                              "(acc += g, the producer's work), outside the step's event pair") if args.memory_acc else
+                             "wall clock over the timed steps between two synchronisations"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK, "algorithmic_bytes_per_launch": dom_bytes,
                      "duration_from": "HIP events inside the timed region" if dom in live else "HIP events, eager pass before the timed region",

@@ -1169,12 +1169,16 @@ __device__ __forceinline__ void place_chunk_tile(const TileRegs& r, u32 a, u32 t
   }
 }
 
-template <bool ZERO_SURE>
+// FORMED: the memory buffer already holds g (the caller accumulated the gradients into it): the pass reads the one
+// row and rewrites it with the zeros, which from K = N/32 on costs less than the read-only pass followed by a
+// scattered store per sent entry.
+template <bool ZERO_SURE, bool FORMED>
 __global__ __launch_bounds__(kBlock, ZERO_SURE ? kChunkWavesPerSimdZero : kChunkWavesPerSimd) void k_filter_chunks(const float* __restrict__ grads, float* __restrict__ err, float eta, u64 N,
                                                           const RowState* __restrict__ rs_in, RowState* __restrict__ rs_out,
                                                           RowCounters* __restrict__ rc, CandTables t, u32 n_chunks,
                                                           u32* __restrict__ status) {
   static_assert(kChunkTiles == 2, "the two wave tiles of a chunk are held in named registers");
+  static_assert(ZERO_SURE || !FORMED, "a formed row is only rewritten for the zeros");
   const u32 m = blockIdx.y;
   __shared__ u32 wsum[kWaves], wsumb[kWaves];
   __shared__ u32 sbase, sbaseb;
@@ -1188,7 +1192,7 @@ __global__ __launch_bounds__(kBlock, ZERO_SURE ? kChunkWavesPerSimdZero : kChunk
   u64* const list_seg = t.wave_seg;
   u64* const list_segb = t.wave_segb;
   u32* const list_nseg = t.wave_nseg;
-  const float* row = grads + (size_t)m * N;
+  const float* row = (FORMED ? err : grads) + (size_t)m * N;
   const u32 a = (u32)((reinterpret_cast<uintptr_t>(row) >> 2) & 3u);
   const u32* rowv = reinterpret_cast<const u32*>(row) - a;
   u32* errv = reinterpret_cast<u32*>(err + (size_t)m * N) - a;
@@ -1200,7 +1204,13 @@ __global__ __launch_bounds__(kBlock, ZERO_SURE ? kChunkWavesPerSimdZero : kChunk
   const u32 last = (u32)(vend / kWaveTile);   // tiles below this index end inside the row
   const bool in0 = t0 >= first && t0 < last, in1 = t1 >= first && t1 < last;  // wave-uniform
   TileRegs r0, r1;
-  {
+  if (FORMED) {
+    const u32 sure_from = st.U;
+    if (in0) load_filter_tile<true>(rowv, a, vend, t0, lane, r0); else load_filter_tile<false>(rowv, a, vend, t0, lane, r0);
+    if (in1) load_filter_tile<true>(rowv, a, vend, t1, lane, r1); else load_filter_tile<false>(rowv, a, vend, t1, lane, r1);
+    if (in0) store_chunk_tile<true>(errv, t0, lane, r0, sure_from); else store_chunk_tile<false>(errv, t0, lane, r0, sure_from);
+    if (in1) store_chunk_tile<true>(errv, t1, lane, r1, sure_from); else store_chunk_tile<false>(errv, t1, lane, r1, sure_from);
+  } else {
     TileRegs e0, e1;
     if (in0) { load_filter_tile<true>(rowv, a, vend, t0, lane, r0); load_filter_tile<true>(errv, a, vend, t0, lane, e0); }
     else { load_filter_tile<false>(rowv, a, vend, t0, lane, r0); load_filter_tile<false>(errv, a, vend, t0, lane, e0); }
@@ -1657,7 +1667,7 @@ static u32 blocks_per_row(u32 M, u32 n_tiles, u32 stream_blocks) {
 u32 resident_stream_blocks(int device, bool with_memory) {
   int cus = 0, per_cu = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) cus = 256;
-  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_chunks<false>, kBlock, 0)
+  const hipError_t e = with_memory ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (k_filter_chunks<false, false>), kBlock, 0)
                                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter, kBlock, 0);
   if (e != hipSuccess || per_cu <= 0) per_cu = 4;
   const u32 n = (u32)cus * (u32)per_cu;
@@ -1810,7 +1820,12 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
   const bool formed = err && !grads;
   if (formed) grads = err;
   float* mem = formed ? nullptr : err;  // the memory to add in, if any
-  const EncodePlan p = plan_encode(M, N, K, ws.pool_bytes, mem ? ws.stream_blocks_mem : ws.stream_blocks, mem != nullptr);
+  // a formed row takes the pass in chunks too once K reaches N/32: rewriting the row with the zeros in it then
+  // costs less than the read-only pass followed by a scattered store per sent entry (M = 8, N = 1.24e8:
+  // 1.73 ms against 1.47 ms at K = N/50, 1.89 ms against 2.8 ms at K = N/20)
+  const bool rewrite = formed && K * 32 >= N;
+  EncodePlan p = plan_encode(M, N, K, ws.pool_bytes, (mem || rewrite) ? ws.stream_blocks_mem : ws.stream_blocks, mem != nullptr || rewrite);
+  if (rewrite && !p.candidates) p = plan_encode(M, N, K, ws.pool_bytes, ws.stream_blocks, false);
   if (mem && !(K > 0 && p.candidates)) {  // no filter pass will run: form g in the memory buffer first
     const u64 total = (u64)M * N;
     const u32 head = (u32)((4 - ((reinterpret_cast<uintptr_t>(err) >> 2) & 3u)) & 3u);
@@ -1868,8 +1883,12 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
       S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepSample1><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, p.sample_rank, 0u, 0u, ws.status, ws.rc)));
       S3GD_SWAP;
       if (p.zero_sure) {
-        S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
-                                                                                                 p.n_chunks, ws.status)));
+        if (formed)
+          S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true, true><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
+                                                                                                         p.n_chunks, ws.status)));
+        else
+          S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<true, false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
+                                                                                                          p.n_chunks, ws.status)));
         S3GD_SWAP;
         // the verdict on the pass, and for a row it sends to the general route the entries back that the pass stored as zeros
         S3GD_LAUNCH(KID_RESOLVE, (k_advance<kStepFilter><<<M, kBlock, 0, s>>>(cur, nxt, ws.hist, k32, 0u, 0u, 0u, ws.status, ws.rc)));
@@ -1877,8 +1896,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
         const u32 rx = (p.n_chunks + kWaves - 1) / kWaves;
         S3GD_LAUNCH(KID_RESOLVE, (k_restore_kept<<<dim3(rx < 1024u ? rx : 1024u, M), kBlock, 0, s>>>(cur, t, p.n_chunks, err, N)));
       } else {
-        S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
-                                                                                                  p.n_chunks, ws.status)));
+        S3GD_LAUNCH(KID_FILTER_MEM, (k_filter_chunks<false, false><<<dim3(p.n_chunks, M), kBlock, 0, s>>>(grads, err, eta, N, cur, nxt, ws.rc, t,
+                                                                                                         p.n_chunks, ws.status)));
         S3GD_SWAP;
       }
     } else {

@@ -243,7 +243,7 @@ def _unsampled_positions(lib, plan, N):
     return sampled
 
 
-def _memory_case_against_the_sample(lib, make_g, N, K, expect_general, expect_mode=None):
+def _memory_case_against_the_sample(lib, make_g, N, K, expect_general, expect_mode=None, formed=False):
     """Row 0 of g = g~ + e is built by `make_g(sampled, plan, rng)` against the positions the sample looks
     at; row 1 is ordinary.  The step with a memory must return the oracle's words, counts, parameters and
     memory (every coordinate: whatever the pass stored as zero and was not sent has to be back)."""
@@ -259,7 +259,18 @@ def _memory_case_against_the_sample(lib, make_g, N, K, expect_general, expect_mo
         assert np.array_equal((Gt[0] + E[0]).astype(np.float32), g0)
         x = rng.standard_normal(N).astype(np.float32)
         want = O.step_with_memory(Gt, E, 1.0, K, x, 1e-3)
-        got = gpu_step_ec(c, Gt, E, 1.0, K, x, 1e-3, fused=True, dense_outputs=False)
+        if formed:  # the buffer already holds g~ + e (s3gd_step_acc): from K = N/32 on the pass rewrites it
+            acc = torch.from_numpy(O.compensate(Gt, E, 1.0)).cuda()
+            words = torch.full((2, K), 0x55555555, dtype=torch.int32, device="cuda")
+            counts = torch.full((2,), 0x55555555, dtype=torch.int32, device="cuda")
+            xd = torch.from_numpy(x.copy()).cuda()
+            c.step_acc(acc, K, xd, 1e-3, words, counts)
+            torch.cuda.synchronize()
+            assert c.last_async_status() == 0
+            got = dict(words=words.cpu().numpy().view(np.uint32), counts=counts.cpu().numpy().view(np.uint32),
+                       err=acc.cpu().numpy(), x=xd.cpu().numpy())
+        else:
+            got = gpu_step_ec(c, Gt, E, 1.0, K, x, 1e-3, fused=True, dense_outputs=False)
         assert_same(got, want, keys=("words", "counts", "err", "x"), what="memory, row built against the sample")
         assert c.last_encode_details()[:2] == (2, expect_general)
         if expect_mode is not None:
@@ -283,11 +294,11 @@ def test_zeroed_entries_come_back_when_the_pool_runs_out(lib):
     _memory_case_against_the_sample(lib, make_g, N, K, expect_general=1)
 
 
-def _hidden_top_row(N, n_top, sampled, rng):
-    """0.001 everywhere; 1500 entries of 0.5, all at sampled positions (both sampled bounds land on them); n_top
+def _hidden_top_row(N, n_top, sampled, rng, n_mid=1500):
+    """0.001 everywhere; n_mid entries of 0.5, all at sampled positions (both sampled bounds land on them); n_top
     large entries, none at a sampled position."""
     g = np.full(N, 0.001, dtype=np.float32)
-    g[rng.choice(np.nonzero(sampled)[0], size=1500, replace=False)] = 0.5
+    g[rng.choice(np.nonzero(sampled)[0], size=n_mid, replace=False)] = 0.5
     top = rng.choice(np.nonzero(~sampled)[0], size=n_top, replace=False)
     g[top] = ((100.0 + rng.random(n_top) * 20.0) * np.sign(rng.standard_normal(n_top))).astype(np.float32)
     return g
@@ -303,6 +314,20 @@ def test_zeroed_entries_come_back_when_too_many_were_taken_for_sure(lib):
         assert plan["sample_rank"] < 1500 and K + 2000 + 1500 + 2048 < plan["cand_stride"], plan
         return _hidden_top_row(N, K + 2000, sampled, rng)
     _memory_case_against_the_sample(lib, make_g, N, K, expect_general=1)
+
+
+@pytest.mark.parametrize("n_extra", [0, 2000], ids=["exactly_K_for_sure", "too_many_for_sure"])
+def test_rewritten_buffer_against_the_sample(lib, n_extra):
+    """The same two rows through s3gd_step_acc at K = N/32, where the pass reads the one buffer and rewrites it
+    with the zeros: with exactly K hidden entries nothing is left for the emit pass to zero; with 2000 more
+    the row ends on the general route and every zero the pass stored is taken back."""
+    N, K = 1 << 22, 1 << 17
+
+    def make_g(sampled, plan, rng):
+        n_mid = plan["sample_rank"] + 800
+        assert K + n_extra + n_mid + 2048 < plan["cand_stride"], plan
+        return _hidden_top_row(N, K + n_extra, sampled, rng, n_mid=n_mid)
+    _memory_case_against_the_sample(lib, make_g, N, K, expect_general=1 if n_extra else 0, expect_mode=0 if n_extra else 3, formed=True)
 
 
 def test_every_sent_entry_zeroed_by_the_pass_itself(lib):
