@@ -91,13 +91,13 @@ def cpu_baseline(cfg, datagen):
                       f"K={k_s}, one step; 1 thread {t_cpu1:.1f} s, {threads} threads over the rows {t_cpup:.1f} s"}
 
 
-def kernel_bytes(name, M, N, K, rows, n_voted, dense_state, tally_out, votes_out):
+def kernel_bytes(name, M, N, K, rows, n_voted, dense_state, tally_out, votes_out, mem_pass_bytes=12.0):
     """Algorithmic bytes one launch of a kernel moves: what the step needs from that pass, not what the
     hardware counters saw.  `rows` = rows of G the pass actually reads."""
     if name in ("filter", "hist_rows_0", "hist_rows_1", "hist_rows_2", "tile_count", "emit_rows"):
         return 4.0 * N * rows
-    if name == "filter_mem":  # reads g~ and e, writes the new memory
-        return 12.0 * N * rows
+    if name == "filter_mem":  # reads g~ and e, writes the new memory (8 bytes an entry when it rewrites the one buffer that holds g)
+        return mem_pass_bytes * N * rows
     if name == "plain_read":
         return 4.0 * M * N
     if name == "randk":  # K gathered gradient entries and K words per row
@@ -347,7 +347,10 @@ def main():
     n_voted = int(seen.sum().item())
     del seen
     n_rows, general, _wide, row_pass, skipped = routes
-    plan = ctx.encode_plan_info(M, N, K, with_memory=args.memory)
+    # s3gd_step_acc takes the pass in chunks, over the one buffer, from K = N/32 on
+    rewrite = args.memory_acc and K * 32 >= N
+    plan = ctx.encode_plan_info(M, N, K, with_memory=args.memory or rewrite)
+    mem_pass_bytes = 8.0 if rewrite else 12.0
     # rows of G each pass reads (the kernels of routes no row takes are enqueued and return at once)
     rows_read = {"filter": (M - skipped) if plan["candidates"] and not plan["chunks"] else 0,
                  "filter_mem": M if plan["candidates"] and plan["chunks"] else 0,
@@ -357,7 +360,7 @@ def main():
         rows_read = {}
 
     def alg_bytes(name, tally_out=False, votes_out=False):
-        return kernel_bytes(name, M, N, K, rows_read.get(name, M), n_voted, args.dense_state, tally_out, votes_out)
+        return kernel_bytes(name, M, N, K, rows_read.get(name, M), n_voted, args.dense_state, tally_out, votes_out, mem_pass_bytes)
 
     def fractions(kern_, votes_out):
         out = {}
@@ -374,7 +377,7 @@ def main():
     achieved = dom_bytes / (kern[dom]["ms_avg"] * 1e-3)
     # bytes of G the step reads as built, plus the words written and read; the floor is one read of G, the words,
     # and a read and a write of every voted parameter (the fused step never moves an unvoted one)
-    per_pass = {"filter_mem": 12.0}
+    per_pass = {"filter_mem": mem_pass_bytes}
     g_bytes = sum(per_pass.get(k, 4.0) * N * r for k, r in rows_read.items() if k in kern)
     as_built = g_bytes + 8.0 * M * K + 8.0 * n_voted
     floor_bytes = (12.0 if args.memory else 4.0) * M * N + 8.0 * M * K + 8.0 * n_voted

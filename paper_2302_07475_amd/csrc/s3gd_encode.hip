@@ -1440,11 +1440,14 @@ __device__ __forceinline__ void load_records(const ListTable& lt, const uint2* p
   }
 }
 
+// WINNERS: the filter pass has already stored +0.0 over the sure entries (t.kept is set), so only the bracket's
+// winners are still to be zeroed in the memory: they get a bit map of their own.
+template <bool WINNERS>
 __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict__ rs, CandTables t, u64 K, const u64* __restrict__ list_counts,
                                                       u32 scanned, u32* __restrict__ words, float* __restrict__ err, u64 N) {
   const u32 m = blockIdx.y;
   __shared__ u32 drop[kDropRound / 32];
-  __shared__ u32 won[kDropRound / 32];  // with `kept`: the bracket's winners, the only sent entries not yet zero in the memory
+  __shared__ u32 won[WINNERS ? kDropRound / 32 : 1];
   __shared__ u32 part_eq[kWaves];
   __shared__ u64 lists_before;
   __shared__ ListTable lt;
@@ -1498,7 +1501,6 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
   load_records(lt, rpool, rlo, rhi, lane, rbuf);
   load_words(lt, wpool, wlo, whi, lane, wbuf);
   float* erow = err ? err + (size_t)m * N : nullptr;
-  const bool bracket_only = erow && t.kept;  // the filter pass has already stored +0.0 over the sure entries
   u32* out = words + (size_t)m * K;
   // the ties among this wave's records (the waves after it must know)
   u32 eq = 0;
@@ -1533,7 +1535,10 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
 
   for (u32 a0 = 0; a0 < wtotal; a0 += kDropRound) {  // block-uniform
     const u32 a1 = a0 + kDropRound < wtotal ? a0 + kDropRound : wtotal;
-    for (u32 i = threadIdx.x; i < (a1 - a0 + 31) / 32; i += blockDim.x) { drop[i] = 0; won[i] = 0; }
+    for (u32 i = threadIdx.x; i < (a1 - a0 + 31) / 32; i += blockDim.x) {
+      drop[i] = 0;
+      if (WINNERS) won[i] = 0;
+    }
     __syncthreads();
     // this wave's records, in order: those of candidates before the round only count as ties seen, those
     // of the round are marked if they lose, and the walk ends at the first one beyond the round
@@ -1557,7 +1562,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
         const u64 eqm = ballot(is_eq);
         const bool sel = key > st.T || (is_eq && eq_seen + ballot_rank(eqm) < st.q);
         if (upto && at >= a0 && !sel) atomicOr(&drop[(at - a0) >> 5], 1u << ((at - a0) & 31u));
-        if (upto && at >= a0 && sel && bracket_only) atomicOr(&won[(at - a0) >> 5], 1u << ((at - a0) & 31u));
+        if (WINNERS && upto && at >= a0 && sel) atomicOr(&won[(at - a0) >> 5], 1u << ((at - a0) & 31u));
         eq_seen += (u32)__popcll(eqm);
         beyond = beyond || ballot(ok && !upto) != 0;
       }
@@ -1595,7 +1600,7 @@ __global__ __launch_bounds__(kBlock) void k_cand_emit(const RowState* __restrict
           const u32 pos = o + ballot_rank(sel_mask);
           if (pos < K) {  // pos < K by construction
             out[pos] = wd[u];
-            if (erow && (!bracket_only || ((won[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u))) erow[wd[u] >> 1] = 0.0f;
+            if (erow && (!WINNERS || ((won[(j - a0) >> 5] >> ((j - a0) & 31u)) & 1u))) erow[wd[u] >> 1] = 0.0f;
           }
         }
         o += (u32)__popcll(sel_mask);
@@ -1938,7 +1943,8 @@ hipError_t launch_encode(const Workspace& ws, const float* grads, float* err, fl
     // and four waves on lists of 300 to 5000 candidates: two waves best throughout)
     const double per_list = p.bound / (double)t.n_lists;
     const u32 ew = per_list < 6144.0 ? 128u : (u32)kBlock;
-    S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<<<dim3(t.n_lists, M), ew, 0, s>>>(cur, t, K, ws.wave_sum, scanned, words, err, N)));
+    if (err && t.kept) S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<true><<<dim3(t.n_lists, M), ew, 0, s>>>(cur, t, K, ws.wave_sum, scanned, words, err, N)));
+    else S3GD_LAUNCH(KID_CAND_EMIT, (k_cand_emit<false><<<dim3(t.n_lists, M), ew, 0, s>>>(cur, t, K, ws.wave_sum, scanned, words, err, N)));
   }
   // General rows: per-tile counts and the emit pass (both return at once for the other rows); the emit
   // kernel also ends the call for every row.
