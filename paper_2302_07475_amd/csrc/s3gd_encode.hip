@@ -876,15 +876,23 @@ __device__ __forceinline__ void store_filter_tile(u32* __restrict__ rowv, u32 ti
 }
 
 // The same for the pass with a memory: entries whose key is at or above `sure_from` are stored as +0.0.
-template <bool INTERIOR>
+// CHANGED_ONLY (the row is rewritten in place): a 64-byte run, the 16 bytes of four neighbouring lanes, is
+// stored only if it holds such an entry.
+template <bool INTERIOR, bool CHANGED_ONLY = false>
 __device__ __forceinline__ void store_chunk_tile(u32* __restrict__ rowv, u32 tile, u32 lane, const TileRegs& r, u32 sure_from) {
   const u64 vbase = (u64)tile * kWaveTile;
 #pragma unroll
   for (int j = 0; j < kLoads; ++j) {
     u32* p = rowv + vbase + (u64)j * 256 + (u64)lane * 4;
     u32 v[4];
+    bool any = false;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (r.b[4 * j + e] & 0x7FFFFFFFu) >= sure_from ? 0u : r.b[4 * j + e];
+    for (int e = 0; e < 4; ++e) {
+      const bool sure = (r.b[4 * j + e] & 0x7FFFFFFFu) >= sure_from && (INTERIOR || ((r.valid >> (4 * j + e)) & 1u));
+      v[e] = sure ? 0u : r.b[4 * j + e];
+      any |= sure;
+    }
+    if (CHANGED_ONLY && ((ballot(any) >> (lane & ~3u)) & 0xFull) == 0) continue;
     if (INTERIOR || ((r.valid >> (4 * j)) & 0xFu) == 0xFu) {
       store_stream16(p, v[0], v[1], v[2], v[3]);
     } else {
@@ -1208,8 +1216,8 @@ __global__ __launch_bounds__(kBlock, ZERO_SURE ? kChunkWavesPerSimdZero : kChunk
     const u32 sure_from = st.U;
     if (in0) load_filter_tile<true>(rowv, a, vend, t0, lane, r0); else load_filter_tile<false>(rowv, a, vend, t0, lane, r0);
     if (in1) load_filter_tile<true>(rowv, a, vend, t1, lane, r1); else load_filter_tile<false>(rowv, a, vend, t1, lane, r1);
-    if (in0) store_chunk_tile<true>(errv, t0, lane, r0, sure_from); else store_chunk_tile<false>(errv, t0, lane, r0, sure_from);
-    if (in1) store_chunk_tile<true>(errv, t1, lane, r1, sure_from); else store_chunk_tile<false>(errv, t1, lane, r1, sure_from);
+    if (in0) store_chunk_tile<true, true>(errv, t0, lane, r0, sure_from); else store_chunk_tile<false, true>(errv, t0, lane, r0, sure_from);
+    if (in1) store_chunk_tile<true, true>(errv, t1, lane, r1, sure_from); else store_chunk_tile<false, true>(errv, t1, lane, r1, sure_from);
   } else {
     TileRegs e0, e1;
     if (in0) { load_filter_tile<true>(rowv, a, vend, t0, lane, r0); load_filter_tile<true>(errv, a, vend, t0, lane, e0); }
