@@ -36,17 +36,19 @@ HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
 # runs of this same command, scaled by the factors a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for
 # WRITE_SIZE).  Counter figures cannot be taken inside this run; they are quoted with the file they come from.
 PROFILED_TRAFFIC = {  # (workload, variant, dominant kernel): bytes read + bytes written per launch
-    ("C5", "", "filter"): (19.2003e9 + 0.0644e9, "profiles/s3gd_step_C5_hbm_traffic.md"),
-    ("C5", "three-calls", "filter"): (19.2003e9 + 0.0644e9, "profiles/s3gd_three_calls_C5_hbm_traffic.md"),
-    ("C4", "", "filter"): (3.9688e9 + 0.0876e9, "profiles/s3gd_step_C4_hbm_traffic.md"),
+    ("C5", "", "filter"): (19.2003e9 + 0.0652e9, "profiles/s3gd_step_C5_hbm_traffic.md"),
+    ("C5", "three-calls", "filter"): (19.2003e9 + 0.0653e9, "profiles/s3gd_three_calls_C5_hbm_traffic.md"),
+    ("C4", "", "filter"): (3.9688e9 + 0.0885e9, "profiles/s3gd_step_C4_hbm_traffic.md"),
     ("C3", "", "filter"): (3.2792e9 + 0.0166e9, "profiles/s3gd_step_C3_hbm_traffic.md"),
-    ("C2", "", "filter"): (0.7181e9 + 0.0183e9, "profiles/s3gd_step_C2_hbm_traffic.md"),
-    ("C4", "sparsity 0.1", "filter"): (3.9688e9 + 0.5572e9, "profiles/s3gd_step_C4_gamma0.1_hbm_traffic.md"),
-    ("C5", "memory", "filter_mem"): (38.4205e9 + 21.2991e9, "profiles/s3gd_step_ec_C5_hbm_traffic.md"),
-    ("C5", "memory-acc", "filter"): (19.2004e9 + 0.0644e9, "profiles/s3gd_step_acc_C5_hbm_traffic.md"),
-    ("C5", "momentum", "filter"): (19.2004e9 + 0.0643e9, "profiles/s3gd_step_momentum_C5_hbm_traffic.md"),
-    ("C5", "momentum dense-state", "vote_momentum"): (9.6932e9 + 9.6004e9, "profiles/s3gd_step_momentum_dense_C5_hbm_traffic.md"),
-    ("C5", "wire", "filter"): (19.2004e9 + 0.0644e9, "profiles/s3gd_wire_format_C5_hbm_traffic.md"),
+    ("C2", "", "filter"): (0.7181e9 + 0.0187e9, "profiles/s3gd_step_C2_hbm_traffic.md"),
+    ("C4", "sparsity 0.1", "filter"): (3.9688e9 + 0.5586e9, "profiles/s3gd_step_C4_gamma0.1_hbm_traffic.md"),
+    ("C5", "memory", "filter_mem"): (38.4211e9 + 21.3004e9, "profiles/s3gd_step_ec_C5_hbm_traffic.md"),
+    ("C4", "memory sparsity 0.1", "filter_mem"): (7.9416e9 + 4.9787e9, "profiles/s3gd_step_ec_C4_gamma0.1_hbm_traffic.md"),
+    ("C4", "memory-acc sparsity 0.1", "filter_mem"): (3.9698e9 + 4.0843e9, "profiles/s3gd_step_acc_C4_gamma0.1_hbm_traffic.md"),
+    ("C5", "memory-acc", "filter"): (19.2003e9 + 0.0649e9, "profiles/s3gd_step_acc_C5_hbm_traffic.md"),
+    ("C5", "momentum", "filter"): (19.2004e9 + 0.0652e9, "profiles/s3gd_step_momentum_C5_hbm_traffic.md"),
+    ("C5", "momentum dense-state", "vote_momentum"): (9.6932e9 + 9.6008e9, "profiles/s3gd_step_momentum_dense_C5_hbm_traffic.md"),
+    ("C5", "wire", "filter"): (19.2004e9 + 0.0653e9, "profiles/s3gd_wire_format_C5_hbm_traffic.md"),
 }
 
 

@@ -196,12 +196,15 @@ S3GD_API int s3gd_step_ec(s3gd_ctx* ctx, const float* grads, float* err, float e
  * The same iteration when the caller has already formed g_m in the memory buffer (Section 2.2, the same
  * two equations): a backward pass that accumulates its gradients into the buffer leaves
  * g_m = g~_m + e_m there (eta = 1), and any other eta is a scaling the caller applies before
- * accumulating.  The encode then reads one tensor instead of two and writes only the zeros:
+ * accumulating.  The encode then reads one tensor instead of two and leaves only the zeros in it:
  *
  *     words = TopKSign(acc_m),   acc_m <- acc_m - TopK(acc_m)      (+0.0 where a sign was sent)
  *
  *   acc    dev, in/out  [M, N] fp32, row stride N, 4-byte aligned: g_m on entry, the new memory on
- *                       return.  Only the sent entries are written.
+ *                       return.  Only the sent entries differ on return; while the call runs, other
+ *                       entries may be stored again with their own value (from K = N/32 on the row is
+ *                       rewritten in 64-byte runs) or hold +0.0 for a time, so nothing else may read
+ *                       the buffer before the call has finished on `stream`.
  *   words, counts, x, lr, tally, votes   as in s3gd_topk_sign_encode / s3gd_step.
  *
  * Bit for bit the result of s3gd_topk_sign_encode_ec / s3gd_step_ec called with gradients and memory
