@@ -371,7 +371,7 @@ S3GD_API uint64_t s3gd_encode_sample_unit_start(uint32_t u, uint64_t unit_stride
  * arrays of n >= S3GD_PROFILE_KERNELS entries), and clears the record.  At most 4096 launches are
  * kept between reads.  Names of the ids come from s3gd_profile_kernel_name (NULL past the end).
  */
-#define S3GD_PROFILE_KERNELS 27
+#define S3GD_PROFILE_KERNELS 26
 S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on);
 S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_sum, uint32_t* launches, int n);
 S3GD_API const char* s3gd_profile_kernel_name(int id);

@@ -596,7 +596,7 @@ S3GD_API int s3gd_profile_read(s3gd_ctx* ctx, s3gd_stream_t stream, float* ms_su
 S3GD_API const char* s3gd_profile_kernel_name(int id) {
   static const char* names[KID_COUNT] = {
       "encode_init", "hist_rows_0", "hist_rows_1", "hist_rows_2", "resolve", "tile_count", "scan_tiles", "emit_rows",
-      "finish_rows", "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
+      "sample", "filter", "cand_select", "cand_emit", "seg_bounds", "vote_dense", "vote_sparse",
       "apply_update", "compensate", "filter_mem", "vote_momentum", "apply_momentum", "pack", "unpack",
       "votes_to_message", "randk", "plain_read", "plain_rmw"};
   return (id >= 0 && id < KID_COUNT) ? names[id] : nullptr;

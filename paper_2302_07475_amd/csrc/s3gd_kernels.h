@@ -28,7 +28,7 @@ inline size_t seg_row_entries(u64 N) { return (size_t)((N + kMomTile - 1) / kMom
 // Kernel ids for the optional per-kernel timing (HIP events on the caller's stream).
 enum KernelId : int {
   KID_ENCODE_INIT = 0,
-  KID_HIST0, KID_HIST1, KID_HIST2, KID_RESOLVE, KID_TILE_COUNT, KID_SCAN_TILES, KID_EMIT, KID_FINISH,
+  KID_HIST0, KID_HIST1, KID_HIST2, KID_RESOLVE, KID_TILE_COUNT, KID_SCAN_TILES, KID_EMIT,
   KID_SAMPLE, KID_FILTER, KID_CAND_SELECT, KID_CAND_EMIT,
   KID_SEG_BOUNDS, KID_VOTE_DENSE, KID_VOTE_SPARSE, KID_UPDATE,
   KID_COMPENSATE, KID_FILTER_MEM, KID_VOTE_MOMENTUM, KID_UPDATE_MOMENTUM,

@@ -26,7 +26,7 @@ EXPORTS = (
     "s3gd_pack_messages", "s3gd_unpack_messages", "s3gd_votes_to_message", "s3gd_randk_sign_encode", "s3gd_step_randk", "s3gd_last_async_status", "s3gd_last_encode_info", "s3gd_last_hip_error",
     "s3gd_strerror", "s3gd_last_row_state", "s3gd_calibrate_read", "s3gd_calibrate_rmw", "s3gd_encode_plan_info", "s3gd_encode_sample_unit_start", "s3gd_profile_enable", "s3gd_profile_read", "s3gd_profile_kernel_name",
 )
-PROFILE_KERNELS = 27
+PROFILE_KERNELS = 26
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
