@@ -56,6 +56,17 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, datagen):
     """The oracle, as it stands, on a bounded sample: all M workers, the first N_s coordinates, K scaled to
     keep K/N.  Timed twice: on one thread (t_cpu1) and with the rows' selections spread over min(M, cores)
@@ -88,7 +99,7 @@ def cpu_baseline(cfg, datagen):
     assert np.array_equal(xp.view(np.uint32), one["x"].view(np.uint32))
     return {"value": cfg.M * n_s / t_cpup, "unit": "gradient elements/s", "cores": threads, "kind": "oracle",
             "single_thread_value": cfg.M * n_s / t_cpu1, "t_cpu1_s": round(t_cpu1, 2), "t_cpuP_s": round(t_cpup, 2),
-            "host_cores_available": cores, "sample_fraction": n_s / cfg.N,
+            "host_cores_available": cores, "cpu_model": cpu_model(), "sample_fraction": n_s / cfg.N,
             "sample": f"all {cfg.M} workers, first {n_s} of {cfg.N} coordinates of {cfg.name} ({100.0 * n_s / cfg.N:.1f} %), "
                       f"K={k_s}, one step; 1 thread {t_cpu1:.1f} s, {threads} threads over the rows {t_cpup:.1f} s"}
 
@@ -217,6 +228,11 @@ def main():
     t0 = time.perf_counter()
     g, x = datagen.to_device(cfg, device="cuda:0")
     log(f"[bench] {cfg.name}: M={cfg.M} N={cfg.N} K={cfg.K} generated and uploaded in {time.perf_counter() - t0:.1f} s")
+    # what the input was: SHA-256 of the first chunk (2^22 coordinates) of worker 0's gradients and of x^0, as generated on the host
+    import hashlib
+    input_sha256 = {"g[0] first chunk": hashlib.sha256(datagen.grad_chunk(cfg, 0, 0, 0).tobytes()).hexdigest(),
+                    "x0 first chunk": hashlib.sha256(datagen.x0_chunk(cfg, 0).tobytes()).hexdigest()}
+    log(f"[bench] input sha256: {input_sha256}")
     M, N, K = cfg.M, cfg.N, cfg.K
     if args.sparsity > 0:
         K = max(1, min(N, int(round(args.sparsity * N))))
@@ -404,7 +420,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "ms_per_step_median_of_event_times": ms_median,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic",
+        "dtype": "u32 keys of fp32 gradients, int32 tally, fp32 update", "data": "synthetic", "input_sha256": input_sha256,
         "config": {"workload": f"{cfg.name}: M={M} workers, N={N} fp32 coords, K={K}", "recipe": cfg.recipe, "entry": entry,
                    "rows": {"general_route": general, "wide_radix_select": _wide, "row_passes_known_threshold": row_pass,
                             "skipped_single_pass": skipped},
