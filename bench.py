@@ -324,28 +324,37 @@ def main():
         prof = ctx.profile_read()
         kern = {k: {"ms_avg": v[0] / v[1], "launches_per_step": v[1] / 3} for k, v in prof.items()}
         ctx.profile_enable(0 if use_graph else 2)
-        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps if pre is not None else 1)]
-        ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
         if pre is None:
-            starts[0].record()
+            # the timed region: exactly `steps` steps between two synchronisations; the only events on the stream are the
+            # pair around the dominant pass (profile mode 2: about 7 us per step)
+            t0 = time.perf_counter()
             for i in range(steps):
                 one_step()
-                ends[i].record()
-        else:
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            live = {} if use_graph else ctx.profile_read()
+            ctx.profile_enable(0)
+            # the same again with an event after every step, for the spread (each event costs the stream a few
+            # microseconds, which is why the timed region has none): a step runs from the end of the one before it
+            ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            ends[0].record()
+            for i in range(steps):
+                one_step()
+                ends[i + 1].record()
+            torch.cuda.synchronize()
+            per_step = [ends[i].elapsed_time(ends[i + 1]) for i in range(steps)]
+        else:  # the producer's work before each step lies outside the step's event pair
+            starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+            ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
             for i in range(steps):
                 pre()
                 starts[i].record()
                 eager_step()
                 ends[i].record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        live = {} if use_graph else ctx.profile_read()
-        ctx.profile_enable(0)
-        if pre is None:  # a step runs from the end of the step before it to its own end: launch gaps included
-            per_step = [starts[0].elapsed_time(ends[0])] + [ends[i - 1].elapsed_time(ends[i]) for i in range(1, steps)]
-        else:  # the producer's work before each step lies outside the step's event pair
+            torch.cuda.synchronize()
+            live = {} if use_graph else ctx.profile_read()
+            ctx.profile_enable(0)
             per_step = [starts[i].elapsed_time(ends[i]) for i in range(steps)]
             dt = sum(per_step) * 1e-3
         for k, v in live.items():  # measured inside the timed region: these replace the figures of the breakdown pass
@@ -427,7 +436,8 @@ def main():
                    "launch": "HIP graph replay" if args.graph else "eager",
                    "timing": ("mean of per-step HIP event times; before each step the gradients are accumulated into the memory "
                               "(acc += g, the producer's work), outside the step's event pair") if args.memory_acc else
-                             "wall clock over the timed steps between two synchronisations"},
+                             "wall clock over the timed steps between two synchronisations; the median of per-step event times comes "
+                             "from a second run of as many steps with an event after each"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK, "algorithmic_bytes_per_launch": dom_bytes,
                      "duration_from": "HIP events inside the timed region" if dom in live else "HIP events, eager pass before the timed region",
