@@ -327,7 +327,7 @@ def main():
         torch.cuda.synchronize()
         if pre is None:
             # the timed region: exactly `steps` steps between two synchronisations; the only events on the stream are the
-            # pair around the dominant pass (profile mode 2: about 7 us per step)
+            # pair around the dominant pass (profile mode 2: about 9 us per step)
             t0 = time.perf_counter()
             for i in range(steps):
                 one_step()

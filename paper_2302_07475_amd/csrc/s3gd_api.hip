@@ -561,7 +561,9 @@ S3GD_API int s3gd_profile_enable(s3gd_ctx* ctx, int on) {
     ctx->prof.ev = new (std::nothrow) hipEvent_t[2 * Profiler::kPairs];
     if (!ctx->prof.ev) return S3GD_E_NOMEM;
     for (int i = 0; i < 2 * Profiler::kPairs; ++i) {
-      const hipError_t e = hipEventCreate(&ctx->prof.ev[i]);
+      // timing only (read after the stream has been synchronised): no system-scope fence, whose cache write-back and
+      // invalidation would idle the stream around every timed kernel
+      const hipError_t e = hipEventCreateWithFlags(&ctx->prof.ev[i], hipEventDisableSystemFence);
       if (e != hipSuccess) {  // leave no half-made event array behind
         for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof.ev[j]);
         delete[] ctx->prof.ev;
